@@ -1,0 +1,227 @@
+/*
+ * kvfuse.h -- C ABI of the MI355X (gfx950) Fast Fusion library.
+ *
+ * Fast Fusion ("Joint Encoding of KV-Cache Blocks for Scalable LLM Serving", method section and
+ * Algorithm 1) fuses similar paged KV-cache blocks of different requests (BFF) or of different chunks of
+ * one request (CFF) into one shared unit-direction block, keeps a norm per logical block, and rewrites the
+ * block table so that several logical blocks point at one physical block.  This library is the
+ * data-parallel hot path of that method for ONE GPU:
+ *
+ *   a1 block norms -> a2 similarity -> a3 assignment -> a4 merge -> a5 block-table rewrite,
+ *   driven level by level over Algorithm 1's binary tree (a6), and a7 paged decode attention that reads
+ *   the cache through the fused table.
+ *
+ * Conventions
+ *   - Plain C.  Every call returns an int status (KVFUSE_OK = 0, else an error code below); the text of
+ *     the last error of a context is available from kvfuse_last_error().  Nothing throws or aborts.
+ *   - "device" pointers are HIP device memory owned by the caller (typically PyTorch tensors); the library
+ *     borrows them for the duration of a call and never frees them.  "host" pointers are ordinary host
+ *     memory read during the call only.  The library allocates no device memory: scratch comes from the
+ *     workspace handed to kvfuse_plan_create / kvfuse_paged_decode_attn, sized by the *_bytes queries.
+ *   - All work is enqueued on the context's stream and is asynchronous unless stated otherwise.
+ *   - A group g is one (layer, KV head): g = layer * kv_heads + kv_head.  Groups are independent.
+ *   - Pool layout: [G][P][t][d] elements, one block (r = t*d elements) contiguous.  dtype bf16 or f32.
+ *     r * sizeof(element) must be a multiple of 128 bytes and r <= 8192 (KVFUSE_ESHAPE otherwise).
+ *   - Representation (method section: "a single unit vector and a norm (scalar) per block"): logical block
+ *     x of group g stands for  scale[g][x] * stored(bt[g][x]).  Blocks that were never fused stay as they
+ *     were written (scale exactly 1); a fused representative is stored as a unit vector rounded to the
+ *     pool dtype, and scale = ||original x|| / ||stored representative||.
+ *   - Decisions (which block fuses into which) are taken on cosines evaluated in fp64 on the stored values.
+ *     The MFMA similarity kernel is a screen whose error is bounded by `band`; every candidate that the
+ *     screen cannot decide (within 2*band of the threshold or of the column maximum) is re-evaluated in
+ *     fp64 by kvfuse_assign, so the result does not depend on MFMA rounding.
+ */
+#ifndef KVFUSE_H
+#define KVFUSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    KVFUSE_OK = 0,
+    KVFUSE_EINVAL = 1,    /* bad argument (null pointer, negative size, overlapping leaves, ...) */
+    KVFUSE_ESHAPE = 2,    /* unsupported dtype / block size / head size */
+    KVFUSE_EOVERFLOW = 3, /* a caller-sized output is too small */
+    KVFUSE_ENOMEM = 4,    /* workspace too small */
+    KVFUSE_EHIP = 5       /* HIP runtime error; see kvfuse_last_error */
+};
+
+enum { KVFUSE_F32 = 0, KVFUSE_BF16 = 1 };
+
+typedef struct kvfuse_ctx kvfuse_ctx;   /* opaque; holds device id, stream, last error; no KV data */
+typedef struct kvfuse_plan kvfuse_plan; /* opaque; Algorithm 1's tree cut into heights + workspace layout */
+
+/* The paged KV cache of all groups (method section: cache laid out as blocks of t tokens). */
+typedef struct kvfuse_pool {
+    void *k;            /* device [G][P][t*d] dtype, keys   (fused rows are overwritten in place) */
+    void *v;            /* device [G][P][t*d] dtype, values (same) */
+    int32_t dtype;      /* KVFUSE_F32 or KVFUSE_BF16 */
+    int32_t G, P, t, d; /* groups, physical blocks per group, tokens per block, head size */
+    double *norm_k;     /* device [G][P] out: ||stored block||_2 in fp64 ("the norm of each r is stored") */
+    double *norm_v;     /* device [G][P] out */
+    float *inv_norm_k;  /* device [G][P] out: (float)(1/norm_k), 0 for a zero block; similarity epilogue operand */
+} kvfuse_pool;
+
+/* Per-group block tables and the per-logical-block rescale. */
+typedef struct kvfuse_table {
+    int32_t n;           /* logical blocks per group */
+    int32_t *bt;         /* device [G][n] in/out: logical -> physical.  Must be injective per group on entry */
+    float *scale_k;      /* device [G][n] out */
+    float *scale_v;      /* device [G][n] out */
+    double *orig_norm_k; /* device [G][n] out: norm of the block each logical entry had before fusion */
+    double *orig_norm_v; /* device [G][n] out */
+    int32_t *refcount;   /* device [G][P] out: logical blocks pointing at each physical block */
+    int32_t *remap;      /* device [G][P] out: -1 = live, else the physical block this one was fused into */
+} kvfuse_table;
+
+/* Algorithm 1's inputs as index lists (host memory).  A leaf is a run of consecutive logical entries (the
+ * full blocks of one request for BFF, of one chunk for CFF); a unit is a run of consecutive leaves (one
+ * request).  The recursion splits the unit list at len/2 (left first); a unit with several leaves is first
+ * fused over its own leaves the same way.  With one unit this is CFF over its chunks; with one leaf per
+ * unit it is BFF.  group_size > 0 applies the method's "every N requests or chunks": consecutive runs of
+ * N units (N leaves when there is a single unit) form independent trees; <= 0 means one tree.
+ * Leaves must be in ascending, non-overlapping logical order. */
+typedef struct kvfuse_tree_spec {
+    int32_t n_leaves;
+    const int32_t *leaf_start;    /* host [n_leaves] */
+    const int32_t *leaf_count;    /* host [n_leaves] */
+    int32_t n_units;
+    const int32_t *unit_leaf_ptr; /* host [n_units + 1] */
+    int32_t group_size;
+} kvfuse_tree_spec;
+
+/* Counters of one kvfuse_fuse_tree run, summed over groups unless noted. */
+typedef struct kvfuse_stats {
+    int64_t logical_blocks;   /* G * n */
+    int64_t physical_blocks;  /* blocks still referenced after fusion */
+    int64_t fused;            /* right blocks fused into a left block, all heights */
+    int64_t near_threshold;   /* decisions whose best cosine lies within `band` of thr (reported separately) */
+    int64_t refined;          /* decisions re-evaluated in fp64 */
+    int64_t cand_overflow;    /* columns with more screen candidates than slots (full fp64 rescan) */
+    double compression_ratio; /* logical / physical (analysis section, corollary) */
+    double sim_flops;         /* sum over nodes of 2 * m_l * m_r * r with the actual set sizes */
+    /* stage times in ms from HIP events on the context's stream; filled only when timing was requested */
+    float ms_norms, ms_similarity, ms_assign, ms_merge, ms_rewrite, ms_total;
+    int32_t n_heights;
+    int32_t reserved;
+} kvfuse_stats;
+
+/* Device views of one height's intermediate results, for tests and tools.  Column c of a height is right
+ * block j = c - r_base[node] of that node; row index i addresses the node's left set. */
+typedef struct kvfuse_height_view {
+    int32_t n_nodes, total_l_cap, total_r_cap, cand_cap;
+    int64_t total_s;           /* sum over nodes of l_cap * r_cap: per-group stride of a dense S buffer */
+    const int32_t *l_off, *r_off, *l_slot, *r_slot, *out_slot, *l_cap, *r_cap, *l_base, *r_base; /* device [n_nodes(+1)] */
+    const int64_t *s_base;     /* device [n_nodes + 1] */
+    const int32_t *set_ids;    /* device [G][n]: surviving physical ids, node sets at their offsets */
+    const int32_t *set_cnt;    /* device [G][n_slots] */
+    const int32_t *assign;     /* device [G][r_stride]: target row i or -1 */
+    const float *best_sim;     /* device [G][r_stride]: largest screened cosine of the column */
+    const int32_t *best_idx;   /* device [G][r_stride] */
+    const int32_t *cand_cnt;   /* device [G][r_stride] */
+    int32_t n_slots, r_stride, l_stride, reserved;
+} kvfuse_height_view;
+
+/* ---- context ------------------------------------------------------------------------------------- */
+
+/* Create a context bound to HIP device `device` and to `hip_stream` (a hipStream_t; NULL = default stream). */
+int kvfuse_create(kvfuse_ctx **ctx, int device, void *hip_stream);
+int kvfuse_destroy(kvfuse_ctx *ctx);
+/* Text of the last error recorded on this context ("" if none).  Valid until the next failing call. */
+const char *kvfuse_last_error(const kvfuse_ctx *ctx);
+
+/* ---- a6: tree schedule (Algorithm 1's recursion, host side) ----------------------------------------- */
+
+/* Bytes of device workspace a plan needs.  cand_cap = screen-candidate slots per right block (>= 1). */
+int kvfuse_workspace_bytes(int32_t G, int32_t n, const kvfuse_tree_spec *spec, int32_t cand_cap, size_t *bytes);
+
+/* Build the recursion tree of Algorithm 1, cut it into heights (nodes of equal height are independent and
+ * are processed by one batched launch per step), lay the intermediate arrays out in `workspace` (device,
+ * 256-byte aligned, kept by the caller until kvfuse_plan_destroy) and upload the node tables.
+ * pool / table descriptors are copied; the arrays they point at must stay valid while the plan is used. */
+int kvfuse_plan_create(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table,
+                       const kvfuse_tree_spec *spec, int32_t cand_cap, void *workspace, size_t workspace_bytes,
+                       kvfuse_plan **plan);
+int kvfuse_plan_destroy(kvfuse_plan *plan);
+int kvfuse_plan_heights(const kvfuse_plan *plan, int32_t *n_heights);
+int kvfuse_plan_view(const kvfuse_plan *plan, int32_t height, kvfuse_height_view *view);
+
+/* ---- a1: norms, leaf step of Algorithm 1 ("normalize") ---------------------------------------------- */
+
+/* Method section: "The norm of each r is stored".  Computes norm_k, norm_v, inv_norm_k for all G*P blocks
+ * (fp64 accumulation), and initialises the table: orig_norm_* from the block each entry points at,
+ * scale = 1, refcount = entries per block, remap = -1. */
+int kvfuse_block_norms(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table);
+
+/* Leaf sets of the plan: every leaf's surviving set = the physical ids of its logical entries. */
+int kvfuse_leaf_sets(kvfuse_ctx *ctx, kvfuse_plan *plan);
+
+/* ---- a2: similarity (Algorithm 1: sim <- k_l k_r^T, keys only) ------------------------------------- */
+
+/* For every node of `height` and every group: cosine of each left block with each right block on the
+ * MFMA units (bf16 x bf16 -> fp32, or f32), normalised with inv_norm_k.  Per right block it records the
+ * column maximum and its row, and the list of rows whose screened cosine exceeds thr - 2*band (at most
+ * cand_cap kept; the count is exact).  dense_s, if not NULL, is device [G][total_s] float and receives
+ * every screened cosine: node k's matrix at s_base[k], row-major [l_cap][r_cap], entries beyond the
+ * current set sizes untouched.  band must be >= r * 2^-22 (the bound assumed on the screen's error). */
+int kvfuse_similarity(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t height, double thr, double band, float *dense_s);
+
+/* ---- a3: assignment (Algorithm 1: indices where sim > thr, one target per right block) ---------- */
+
+/* Right block j fuses into the left row with the largest cosine, lowest row on exact ties, iff that cosine
+ * is > thr (strict).  Cosines that decide are fp64.  Then, per node: members grouped by target (ascending j),
+ * evicted blocks entered in table.remap, the surviving set cat(left, non-fused right in order) written in
+ * place, and the list of targets to rebuild handed to kvfuse_merge. */
+int kvfuse_assign(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t height, double thr, double band);
+
+/* ---- a4: merge (Algorithm 1: k_l(row) <- normalize(k_l(row) + sum k_r(i)), same for v) --------- */
+
+/* For every target chosen by kvfuse_assign at this height: unit-vector sum of the target and its members
+ * (fp64), renormalised, rounded to the pool dtype (nearest even) and written in place at the target's
+ * physical block, for K and, with the same members, V; norm_k, norm_v, inv_norm_k of the target are
+ * recomputed from the rounded values. */
+int kvfuse_merge(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t height);
+
+/* ---- a5: block-table rewrite (Algorithm 1: evict, update block-table) ---------------------------- */
+
+/* Repoints every logical entry whose physical block was evicted (following table.remap to a live block),
+ * recounts references, refreshes scale_k / scale_v of entries that point at a fused representative, and
+ * lists the freed physical ids.  free_list: device [G][P] int32 (ascending ids per group), n_free, n_phys:
+ * device [G] int32.  Any of the three may be NULL. */
+int kvfuse_rewrite_block_table(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table,
+                               int32_t *free_list, int32_t *n_free, int32_t *n_phys);
+
+/* ---- whole pipeline ---------------------------------------------------------------------------------- */
+
+/* a1 .. a5 over all heights of the plan.  If stats is not NULL the call synchronises the stream at the end
+ * and fills it; want_timing additionally brackets the stages with HIP events on the stream. */
+int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band, int32_t *free_list,
+                     int32_t *n_free, int32_t *n_phys, kvfuse_stats *stats, int32_t want_timing);
+
+/* ---- a7: paged decode attention through the (fused) table -------------------------------------------- */
+
+/* Workspace bytes for a decode call over n_layers layers, B requests, Hq query heads, kv_heads KV heads. */
+int kvfuse_decode_workspace_bytes(int32_t n_layers, int32_t B, int32_t Hq, int32_t kv_heads, int32_t d,
+                                  int32_t max_blocks, size_t *bytes);
+
+/* One decode step of softmax attention (analysis section: logits q.k/sqrt(d)) for layers
+ * [layer_begin, layer_begin + n_layers): request b, query head h reads KV head h / (Hq / kv_heads) of the
+ * layer's groups through table.bt, each logical block rescaled by scale_k / scale_v.
+ *   q        device [n_layers][B][Hq][d] pool dtype
+ *   req_start device [B] int32: first logical entry of request b;  ctx_len device [B] int32 tokens
+ *   max_blocks = max over b of ceil(ctx_len[b] / t) (host value, sizes the launch)
+ *   out      device [n_layers][B][Hq][d] float
+ * Supported: t a multiple of 16, d in {64, 128}, Hq / kv_heads <= 16. */
+int kvfuse_paged_decode_attn(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table, int32_t kv_heads,
+                             int32_t layer_begin, int32_t n_layers, const void *q, const int32_t *req_start,
+                             const int32_t *ctx_len, int32_t B, int32_t Hq, int32_t max_blocks, float sm_scale,
+                             void *workspace, size_t workspace_bytes, float *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVFUSE_H */

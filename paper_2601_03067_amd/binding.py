@@ -1,0 +1,296 @@
+"""ctypes binding of libkvfuse.so: the same entry points as include/kvfuse.h, argument marshalling only.
+
+Every step of the hot path runs inside the HIP library.  PyTorch is used by callers for device memory and
+streams; this module only turns tensors into pointers.  There is no fallback: if the library has not been
+built (``python -m paper_2601_03067_amd.build``) importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkvfuse.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2601_03067_amd.build` (needs hipcc)")
+lib = C.CDLL(LIB_PATH)
+
+OK, EINVAL, ESHAPE, EOVERFLOW, ENOMEM, EHIP = range(6)
+F32, BF16 = 0, 1
+
+EXPORTS = [
+    "kvfuse_create", "kvfuse_destroy", "kvfuse_last_error", "kvfuse_workspace_bytes", "kvfuse_plan_create",
+    "kvfuse_plan_destroy", "kvfuse_plan_heights", "kvfuse_plan_view", "kvfuse_block_norms", "kvfuse_leaf_sets",
+    "kvfuse_similarity", "kvfuse_assign", "kvfuse_merge", "kvfuse_rewrite_block_table", "kvfuse_fuse_tree",
+    "kvfuse_decode_workspace_bytes", "kvfuse_paged_decode_attn",
+]
+
+_vp, _i32, _i64, _f32, _f64 = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_double
+
+
+class Pool(C.Structure):
+    _fields_ = [("k", _vp), ("v", _vp), ("dtype", _i32), ("G", _i32), ("P", _i32), ("t", _i32), ("d", _i32),
+                ("norm_k", _vp), ("norm_v", _vp), ("inv_norm_k", _vp)]
+
+
+class Table(C.Structure):
+    _fields_ = [("n", _i32), ("bt", _vp), ("scale_k", _vp), ("scale_v", _vp), ("orig_norm_k", _vp),
+                ("orig_norm_v", _vp), ("refcount", _vp), ("remap", _vp)]
+
+
+class TreeSpec(C.Structure):
+    _fields_ = [("n_leaves", _i32), ("leaf_start", _vp), ("leaf_count", _vp), ("n_units", _i32),
+                ("unit_leaf_ptr", _vp), ("group_size", _i32)]
+
+
+class Stats(C.Structure):
+    _fields_ = [("logical_blocks", _i64), ("physical_blocks", _i64), ("fused", _i64), ("near_threshold", _i64),
+                ("refined", _i64), ("cand_overflow", _i64), ("compression_ratio", _f64), ("sim_flops", _f64),
+                ("ms_norms", _f32), ("ms_similarity", _f32), ("ms_assign", _f32), ("ms_merge", _f32),
+                ("ms_rewrite", _f32), ("ms_total", _f32), ("n_heights", _i32), ("reserved", _i32)]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved"}
+
+
+class HeightView(C.Structure):
+    _fields_ = [("n_nodes", _i32), ("total_l_cap", _i32), ("total_r_cap", _i32), ("cand_cap", _i32), ("total_s", _i64),
+                ("l_off", _vp), ("r_off", _vp), ("l_slot", _vp), ("r_slot", _vp), ("out_slot", _vp), ("l_cap", _vp),
+                ("r_cap", _vp), ("l_base", _vp), ("r_base", _vp), ("s_base", _vp), ("set_ids", _vp), ("set_cnt", _vp),
+                ("assign", _vp), ("best_sim", _vp), ("best_idx", _vp), ("cand_cnt", _vp), ("n_slots", _i32),
+                ("r_stride", _i32), ("l_stride", _i32), ("reserved", _i32)]
+
+
+lib.kvfuse_last_error.restype = C.c_char_p
+lib.kvfuse_last_error.argtypes = [_vp]
+lib.kvfuse_create.argtypes = [C.POINTER(_vp), C.c_int, _vp]
+lib.kvfuse_destroy.argtypes = [_vp]
+lib.kvfuse_workspace_bytes.argtypes = [_i32, _i32, C.POINTER(TreeSpec), _i32, C.POINTER(C.c_size_t)]
+lib.kvfuse_plan_create.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), C.POINTER(TreeSpec), _i32, _vp, C.c_size_t,
+                                   C.POINTER(_vp)]
+lib.kvfuse_plan_destroy.argtypes = [_vp]
+lib.kvfuse_plan_heights.argtypes = [_vp, C.POINTER(_i32)]
+lib.kvfuse_plan_view.argtypes = [_vp, _i32, C.POINTER(HeightView)]
+lib.kvfuse_block_norms.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table)]
+lib.kvfuse_leaf_sets.argtypes = [_vp, _vp]
+lib.kvfuse_similarity.argtypes = [_vp, _vp, _i32, _f64, _f64, _vp]
+lib.kvfuse_assign.argtypes = [_vp, _vp, _i32, _f64, _f64]
+lib.kvfuse_merge.argtypes = [_vp, _vp, _i32]
+lib.kvfuse_rewrite_block_table.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _vp, _vp, _vp]
+lib.kvfuse_fuse_tree.argtypes = [_vp, _vp, _f64, _f64, _vp, _vp, _vp, C.POINTER(Stats), _i32]
+lib.kvfuse_decode_workspace_bytes.argtypes = [_i32, _i32, _i32, _i32, _i32, _i32, C.POINTER(C.c_size_t)]
+lib.kvfuse_paged_decode_attn.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _i32, _i32, _i32, _vp, _vp, _vp, _i32,
+                                         _i32, _i32, _f32, _vp, C.c_size_t, _vp]
+
+
+class KvfuseError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"kvfuse error {code}: {text}")
+        self.code = code
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _dtype_code(dt):
+    if dt == torch.bfloat16:
+        return BF16
+    if dt == torch.float32:
+        return F32
+    raise KvfuseError(ESHAPE, f"unsupported pool dtype {dt}")
+
+
+class Context:
+    """kvfuse_create / kvfuse_destroy on the current torch stream of ``device``."""
+
+    def __init__(self, device="cuda:0", stream=None):
+        dev = torch.device(device)
+        self.device = dev
+        self.stream = stream if stream is not None else torch.cuda.current_stream(dev)
+        self.h = _vp()
+        rc = lib.kvfuse_create(C.byref(self.h), dev.index or 0, C.c_void_p(self.stream.cuda_stream))
+        if rc:
+            raise KvfuseError(rc, "kvfuse_create failed")
+
+    def check(self, rc):
+        if rc:
+            raise KvfuseError(rc, lib.kvfuse_last_error(self.h).decode())
+
+    def close(self):
+        if self.h:
+            lib.kvfuse_destroy(self.h)
+            self.h = _vp()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Cache:
+    """Device buffers of one paged KV cache plus the descriptor structs that point at them (allocation only)."""
+
+    def __init__(self, K: torch.Tensor, V: torch.Tensor, bt: torch.Tensor, t: int, d: int):
+        assert K.is_contiguous() and V.is_contiguous() and bt.is_contiguous() and K.shape == V.shape
+        G, P, r = K.shape
+        assert r == t * d and bt.shape[0] == G and bt.dtype == torch.int32
+        dev = K.device
+        n = bt.shape[1]
+        self.K, self.V, self.bt, self.t, self.d, self.G, self.P, self.n = K, V, bt, t, d, G, P, n
+        self.norm_k = torch.empty(G, P, device=dev, dtype=torch.float64)
+        self.norm_v = torch.empty(G, P, device=dev, dtype=torch.float64)
+        self.inv_norm_k = torch.empty(G, P, device=dev, dtype=torch.float32)
+        self.scale_k = torch.empty(G, n, device=dev, dtype=torch.float32)
+        self.scale_v = torch.empty(G, n, device=dev, dtype=torch.float32)
+        self.orig_norm_k = torch.empty(G, n, device=dev, dtype=torch.float64)
+        self.orig_norm_v = torch.empty(G, n, device=dev, dtype=torch.float64)
+        self.refcount = torch.empty(G, P, device=dev, dtype=torch.int32)
+        self.remap = torch.empty(G, P, device=dev, dtype=torch.int32)
+        self.free_list = torch.empty(G, P, device=dev, dtype=torch.int32)
+        self.n_free = torch.empty(G, device=dev, dtype=torch.int32)
+        self.n_phys = torch.empty(G, device=dev, dtype=torch.int32)
+        self.pool = Pool(_ptr(K), _ptr(V), _dtype_code(K.dtype), G, P, t, d, _ptr(self.norm_k), _ptr(self.norm_v),
+                         _ptr(self.inv_norm_k))
+        self.table = Table(n, _ptr(bt), _ptr(self.scale_k), _ptr(self.scale_v), _ptr(self.orig_norm_k),
+                           _ptr(self.orig_norm_v), _ptr(self.refcount), _ptr(self.remap))
+
+    def identity_scales(self):
+        """Table state of an unfused cache (for decode attention without a fusion pass)."""
+        self.scale_k.fill_(1.0)
+        self.scale_v.fill_(1.0)
+
+
+def tree_spec(leaf_start, leaf_count, unit_leaf_ptr, group_size=0):
+    ls = np.ascontiguousarray(leaf_start, np.int32)
+    lc = np.ascontiguousarray(leaf_count, np.int32)
+    up = np.ascontiguousarray(unit_leaf_ptr, np.int32)
+    spec = TreeSpec(len(ls), ls.ctypes.data, lc.ctypes.data, len(up) - 1, up.ctypes.data, int(group_size))
+    spec._keep = (ls, lc, up)   # host arrays must outlive the struct
+    return spec
+
+
+def workspace_bytes(G, n, spec, cand_cap=16):
+    out = C.c_size_t(0)
+    rc = lib.kvfuse_workspace_bytes(G, n, C.byref(spec), cand_cap, C.byref(out))
+    if rc:
+        raise KvfuseError(rc, "kvfuse_workspace_bytes failed")
+    return out.value
+
+
+class Plan:
+    """kvfuse_plan_create over a caller-allocated (torch) workspace."""
+
+    def __init__(self, ctx: Context, cache: Cache, spec: TreeSpec, cand_cap: int = 16):
+        self.ctx, self.cache, self.spec, self.cand_cap = ctx, cache, spec, cand_cap
+        nbytes = workspace_bytes(cache.G, cache.n, spec, cand_cap)
+        self.workspace = torch.empty(nbytes + 256, device=cache.K.device, dtype=torch.uint8)
+        base = (self.workspace.data_ptr() + 255) & ~255
+        self.h = _vp()
+        ctx.check(lib.kvfuse_plan_create(ctx.h, C.byref(cache.pool), C.byref(cache.table), C.byref(spec), cand_cap,
+                                         C.c_void_p(base), nbytes, C.byref(self.h)))
+
+    @property
+    def n_heights(self):
+        out = _i32(0)
+        self.ctx.check(lib.kvfuse_plan_heights(self.h, C.byref(out)))
+        return out.value
+
+    def view(self, height):
+        v = HeightView()
+        self.ctx.check(lib.kvfuse_plan_view(self.h, height, C.byref(v)))
+        return v
+
+    def close(self):
+        if self.h:
+            lib.kvfuse_plan_destroy(self.h)
+            self.h = _vp()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def block_norms(ctx, cache):
+    ctx.check(lib.kvfuse_block_norms(ctx.h, C.byref(cache.pool), C.byref(cache.table)))
+
+
+def leaf_sets(ctx, plan):
+    ctx.check(lib.kvfuse_leaf_sets(ctx.h, plan.h))
+
+
+def similarity(ctx, plan, height, thr, band=1e-3, dense_s=None):
+    ctx.check(lib.kvfuse_similarity(ctx.h, plan.h, height, thr, band, _ptr(dense_s)))
+
+
+def assign(ctx, plan, height, thr, band=1e-3):
+    ctx.check(lib.kvfuse_assign(ctx.h, plan.h, height, thr, band))
+
+
+def merge(ctx, plan, height):
+    ctx.check(lib.kvfuse_merge(ctx.h, plan.h, height))
+
+
+def rewrite_block_table(ctx, cache, want_lists=True):
+    ctx.check(lib.kvfuse_rewrite_block_table(ctx.h, C.byref(cache.pool), C.byref(cache.table),
+                                             _ptr(cache.free_list) if want_lists else None,
+                                             _ptr(cache.n_free) if want_lists else None,
+                                             _ptr(cache.n_phys) if want_lists else None))
+
+
+def fuse_tree(ctx, plan, thr, band=1e-3, want_stats=True, want_timing=False):
+    cache = plan.cache
+    st = Stats()
+    ctx.check(lib.kvfuse_fuse_tree(ctx.h, plan.h, thr, band, _ptr(cache.free_list), _ptr(cache.n_free), _ptr(cache.n_phys),
+                                   C.byref(st) if want_stats else None, 1 if want_timing else 0))
+    return st if want_stats else None
+
+
+def decode_workspace_bytes(n_layers, B, Hq, kv_heads, d, max_blocks):
+    out = C.c_size_t(0)
+    rc = lib.kvfuse_decode_workspace_bytes(n_layers, B, Hq, kv_heads, d, max_blocks, C.byref(out))
+    if rc:
+        raise KvfuseError(rc, "kvfuse_decode_workspace_bytes failed")
+    return out.value
+
+
+def paged_decode_attn(ctx, cache, kv_heads, q, req_start, ctx_len, max_blocks, layer_begin=0, sm_scale=None,
+                      workspace=None, out=None):
+    """q [n_layers][B][Hq][d] (pool dtype) -> out [n_layers][B][Hq][d] float32."""
+    n_layers, B, Hq, d = q.shape
+    assert q.is_contiguous() and q.dtype == cache.K.dtype and d == cache.d
+    if sm_scale is None:
+        sm_scale = 1.0 / float(d) ** 0.5
+    if out is None:
+        out = torch.empty(n_layers, B, Hq, d, device=q.device, dtype=torch.float32)
+    nbytes = decode_workspace_bytes(n_layers, B, Hq, kv_heads, d, max_blocks)
+    if workspace is None or workspace.numel() < nbytes:
+        workspace = torch.empty(nbytes, device=q.device, dtype=torch.uint8)
+    ctx.check(lib.kvfuse_paged_decode_attn(ctx.h, C.byref(cache.pool), C.byref(cache.table), kv_heads, layer_begin, n_layers,
+                                           _ptr(q), _ptr(req_start), _ptr(ctx_len), B, Hq, max_blocks, sm_scale,
+                                           _ptr(workspace), workspace.numel(), _ptr(out)))
+    return out
+
+
+_hip = None
+
+
+def device_array(ptr, count, dtype, device):
+    """Copy ``count`` elements of a device array given by raw pointer into a host numpy array (tests, tools)."""
+    global _hip
+    if _hip is None:
+        _hip = C.CDLL("libamdhip64.so")
+        _hip.hipMemcpy.argtypes = [_vp, _vp, C.c_size_t, C.c_int]
+    torch.cuda.synchronize(device)
+    out = np.empty(count, dtype=dtype)
+    if count:
+        rc = _hip.hipMemcpy(out.ctypes.data, ptr, out.nbytes, 2)   # hipMemcpyDeviceToHost
+        if rc != 0:
+            raise KvfuseError(EHIP, f"hipMemcpy failed: {rc}")
+    return out

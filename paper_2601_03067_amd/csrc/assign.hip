@@ -1,0 +1,287 @@
+// a3: thresholded arg-max assignment (Algorithm 1: "indices where sim(row) > thr", read as one target per right
+// block: the left row with the largest cosine, lowest row on exact ties, strict '>').
+//
+// Two kernels per height:
+//   decide   one wavefront per right block.  The MFMA screen has left a short candidate list per column.  A column
+//            with no candidate cannot fuse.  A column whose best candidate is clear of the threshold and of every
+//            other candidate by more than 2*band is decided from the screen.  Everything else is re-evaluated in
+//            fp64 on the stored values (wave-wide dot products in a fixed lane order, so identical blocks give
+//            identical cosines and the lowest-row rule applies to them exactly as on a CPU).
+//   finalize one workgroup per (group, node): members grouped by target in ascending right index (CSR), evicted
+//            blocks entered in the remap table, targets to rebuild appended to the merge work list, and the node's
+//            surviving set cat(left, non-fused right in order) compacted in place for the parent node.
+#include "common.h"
+
+namespace kvfuse {
+
+__device__ __forceinline__ int find_node(const int32_t *__restrict__ base, int n_nodes, int idx)
+{
+    int lo = 0, hi = n_nodes;   // largest k with base[k] <= idx
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (base[mid] <= idx)
+            lo = mid;
+        else
+            hi = mid;
+    }
+    return lo;
+}
+
+template <typename T>
+__device__ __forceinline__ double cosine_f64(const T *__restrict__ pool_g, int r, const double *__restrict__ norm_g,
+                                             int a, int b, int lane)
+{
+    const double na = norm_g[a], nb = norm_g[b];
+    const uint4 *pa = reinterpret_cast<const uint4 *>(pool_g + (int64_t)a * r);
+    const uint4 *pb = reinterpret_cast<const uint4 *>(pool_g + (int64_t)b * r);
+    const int chunks = r / Elem<T>::PER16;
+    double dot = 0.0;
+    for (int c = lane; c < chunks; c += 64) {
+        double x[Elem<T>::PER16], y[Elem<T>::PER16];
+        Elem<T>::widen(pa[c], x);
+        Elem<T>::widen(pb[c], y);
+#pragma unroll
+        for (int i = 0; i < Elem<T>::PER16; ++i)
+            dot = fma(x[i], y[i], dot);
+    }
+    dot = wave_sum(dot);
+    return (na == 0.0 || nb == 0.0) ? 0.0 : dot / (na * nb);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void assign_decide_kernel(PoolDesc pool, WorkDesc w, HeightDesc h, int height, double thr,
+                                                            double band)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0)
+        w.n_active[height] = 0;   // the finalize kernel, next on the stream, appends to this list
+    const int lane = threadIdx.x & 63;
+    const int64_t wv = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (wv >= (int64_t)w.G * h.total_r_cap)
+        return;
+    const int g = (int)(wv / h.total_r_cap);
+    const int c = (int)(wv - (int64_t)g * h.total_r_cap);
+    const int node = find_node(h.r_base, h.n_nodes, c);
+    const int j = c - h.r_base[node];
+    const int ml = w.set_cnt[(int64_t)g * w.n_slots + h.l_slot[node]];
+    const int mr = w.set_cnt[(int64_t)g * w.n_slots + h.r_slot[node]];
+    if (j >= mr)
+        return;
+    const int64_t cidx = (int64_t)g * w.r_stride + c;
+    const int32_t *l_ids = w.set_ids + (int64_t)g * w.n + h.l_off[node];
+    const int b = w.set_ids[(int64_t)g * w.n + h.r_off[node] + j];
+    const T *pool_g = (const T *)pool.k + (int64_t)g * pool.P * pool.r;
+    const double *norm_g = pool.norm_k + (int64_t)g * pool.P;
+
+    const int cnt = ml > 0 ? w.cand_cnt[cidx] : 0;
+    int result = -1;
+    int near = 0, refined = 0, overflow = 0;
+    if (cnt > 0 && cnt <= w.cand_cap) {
+        int ci = 0x7FFFFFFF;
+        float cv = -INFINITY;
+        if (lane < cnt) {
+            ci = w.cand_idx[cidx * w.cand_cap + lane];
+            cv = w.cand_val[cidx * w.cand_cap + lane];
+        }
+        float smax = cv;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1)
+            smax = fmaxf(smax, __shfl_xor(smax, off, 64));
+        const bool contender = lane < cnt && (double)cv >= (double)smax - 2.0 * band;
+        unsigned long long mask = __ballot(contender);
+        if (__popcll(mask) == 1 && (double)smax > thr + 2.0 * band) {
+            result = __shfl(ci, __ffsll((long long)mask) - 1, 64);
+        } else {
+            refined = 1;
+            double bv = -INFINITY;
+            int bi = 0x7FFFFFFF;
+            while (mask) {
+                const int src = __ffsll((long long)mask) - 1;
+                mask &= mask - 1;
+                const int i = __shfl(ci, src, 64);
+                const double cs = cosine_f64<T>(pool_g, pool.r, norm_g, l_ids[i], b, lane);
+                if (cs > bv || (cs == bv && i < bi)) {
+                    bv = cs;
+                    bi = i;
+                }
+            }
+            if (bv > thr)
+                result = bi;
+            near = fabs(bv - thr) <= band;
+        }
+    } else if (cnt > w.cand_cap) {
+        // more screen candidates than slots: rescan the whole column in fp64 (ascending rows, strict '>')
+        overflow = 1;
+        refined = 1;
+        double bv = -INFINITY;
+        int bi = -1;
+        for (int i = 0; i < ml; ++i) {
+            const double cs = cosine_f64<T>(pool_g, pool.r, norm_g, l_ids[i], b, lane);
+            if (cs > bv) {
+                bv = cs;
+                bi = i;
+            }
+        }
+        if (bv > thr)
+            result = bi;
+        near = fabs(bv - thr) <= band;
+    }
+    if (lane == 0) {
+        w.assign[cidx] = result;
+        int32_t *cn = w.counters + (int64_t)g * 8;
+        if (near)
+            atomicAdd(&cn[1], 1);
+        if (refined)
+            atomicAdd(&cn[2], 1);
+        if (overflow)
+            atomicAdd(&cn[3], 1);
+    }
+}
+
+// Exclusive scan of one int64 per thread over a 256-thread workgroup; returns the exclusive prefix and the total.
+__device__ __forceinline__ int64_t block_exscan_256(int64_t x, int64_t *lds4, int64_t &total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int64_t inc = x;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int64_t y = __shfl_up(inc, off, 64);
+        if (lane >= off)
+            inc += y;
+    }
+    __syncthreads();
+    if (lane == 63)
+        lds4[wave] = inc;
+    __syncthreads();
+    int64_t pre = 0;
+    for (int k = 0; k < wave; ++k)
+        pre += lds4[k];
+    total = lds4[0] + lds4[1] + lds4[2] + lds4[3];
+    return pre + inc - x;
+}
+
+__device__ __forceinline__ int ld_relaxed(const int32_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__global__ __launch_bounds__(256) void assign_finalize_kernel(int P, TableDesc tab, WorkDesc w, HeightDesc h, int height)
+{
+    __shared__ int64_t lds4[4];
+    __shared__ int lds_base;
+    const int g = blockIdx.x / h.n_nodes;
+    const int node = blockIdx.x - g * h.n_nodes;
+    const int tid = threadIdx.x;
+    const int ml = w.set_cnt[(int64_t)g * w.n_slots + h.l_slot[node]];
+    const int mr = w.set_cnt[(int64_t)g * w.n_slots + h.r_slot[node]];
+    int32_t *l_ids = w.set_ids + (int64_t)g * w.n + h.l_off[node];
+    int32_t *r_ids = w.set_ids + (int64_t)g * w.n + h.r_off[node];
+    const int32_t *assign = w.assign + (int64_t)g * w.r_stride + h.r_base[node];
+    int32_t *members = w.seg_members + (int64_t)g * w.r_stride + h.r_base[node];
+    int32_t *seg_cnt = w.seg_cnt + (int64_t)g * w.l_stride + h.l_base[node];
+    int32_t *seg_ptr = w.seg_ptr + (int64_t)g * w.l_stride + h.l_base[node];
+
+    // 1. members per target
+    for (int i = tid; i < ml; i += 256)
+        seg_cnt[i] = 0;
+    __syncthreads();
+    for (int j = tid; j < mr; j += 256) {
+        const int a = assign[j];
+        if (a >= 0)
+            atomicAdd(&seg_cnt[a], 1);
+    }
+    __syncthreads();
+
+    // 2. segment offsets (exclusive scan) and the merge work list
+    int64_t run = 0;
+    for (int i0 = 0; i0 < ml; i0 += 256) {
+        const int i = i0 + tid;
+        const int cnt = i < ml ? ld_relaxed(&seg_cnt[i]) : 0;
+        int64_t total;
+        const int64_t pre = block_exscan_256(((int64_t)(cnt > 0) << 40) | (int64_t)cnt, lds4, total);
+        const int n_act = (int)(total >> 40);
+        if (tid == 0)
+            lds_base = n_act > 0 ? atomicAdd(&w.n_active[height], n_act) : 0;
+        __syncthreads();
+        if (i < ml) {
+            seg_ptr[i] = (int)(run + (pre & 0xFFFFFFFFFFll));
+            if (cnt > 0)
+                w.active[lds_base + (int)(pre >> 40)] = g * w.l_stride + h.l_base[node] + i;
+        }
+        run += total & 0xFFFFFFFFFFll;
+        __syncthreads();
+    }
+
+    // 3. scatter right indices into their segments (seg_ptr runs on to the segment end), then order each segment
+    for (int j = tid; j < mr; j += 256) {
+        const int a = assign[j];
+        if (a >= 0)
+            members[atomicAdd(&seg_ptr[a], 1)] = j;
+    }
+    __syncthreads();
+    for (int i = tid; i < ml; i += 256) {
+        const int cnt = ld_relaxed(&seg_cnt[i]);
+        if (cnt > 1) {
+            const int start = ld_relaxed(&seg_ptr[i]) - cnt;
+            for (int x = 1; x < cnt; ++x) {
+                const int key = members[start + x];
+                int y = x - 1;
+                while (y >= 0) {
+                    const int m = members[start + y];
+                    if (m <= key)
+                        break;
+                    members[start + y + 1] = m;
+                    --y;
+                }
+                members[start + y + 1] = key;
+            }
+        }
+    }
+    __syncthreads();
+    // right index -> physical id, before the right set is compacted away
+    for (int k = tid; k < (int)run; k += 256)
+        members[k] = r_ids[members[k]];
+    __syncthreads();
+
+    // 4. remap of evicted blocks and in-place compaction of the survivors behind the left set
+    int kept = 0;
+    for (int j0 = 0; j0 < mr; j0 += 256) {
+        const int j = j0 + tid;
+        int id = -1, a = -1;
+        if (j < mr) {
+            id = r_ids[j];
+            a = assign[j];
+        }
+        int64_t total;
+        const int64_t pre = block_exscan_256((j < mr && a < 0) ? 1 : 0, lds4, total);   // barriers inside: all ids are read
+        if (j < mr) {
+            if (a >= 0)
+                tab.remap[(int64_t)g * P + id] = l_ids[a];
+            else
+                l_ids[ml + kept + (int)pre] = id;
+        }
+        kept += (int)total;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        w.set_cnt[(int64_t)g * w.n_slots + h.out_slot[node]] = ml + kept;
+        if (mr - kept > 0)
+            atomicAdd(&w.counters[(int64_t)g * 8 + 0], mr - kept);
+    }
+}
+
+void launch_assign(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, const WorkDesc &w, const HeightDesc &h,
+                   int height, double thr, double band)
+{
+    const int64_t waves = (int64_t)w.G * h.total_r_cap;
+    if (waves > 0) {
+        const unsigned grid = (unsigned)((waves + 3) / 4);
+        if (pool.dtype == KVFUSE_BF16)
+            assign_decide_kernel<bf16_t><<<grid, 256, 0, s>>>(pool, w, h, height, thr, band);
+        else
+            assign_decide_kernel<float><<<grid, 256, 0, s>>>(pool, w, h, height, thr, band);
+    }
+    if (w.G * h.n_nodes > 0)
+        assign_finalize_kernel<<<(unsigned)(w.G * h.n_nodes), 256, 0, s>>>(pool.P, tab, w, h, height);
+}
+
+}  // namespace kvfuse

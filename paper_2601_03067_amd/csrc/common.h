@@ -1,0 +1,197 @@
+// Internal declarations shared by the kvfuse HIP sources (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/kvfuse.h"
+
+namespace kvfuse {
+
+// ---------------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------------
+
+struct Ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    std::string err;
+    hipEvent_t ev[16] = {};
+    bool ev_ready = false;
+};
+
+int fail(Ctx *c, int code, const std::string &msg);
+
+#define KVF_HIP(ctx, expr)                                                                        \
+    do {                                                                                          \
+        hipError_t e__ = (expr);                                                                  \
+        if (e__ != hipSuccess)                                                                    \
+            return ::kvfuse::fail((ctx), KVFUSE_EHIP, std::string(#expr) + ": " + hipGetErrorString(e__)); \
+    } while (0)
+
+// Tables of one tree height, all device pointers into the plan workspace (identical for every group).
+struct HeightDesc {
+    int32_t n_nodes;
+    int32_t total_l_cap, total_r_cap;
+    int32_t n_panels;            // similarity launch: column panels per group
+    const int32_t *l_off, *r_off, *l_slot, *r_slot, *out_slot, *l_cap, *r_cap;
+    const int32_t *l_base, *r_base;   // [n_nodes + 1] prefix sums of the capacities
+    const int64_t *s_base;            // [n_nodes + 1] prefix sums of l_cap * r_cap
+    const int32_t *panel_node, *panel_col0;   // [n_panels]
+    int64_t total_s;
+};
+
+// Group-strided work arrays of a plan (device).
+struct WorkDesc {
+    int32_t G, n, n_slots, r_stride, l_stride, cand_cap;
+    int32_t *set_ids;    // [G][n]
+    int32_t *set_cnt;    // [G][n_slots]
+    int32_t *assign;     // [G][r_stride]
+    float *best_sim;     // [G][r_stride]
+    int32_t *best_idx;   // [G][r_stride]
+    int32_t *cand_cnt;   // [G][r_stride]
+    int32_t *cand_idx;   // [G][r_stride][cand_cap]
+    float *cand_val;     // [G][r_stride][cand_cap]
+    int32_t *seg_cnt;    // [G][l_stride]
+    int32_t *seg_ptr;    // [G][l_stride]
+    int32_t *seg_members;// [G][r_stride]
+    int32_t *active;     // [G * l_stride] packed g * l_stride + target index
+    int32_t *n_active;   // [max_heights]
+    int32_t *counters;   // [G][8]: 0 fused, 1 near-threshold, 2 refined, 3 candidate overflow, 4 invalid ids
+};
+
+struct PoolDesc {
+    void *k, *v;
+    int32_t dtype, G, P, r, t, d;
+    double *norm_k, *norm_v;
+    float *inv_norm_k;
+};
+
+struct TableDesc {
+    int32_t n;
+    int32_t *bt;
+    float *scale_k, *scale_v;
+    double *orig_norm_k, *orig_norm_v;
+    int32_t *refcount, *remap;
+};
+
+static inline PoolDesc to_desc(const kvfuse_pool &p)
+{
+    return PoolDesc{p.k, p.v, p.dtype, p.G, p.P, p.t * p.d, p.t, p.d, p.norm_k, p.norm_v, p.inv_norm_k};
+}
+static inline TableDesc to_desc(const kvfuse_table &t)
+{
+    return TableDesc{t.n, t.bt, t.scale_k, t.scale_v, t.orig_norm_k, t.orig_norm_v, t.refcount, t.remap};
+}
+
+// launchers, one per source file
+void launch_block_norms(hipStream_t s, const PoolDesc &pool, const TableDesc &tab);
+void launch_leaf_sets(hipStream_t s, const WorkDesc &w, const TableDesc &tab, int P, const int32_t *slot_init);
+void launch_similarity(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const HeightDesc &h, float thr_floor,
+                       float *dense_s);
+void launch_assign(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, const WorkDesc &w, const HeightDesc &h,
+                   int height, double thr, double band);
+void launch_merge(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const HeightDesc &h, int height);
+void launch_rewrite(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, int32_t *free_list, int32_t *n_free,
+                    int32_t *n_phys);
+size_t decode_workspace_bytes(int n_layers, int B, int Hq, int kv_heads, int d, int max_blocks);
+int launch_decode(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, int kv_heads, int layer_begin, int n_layers,
+                  const void *q, const int32_t *req_start, const int32_t *ctx_len, int B, int Hq, int max_blocks,
+                  float sm_scale, void *workspace, size_t workspace_bytes, float *out);
+
+// ---------------------------------------------------------------------------------------------------
+// device side
+// ---------------------------------------------------------------------------------------------------
+#if defined(__HIPCC__)
+
+typedef uint16_t bf16_t;   // raw bfloat16 bits
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+
+// 16 bytes of pool data widened to fp64: 8 bfloat16 or 4 float values.
+template <typename T> struct Elem;
+template <> struct Elem<bf16_t> {
+    static constexpr int PER16 = 8;
+    __device__ static __forceinline__ void widen(const uint4 &raw, double *out)
+    {
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            out[2 * i] = (double)__uint_as_float(w[i] << 16);
+            out[2 * i + 1] = (double)__uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    }
+};
+template <> struct Elem<float> {
+    static constexpr int PER16 = 4;
+    __device__ static __forceinline__ void widen(const uint4 &raw, double *out)
+    {
+        out[0] = (double)__uint_as_float(raw.x);
+        out[1] = (double)__uint_as_float(raw.y);
+        out[2] = (double)__uint_as_float(raw.z);
+        out[3] = (double)__uint_as_float(raw.w);
+    }
+};
+
+// Sum over the 64 lanes of a wavefront in a fixed butterfly order; every lane gets the result.
+__device__ __forceinline__ double wave_sum(double x)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1)
+        x += __shfl_xor(x, off, 64);
+    return x;
+}
+
+// Sum over a 256-thread workgroup in a fixed order (wave butterflies, then waves 0..3 left to right).
+__device__ __forceinline__ double block_sum_256(double x, double *lds4)
+{
+    x = wave_sum(x);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0)
+        lds4[threadIdx.x >> 6] = x;
+    __syncthreads();
+    return ((lds4[0] + lds4[1]) + lds4[2]) + lds4[3];
+}
+
+// Nearest-even rounding of a finite double straight to bfloat16 bits (no intermediate binary32 rounding).
+__device__ __forceinline__ uint32_t f64_to_bf16_rne(double x)
+{
+    const uint64_t b = (uint64_t)__double_as_longlong(x);
+    const uint32_t sign = (uint32_t)(b >> 63) << 15;
+    const int ex = (int)((b >> 52) & 0x7FF);
+    const uint64_t mant = b & 0xFFFFFFFFFFFFFull;
+    if (ex == 0x7FF)
+        return sign | 0x7F80u | (mant ? 0x40u : 0u);
+    if (ex == 0)
+        return sign;                         // double subnormals are far below the bfloat16 range
+    const int e = ex - 1023 + 127;           // biased bfloat16 exponent
+    if (e >= 255)
+        return sign | 0x7F80u;
+    const uint64_t sig = mant | (1ull << 52);
+    int shift = 45;                          // 52 - 7 mantissa bits
+    uint32_t base;
+    if (e >= 1) {
+        base = ((uint32_t)e << 7) - 128u;    // exponent field, the implicit one of sig is added back below
+    } else {
+        shift += 1 - e;
+        base = 0u;
+        if (shift > 54)
+            return sign;
+    }
+    const uint64_t q = sig >> shift;
+    const uint64_t rem = sig & ((1ull << shift) - 1ull);
+    const uint64_t half = 1ull << (shift - 1);
+    uint32_t out = base + (uint32_t)q;
+    if (rem > half || (rem == half && (q & 1ull)))
+        out += 1u;                            // a carry runs into the exponent field, which is what rounding up needs
+    if (out >= 0x7F80u)
+        out = 0x7F80u;
+    return sign | out;
+}
+
+#endif // __HIPCC__
+
+}  // namespace kvfuse

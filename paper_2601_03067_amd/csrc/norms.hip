@@ -1,0 +1,134 @@
+// a1: block norms and table initialisation (method section: "The norm of each r is stored"; leaf step of
+// Algorithm 1).  Pure HBM stream: every K and V byte is read once; one wavefront per block, 16-byte loads,
+// fp64 accumulation in a fixed order so that identical blocks get bit-identical norms.
+#include "common.h"
+
+namespace kvfuse {
+
+template <typename T>
+__global__ __launch_bounds__(256) void block_norms_kernel(const T *__restrict__ kpool, const T *__restrict__ vpool,
+                                                          int64_t n_blocks, int r, double *__restrict__ norm_k,
+                                                          double *__restrict__ norm_v, float *__restrict__ inv_norm_k)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);   // wave index over 2 * n_blocks
+    if (w >= 2 * n_blocks)
+        return;
+    const bool is_v = w >= n_blocks;
+    const int64_t b = is_v ? w - n_blocks : w;
+    const uint4 *src = reinterpret_cast<const uint4 *>((is_v ? vpool : kpool) + b * (int64_t)r);
+    const int chunks = r / Elem<T>::PER16;
+    double ss = 0.0;
+    for (int c = lane; c < chunks; c += 64) {
+        const uint4 raw = src[c];
+        double x[Elem<T>::PER16];
+        Elem<T>::widen(raw, x);
+#pragma unroll
+        for (int i = 0; i < Elem<T>::PER16; ++i)
+            ss = fma(x[i], x[i], ss);
+    }
+    ss = wave_sum(ss);
+    if (lane == 0) {
+        const double nrm = sqrt(ss);
+        if (is_v) {
+            norm_v[b] = nrm;
+        } else {
+            norm_k[b] = nrm;
+            inv_norm_k[b] = nrm > 0.0 ? (float)(1.0 / nrm) : 0.0f;
+        }
+    }
+}
+
+__global__ void table_clear_kernel(int32_t *__restrict__ refcount, int32_t *__restrict__ remap, int64_t total)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < total) {
+        refcount[i] = 0;
+        remap[i] = -1;
+    }
+}
+
+__global__ void table_init_kernel(TableDesc tab, int G, int P, const double *__restrict__ norm_k,
+                                  const double *__restrict__ norm_v)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)G * tab.n)
+        return;
+    const int g = (int)(i / tab.n);
+    const int p = tab.bt[i];
+    if (p < 0 || p >= P) {       // invalid id: leave a poisoned entry rather than touch memory out of range
+        tab.orig_norm_k[i] = 0.0;
+        tab.orig_norm_v[i] = 0.0;
+        tab.scale_k[i] = 0.0f;
+        tab.scale_v[i] = 0.0f;
+        return;
+    }
+    tab.orig_norm_k[i] = norm_k[(int64_t)g * P + p];
+    tab.orig_norm_v[i] = norm_v[(int64_t)g * P + p];
+    tab.scale_k[i] = 1.0f;
+    tab.scale_v[i] = 1.0f;
+    atomicAdd(&tab.refcount[(int64_t)g * P + p], 1);
+}
+
+void launch_block_norms(hipStream_t s, const PoolDesc &pool, const TableDesc &tab)
+{
+    const int64_t nb = (int64_t)pool.G * pool.P;
+    const unsigned grid = (unsigned)((2 * nb + 3) / 4);
+    if (nb > 0) {
+        if (pool.dtype == KVFUSE_BF16)
+            block_norms_kernel<bf16_t><<<grid, 256, 0, s>>>((const bf16_t *)pool.k, (const bf16_t *)pool.v, nb, pool.r,
+                                                            pool.norm_k, pool.norm_v, pool.inv_norm_k);
+        else
+            block_norms_kernel<float><<<grid, 256, 0, s>>>((const float *)pool.k, (const float *)pool.v, nb, pool.r,
+                                                           pool.norm_k, pool.norm_v, pool.inv_norm_k);
+        table_clear_kernel<<<(unsigned)((nb + 255) / 256), 256, 0, s>>>(tab.refcount, tab.remap, nb);
+    }
+    const int64_t ne = (int64_t)pool.G * tab.n;
+    if (ne > 0)
+        table_init_kernel<<<(unsigned)((ne + 255) / 256), 256, 0, s>>>(tab, pool.G, pool.P, pool.norm_k, pool.norm_v);
+}
+
+// Leaf sets = physical ids of the leaves' logical entries.  An id outside [0, P) (a caller error) is clamped
+// so that no later kernel can read out of range, and counted in counters[g][4].
+__global__ void leaf_sets_kernel(WorkDesc w, int P, const int32_t *__restrict__ bt, const int32_t *__restrict__ slot_init)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t ne = (int64_t)w.G * w.n;
+    if (i < (int64_t)w.G * 8)
+        w.counters[i] = 0;
+    if (i < ne) {
+        int p = bt[i];
+        if (p < 0 || p >= P)
+            p = p < 0 ? 0 : P - 1;
+        w.set_ids[i] = p;
+    }
+    const int64_t ns = (int64_t)w.G * w.n_slots;
+    if (i < ns)
+        w.set_cnt[i] = slot_init[i % w.n_slots];
+}
+
+__global__ void check_ids_kernel(WorkDesc w, int P, const int32_t *__restrict__ bt)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < (int64_t)w.G * w.n) {
+        const int p = bt[i];
+        if (p < 0 || p >= P)
+            atomicAdd(&w.counters[(i / w.n) * 8 + 4], 1);
+    }
+}
+
+void launch_leaf_sets(hipStream_t s, const WorkDesc &w, const TableDesc &tab, int P, const int32_t *slot_init)
+{
+    int64_t total = (int64_t)w.G * w.n;
+    const int64_t ns = (int64_t)w.G * w.n_slots;
+    if (ns > total)
+        total = ns;
+    if ((int64_t)w.G * 8 > total)
+        total = (int64_t)w.G * 8;
+    if (total > 0)
+        leaf_sets_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(w, P, tab.bt, slot_init);
+    if ((int64_t)w.G * w.n > 0)
+        check_ids_kernel<<<(unsigned)(((int64_t)w.G * w.n + 255) / 256), 256, 0, s>>>(w, P, tab.bt);
+}
+
+}  // namespace kvfuse

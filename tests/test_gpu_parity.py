@@ -1,0 +1,354 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Bars: block tables, assignments, reference counts, free lists and fused pool bytes bit-exact; norms 1e-13
+relative (fp64 sums in a different order); scales 2e-7 relative (fp32 storage); screened cosines within the
+screen's stated error band; attention within 2e-2 max-abs (checked much tighter where fp32 allows).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_03067_amd import workloads as wl
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+@pytest.fixture(scope="module")
+def kb():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return gu.load_binding()
+
+
+def _small_bf16(n_req=6, tokens=1200, layers=1, kv_heads=3, t=8, d=32, near_pool=24, prefix_tokens=96, seed=wl.MASTER_SEED):
+    """Llama-shaped recipe shrunk so that the oracle takes seconds: r = 256, 150 blocks per request (ragged vs the
+    128-wide tiles of the similarity kernel)."""
+    return wl.llama8b_bff(n_req=n_req, tokens=tokens, layers=layers, kv_heads=kv_heads, prefix_tokens=prefix_tokens,
+                          near_pool=near_pool, t=t, d=d, seed=seed)
+
+
+# ------------------------------------------------------------------------------------------ a1 norms
+
+@pytest.mark.parametrize("which", ["tiny_f32", "small_bf16"])
+def test_block_norms_match_oracle(kb, oracle, which):
+    rec = wl.tiny_bff() if which == "tiny_f32" else _small_bf16()
+    _say("norms", which, "G", rec.G, "n", rec.n, "r", rec.r)
+    mat = wl.materialise(rec, DEV, phys_perm=True)
+    ctx = kb.Context(DEV)
+    cache = kb.Cache(mat["K"], mat["V"], mat["bt"], rec.t, rec.d)
+    kb.block_norms(ctx, cache)
+    torch.cuda.synchronize()
+    for g in range(rec.G):
+        nk = oracle.block_norms(wl.to_numpy_pool(mat["K"][g]))
+        nv = oracle.block_norms(wl.to_numpy_pool(mat["V"][g]))
+        np.testing.assert_allclose(cache.norm_k[g].cpu().numpy(), nk, rtol=1e-14)
+        np.testing.assert_allclose(cache.norm_v[g].cpu().numpy(), nv, rtol=1e-14)
+        np.testing.assert_allclose(cache.inv_norm_k[g].cpu().numpy(), 1.0 / nk, rtol=1e-6)
+        bt = mat["bt"][g].cpu().numpy()
+        np.testing.assert_allclose(cache.orig_norm_k[g].cpu().numpy(), nk[bt], rtol=1e-14)
+        assert (cache.scale_k[g] == 1).all() and (cache.refcount[g] == 1).all() and (cache.remap[g] == -1).all()
+
+
+# ------------------------------------------------------------------------------------------ a2..a5 one node at a time
+
+def _two_leaf_case(kind):
+    """One tree node: left leaf and right leaf with planted duplicates, ragged against the 128 x 128 tiles."""
+    rng = np.random.default_rng(5 if kind == "f32" else 6)
+    ml, mr = (150, 201) if kind == "bf16" else (70, 45)
+    r = 256 if kind == "bf16" else 96
+    n = ml + mr
+    protos = rng.standard_normal((40, r))
+    x = rng.standard_normal((n, r))
+    pick = rng.integers(0, 40, n)
+    dup = rng.random(n) < 0.5
+    x[dup] = protos[pick[dup]] + 0.05 * rng.standard_normal((int(dup.sum()), r))
+    x[ml + 3] = x[7]                      # exact duplicate across the node
+    x[ml + 4] = x[7]                      # two right blocks for one target
+    x[9] = x[8]                           # identical left rows: lowest row must win
+    x[ml + 5] = x[8] + 1e-4 * rng.standard_normal(r)
+    x[11] = 0.0                           # zero blocks on both sides
+    x[ml + 6] = 0.0
+    y = rng.standard_normal((n, r))
+    dt = torch.bfloat16 if kind == "bf16" else torch.float32
+    K = torch.tensor(x, dtype=torch.float32).to(dt)[None].contiguous()
+    V = torch.tensor(y, dtype=torch.float32).to(dt)[None].contiguous()
+    perm = rng.permutation(n)
+    Kp, Vp = torch.empty_like(K), torch.empty_like(V)
+    Kp[0][perm] = K[0]
+    Vp[0][perm] = V[0]
+    bt = torch.tensor(perm, dtype=torch.int32)[None].contiguous()
+    t, d = (8, 32) if kind == "bf16" else (4, 24)
+    return Kp, Vp, bt, ml, mr, t, d
+
+
+@pytest.mark.parametrize("kind", ["f32", "bf16"])
+@pytest.mark.parametrize("cand_cap", [16, 1])
+def test_single_node_steps_match_oracle(kb, oracle, kind, cand_cap):
+    _say("single node", kind, "cand_cap", cand_cap)
+    K, V, bt, ml, mr, t, d = _two_leaf_case(kind)
+    thr, band = 0.9, 1e-3
+    Kh, Vh, bth = wl.to_numpy_pool(K[0]), wl.to_numpy_pool(V[0]), bt[0].numpy().copy()
+    K, V, bt = K.to(DEV), V.to(DEV), bt.to(DEV)
+    ctx = kb.Context(DEV)
+    cache = kb.Cache(K, V, bt, t, d)
+    spec = kb.tree_spec([0, ml], [ml, mr], [0, 1, 2])
+    plan = kb.Plan(ctx, cache, spec, cand_cap)
+    assert plan.n_heights == 1
+    kb.block_norms(ctx, cache)
+    kb.leaf_sets(ctx, plan)
+    view = plan.view(0)
+    dense = torch.full((1, view.total_s), float("nan"), device=DEV)
+    kb.similarity(ctx, plan, 0, thr, band, dense)
+    torch.cuda.synchronize()
+
+    # oracle, step by step
+    nk, nv = oracle.block_norms(Kh), oracle.block_norms(Vh)
+    L, R = bth[:ml], bth[ml:]
+    S = oracle.similarity(Kh, nk, L, R)
+    S_gpu = dense[0].cpu().numpy().reshape(ml, mr).astype(np.float64)
+    err = np.abs(S_gpu - S).max()
+    _say("  screen max |cos_gpu - cos_oracle| =", err)
+    assert err <= Kh.shape[1] * 2.0 ** -22, "screen error exceeds the bound the fp64 re-check relies on"
+    best = kb.device_array(view.best_sim, mr, np.float32, DEV)
+    assert np.abs(best - S.max(0)).max() <= 1e-4
+    cnt = kb.device_array(view.cand_cnt, mr, np.int32, DEV)
+    lo, hi = (S > thr - 2 * band + 1e-4).sum(0), (S > thr - 2 * band - 1e-4).sum(0)
+    assert (cnt >= lo).all() and (cnt <= hi).all()
+    assert cand_cap == 16 or (cnt > 1).any(), "the cand_cap = 1 case must exercise the overflow rescan"
+
+    kb.assign(ctx, plan, 0, thr, band)
+    torch.cuda.synchronize()
+    a_or, best_or, second_or = oracle.assign(S, thr)
+    a_gpu = kb.device_array(view.assign, mr, np.int32, DEV)
+    assert (a_or >= 0).sum() >= 10
+    assert np.array_equal(a_gpu, a_or), f"assignments differ at {np.nonzero(a_gpu != a_or)[0]}"
+    # survivors = cat(left, non-fused right)
+    slots = kb.device_array(view.set_cnt, view.n_slots, np.int32, DEV)
+    out_slot = kb.device_array(view.out_slot, 1, np.int32, DEV)[0]
+    want_set = np.concatenate([L, R[a_or < 0]])
+    assert slots[out_slot] == len(want_set)
+    assert np.array_equal(kb.device_array(view.set_ids, len(want_set), np.int32, DEV), want_set)
+
+    kb.merge(ctx, plan, 0)
+    kb.rewrite_block_table(ctx, cache)
+    torch.cuda.synchronize()
+    Ko, Vo = Kh.copy(), Vh.copy()
+    nko, nvo = nk.copy(), nv.copy()
+    oracle.merge(Ko, nko, L, R, a_or)
+    oracle.merge(Vo, nvo, L, R, a_or)
+    bto = bth.copy()
+    sk, sv = np.ones(len(bto)), np.ones(len(bto))
+    rc = np.ones(len(nk), np.int32)
+    freed = oracle.rewrite(bto, L, R, a_or, nk[bth], nv[bth], nko, nvo, sk, sv, rc)
+    Kg, Vg = wl.to_numpy_pool(cache.K[0]), wl.to_numpy_pool(cache.V[0])
+    live = np.unique(bto)
+    assert np.array_equal(Kg[live], Ko[live]) and np.array_equal(Vg[live], Vo[live]), "fused blocks differ from the oracle"
+    assert np.array_equal(cache.bt[0].cpu().numpy(), bto)
+    assert np.array_equal(cache.refcount[0].cpu().numpy(), rc)
+    assert sorted(freed.tolist()) == cache.free_list[0, : int(cache.n_free[0])].cpu().numpy().tolist()
+    np.testing.assert_allclose(cache.scale_k[0].cpu().numpy(), sk, rtol=2e-7)
+    np.testing.assert_allclose(cache.scale_v[0].cpu().numpy(), sv, rtol=2e-7)
+    np.testing.assert_allclose(cache.norm_k[0].cpu().numpy()[live], nko[live], rtol=1e-13)
+
+
+# ------------------------------------------------------------------------------------------ whole tree
+
+def _run_tree_case(kb, oracle, rec, name, cand_cap=16, thr=None, phys_perm=True, group_size=None, groups=None):
+    _say("tree case", name, "G", rec.G, "n", rec.n, "r", rec.r, "leaves", len(rec.leaf_start), "cand_cap", cand_cap)
+    mat = wl.materialise(rec, DEV, groups=groups, phys_perm=phys_perm)
+    host = gu.host_copy(mat)
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, thr=thr, cand_cap=cand_cap, group_size=group_size)
+    res = gu.oracle_fuse(oracle, rec, host, thr=thr, group_size=group_size)
+    safe = gu.check_ambiguity(res, name)
+    for g in safe:
+        gu.compare_group(res[g], cache, g, rec.dtype == torch.float32, name)
+    assert len(safe) >= max(1, len(res) - 1)
+    if len(safe) == len(res):
+        assert stats.fused == sum(int(r.stats[1]) for r in res)
+        assert stats.near_threshold == sum(int(r.stats[2]) for r in res)
+        assert stats.physical_blocks == sum(r.n_physical for r in res)
+        assert math.isclose(stats.compression_ratio, sum(len(r.bt) for r in res) / sum(r.n_physical for r in res))
+    _say("  fused", stats.fused, "refined", stats.refined, "overflow", stats.cand_overflow, "CR", round(stats.compression_ratio, 4))
+    return cache, plan, stats, res, mat
+
+
+def test_tree_tiny_config_all_groups(kb, oracle):
+    """Config 1 as specified: fp32, 2 groups, 4 requests x 8 blocks, thr 0.95 -> 22 physical blocks per group."""
+    rec = wl.tiny_bff()
+    cache, plan, stats, res, mat = _run_tree_case(kb, oracle, rec, "tiny_bff")
+    assert stats.physical_blocks == 2 * 22 and stats.fused == 20 and stats.near_threshold == 0
+    assert math.isclose(stats.compression_ratio, 32 / 22)
+
+
+def test_tree_threshold_above_one_is_identity(kb, oracle):
+    rec = wl.tiny_bff()
+    mat = wl.materialise(rec, DEV)
+    K0, V0 = mat["K"].clone(), mat["V"].clone()
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, thr=1.5)
+    assert stats.fused == 0 and stats.compression_ratio == 1.0
+    assert torch.equal(cache.K, K0) and torch.equal(cache.V, V0)
+    assert torch.equal(cache.bt, torch.arange(rec.n, device=DEV, dtype=torch.int32).expand(rec.G, -1))
+    assert (cache.scale_k == 1).all() and (cache.scale_v == 1).all() and (cache.refcount == 1).all()
+    assert (cache.n_free == 0).all() and (cache.n_phys == rec.n).all()
+
+
+@pytest.mark.parametrize("cand_cap", [16, 2])
+def test_tree_small_bf16_bff(kb, oracle, cand_cap):
+    """Six ragged-vs-tile requests of 150 blocks, shared prefix + near-duplicate pool, several tiles per node."""
+    _run_tree_case(kb, oracle, _small_bf16(), "small_bf16_bff", cand_cap=cand_cap)
+
+
+def test_tree_seven_requests_non_power_of_two(kb, oracle):
+    _run_tree_case(kb, oracle, _small_bf16(n_req=7, tokens=520, kv_heads=2), "bff_7_requests")
+
+
+def test_tree_group_size(kb, oracle):
+    rec = _small_bf16(n_req=8, tokens=400, kv_heads=2)
+    _run_tree_case(kb, oracle, rec, "bff_group_size_3", group_size=3)
+
+
+def test_tree_cff_chunks(kb, oracle):
+    rec = wl.cff_long(tokens=8 * 600, chunk_tokens=8 * 75, layers=1, kv_heads=2, t=8, d=32)
+    cache, plan, stats, res, mat = _run_tree_case(kb, oracle, rec, "cff_small")
+    assert stats.fused > 50
+
+
+def test_tree_mixed_chunks_then_requests(kb, oracle):
+    rec = wl.mixed(n_req=9, min_tokens=40, max_tokens=900, chunk_tokens=256, layers=1, kv_heads=2, pool=48, t=8, d=32)
+    cache, plan, stats, res, mat = _run_tree_case(kb, oracle, rec, "mixed_small")
+    assert stats.fused > 50
+    # partial tail blocks are in no leaf: they keep their own block and scale 1
+    for b in range(rec.B):
+        if rec.ctx_len[b] % rec.t:
+            x = rec.req_start[b] + rec.req_blocks[b] - 1
+            assert int(cache.refcount[0, cache.bt[0, x]]) == 1 and float(cache.scale_k[0, x]) == 1.0
+
+
+def test_tree_zipf_many_near_ties(kb, oracle):
+    """Config 4's structure shrunk: every block is a noisy copy of a Zipf-drawn base, so most right blocks have
+    several near-tied left candidates and the fp64 re-check decides."""
+    rec = wl.zipf_bff(n_req=8, tokens=32 * 40, layers=1, kv_heads=2, pool=60, t=32, d=64, thr=0.9)
+    cache, plan, stats, res, mat = _run_tree_case(kb, oracle, rec, "zipf_small", cand_cap=8)
+    assert stats.refined > 20
+
+
+def test_tree_is_deterministic(kb):
+    rec = _small_bf16(n_req=5, tokens=480, kv_heads=2)
+    outs = []
+    for _ in range(2):
+        mat = wl.materialise(rec, DEV, phys_perm=True)
+        cache, plan, stats, ctx = gu.gpu_fuse(rec, mat)
+        outs.append((cache.bt.clone(), cache.K.clone(), cache.V.clone(), cache.scale_k.clone(), cache.refcount.clone()))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+def test_bad_arguments_are_reported_not_crashed(kb):
+    rec = wl.tiny_bff()
+    mat = wl.materialise(rec, DEV)
+    ctx = kb.Context(DEV)
+    cache = kb.Cache(mat["K"], mat["V"], mat["bt"], rec.t, rec.d)
+    with pytest.raises(kb.KvfuseError) as e:
+        kb.Plan(ctx, cache, kb.tree_spec([0, 4], [8, 8], [0, 1, 2]))        # overlapping leaves
+    assert e.value.code == kb.EINVAL
+    plan = kb.Plan(ctx, cache, kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr))
+    with pytest.raises(kb.KvfuseError) as e:
+        kb.similarity(ctx, plan, 7, 0.9)                                    # no such height
+    assert e.value.code == kb.EINVAL
+    with pytest.raises(kb.KvfuseError) as e:
+        kb.fuse_tree(ctx, plan, 0.9, band=1e-9)                             # band below the screen's error bound
+    assert e.value.code == kb.EINVAL
+    bad = kb.Cache(mat["K"][:, :, :1000].contiguous(), mat["V"][:, :, :1000].contiguous(), mat["bt"], 8, 125)
+    with pytest.raises(kb.KvfuseError) as e:
+        kb.block_norms(ctx, bad)                                            # block bytes not a multiple of 128
+    assert e.value.code == kb.ESHAPE
+    # an id outside the pool is clamped inside the kernels and reported by the pipeline
+    mat2 = wl.materialise(rec, DEV)
+    mat2["bt"][0, 3] = 10 ** 6
+    cache2 = kb.Cache(mat2["K"], mat2["V"], mat2["bt"], rec.t, rec.d)
+    plan2 = kb.Plan(ctx, cache2, kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr))
+    with pytest.raises(kb.KvfuseError) as e:
+        kb.fuse_tree(ctx, plan2, 0.95)
+    assert e.value.code == kb.EINVAL
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------------------------------ a7 decode attention
+
+def _attn_oracle(oracle, rec, cache, q, layer, H):
+    gs = [layer * H + h for h in range(H)]
+    Kp = [wl.to_numpy_pool(cache.K[g]) for g in gs]
+    Vp = [wl.to_numpy_pool(cache.V[g]) for g in gs]
+    bt = [cache.bt[g].cpu().numpy() for g in gs]
+    sk = [cache.scale_k[g].cpu().numpy().astype(np.float64) for g in gs]
+    sv = [cache.scale_v[g].cpu().numpy().astype(np.float64) for g in gs]
+    qh = q.float().cpu().numpy().astype(np.float64)
+    return oracle.paged_decode_attention(qh, Kp, Vp, bt, sk, sv, rec.req_start, rec.ctx_len, rec.t, rec.d)
+
+
+def _decode(kb, ctx, rec, cache, q):
+    rs = torch.tensor(rec.req_start, dtype=torch.int32, device=DEV)
+    cl = torch.tensor(rec.ctx_len, dtype=torch.int32, device=DEV)
+    mb = int(((rec.ctx_len + rec.t - 1) // rec.t).max())
+    out = kb.paged_decode_attn(ctx, cache, rec.kv_heads, q, rs, cl, mb)
+    torch.cuda.synchronize()
+    return out.cpu().numpy().astype(np.float64)
+
+
+def test_decode_tiny_config_fused_and_unfused(kb, oracle):
+    """Config 1's four decode queries: after fusion, and with thr > 1 where attention must equal unfused paged
+    attention (same kernel on the untouched table) bit for bit."""
+    rec = wl.tiny_bff()
+    q = wl.queries(rec, DEV)
+    mat = wl.materialise(rec, DEV)
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat)
+    out = _decode(kb, ctx, rec, cache, q)
+    ref = _attn_oracle(oracle, rec, cache, q[0], 0, rec.kv_heads)
+    err = np.abs(out[0] - ref).max()
+    _say("decode tiny fused: max abs err", err)
+    assert err <= 2e-2 and err <= 1e-4
+    mat1 = wl.materialise(rec, DEV)
+    cache1, plan1, stats1, ctx1 = gu.gpu_fuse(rec, mat1, thr=1.5)
+    out1 = _decode(kb, ctx1, rec, cache1, q)
+    mat2 = wl.materialise(rec, DEV)
+    cache2 = kb.Cache(mat2["K"], mat2["V"], mat2["bt"], rec.t, rec.d)
+    cache2.identity_scales()
+    out2 = _decode(kb, ctx1, rec, cache2, q)
+    assert np.array_equal(out1, out2)
+    ref2 = _attn_oracle(oracle, rec, cache2, q[0], 0, rec.kv_heads)
+    assert np.abs(out2[0] - ref2).max() <= 1e-4
+
+
+@pytest.mark.parametrize("case", ["bf16_d128_gqa4", "bf16_d64_gqa8_t32", "bf16_split_long", "f32_d128_ragged"])
+def test_decode_matches_oracle(kb, oracle, case):
+    _say("decode case", case)
+    if case == "bf16_d128_gqa4":
+        rec = wl.llama8b_bff(n_req=5, tokens=16 * 37, layers=2, kv_heads=2, prefix_tokens=64, near_pool=16)
+    elif case == "bf16_d64_gqa8_t32":
+        rec = wl.zipf_bff(n_req=4, tokens=32 * 9, layers=1, kv_heads=2, pool=30, t=32, d=64)
+    elif case == "bf16_split_long":
+        rec = wl.cff_long(tokens=16 * 700, chunk_tokens=16 * 100, layers=1, kv_heads=2)
+    else:
+        rec = wl.mixed(n_req=6, min_tokens=20, max_tokens=700, chunk_tokens=256, layers=1, kv_heads=2, pool=40,
+                       dtype=torch.float32)
+    mat = wl.materialise(rec, DEV, phys_perm=True)
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat)
+    assert stats.fused > 0
+    q = wl.queries(rec, DEV)
+    out = _decode(kb, ctx, rec, cache, q)
+    worst = 0.0
+    for layer in range(rec.layers):
+        ref = _attn_oracle(oracle, rec, cache, q[layer], layer, rec.kv_heads)
+        worst = max(worst, float(np.abs(out[layer] - ref).max()))
+    _say("  max abs err", worst)
+    assert worst <= 2e-2
+    assert worst <= (1e-4 if rec.dtype == torch.float32 else 5e-3)
