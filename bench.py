@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Benchmark of the Fast Fusion hot path on ONE MI355X.
+
+A step = one pass of the whole hot path over one batch of synthetic input that is already resident in HBM:
+block norms -> per tree height (similarity, assignment, merge) -> block-table rewrite -> one decode-attention
+step of every request over every layer through the fused table.  Fusion rewrites the pool in place, so the pool
+and table are restored from a device snapshot between steps, outside the timed region.
+
+Prints ONE JSON line.  `value` = logical KV blocks (per layer and KV head) pushed through the whole path per
+second.  `roofline` describes the dominant kernel, the MFMA similarity GEMM: algorithmic flops (2 m_l m_r r per
+tree node with the actual set sizes) over its HIP-event time on the launch stream.  `cpu_baseline` times the CPU
+oracle on a bounded sample of the same workload on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def make_recipe(wl, name):
+    if name == "llama8b_bff":
+        return wl.llama8b_bff()
+    if name == "cff_long":
+        return wl.cff_long()
+    if name == "tiny_bff":
+        return wl.tiny_bff()
+    if name == "llama8b_bff_small":          # quick functional check, not a benchmark configuration
+        return wl.llama8b_bff(n_req=16, layers=4)
+    raise SystemExit(f"unknown workload {name}")
+
+
+def cpu_baseline(wl, seconds_hint=20.0):
+    """Time the oracle (as it stands) on host threads over a bounded sample of the Llama-3-8B BFF workload:
+    the first groups of the same recipe at 32 requests x 128 blocks, one group per thread."""
+    import oracle
+    import torch
+    cores = min(16, os.cpu_count() or 1)
+    rec = wl.llama8b_bff(n_req=32, layers=1, kv_heads=cores)
+    dev = "cuda:0" if torch.cuda.is_available() else "cpu"
+    mat = wl.materialise(rec, dev)
+    Ks = [wl.to_numpy_pool(mat["K"][g]) for g in range(rec.G)]
+    Vs = [wl.to_numpy_pool(mat["V"][g]) for g in range(rec.G)]
+    bts = [mat["bt"][g].cpu().numpy() for g in range(rec.G)]
+    del mat
+    oracle.build()
+    t0 = time.perf_counter()
+    res = oracle.fuse_groups(Ks, Vs, bts, rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr, rec.thr, threads=cores)
+    dt = time.perf_counter() - t0
+    blocks = rec.G * rec.n
+    return {"value": blocks / dt, "unit": "blocks/s", "cores": cores, "kind": "oracle",
+            "sample": f"{rec.G} groups x 32 requests x 128 blocks of the llama8b_bff recipe (fusion only, {dt:.1f} s wall), "
+                      f"CR {sum(len(r.bt) for r in res) / sum(r.n_physical for r in res):.3f}"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="llama8b_bff")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cand-cap", type=int, default=16)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (groups would shard with no "
+                         "exchange); run with --gpus 1")
+
+    import torch
+    from paper_2601_03067_amd import binding as kb
+    from paper_2601_03067_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    rec = make_recipe(wl, args.workload)
+    t_gen = time.perf_counter()
+    mat = wl.materialise(rec, dev)
+    q = wl.queries(rec, dev)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+    K0, V0, bt0 = mat["K"].clone(), mat["V"].clone(), mat["bt"].clone()
+
+    ctx = kb.Context(dev)
+    cache = kb.Cache(mat["K"], mat["V"], mat["bt"], rec.t, rec.d)
+    plan = kb.Plan(ctx, cache, kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr, rec.group_size), args.cand_cap)
+    rs = torch.tensor(rec.req_start, dtype=torch.int32, device=dev)
+    cl = torch.tensor(rec.ctx_len, dtype=torch.int32, device=dev)
+    max_blocks = int(((rec.ctx_len + rec.t - 1) // rec.t).max())
+    ws = torch.empty(kb.decode_workspace_bytes(rec.layers, rec.B, rec.q_heads, rec.kv_heads, rec.d, max_blocks),
+                     device=dev, dtype=torch.uint8)
+    out = torch.empty(rec.layers, rec.B, rec.q_heads, rec.d, device=dev, dtype=torch.float32)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+
+    def restore():
+        cache.K.copy_(K0)
+        cache.V.copy_(V0)
+        cache.bt.copy_(bt0)
+
+    def step():
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev[0].record()
+        st = kb.fuse_tree(ctx, plan, rec.thr, want_stats=True, want_timing=True)
+        ev[1].record()
+        kb.paged_decode_attn(ctx, cache, rec.kv_heads, q, rs, cl, max_blocks, workspace=ws, out=out)
+        ev[2].record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3
+        return wall, st, ev[1].elapsed_time(ev[2])
+
+    for _ in range(args.warmup):
+        restore()
+        step()
+    walls, sims, decs, stats = [], [], [], None
+    stage = {"norms": 0.0, "similarity": 0.0, "assign": 0.0, "merge": 0.0, "rewrite": 0.0, "decode": 0.0}
+    for _ in range(args.steps):
+        restore()
+        wall, st, dec = step()
+        walls.append(wall)
+        stats = st
+        stage["norms"] += st.ms_norms; stage["similarity"] += st.ms_similarity; stage["assign"] += st.ms_assign
+        stage["merge"] += st.ms_merge; stage["rewrite"] += st.ms_rewrite; stage["decode"] += dec
+    k = max(args.steps, 1)
+    stage = {a: b / k for a, b in stage.items()}
+    ms_step = sum(walls) / k
+    blocks = rec.G * rec.n
+    elem = 2 if rec.dtype == torch.bfloat16 else 4
+    blk_bytes = rec.r * elem
+    sim_tflops = stats.sim_flops / (stage["similarity"] * 1e-3) / 1e12 if stage["similarity"] > 0 else 0.0
+    peak = 2500.0 if rec.dtype == torch.bfloat16 else 157.3
+    phys_bytes = stats.physical_blocks * blk_bytes * 2
+    logi_bytes = stats.logical_blocks * blk_bytes * 2
+    merge_bytes = None
+    line = {
+        "metric": "KV blocks fused/sec (+ % MFMA peak); fused-table decode attn HBM GB/s",
+        "value": blocks / (ms_step * 1e-3),
+        "unit": "blocks/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if rec.dtype == torch.bfloat16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{rec.name}: {rec.layers} layers x {rec.kv_heads} KV heads, d {rec.d}, block {rec.t}, "
+                               f"{rec.B} requests, {rec.n} logical blocks per group, thr {rec.thr}",
+                   "groups": rec.G, "logical_blocks": blocks, "physical_blocks_after": stats.physical_blocks,
+                   "compression_ratio": stats.compression_ratio, "fused": stats.fused,
+                   "near_threshold": stats.near_threshold, "refined_fp64": stats.refined,
+                   "cand_overflow": stats.cand_overflow, "tree_heights": stats.n_heights},
+        "stages_ms": stage,
+        "decode": {"ms": stage["decode"], "physical_GBps": phys_bytes / (stage["decode"] * 1e-3) / 1e9,
+                   "logical_GBps": logi_bytes / (stage["decode"] * 1e-3) / 1e9, "hbm_peak_GBps": 8000.0,
+                   "frac_of_hbm_peak_physical": phys_bytes / (stage["decode"] * 1e-3) / 1e9 / 8000.0},
+        "norms": {"ms": stage["norms"], "GBps": logi_bytes / (stage["norms"] * 1e-3) / 1e9},
+        "roofline": {"kernel": "similarity_kernel", "bound": "mfma", "achieved": sim_tflops, "peak": peak,
+                     "unit": "TFLOP/s", "frac": sim_tflops / peak, "traffic": None,
+                     "flops_per_step": stats.sim_flops, "ms_per_step": stage["similarity"]},
+        "generation_s": t_gen,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -120,8 +120,9 @@ typedef struct kvfuse_height_view {
     const int32_t *set_ids;    /* device [G][n]: surviving physical ids, node sets at their offsets */
     const int32_t *set_cnt;    /* device [G][n_slots] */
     const int32_t *assign;     /* device [G][r_stride]: target row i or -1 */
-    const float *best_sim;     /* device [G][r_stride]: largest screened cosine of the column */
-    const int32_t *best_idx;   /* device [G][r_stride] */
+    const unsigned long long *best_packed; /* device [G][r_stride]: column maximum of the screen, packed as
+                                  (ordered cosine bits << 32) | (0xFFFFFFFF - row); ordered bits = ~b if the float's
+                                  sign bit is set, else b | 0x80000000; 0 = no left row */
     const int32_t *cand_cnt;   /* device [G][r_stride] */
     int32_t n_slots, r_stride, l_stride, reserved;
 } kvfuse_height_view;

@@ -60,7 +60,7 @@ class HeightView(C.Structure):
     _fields_ = [("n_nodes", _i32), ("total_l_cap", _i32), ("total_r_cap", _i32), ("cand_cap", _i32), ("total_s", _i64),
                 ("l_off", _vp), ("r_off", _vp), ("l_slot", _vp), ("r_slot", _vp), ("out_slot", _vp), ("l_cap", _vp),
                 ("r_cap", _vp), ("l_base", _vp), ("r_base", _vp), ("s_base", _vp), ("set_ids", _vp), ("set_cnt", _vp),
-                ("assign", _vp), ("best_sim", _vp), ("best_idx", _vp), ("cand_cnt", _vp), ("n_slots", _i32),
+                ("assign", _vp), ("best_packed", _vp), ("cand_cnt", _vp), ("n_slots", _i32),
                 ("r_stride", _i32), ("l_stride", _i32), ("reserved", _i32)]
 
 
@@ -276,6 +276,17 @@ def paged_decode_attn(ctx, cache, kv_heads, q, req_start, ctx_len, max_blocks, l
                                            _ptr(q), _ptr(req_start), _ptr(ctx_len), B, Hq, max_blocks, sm_scale,
                                            _ptr(workspace), workspace.numel(), _ptr(out)))
     return out
+
+
+def unpack_best(packed):
+    """Column maxima as stored by the similarity step -> (cosine float32 array, row int64 array; row -1 = none)."""
+    packed = np.asarray(packed, np.uint64)
+    ordered = (packed >> np.uint64(32)).astype(np.uint32)
+    bits = np.where(ordered & np.uint32(0x80000000), ordered & np.uint32(0x7FFFFFFF), ~ordered)
+    val = bits.astype(np.uint32).view(np.float32)
+    row = (np.uint64(0xFFFFFFFF) - (packed & np.uint64(0xFFFFFFFF))).astype(np.int64)
+    none = packed == 0
+    return np.where(none, np.float32(-np.inf), val), np.where(none, -1, row)
 
 
 _hip = None

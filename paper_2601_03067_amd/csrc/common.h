@@ -32,15 +32,22 @@ int fail(Ctx *c, int code, const std::string &msg);
             return ::kvfuse::fail((ctx), KVFUSE_EHIP, std::string(#expr) + ": " + hipGetErrorString(e__)); \
     } while (0)
 
+// Work items of the similarity launch of one height (device arrays, identical for every group): item k covers
+// right blocks [col0, col0 + BN) x left blocks [row0, row0 + rows) of node `node`.
+struct TileTable {
+    int32_t n_items;
+    const int32_t *node, *col0, *row0, *rows;
+};
+
 // Tables of one tree height, all device pointers into the plan workspace (identical for every group).
 struct HeightDesc {
     int32_t n_nodes;
     int32_t total_l_cap, total_r_cap;
-    int32_t n_panels;            // similarity launch: column panels per group
     const int32_t *l_off, *r_off, *l_slot, *r_slot, *out_slot, *l_cap, *r_cap;
     const int32_t *l_base, *r_base;   // [n_nodes + 1] prefix sums of the capacities
     const int64_t *s_base;            // [n_nodes + 1] prefix sums of l_cap * r_cap
-    const int32_t *panel_node, *panel_col0;   // [n_panels]
+    TileTable big, small;             // only the one selected by use_big_tiles is filled
+    bool use_big_tiles;
     int64_t total_s;
 };
 
@@ -50,8 +57,7 @@ struct WorkDesc {
     int32_t *set_ids;    // [G][n]
     int32_t *set_cnt;    // [G][n_slots]
     int32_t *assign;     // [G][r_stride]
-    float *best_sim;     // [G][r_stride]
-    int32_t *best_idx;   // [G][r_stride]
+    unsigned long long *best_packed;   // [G][r_stride] (ordered cosine << 32) | (0xFFFFFFFF - row); 0 = none
     int32_t *cand_cnt;   // [G][r_stride]
     int32_t *cand_idx;   // [G][r_stride][cand_cap]
     float *cand_val;     // [G][r_stride][cand_cap]

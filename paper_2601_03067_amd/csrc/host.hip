@@ -26,7 +26,9 @@ struct Node {
 };
 
 struct HostHeight {
-    std::vector<int32_t> l_off, r_off, l_slot, r_slot, out_slot, l_cap, r_cap, l_base, r_base, panel_node, panel_col0;
+    std::vector<int32_t> l_off, r_off, l_slot, r_slot, out_slot, l_cap, r_cap, l_base, r_base;
+    std::vector<int32_t> it_node, it_col0, it_row0, it_rows;   // similarity work items
+    bool big = false;
     std::vector<int64_t> s_base;
     HeightDesc dev;
 };
@@ -42,7 +44,8 @@ struct Plan {
     int max_r = 0, max_l = 0;
 };
 
-constexpr int kPanel = 128;        // right blocks per similarity workgroup (BN of the kernel)
+// Similarity tile shapes (must match the two kernel instantiations): big 256 x 256, small 128 x 128.
+constexpr int kBigM = 256, kBigN = 256, kSmallM = 128, kSmallN = 128;
 constexpr int kMaxHeights = 64;
 
 struct TreeBuilder {
@@ -169,10 +172,34 @@ static void build_heights(const std::vector<Node> &nodes, std::vector<HostHeight
             h.l_base[k + 1] = h.l_base[k] + h.l_cap[k];
             h.r_base[k + 1] = h.r_base[k] + h.r_cap[k];
             h.s_base[k + 1] = h.s_base[k] + (int64_t)h.l_cap[k] * h.r_cap[k];
-            for (int c = 0; c < h.r_cap[k]; c += kPanel) {
-                h.panel_node.push_back(k);
-                h.panel_col0.push_back(c);
-            }
+        }
+        // Tile shape: big tiles when the typical node (weighted by its work) is at least one big tile in both
+        // directions; small tiles waste less padding on the low heights.
+        double wsum = 0.0, wmin = 0.0;
+        for (int k = 0; k < nn; ++k) {
+            const double wk = (double)h.l_cap[k] * h.r_cap[k];
+            wsum += wk;
+            wmin += wk * std::min(h.l_cap[k], h.r_cap[k]);
+        }
+        h.big = wsum > 0.0 && wmin / wsum >= 256.0;
+        const int bm = h.big ? kBigM : kSmallM, bn = h.big ? kBigN : kSmallN;
+        // Work items in patch order: 8 panels x all row chunks of a node are consecutive, so that the workgroups
+        // resident on one XCD at a time share left tiles and right panels in its L2.
+        for (int k = 0; k < nn; ++k) {
+            const int n_cp = (h.r_cap[k] + bn - 1) / bn;
+            const int n_rtile = (h.l_cap[k] + bm - 1) / bm;
+            if (n_cp == 0 || n_rtile == 0)
+                continue;
+            const int rt = (n_rtile + 3) / 4;               // row tiles per work item: about 4 chunks per panel
+            const int n_rc = (n_rtile + rt - 1) / rt;
+            for (int cpg = 0; cpg < n_cp; cpg += 8)
+                for (int rc = 0; rc < n_rc; ++rc)
+                    for (int cp = cpg; cp < std::min(cpg + 8, n_cp); ++cp) {
+                        h.it_node.push_back(k);
+                        h.it_col0.push_back(cp * bn);
+                        h.it_row0.push_back(rc * rt * bm);
+                        h.it_rows.push_back(rt * bm);
+                    }
         }
     }
 }
@@ -200,8 +227,7 @@ static void carve(Carver &cv, int G, int n, int n_slots, int max_r, int max_l, i
     w.set_ids = cv.take<int32_t>((size_t)G * n);
     w.set_cnt = cv.take<int32_t>((size_t)G * n_slots);
     w.assign = cv.take<int32_t>(R);
-    w.best_sim = cv.take<float>(R);
-    w.best_idx = cv.take<int32_t>(R);
+    w.best_packed = cv.take<unsigned long long>(R);
     w.cand_cnt = cv.take<int32_t>(R);
     w.cand_idx = cv.take<int32_t>(R * cand_cap);
     w.cand_val = cv.take<float>(R * cand_cap);
@@ -219,7 +245,14 @@ static void carve(Carver &cv, int G, int n, int n_slots, int max_r, int max_l, i
         d.total_l_cap = h.l_base[nn];
         d.total_r_cap = h.r_base[nn];
         d.total_s = h.s_base[nn];
-        d.n_panels = (int)h.panel_node.size();
+        d.use_big_tiles = h.big;
+        TileTable tt;
+        tt.n_items = (int)h.it_node.size();
+        tt.node = cv.take<int32_t>(h.it_node.size());
+        tt.col0 = cv.take<int32_t>(h.it_col0.size());
+        tt.row0 = cv.take<int32_t>(h.it_row0.size());
+        tt.rows = cv.take<int32_t>(h.it_rows.size());
+        d.big = d.small = tt;
         d.l_off = cv.take<int32_t>(nn);
         d.r_off = cv.take<int32_t>(nn);
         d.l_slot = cv.take<int32_t>(nn);
@@ -230,8 +263,6 @@ static void carve(Carver &cv, int G, int n, int n_slots, int max_r, int max_l, i
         d.l_base = cv.take<int32_t>(nn + 1);
         d.r_base = cv.take<int32_t>(nn + 1);
         d.s_base = cv.take<int64_t>(nn + 1);
-        d.panel_node = cv.take<int32_t>(h.panel_node.size());
-        d.panel_col0 = cv.take<int32_t>(h.panel_col0.size());
     }
 }
 
@@ -394,8 +425,10 @@ int kvfuse_plan_create(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_ta
         if (e == hipSuccess) e = upload(c->stream, d.l_base, h.l_base);
         if (e == hipSuccess) e = upload(c->stream, d.r_base, h.r_base);
         if (e == hipSuccess) e = upload(c->stream, d.s_base, h.s_base);
-        if (e == hipSuccess) e = upload(c->stream, d.panel_node, h.panel_node);
-        if (e == hipSuccess) e = upload(c->stream, d.panel_col0, h.panel_col0);
+        if (e == hipSuccess) e = upload(c->stream, d.big.node, h.it_node);
+        if (e == hipSuccess) e = upload(c->stream, d.big.col0, h.it_col0);
+        if (e == hipSuccess) e = upload(c->stream, d.big.row0, h.it_row0);
+        if (e == hipSuccess) e = upload(c->stream, d.big.rows, h.it_rows);
     }
     if (e == hipSuccess)
         e = hipStreamSynchronize(c->stream);   // the host vectors may now be reused or freed
@@ -431,8 +464,8 @@ int kvfuse_plan_view(const kvfuse_plan *plan, int32_t height, kvfuse_height_view
     v->total_s = d.total_s;
     v->l_off = d.l_off; v->r_off = d.r_off; v->l_slot = d.l_slot; v->r_slot = d.r_slot; v->out_slot = d.out_slot;
     v->l_cap = d.l_cap; v->r_cap = d.r_cap; v->l_base = d.l_base; v->r_base = d.r_base; v->s_base = d.s_base;
-    v->set_ids = w.set_ids; v->set_cnt = w.set_cnt; v->assign = w.assign; v->best_sim = w.best_sim;
-    v->best_idx = w.best_idx; v->cand_cnt = w.cand_cnt;
+    v->set_ids = w.set_ids; v->set_cnt = w.set_cnt; v->assign = w.assign; v->best_packed = w.best_packed;
+    v->cand_cnt = w.cand_cnt;
     v->n_slots = w.n_slots; v->r_stride = w.r_stride; v->l_stride = w.l_stride; v->reserved = 0;
     return KVFUSE_OK;
 }

@@ -118,8 +118,10 @@ def test_single_node_steps_match_oracle(kb, oracle, kind, cand_cap):
     err = np.abs(S_gpu - S).max()
     _say("  screen max |cos_gpu - cos_oracle| =", err)
     assert err <= Kh.shape[1] * 2.0 ** -22, "screen error exceeds the bound the fp64 re-check relies on"
-    best = kb.device_array(view.best_sim, mr, np.float32, DEV)
+    best, best_row = kb.unpack_best(kb.device_array(view.best_packed, mr, np.uint64, DEV))
     assert np.abs(best - S.max(0)).max() <= 1e-4
+    clear = np.sort(S, 0)[-1] - np.sort(S, 0)[-2] > 1e-3          # columns whose maximum is unambiguous
+    assert np.array_equal(best_row[clear], S.argmax(0)[clear])
     cnt = kb.device_array(view.cand_cnt, mr, np.int32, DEV)
     lo, hi = (S > thr - 2 * band + 1e-4).sum(0), (S > thr - 2 * band - 1e-4).sum(0)
     assert (cnt >= lo).all() and (cnt <= hi).all()
