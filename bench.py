@@ -67,6 +67,9 @@ def main():
     ap.add_argument("--workload", default="llama8b_bff")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cand-cap", type=int, default=16)
+    ap.add_argument("--calib-copy-gib", type=float, default=0.0,
+                    help="also run a plain device copy of this many GiB (3 times) so that rocprofv3 --pmc FETCH_SIZE / "
+                         "WRITE_SIZE readings can be scaled by a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (groups would shard with no "
@@ -113,6 +116,15 @@ def main():
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) * 1e3
         return wall, st, ev[1].elapsed_time(ev[2])
+
+    if args.calib_copy_gib > 0:
+        nelem = int(args.calib_copy_gib * (1 << 30)) // 4
+        src = torch.ones(nelem, device=dev, dtype=torch.float32)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)        # one elementwise kernel: reads nelem * 4 bytes, writes nelem * 4 bytes
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         restore()

@@ -198,6 +198,29 @@ __device__ __forceinline__ uint32_t f64_to_bf16_rne(double x)
     return sign | out;
 }
 
+// Same result as f64_to_bf16_rne for finite inputs in the binary32 normal range, with one fp64 instruction: round
+// to binary32 first (nearest even).  Every bfloat16 rounding boundary is a binary32 number and that rounding is
+// monotonic, so unless the binary32 value sits exactly on a boundary it lies on the same side of it as x and the
+// second rounding is safe; on a boundary the comparison with x itself decides (equal = a true tie, to even).
+__device__ __forceinline__ uint32_t f64_to_bf16_fast(double x)
+{
+    const float f = (float)x;
+    const uint32_t b = __float_as_uint(f);
+    const uint32_t ex = (b >> 23) & 0xFFu;
+    if (ex == 0u || ex == 0xFFu)
+        return f64_to_bf16_rne(x);            // zero, subnormal, infinity, NaN: the exact path
+    uint32_t up;
+    if ((b & 0xFFFFu) == 0x8000u) {
+        const double fd = (double)f;
+        const bool away = fabs(x) > fabs(fd);
+        const bool tie = x == fd;
+        up = (away || (tie && ((b >> 16) & 1u))) ? 1u : 0u;
+    } else {
+        up = (b >> 15) & 1u;
+    }
+    return (b >> 16) + up;
+}
+
 #endif // __HIPCC__
 
 }  // namespace kvfuse

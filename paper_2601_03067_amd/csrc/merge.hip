@@ -3,9 +3,12 @@
 //
 // Operands are the current unit representatives, i.e. stored block / its stored norm.  HBM-bound: a target with m
 // members reads 1 + m blocks and writes one, for K and for V; blocks that are not fused are never touched.  One
-// workgroup per target (a persistent grid strides over the work list left by the assignment step), 16-byte
-// coalesced loads, the whole block held in registers as fp64, two fixed-order workgroup reductions (length of the
-// sum, norm of the rounded result).  The result is rounded once, from fp64, to the pool dtype.
+// wavefront per (target, tensor) -- a persistent grid strides over the work list left by the assignment step --
+// with 16-byte coalesced loads, the loads of the target and of its first members issued together, the whole block
+// held in registers as fp64 and two fixed-order wavefront reductions (length of the sum, norm of the rounded
+// result); no barriers.  Blocks too long for one wavefront's registers take the workgroup-per-target kernel.
+// Unit vectors are formed by multiplying with the fp64 reciprocal of the norm (within one fp64 ulp of a
+// division); the result is rounded once, from fp64, to the pool dtype.
 #include "common.h"
 
 namespace kvfuse {
@@ -17,7 +20,7 @@ template <> struct Store16<bf16_t> {
         uint32_t h[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            h[i] = f64_to_bf16_rne(u[i]);
+            h[i] = f64_to_bf16_fast(u[i]);
             back[i] = (double)__uint_as_float(h[i] << 16);
         }
         return make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
@@ -50,6 +53,108 @@ __device__ __forceinline__ int find_base(const int32_t *__restrict__ base, int n
     return lo;
 }
 
+// One wavefront per (target, tensor); CPL = 16-byte chunks per lane.
+template <typename T, int CPL>
+__global__ __launch_bounds__(256) void merge_wave_kernel(PoolDesc pool, WorkDesc w, HeightDesc h, int height)
+{
+    constexpr int PER = Elem<T>::PER16;
+    const int lane = threadIdx.x & 63;
+    const int chunks = pool.r / PER;
+    const int n_items = 2 * w.n_active[height];
+    const int n_waves = gridDim.x * 4;
+    for (int it = blockIdx.x * 4 + (threadIdx.x >> 6); it < n_items; it += n_waves) {
+        const int kv = it & 1;
+        const int packed = w.active[it >> 1];
+        const int g = packed / w.l_stride;
+        const int ti = packed - g * w.l_stride;
+        const int node = find_base(h.l_base, h.n_nodes, ti);
+        const int a = w.set_ids[(int64_t)g * w.n + h.l_off[node] + (ti - h.l_base[node])];
+        const int cnt = w.seg_cnt[(int64_t)g * w.l_stride + ti];
+        const int start = w.seg_ptr[(int64_t)g * w.l_stride + ti] - cnt;
+        const int32_t *members = w.seg_members + (int64_t)g * w.r_stride + h.r_base[node] + start;
+        T *pool_g = (T *)(kv ? pool.v : pool.k) + (int64_t)g * pool.P * pool.r;
+        double *norm_g = (kv ? pool.norm_v : pool.norm_k) + (int64_t)g * pool.P;
+
+        // the target and the first two members are fetched together; further members (rare) follow one by one
+        const int b1 = cnt > 0 ? members[0] : a;
+        const int b2 = cnt > 1 ? members[1] : a;
+        const uint4 *sa = reinterpret_cast<const uint4 *>(pool_g + (int64_t)a * pool.r);
+        const uint4 *s1 = reinterpret_cast<const uint4 *>(pool_g + (int64_t)b1 * pool.r);
+        const uint4 *s2 = reinterpret_cast<const uint4 *>(pool_g + (int64_t)b2 * pool.r);
+        uint4 xa[CPL], x1[CPL], x2[CPL];
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) {
+            const int ch = lane + 64 * c;
+            const bool in = ch < chunks;
+            xa[c] = in ? sa[ch] : make_uint4(0, 0, 0, 0);
+            x1[c] = in ? s1[ch] : make_uint4(0, 0, 0, 0);
+            x2[c] = in ? s2[ch] : make_uint4(0, 0, 0, 0);
+        }
+        const double na = norm_g[a], n1 = norm_g[b1], n2 = norm_g[b2];
+        const double ia = na == 0.0 ? 0.0 : 1.0 / na;
+        const double i1 = (cnt > 0 && n1 != 0.0) ? 1.0 / n1 : 0.0;
+        const double i2 = (cnt > 1 && n2 != 0.0) ? 1.0 / n2 : 0.0;
+        double acc[CPL][PER];
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) {
+            double ya[PER], y1[PER], y2[PER];
+            Elem<T>::widen(xa[c], ya);
+            Elem<T>::widen(x1[c], y1);
+            Elem<T>::widen(x2[c], y2);
+#pragma unroll
+            for (int e = 0; e < PER; ++e)
+                acc[c][e] = fma(y2[e], i2, fma(y1[e], i1, ya[e] * ia));
+        }
+        for (int m = 2; m < cnt; ++m) {
+            const int b = members[m];
+            const double nb = norm_g[b];
+            const double ib = nb == 0.0 ? 0.0 : 1.0 / nb;
+            const uint4 *sb = reinterpret_cast<const uint4 *>(pool_g + (int64_t)b * pool.r);
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+                const int ch = lane + 64 * c;
+                double y[PER];
+                Elem<T>::widen(ch < chunks ? sb[ch] : make_uint4(0, 0, 0, 0), y);
+#pragma unroll
+                for (int e = 0; e < PER; ++e)
+                    acc[c][e] = fma(y[e], ib, acc[c][e]);
+            }
+        }
+        double ss = 0.0;
+#pragma unroll
+        for (int c = 0; c < CPL; ++c)
+#pragma unroll
+            for (int e = 0; e < PER; ++e)
+                ss = fma(acc[c][e], acc[c][e], ss);
+        const double len = sqrt(wave_sum(ss));
+        const double il = len == 0.0 ? 0.0 : 1.0 / len;
+        uint4 *dst = reinterpret_cast<uint4 *>(pool_g + (int64_t)a * pool.r);
+        double ss2 = 0.0;
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) {
+            const int ch = lane + 64 * c;
+            double u[PER], back[PER];
+#pragma unroll
+            for (int e = 0; e < PER; ++e)
+                u[e] = acc[c][e] * il;
+            const uint4 packed_out = Store16<T>::pack(u, back);
+            if (ch < chunks) {
+                dst[ch] = packed_out;
+#pragma unroll
+                for (int e = 0; e < PER; ++e)
+                    ss2 = fma(back[e], back[e], ss2);
+            }
+        }
+        const double nrm = sqrt(wave_sum(ss2));
+        if (lane == 0) {
+            norm_g[a] = nrm;
+            if (kv == 0)
+                pool.inv_norm_k[(int64_t)g * pool.P + a] = nrm > 0.0 ? (float)(1.0 / nrm) : 0.0f;
+        }
+    }
+}
+
+// Workgroup per target: for blocks longer than one wavefront can hold in registers.
 template <typename T, int MAXC>
 __global__ __launch_bounds__(256) void merge_kernel(PoolDesc pool, WorkDesc w, HeightDesc h, int height)
 {
@@ -92,7 +197,7 @@ __global__ __launch_bounds__(256) void merge_kernel(PoolDesc pool, WorkDesc w, H
                         Elem<T>::widen(src[ch], x);
 #pragma unroll
                         for (int e = 0; e < PER; ++e)
-                            acc[c][e] += x[e] / nb;
+                            acc[c][e] = fma(x[e], 1.0 / nb, acc[c][e]);
                     }
                 }
             }
@@ -112,7 +217,7 @@ __global__ __launch_bounds__(256) void merge_kernel(PoolDesc pool, WorkDesc w, H
                     double u[PER], back[PER];
 #pragma unroll
                     for (int e = 0; e < PER; ++e)
-                        u[e] = len == 0.0 ? 0.0 : acc[c][e] / len;
+                        u[e] = len == 0.0 ? 0.0 : acc[c][e] * (1.0 / len);
                     dst[ch] = Store16<T>::pack(u, back);
 #pragma unroll
                     for (int e = 0; e < PER; ++e)
@@ -138,6 +243,24 @@ void launch_merge(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const 
     const int per = pool.dtype == KVFUSE_BF16 ? 8 : 4;
     const int chunks = pool.r / per;
     const int maxc = (chunks + 255) / 256;
+    const int cpl = (chunks + 63) / 64;
+    if (cpl <= 8) {
+        const unsigned wgrid = (unsigned)(want < 256 * 8 ? (want + 1) / 2 + 1 : 256 * 8);
+#define KVF_MERGE_W(T, C) merge_wave_kernel<T, C><<<wgrid, 256, 0, s>>>(pool, w, h, height)
+        if (pool.dtype == KVFUSE_BF16) {
+            if (cpl <= 1) KVF_MERGE_W(bf16_t, 1);
+            else if (cpl <= 2) KVF_MERGE_W(bf16_t, 2);
+            else if (cpl <= 4) KVF_MERGE_W(bf16_t, 4);
+            else KVF_MERGE_W(bf16_t, 8);
+        } else {
+            if (cpl <= 1) KVF_MERGE_W(float, 1);
+            else if (cpl <= 2) KVF_MERGE_W(float, 2);
+            else if (cpl <= 4) KVF_MERGE_W(float, 4);
+            else KVF_MERGE_W(float, 8);
+        }
+#undef KVF_MERGE_W
+        return;
+    }
 #define KVF_MERGE(T, C) merge_kernel<T, C><<<grid, 256, 0, s>>>(pool, w, h, height)
     if (pool.dtype == KVFUSE_BF16) {
         if (maxc <= 1) KVF_MERGE(bf16_t, 1);

@@ -16,8 +16,9 @@
 //
 // Tiling.  WM x WN wavefronts, each TM x TN MFMA tiles of 32 x 32 (v_mfma_f32_32x32x16_bf16, or 4 x
 // v_mfma_f32_32x32x2_f32 per 16-byte fragment for f32 pools).  K is walked in 128-byte slices per row, double
-// buffered in LDS with a 16-byte-chunk XOR swizzle (chunk ^ (row & 7)) so that both the 16-byte stores and the
-// MFMA fragment reads are bank-conflict free.  Global loads of the next slice are in flight during the MFMAs.
+// buffered in LDS with a 16-byte-chunk XOR swizzle (chunk ^ ((row >> 1) & 7)): the LDS has 64 four-byte banks, so
+// two 128-byte rows make one sweep over the banks, and with this swizzle both the 16-byte stores (16 lanes = 2 rows x
+// 8 chunks) and the MFMA fragment reads (16 lanes = 16 rows, one chunk) touch every bank exactly once.  Global loads of the next slice are in flight during the MFMAs.
 #include "common.h"
 
 namespace kvfuse {
@@ -121,7 +122,7 @@ __global__ __launch_bounds__(64 * WM * WN) void similarity_kernel(
 #define KVF_COL_PTR(P) (kg + (int64_t)r_ids[min(col0 + ld_r + RPP * (P), mr - 1)] * row_bytes + ld_c * 16)
 #define KVF_ROW_PTR(RT, P) (kg + (int64_t)l_ids[min(row0 + (RT) * BM + ld_r + RPP * (P), row_end - 1)] * row_bytes + ld_c * 16)
 #define KVF_LD(PTR, KO) (*reinterpret_cast<const uint4 *>((PTR) + (KO)))
-#define KVF_SLOT(P) ((ld_r + RPP * (P)) * 8 + (ld_c ^ ((ld_r + RPP * (P)) & 7)))
+#define KVF_SLOT(P) ((ld_r + RPP * (P)) * 8 + (ld_c ^ (((ld_r + RPP * (P)) >> 1) & 7)))
     const char *pb0 = KVF_COL_PTR(0), *pb1 = KVF_COL_PTR(1), *pb2 = KVF_COL_PTR(2), *pb3 = KVF_COL_PTR(3);
     const char *pa0 = KVF_ROW_PTR(0, 0), *pa1 = KVF_ROW_PTR(0, 1), *pa2 = KVF_ROW_PTR(0, 2), *pa3 = KVF_ROW_PTR(0, 3);
     const int sl0 = KVF_SLOT(0), sl1 = KVF_SLOT(1), sl2 = KVF_SLOT(2), sl3 = KVF_SLOT(3);
@@ -190,12 +191,12 @@ __global__ __launch_bounds__(64 * WM * WN) void similarity_kernel(
 #pragma unroll
             for (int mt = 0; mt < TM; ++mt) {
                 const int row = (wm * TM + mt) * 32 + (lane & 31);
-                fa[mt] = la[row * 8 + (chunk ^ (row & 7))];
+                fa[mt] = la[row * 8 + (chunk ^ ((row >> 1) & 7))];
             }
 #pragma unroll
             for (int nt = 0; nt < TN; ++nt) {
                 const int row = (wn * TN + nt) * 32 + (lane & 31);
-                fb[nt] = lb[row * 8 + (chunk ^ (row & 7))];
+                fb[nt] = lb[row * 8 + (chunk ^ ((row >> 1) & 7))];
             }
 #pragma unroll
             for (int mt = 0; mt < TM; ++mt)

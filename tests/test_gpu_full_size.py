@@ -1,0 +1,92 @@
+"""Parity at BASELINE's full size, in the launch configuration bench.py times: the Llama-3-8B-shaped BFF workload
+(256 groups x 8192 blocks, bf16).  The oracle needs about a minute of one host core per group, so it checks a
+seeded sample of groups exactly (tables, pools, counts) and every group through invariants that hold at any size;
+decode attention is checked on sampled (layer, request) outputs that the oracle computes one by one.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_03067_amd import workloads as wl
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.mark.timeout(900)
+def test_llama8b_bff_full_size_sampled_groups_and_invariants(oracle):
+    kb = gu.load_binding()
+    rec = wl.llama8b_bff()
+    print("materialise", rec.name, "G", rec.G, "n", rec.n, flush=True)
+    mat = wl.materialise(rec, DEV)
+    rng = np.random.default_rng(20260103)
+    sample = sorted({0, rec.G - 1, *rng.choice(rec.G, size=2, replace=False).tolist()})
+    host = {g: (wl.to_numpy_pool(mat["K"][g]), wl.to_numpy_pool(mat["V"][g]), mat["bt"][g].cpu().numpy().copy()) for g in sample}
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, cand_cap=16)
+    print("gpu fused", stats.fused, "CR", stats.compression_ratio, "refined", stats.refined, flush=True)
+
+    # ---- invariants on every group
+    n, P = rec.n, rec.n
+    bt = cache.bt.cpu().numpy()
+    rc = cache.refcount.cpu().numpy()
+    remap = cache.remap.cpu().numpy()
+    n_phys = cache.n_phys.cpu().numpy()
+    n_free = cache.n_free.cpu().numpy()
+    assert (rc.sum(1) == n).all()
+    assert stats.logical_blocks == rec.G * n and stats.physical_blocks == int(n_phys.sum())
+    assert math.isclose(stats.compression_ratio, rec.G * n / n_phys.sum())        # CR = logical / physical
+    p = rec.req_blocks[0]
+    pre = 512 // rec.t
+    sk = cache.scale_k.cpu().numpy()
+    nk = cache.norm_k.cpu().numpy()
+    for g in range(rec.G):
+        live = np.unique(bt[g])
+        assert len(live) == n_phys[g] and n_phys[g] + n_free[g] == P
+        assert (remap[g][live] == -1).all() and (rc[g][live] > 0).all()            # nothing points at an evicted block
+        assert np.array_equal(np.bincount(bt[g], minlength=P), rc[g])
+        first = bt[g][:pre]
+        assert all(np.array_equal(bt[g][q * p: q * p + pre], first) for q in range(rec.B))   # identical prefixes always fuse
+        fused = live[rc[g][live] > 1]
+        assert np.abs(nk[g][fused] - 1.0).max() < 3e-3                             # representatives are unit up to bf16 rounding
+        assert (sk[g][rc[g][bt[g]] == 1] == 1.0).all()                             # untouched blocks keep scale exactly 1
+
+    # ---- exact comparison on the sampled groups
+    print("oracle on groups", sample, flush=True)
+    res = gu.oracle_fuse(oracle, rec, ([host[g][0] for g in sample], [host[g][1] for g in sample], [host[g][2] for g in sample]),
+                         threads=len(sample))
+    safe = gu.check_ambiguity(res, "llama8b_bff full size")
+    assert len(safe) >= len(sample) - 1
+    for i in safe:
+        gu.compare_group(res[i], _GroupView(cache, sample[i]), 0, False, f"full size group {sample[i]}")
+    print("sampled groups match", flush=True)
+
+    # ---- decode attention on sampled outputs (layer, request), all query heads
+    q = wl.queries(rec, DEV)
+    rs = torch.tensor(rec.req_start, dtype=torch.int32, device=DEV)
+    cl = torch.tensor(rec.ctx_len, dtype=torch.int32, device=DEV)
+    out = kb.paged_decode_attn(ctx, cache, rec.kv_heads, q, rs, cl, int(rec.req_blocks.max()))
+    torch.cuda.synchronize()
+    worst = 0.0
+    for layer, b in ((0, 0), (17, 41), (rec.layers - 1, rec.B - 1)):
+        gs = [layer * rec.kv_heads + h for h in range(rec.kv_heads)]
+        ref = oracle.paged_decode_attention(
+            q[layer, b: b + 1].float().cpu().numpy(), [wl.to_numpy_pool(cache.K[g]) for g in gs],
+            [wl.to_numpy_pool(cache.V[g]) for g in gs], [bt[g] for g in gs], [sk[g].astype(np.float64) for g in gs],
+            [cache.scale_v[g].cpu().numpy().astype(np.float64) for g in gs], rec.req_start[b: b + 1], rec.ctx_len[b: b + 1],
+            rec.t, rec.d)
+        worst = max(worst, float(np.abs(out[layer, b].cpu().numpy() - ref[0]).max()))
+    print("decode max abs err on sampled outputs", worst, flush=True)
+    assert worst <= 2e-2
+
+
+class _GroupView:
+    """Presents group g of a big cache as group 0 to gu.compare_group."""
+
+    def __init__(self, cache, g):
+        for name in ("bt", "K", "V", "refcount", "n_free", "free_list", "n_phys", "scale_k", "scale_v", "norm_k", "norm_v",
+                     "orig_norm_k"):
+            setattr(self, name, getattr(cache, name)[g: g + 1])
