@@ -54,6 +54,18 @@ __device__ __forceinline__ unsigned long long pack_best(float s, int row)
     return ((unsigned long long)ord << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)row);
 }
 
+// Rare path of the epilogue: append (row, cosine) to the
+// candidate list of a column; the count is exact even when the list is full.
+__device__ __forceinline__ void emit_candidate(int32_t *__restrict__ cand_cnt, int32_t *__restrict__ cand_idx,
+                                                         float *__restrict__ cand_val, int64_t column, int cap, int row, float s)
+{
+    const int slot = atomicAdd(&cand_cnt[column], 1);
+    if (slot < cap) {
+        cand_idx[column * cap + slot] = row;
+        cand_val[column * cap + slot] = s;
+    }
+}
+
 struct SimArgs {
     int32_t G, n, n_slots, r_stride, cand_cap, P, n_items;
     int32_t row_bytes;             // bytes of one block row
@@ -61,8 +73,8 @@ struct SimArgs {
     int64_t total_s;
 };
 
-template <typename T, int WM, int WN, int TM, int TN>
-__global__ __launch_bounds__(64 * WM * WN) void similarity_kernel(
+template <typename T, int WM, int WN, int TM, int TN, bool DENSE>
+__global__ __launch_bounds__(64 * WM * WN, (WM * WN * TM * TN >= 64 ? 1 : 2)) void similarity_kernel(
     SimArgs A, const char *__restrict__ kpool, const float *__restrict__ inv_norm, const int32_t *__restrict__ set_ids,
     const int32_t *__restrict__ set_cnt, const int32_t *__restrict__ item_node, const int32_t *__restrict__ item_col0,
     const int32_t *__restrict__ item_row0, const int32_t *__restrict__ item_rows, const int32_t *__restrict__ l_off,
@@ -77,11 +89,19 @@ __global__ __launch_bounds__(64 * WM * WN) void similarity_kernel(
     constexpr int LA = BM * 8 / NT;   // 16-byte chunks of the left tile per thread and K slice
     constexpr int LB = BN * 8 / NT;
     constexpr int RPP = NT / 8;       // rows covered by one pass of the loaders
-    static_assert(LA == 4 && LB == 4, "the loaders below are written out for 4 + 4 chunks per thread");
+    static_assert((LA == 4 || LA == 8) && LA == LB, "the loaders below are written out for 4 + 4 or 8 + 8 chunks per thread");
+    constexpr bool L8 = LA == 8;
 
     __shared__ uint4 lds_a[2][BM * 8];
     __shared__ uint4 lds_b[2][BN * 8];
     __shared__ float lds_invl[BM];
+    // Epilogue state lives in LDS, not in registers, so that the main loop has the register file to itself:
+    // per column of the panel the inverse norm and the candidate floor in accumulator units, per thread and
+    // column tile the running maximum (key, row tile).
+    __shared__ float lds_invr[BN];
+    __shared__ float lds_tcol[BN];
+    __shared__ uint32_t lds_bkey[TN][NT];
+    __shared__ int lds_brt[TN][NT];
 
     // hardware workgroup id -> item: XCD x (ids congruent x mod 8) walks items [x * per_xcd, (x + 1) * per_xcd)
     const int per_xcd = gridDim.x >> 3;
@@ -123,19 +143,37 @@ __global__ __launch_bounds__(64 * WM * WN) void similarity_kernel(
 #define KVF_ROW_PTR(RT, P) (kg + (int64_t)l_ids[min(row0 + (RT) * BM + ld_r + RPP * (P), row_end - 1)] * row_bytes + ld_c * 16)
 #define KVF_LD(PTR, KO) (*reinterpret_cast<const uint4 *>((PTR) + (KO)))
 #define KVF_SLOT(P) ((ld_r + RPP * (P)) * 8 + (ld_c ^ (((ld_r + RPP * (P)) >> 1) & 7)))
-    const char *pb0 = KVF_COL_PTR(0), *pb1 = KVF_COL_PTR(1), *pb2 = KVF_COL_PTR(2), *pb3 = KVF_COL_PTR(3);
-    const char *pa0 = KVF_ROW_PTR(0, 0), *pa1 = KVF_ROW_PTR(0, 1), *pa2 = KVF_ROW_PTR(0, 2), *pa3 = KVF_ROW_PTR(0, 3);
-    const int sl0 = KVF_SLOT(0), sl1 = KVF_SLOT(1), sl2 = KVF_SLOT(2), sl3 = KVF_SLOT(3);
+    // X(i) expands once per staged chunk i; chunks 4..7 exist only in the 8 + 8 configuration
+#define KVF_FOR4(X) X(0) X(1) X(2) X(3)
+#define KVF_FOR48(X) X(4) X(5) X(6) X(7)
+#define KVF_DECL(i)                                                  \
+    const char *pb##i = KVF_COL_PTR((i) < LA ? (i) : 0);             \
+    const char *pa##i = KVF_ROW_PTR(0, (i) < LA ? (i) : 0);          \
+    const int sl##i = KVF_SLOT((i) < LA ? (i) : 0);                  \
+    uint4 ra##i, rb##i;
+    KVF_FOR4(KVF_DECL)
+    KVF_FOR48(KVF_DECL)
+#define KVF_NEWROWS(i) pa##i = KVF_ROW_PTR(pf_rt, i);
+#define KVF_LOAD(i) ra##i = KVF_LD(pa##i, ko); rb##i = KVF_LD(pb##i, ko);
+#define KVF_STORE(i) na[sl##i] = ra##i; nb[sl##i] = rb##i;
 
-    // per-lane epilogue state: the lane holds column (lane & 31) of each of its TN tiles
-    float inv_r[TN], best[TN];
-    int best_i[TN];
+    // per-lane epilogue state: the lane holds column (lane & 31) of each of its TN tiles.  The column maximum is
+    // kept as an integer key: the bits of max(acc * inv_l, 0) with the low CODE_BITS replaced by (all ones - position
+    // in the wavefront's tile), so that one unsigned max per element tracks value and row; bkey_rt remembers the
+    // row tile.  The value therefore carries 23 - CODE_BITS mantissa bits, which is ample for a diagnostic; decisions
+    // are taken from the candidate lists, never from it.
+    constexpr uint32_t CODE_MASK = TM * 16 - 1;
+    for (int x = tid; x < BN; x += NT) {
+        const int col = col0 + x;
+        const float ir = col < mr ? inv_g[r_ids[col]] : 0.0f;
+        lds_invr[x] = ir;
+        // acc * inv_l > tcol  <=>  cosine > thr_floor.  A zero right block has cosine 0 with everything.
+        lds_tcol[x] = col >= mr ? INFINITY : (ir > 0.0f ? A.thr_floor / ir : (A.thr_floor < 0.0f ? -INFINITY : INFINITY));
+    }
 #pragma unroll
     for (int nt = 0; nt < TN; ++nt) {
-        const int col = col0 + (wn * TN + nt) * 32 + (lane & 31);
-        inv_r[nt] = col < mr ? inv_g[r_ids[col]] : 0.0f;
-        best[nt] = -INFINITY;
-        best_i[nt] = 0x7FFFFFFF;
+        lds_bkey[nt][tid] = 0u;
+        lds_brt[nt][tid] = 0;
     }
 
     floatx16 acc[TM][TN];
@@ -148,15 +186,19 @@ __global__ __launch_bounds__(64 * WM * WN) void similarity_kernel(
                 acc[mt][nt][e] = 0.0f;
 
     int pf_kt = 1, pf_rt = 0;
-    // first slice
-    uint4 ra0 = KVF_LD(pa0, 0), ra1 = KVF_LD(pa1, 0), ra2 = KVF_LD(pa2, 0), ra3 = KVF_LD(pa3, 0);
-    uint4 rb0 = KVF_LD(pb0, 0), rb1 = KVF_LD(pb1, 0), rb2 = KVF_LD(pb2, 0), rb3 = KVF_LD(pb3, 0);
+    {   // first slice
+        const int64_t ko = 0;
+        uint4 *__restrict__ na = lds_a[0];
+        uint4 *__restrict__ nb = lds_b[0];
+        KVF_FOR4(KVF_LOAD)
+        if constexpr (L8) { KVF_FOR48(KVF_LOAD) }
+        KVF_FOR4(KVF_STORE)
+        if constexpr (L8) { KVF_FOR48(KVF_STORE) }
+    }
     if (pf_kt == nk) {
         pf_kt = 0;
         pf_rt = 1;
     }
-    lds_a[0][sl0] = ra0; lds_a[0][sl1] = ra1; lds_a[0][sl2] = ra2; lds_a[0][sl3] = ra3;
-    lds_b[0][sl0] = rb0; lds_b[0][sl1] = rb1; lds_b[0][sl2] = rb2; lds_b[0][sl3] = rb3;
     __syncthreads();
 
     for (int it = 0; it < total_it; ++it) {
@@ -167,16 +209,17 @@ __global__ __launch_bounds__(64 * WM * WN) void similarity_kernel(
         if (kt == 0) {
             for (int x = tid; x < BM; x += NT) {
                 const int row = row0 + rt * BM + x;
-                lds_invl[x] = row < row_end ? inv_g[l_ids[row]] : 0.0f;
+                lds_invl[x] = row < row_end ? inv_g[l_ids[row]] : __uint_as_float(0x7FC00000u);
             }
         }
         if (more) {
             if (pf_kt == 0) {      // the prefetch enters a new tile of left rows
-                pa0 = KVF_ROW_PTR(pf_rt, 0); pa1 = KVF_ROW_PTR(pf_rt, 1); pa2 = KVF_ROW_PTR(pf_rt, 2); pa3 = KVF_ROW_PTR(pf_rt, 3);
+                KVF_FOR4(KVF_NEWROWS)
+                if constexpr (L8) { KVF_FOR48(KVF_NEWROWS) }
             }
             const int64_t ko = (int64_t)pf_kt * 128;
-            ra0 = KVF_LD(pa0, ko); ra1 = KVF_LD(pa1, ko); ra2 = KVF_LD(pa2, ko); ra3 = KVF_LD(pa3, ko);
-            rb0 = KVF_LD(pb0, ko); rb1 = KVF_LD(pb1, ko); rb2 = KVF_LD(pb2, ko); rb3 = KVF_LD(pb3, ko);
+            KVF_FOR4(KVF_LOAD)
+            if constexpr (L8) { KVF_FOR48(KVF_LOAD) }
             if (++pf_kt == nk) {
                 pf_kt = 0;
                 ++pf_rt;
@@ -207,39 +250,75 @@ __global__ __launch_bounds__(64 * WM * WN) void similarity_kernel(
         if (more) {
             uint4 *__restrict__ na = lds_a[cur ^ 1];
             uint4 *__restrict__ nb = lds_b[cur ^ 1];
-            na[sl0] = ra0; na[sl1] = ra1; na[sl2] = ra2; na[sl3] = ra3;
-            nb[sl0] = rb0; nb[sl1] = rb1; nb[sl2] = rb2; nb[sl3] = rb3;
+            KVF_FOR4(KVF_STORE)
+            if constexpr (L8) { KVF_FOR48(KVF_STORE) }
         }
         if (kt == nk - 1) {
             __syncthreads();   // lds_invl of this row tile is visible even when nk == 1
+            uint32_t kmax[TN];
+            float tcol[TN];
 #pragma unroll
             for (int nt = 0; nt < TN; ++nt) {
-                const int col = col0 + (wn * TN + nt) * 32 + (lane & 31);
+                kmax[nt] = 0u;
+                tcol[nt] = lds_tcol[(wn * TN + nt) * 32 + (lane & 31)];
+            }
+            // Rows past the end of the set carry a NaN inverse norm: their products compare false against the
+            // candidate floor and turn into key 0, so the unrolled code needs no validity tests.
 #pragma unroll
-                for (int mt = 0; mt < TM; ++mt) {
+            for (int mt = 0; mt < TM; ++mt)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const int rl = (wm * TM + mt) * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
-                        const int row = row0 + rt * BM + rl;
-                        const float s = acc[mt][nt][e] * lds_invl[rl] * inv_r[nt];
-                        acc[mt][nt][e] = 0.0f;
-                        if (row < row_end && col < mr) {
-                            if (dense_s)
-                                dense_s[(int64_t)g * A.total_s + s_base[node] + (int64_t)row * r_cap[node] + col] = s;
-                            if (s > A.thr_floor) {
-                                const int slot = atomicAdd(&cand_cnt[cbase + col], 1);
-                                if (slot < A.cand_cap) {
-                                    cand_idx[(cbase + col) * A.cand_cap + slot] = row;
-                                    cand_val[(cbase + col) * A.cand_cap + slot] = s;
-                                }
-                            }
-                            if (s > best[nt]) {
-                                best[nt] = s;
-                                best_i[nt] = row;
-                            }
+                for (int eg = 0; eg < 4; ++eg) {
+                    const int rl0 = (wm * TM + mt) * 32 + eg * 8 + half * 4;
+                    const float4 il4 = *reinterpret_cast<const float4 *>(&lds_invl[rl0]);   // 4 consecutive left rows
+                    const float il[4] = {il4.x, il4.y, il4.z, il4.w};
+#pragma unroll
+                    for (int nt = 0; nt < TN; ++nt) {
+                        float t[4];
+                        bool hit = false;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            t[q] = acc[mt][nt][eg * 4 + q] * il[q];
+                            hit |= t[q] > tcol[nt];
+                            const uint32_t key = (__float_as_uint(fmaxf(t[q], 0.0f)) & ~CODE_MASK) |
+                                                 (CODE_MASK - (uint32_t)(mt * 16 + eg * 4 + q));
+                            kmax[nt] = max(kmax[nt], key);
+                        }
+                        if (hit) {      // rare: an entry clears the candidate floor
+                            const int64_t column = cbase + col0 + (wn * TN + nt) * 32 + (lane & 31);
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                if (t[q] > tcol[nt])
+                                    emit_candidate(cand_cnt, cand_idx, cand_val, column, A.cand_cap, row0 + rt * BM + rl0 + q,
+                                                   t[q] * lds_invr[(wn * TN + nt) * 32 + (lane & 31)]);
                         }
                     }
                 }
+            if constexpr (DENSE) {      // separate instantiation for tests: writes every screened cosine
+#pragma unroll
+                for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < TN; ++nt)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            const int rl = (wm * TM + mt) * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
+                            const int row = row0 + rt * BM + rl;
+                            const int col = col0 + (wn * TN + nt) * 32 + (lane & 31);
+                            if (row < row_end && col < mr)
+                                dense_s[(int64_t)g * A.total_s + s_base[node] + (int64_t)row * r_cap[node] + col] =
+                                    acc[mt][nt][e] * lds_invl[rl] * lds_invr[(wn * TN + nt) * 32 + (lane & 31)];
+                        }
+            }
+#pragma unroll
+            for (int nt = 0; nt < TN; ++nt) {
+                if (kmax[nt] > lds_bkey[nt][tid]) {
+                    lds_bkey[nt][tid] = kmax[nt];
+                    lds_brt[nt][tid] = rt;
+                }
+#pragma unroll
+                for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        acc[mt][nt][e] = 0.0f;
             }
         }
         __syncthreads();
@@ -250,14 +329,14 @@ __global__ __launch_bounds__(64 * WM * WN) void similarity_kernel(
 #pragma unroll
     for (int nt = 0; nt < TN; ++nt) {
         const int col = col0 + (wn * TN + nt) * 32 + (lane & 31);
-        const float ov = __shfl_xor(best[nt], 32, 64);
-        const int oi = __shfl_xor(best_i[nt], 32, 64);
-        if (ov > best[nt] || (ov == best[nt] && oi < best_i[nt])) {
-            best[nt] = ov;
-            best_i[nt] = oi;
-        }
-        if (half == 0 && col < mr && best_i[nt] != 0x7FFFFFFF)
-            atomicMax(&best_packed[cbase + col], pack_best(best[nt], best_i[nt]));
+        const uint32_t bkey = lds_bkey[nt][tid];
+        const int code = (int)(CODE_MASK - (bkey & CODE_MASK));
+        const int row = min(row_end - 1, row0 + lds_brt[nt][tid] * BM + (wm * TM + (code >> 4)) * 32 + ((code & 15) >> 2) * 8 + half * 4 + (code & 3));
+        unsigned long long pk = bkey ? pack_best(__uint_as_float(bkey & ~CODE_MASK) * lds_invr[(wn * TN + nt) * 32 + (lane & 31)], row) : 0ull;
+        const unsigned long long other = __shfl_xor(pk, 32, 64);
+        pk = other > pk ? other : pk;
+        if (half == 0 && col < mr && pk)
+            atomicMax(&best_packed[cbase + col], pk);
     }
 }
 
@@ -285,10 +364,21 @@ static void launch_cfg(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, c
     A.thr_floor = thr_floor;
     A.total_s = h.total_s;
     const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
-    similarity_kernel<T, WM, WN, TM, TN><<<grid, 64 * WM * WN, 0, s>>>(
-        A, (const char *)pool.k, pool.inv_norm_k, w.set_ids, w.set_cnt, tt.node, tt.col0, tt.row0, tt.rows, h.l_off, h.r_off,
-        h.l_slot, h.r_slot, h.r_base, h.r_cap, h.s_base, w.best_packed, w.cand_cnt, w.cand_idx, w.cand_val, dense_s);
+#define KVF_SIM_LAUNCH(D)                                                                                              \
+    similarity_kernel<T, WM, WN, TM, TN, D><<<grid, 64 * WM * WN, 0, s>>>(                                             \
+        A, (const char *)pool.k, pool.inv_norm_k, w.set_ids, w.set_cnt, tt.node, tt.col0, tt.row0, tt.rows, h.l_off, h.r_off, \
+        h.l_slot, h.r_slot, h.r_base, h.r_cap, h.s_base, w.best_packed, w.cand_cnt, w.cand_idx, w.cand_val, dense_s)
+    if (dense_s)
+        KVF_SIM_LAUNCH(true);
+    else
+        KVF_SIM_LAUNCH(false);
+#undef KVF_SIM_LAUNCH
 }
+
+// Big tile: 256 x 256 as 4 x 2 wavefronts of 64 x 128 each (two wavefronts per SIMD, 128 accumulators each).
+#ifndef KVF_BIG_CFG
+#define KVF_BIG_CFG 4, 2, 2, 4
+#endif
 
 void launch_similarity(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const HeightDesc &h, float thr_floor,
                        float *dense_s)
@@ -299,12 +389,12 @@ void launch_similarity(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, c
     const bool big = h.use_big_tiles;
     if (pool.dtype == KVFUSE_BF16) {
         if (big)
-            launch_cfg<bf16_t, 4, 2, 2, 4>(s, pool, w, h, h.big, thr_floor, dense_s);
+            launch_cfg<bf16_t, KVF_BIG_CFG>(s, pool, w, h, h.big, thr_floor, dense_s);
         else
             launch_cfg<bf16_t, 2, 2, 2, 2>(s, pool, w, h, h.small, thr_floor, dense_s);
     } else {
         if (big)
-            launch_cfg<float, 4, 2, 2, 4>(s, pool, w, h, h.big, thr_floor, dense_s);
+            launch_cfg<float, KVF_BIG_CFG>(s, pool, w, h, h.big, thr_floor, dense_s);
         else
             launch_cfg<float, 2, 2, 2, 2>(s, pool, w, h, h.small, thr_floor, dense_s);
     }
