@@ -119,10 +119,10 @@ def main():
 
     if args.calib_copy_gib > 0:
         nelem = int(args.calib_copy_gib * (1 << 30)) // 4
-        src = torch.ones(nelem, device=dev, dtype=torch.float32)
+        src = torch.ones(nelem, device=dev, dtype=torch.int32)
         dst = torch.empty_like(src)
         for _ in range(3):
-            torch.add(src, 1.0, out=dst)        # one elementwise kernel: reads nelem * 4 bytes, writes nelem * 4 bytes
+            torch.bitwise_not(src, out=dst)     # one elementwise kernel: reads nelem * 4 bytes, writes nelem * 4 bytes
         torch.cuda.synchronize()
         del src, dst
 
@@ -148,7 +148,12 @@ def main():
     peak = 2500.0 if rec.dtype == torch.bfloat16 else 157.3
     phys_bytes = stats.physical_blocks * blk_bytes * 2
     logi_bytes = stats.logical_blocks * blk_bytes * 2
-    merge_bytes = None
+    traffic = None      # HBM bytes per similarity launch, from the committed rocprofv3 counter summary of this workload
+    prof = os.path.join(ROOT, "profiles", f"{rec.name}_kernels.md")
+    if args.workload == rec.name and os.path.exists(prof):
+        for ln in open(prof):
+            if ln.startswith("traffic_bytes_per_similarity_launch"):
+                traffic = float(ln.split("=")[1].split()[0])
     line = {
         "metric": "KV blocks fused/sec (+ % MFMA peak); fused-table decode attn HBM GB/s",
         "value": blocks / (ms_step * 1e-3),
@@ -168,7 +173,8 @@ def main():
                    "frac_of_hbm_peak_physical": phys_bytes / (stage["decode"] * 1e-3) / 1e9 / 8000.0},
         "norms": {"ms": stage["norms"], "GBps": logi_bytes / (stage["norms"] * 1e-3) / 1e9},
         "roofline": {"kernel": "similarity_kernel", "bound": "mfma", "achieved": sim_tflops, "peak": peak,
-                     "unit": "TFLOP/s", "frac": sim_tflops / peak, "traffic": None,
+                     "unit": "TFLOP/s", "frac": sim_tflops / peak, "traffic": traffic,
+                     "launches_per_step": stats.n_heights,
                      "flops_per_step": stats.sim_flops, "ms_per_step": stage["similarity"]},
         "generation_s": t_gen,
     }

@@ -292,6 +292,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN * TM * TN >= 64 ? 1 : 2)) vo
                                                    t[q] * lds_invr[(wn * TN + nt) * 32 + (lane & 31)]);
                         }
                     }
+                    __builtin_amdgcn_sched_barrier(0);   // keep the scheduler from widening live ranges across groups
                 }
             if constexpr (DENSE) {      // separate instantiation for tests: writes every screened cosine
 #pragma unroll
