@@ -67,6 +67,7 @@ def main():
     ap.add_argument("--workload", default="llama8b_bff")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cand-cap", type=int, default=16)
+    ap.add_argument("--thr", type=float, default=None, help="override the workload's similarity threshold")
     ap.add_argument("--calib-copy-gib", type=float, default=0.0,
                     help="also run a plain device copy of this many GiB (3 times) so that rocprofv3 --pmc FETCH_SIZE / "
                          "WRITE_SIZE readings can be scaled by a kernel of known traffic")
@@ -82,6 +83,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     rec = make_recipe(wl, args.workload)
+    if args.thr is not None:
+        rec.thr = args.thr
     t_gen = time.perf_counter()
     mat = wl.materialise(rec, dev)
     q = wl.queries(rec, dev)

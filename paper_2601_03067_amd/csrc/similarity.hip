@@ -102,6 +102,14 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN * TM * TN >= 64 ? 1 : 2)) vo
     __shared__ float lds_tcol[BN];
     __shared__ uint32_t lds_bkey[TN][NT];
     __shared__ int lds_brt[TN][NT];
+    // Candidates found by this workgroup are staged here (LDS atomics are cheap) and appended to the global lists
+    // in one parallel burst at the end; waiting for a global atomic's return value inside the epilogue would stall
+    // the wavefront for a memory round trip per candidate.
+    constexpr int MAXC = BM * BN / 64;
+    __shared__ int lds_ncand;
+    __shared__ int lds_cand_row[MAXC];
+    __shared__ int lds_cand_col[MAXC];
+    __shared__ float lds_cand_val[MAXC];
 
     // hardware workgroup id -> item: XCD x (ids congruent x mod 8) walks items [x * per_xcd, (x + 1) * per_xcd)
     const int per_xcd = gridDim.x >> 3;
@@ -175,6 +183,8 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN * TM * TN >= 64 ? 1 : 2)) vo
         lds_bkey[nt][tid] = 0u;
         lds_brt[nt][tid] = 0;
     }
+    if (tid == 0)
+        lds_ncand = 0;
 
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -284,12 +294,21 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN * TM * TN >= 64 ? 1 : 2)) vo
                             kmax[nt] = max(kmax[nt], key);
                         }
                         if (hit) {      // rare: an entry clears the candidate floor
-                            const int64_t column = cbase + col0 + (wn * TN + nt) * 32 + (lane & 31);
+                            const int cl = (wn * TN + nt) * 32 + (lane & 31);
 #pragma unroll
                             for (int q = 0; q < 4; ++q)
-                                if (t[q] > tcol[nt])
-                                    emit_candidate(cand_cnt, cand_idx, cand_val, column, A.cand_cap, row0 + rt * BM + rl0 + q,
-                                                   t[q] * lds_invr[(wn * TN + nt) * 32 + (lane & 31)]);
+                                if (t[q] > tcol[nt]) {
+                                    const int row = row0 + rt * BM + rl0 + q;
+                                    const float sv = t[q] * lds_invr[cl];
+                                    const int k = atomicAdd(&lds_ncand, 1);
+                                    if (k < MAXC) {
+                                        lds_cand_row[k] = row;
+                                        lds_cand_col[k] = cl;
+                                        lds_cand_val[k] = sv;
+                                    } else {
+                                        emit_candidate(cand_cnt, cand_idx, cand_val, cbase + col0 + cl, A.cand_cap, row, sv);
+                                    }
+                                }
                         }
                     }
                     __builtin_amdgcn_sched_barrier(0);   // keep the scheduler from widening live ranges across groups
@@ -323,6 +342,14 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN * TM * TN >= 64 ? 1 : 2)) vo
             }
         }
         __syncthreads();
+    }
+
+    // staged candidates -> global lists (the loop's last barrier made the staging area visible)
+    {
+        const int nc = min(lds_ncand, MAXC);
+        for (int k = tid; k < nc; k += NT)
+            emit_candidate(cand_cnt, cand_idx, cand_val, cbase + col0 + lds_cand_col[k], A.cand_cap, lds_cand_row[k],
+                           lds_cand_val[k]);
     }
 
     // column maxima of this item: lane halves hold different rows of a column; all chunks of a panel and all
