@@ -3,10 +3,10 @@
 //
 // Operands are the current unit representatives, i.e. stored block / its stored norm.  HBM-bound: a target with m
 // members reads 1 + m blocks and writes one, for K and for V; blocks that are not fused are never touched.  One
-// wavefront per (target, tensor) -- a persistent grid strides over the work list left by the assignment step --
-// with 16-byte coalesced loads, the loads of the target and of its first members issued together, the whole block
-// held in registers as fp64 and two fixed-order wavefront reductions (length of the sum, norm of the rounded
-// result); no barriers.  Blocks too long for one wavefront's registers take the workgroup-per-target kernel.
+// or two wavefronts per (target, tensor) -- a persistent grid strides over the work list left by the assignment
+// step -- with 16-byte coalesced loads, the loads of the target and of its first members issued together, the whole
+// block held in registers as fp64 and two fixed-order reductions (length of the sum, norm of the rounded result).
+// Blocks too long for two wavefronts' registers take the workgroup-per-target kernel.
 // Unit vectors are formed by multiplying with the fp64 reciprocal of the norm (within one fp64 ulp of a
 // division); the result is rounded once, from fp64, to the pool dtype.
 #include "common.h"
@@ -53,23 +53,33 @@ __device__ __forceinline__ int find_base(const int32_t *__restrict__ base, int n
     return lo;
 }
 
-// One wavefront per (target, tensor); CPL = 16-byte chunks per lane.
-template <typename T, int CPL>
-__global__ __launch_bounds__(256) void merge_wave_kernel(PoolDesc pool, WorkDesc w, HeightDesc h, int height)
+// GW wavefronts per (target, tensor) item, 4 / GW items per workgroup; CPT = 16-byte chunks per thread.  With GW = 1
+// there are no barriers at all; with GW = 2 each thread holds half as much and more items are in flight per CU.
+template <typename T, int CPT, int GW>
+__global__ __launch_bounds__(256) void merge_group_kernel(PoolDesc pool, WorkDesc w, HeightDesc h, int height)
 {
     constexpr int PER = Elem<T>::PER16;
-    const int lane = threadIdx.x & 63;
+    constexpr int GT = 64 * GW;          // threads per item
+    constexpr int GPW = 4 / GW;          // items per workgroup
+    __shared__ double red[GPW][GW];
+    const int grp = threadIdx.x / GT;
+    const int tg = threadIdx.x % GT;
+    const int wv = tg >> 6;
     const int chunks = pool.r / PER;
     const int n_items = 2 * w.n_active[height];
-    const int n_waves = gridDim.x * 4;
-    for (int it = blockIdx.x * 4 + (threadIdx.x >> 6); it < n_items; it += n_waves) {
-        const int kv = it & 1;
-        const int packed = w.active[it >> 1];
+    const int stride = gridDim.x * GPW;
+    const int n_iter = (n_items + stride - 1) / stride;      // same for every thread of the workgroup (barriers below)
+    for (int k = 0; k < n_iter; ++k) {
+        const int it = k * stride + blockIdx.x * GPW + grp;
+        const bool live = it < n_items;
+        const int itc = live ? it : 0;
+        const int kv = itc & 1;
+        const int packed = n_items > 0 ? w.active[itc >> 1] : 0;
         const int g = packed / w.l_stride;
         const int ti = packed - g * w.l_stride;
         const int node = find_base(h.l_base, h.n_nodes, ti);
         const int a = w.set_ids[(int64_t)g * w.n + h.l_off[node] + (ti - h.l_base[node])];
-        const int cnt = w.seg_cnt[(int64_t)g * w.l_stride + ti];
+        const int cnt = live ? w.seg_cnt[(int64_t)g * w.l_stride + ti] : 0;
         const int start = w.seg_ptr[(int64_t)g * w.l_stride + ti] - cnt;
         const int32_t *members = w.seg_members + (int64_t)g * w.r_stride + h.r_base[node] + start;
         T *pool_g = (T *)(kv ? pool.v : pool.k) + (int64_t)g * pool.P * pool.r;
@@ -81,11 +91,11 @@ __global__ __launch_bounds__(256) void merge_wave_kernel(PoolDesc pool, WorkDesc
         const uint4 *sa = reinterpret_cast<const uint4 *>(pool_g + (int64_t)a * pool.r);
         const uint4 *s1 = reinterpret_cast<const uint4 *>(pool_g + (int64_t)b1 * pool.r);
         const uint4 *s2 = reinterpret_cast<const uint4 *>(pool_g + (int64_t)b2 * pool.r);
-        uint4 xa[CPL], x1[CPL], x2[CPL];
+        uint4 xa[CPT], x1[CPT], x2[CPT];
 #pragma unroll
-        for (int c = 0; c < CPL; ++c) {
-            const int ch = lane + 64 * c;
-            const bool in = ch < chunks;
+        for (int c = 0; c < CPT; ++c) {
+            const int ch = tg + GT * c;
+            const bool in = live && ch < chunks;
             xa[c] = in ? sa[ch] : make_uint4(0, 0, 0, 0);
             x1[c] = in ? s1[ch] : make_uint4(0, 0, 0, 0);
             x2[c] = in ? s2[ch] : make_uint4(0, 0, 0, 0);
@@ -94,9 +104,9 @@ __global__ __launch_bounds__(256) void merge_wave_kernel(PoolDesc pool, WorkDesc
         const double ia = na == 0.0 ? 0.0 : 1.0 / na;
         const double i1 = (cnt > 0 && n1 != 0.0) ? 1.0 / n1 : 0.0;
         const double i2 = (cnt > 1 && n2 != 0.0) ? 1.0 / n2 : 0.0;
-        double acc[CPL][PER];
+        double acc[CPT][PER];
 #pragma unroll
-        for (int c = 0; c < CPL; ++c) {
+        for (int c = 0; c < CPT; ++c) {
             double ya[PER], y1[PER], y2[PER];
             Elem<T>::widen(xa[c], ya);
             Elem<T>::widen(x1[c], y1);
@@ -111,8 +121,8 @@ __global__ __launch_bounds__(256) void merge_wave_kernel(PoolDesc pool, WorkDesc
             const double ib = nb == 0.0 ? 0.0 : 1.0 / nb;
             const uint4 *sb = reinterpret_cast<const uint4 *>(pool_g + (int64_t)b * pool.r);
 #pragma unroll
-            for (int c = 0; c < CPL; ++c) {
-                const int ch = lane + 64 * c;
+            for (int c = 0; c < CPT; ++c) {
+                const int ch = tg + GT * c;
                 double y[PER];
                 Elem<T>::widen(ch < chunks ? sb[ch] : make_uint4(0, 0, 0, 0), y);
 #pragma unroll
@@ -122,31 +132,53 @@ __global__ __launch_bounds__(256) void merge_wave_kernel(PoolDesc pool, WorkDesc
         }
         double ss = 0.0;
 #pragma unroll
-        for (int c = 0; c < CPL; ++c)
+        for (int c = 0; c < CPT; ++c)
 #pragma unroll
             for (int e = 0; e < PER; ++e)
                 ss = fma(acc[c][e], acc[c][e], ss);
-        const double len = sqrt(wave_sum(ss));
+        ss = wave_sum(ss);
+        if constexpr (GW > 1) {      // fixed-order sum over the item's wavefronts
+            if ((tg & 63) == 0)
+                red[grp][wv] = ss;
+            __syncthreads();
+            ss = 0.0;
+#pragma unroll
+            for (int q = 0; q < GW; ++q)
+                ss += red[grp][q];
+            __syncthreads();
+        }
+        const double len = sqrt(ss);
         const double il = len == 0.0 ? 0.0 : 1.0 / len;
         uint4 *dst = reinterpret_cast<uint4 *>(pool_g + (int64_t)a * pool.r);
         double ss2 = 0.0;
 #pragma unroll
-        for (int c = 0; c < CPL; ++c) {
-            const int ch = lane + 64 * c;
+        for (int c = 0; c < CPT; ++c) {
+            const int ch = tg + GT * c;
             double u[PER], back[PER];
 #pragma unroll
             for (int e = 0; e < PER; ++e)
                 u[e] = acc[c][e] * il;
             const uint4 packed_out = Store16<T>::pack(u, back);
-            if (ch < chunks) {
+            if (live && ch < chunks) {
                 dst[ch] = packed_out;
 #pragma unroll
                 for (int e = 0; e < PER; ++e)
                     ss2 = fma(back[e], back[e], ss2);
             }
         }
-        const double nrm = sqrt(wave_sum(ss2));
-        if (lane == 0) {
+        ss2 = wave_sum(ss2);
+        if constexpr (GW > 1) {
+            if ((tg & 63) == 0)
+                red[grp][wv] = ss2;
+            __syncthreads();
+            ss2 = 0.0;
+#pragma unroll
+            for (int q = 0; q < GW; ++q)
+                ss2 += red[grp][q];
+            __syncthreads();
+        }
+        const double nrm = sqrt(ss2);
+        if (live && tg == 0) {
             norm_g[a] = nrm;
             if (kv == 0)
                 pool.inv_norm_k[(int64_t)g * pool.P + a] = nrm > 0.0 ? (float)(1.0 / nrm) : 0.0f;
@@ -246,19 +278,20 @@ void launch_merge(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const 
     const int cpl = (chunks + 63) / 64;
     if (cpl <= 8) {
         const unsigned wgrid = (unsigned)(want < 256 * 8 ? (want + 1) / 2 + 1 : 256 * 8);
-#define KVF_MERGE_W(T, C) merge_wave_kernel<T, C><<<wgrid, 256, 0, s>>>(pool, w, h, height)
+        // blocks of 4 or 8 chunks per lane are split over two wavefronts (fewer registers, more items in flight)
+#define KVF_MERGE_G(T, C, W) merge_group_kernel<T, C, W><<<wgrid, 256, 0, s>>>(pool, w, h, height)
         if (pool.dtype == KVFUSE_BF16) {
-            if (cpl <= 1) KVF_MERGE_W(bf16_t, 1);
-            else if (cpl <= 2) KVF_MERGE_W(bf16_t, 2);
-            else if (cpl <= 4) KVF_MERGE_W(bf16_t, 4);
-            else KVF_MERGE_W(bf16_t, 8);
+            if (cpl <= 1) KVF_MERGE_G(bf16_t, 1, 1);
+            else if (cpl <= 2) KVF_MERGE_G(bf16_t, 2, 1);
+            else if (cpl <= 4) KVF_MERGE_G(bf16_t, 2, 2);
+            else KVF_MERGE_G(bf16_t, 4, 2);
         } else {
-            if (cpl <= 1) KVF_MERGE_W(float, 1);
-            else if (cpl <= 2) KVF_MERGE_W(float, 2);
-            else if (cpl <= 4) KVF_MERGE_W(float, 4);
-            else KVF_MERGE_W(float, 8);
+            if (cpl <= 1) KVF_MERGE_G(float, 1, 1);
+            else if (cpl <= 2) KVF_MERGE_G(float, 2, 1);
+            else if (cpl <= 4) KVF_MERGE_G(float, 2, 2);
+            else KVF_MERGE_G(float, 4, 2);
         }
-#undef KVF_MERGE_W
+#undef KVF_MERGE_G
         return;
     }
 #define KVF_MERGE(T, C) merge_kernel<T, C><<<grid, 256, 0, s>>>(pool, w, h, height)
