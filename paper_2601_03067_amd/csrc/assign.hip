@@ -1,12 +1,13 @@
 // a3: thresholded arg-max assignment (Algorithm 1: "indices where sim(row) > thr", read as one target per right
 // block: the left row with the largest cosine, lowest row on exact ties, strict '>').
 //
-// Two kernels per height:
-//   decide   one wavefront per right block.  The MFMA screen has left a short candidate list per column.  A column
+// Three kernels per height:
+//   screen   one thread per right block.  The MFMA screen has left a short candidate list per column.  A column
 //            with no candidate cannot fuse.  A column whose best candidate is clear of the threshold and of every
-//            other candidate by more than 2*band is decided from the screen.  Everything else is re-evaluated in
-//            fp64 on the stored values (wave-wide dot products in a fixed lane order, so identical blocks give
-//            identical cosines and the lowest-row rule applies to them exactly as on a CPU).
+//            other candidate by more than 2*band is decided from the screen.  Everything else goes to a list.
+//   refine   one wavefront per listed column: re-evaluation in fp64 on the stored values (wave-wide dot products
+//            in a fixed lane order, so identical blocks give identical cosines and the lowest-row rule applies to
+//            them exactly as on a CPU).
 //   finalize one workgroup per (group, node): members grouped by target in ascending right index (CSR), evicted
 //            blocks entered in the remap table, targets to rebuild appended to the merge work list, and the node's
 //            surviving set cat(left, non-fused right in order) compacted in place for the parent node.
@@ -48,18 +49,21 @@ __device__ __forceinline__ double cosine_f64(const T *__restrict__ pool_g, int r
     return (na == 0.0 || nb == 0.0) ? 0.0 : dot / (na * nb);
 }
 
-template <typename T>
-__global__ __launch_bounds__(256) void assign_decide_kernel(PoolDesc pool, WorkDesc w, HeightDesc h, int height, double thr,
-                                                            double band)
+__global__ void assign_reset_kernel(WorkDesc w, int height)
 {
-    if (blockIdx.x == 0 && threadIdx.x == 0)
-        w.n_active[height] = 0;   // the finalize kernel, next on the stream, appends to this list
-    const int lane = threadIdx.x & 63;
-    const int64_t wv = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (wv >= (int64_t)w.G * h.total_r_cap)
+    w.n_active[height] = 0;   // the finalize kernel appends to this list
+    w.n_refine[height] = 0;   // the screen kernel appends to this one
+}
+
+// One THREAD per right block: everything the screen settles on its own (no candidate; or one candidate clear of the
+// threshold and of all others by more than 2 * band).  Columns it cannot settle go to the re-check list.
+__global__ __launch_bounds__(256) void assign_screen_kernel(WorkDesc w, HeightDesc h, int height, double thr, double band)
+{
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= (int64_t)w.G * h.total_r_cap)
         return;
-    const int g = (int)(wv / h.total_r_cap);
-    const int c = (int)(wv - (int64_t)g * h.total_r_cap);
+    const int g = (int)(id / h.total_r_cap);
+    const int c = (int)(id - (int64_t)g * h.total_r_cap);
     const int node = find_node(h.r_base, h.n_nodes, c);
     const int j = c - h.r_base[node];
     const int ml = w.set_cnt[(int64_t)g * w.n_slots + h.l_slot[node]];
@@ -67,33 +71,68 @@ __global__ __launch_bounds__(256) void assign_decide_kernel(PoolDesc pool, WorkD
     if (j >= mr)
         return;
     const int64_t cidx = (int64_t)g * w.r_stride + c;
-    const int32_t *l_ids = w.set_ids + (int64_t)g * w.n + h.l_off[node];
-    const int b = w.set_ids[(int64_t)g * w.n + h.r_off[node] + j];
-    const T *pool_g = (const T *)pool.k + (int64_t)g * pool.P * pool.r;
-    const double *norm_g = pool.norm_k + (int64_t)g * pool.P;
-
     const int cnt = ml > 0 ? w.cand_cnt[cidx] : 0;
     int result = -1;
-    int near = 0, refined = 0, overflow = 0;
-    if (cnt > 0 && cnt <= w.cand_cap) {
-        int ci = 0x7FFFFFFF;
-        float cv = -INFINITY;
-        if (lane < cnt) {
-            ci = w.cand_idx[cidx * w.cand_cap + lane];
-            cv = w.cand_val[cidx * w.cand_cap + lane];
+    bool recheck = cnt > w.cand_cap;
+    if (cnt > 0 && !recheck) {
+        float smax = -INFINITY;
+        int imax = -1;
+        for (int k = 0; k < cnt; ++k) {
+            const float cv = w.cand_val[cidx * w.cand_cap + k];
+            if (cv > smax) {
+                smax = cv;
+                imax = w.cand_idx[cidx * w.cand_cap + k];
+            }
         }
-        float smax = cv;
+        int contenders = 0;
+        for (int k = 0; k < cnt; ++k)
+            contenders += (double)w.cand_val[cidx * w.cand_cap + k] >= (double)smax - 2.0 * band;
+        if (contenders == 1 && (double)smax > thr + 2.0 * band)
+            result = imax;
+        else
+            recheck = true;
+    }
+    if (recheck)
+        w.refine[atomicAdd(&w.n_refine[height], 1)] = (int32_t)cidx;
+    else
+        w.assign[cidx] = result;
+}
+
+// One WAVEFRONT per listed column: fp64 cosines of the contenders (or of the whole column when the candidate list
+// overflowed), strict '>' against thr, lowest row on exact ties.
+template <typename T>
+__global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkDesc w, HeightDesc h, int height, double thr,
+                                                            double band)
+{
+    const int lane = threadIdx.x & 63;
+    const int n_items = w.n_refine[height];
+    const int n_waves = gridDim.x * 4;
+    for (int it = blockIdx.x * 4 + (threadIdx.x >> 6); it < n_items; it += n_waves) {
+        const int64_t cidx = w.refine[it];
+        const int g = (int)(cidx / w.r_stride);
+        const int c = (int)(cidx - (int64_t)g * w.r_stride);
+        const int node = find_node(h.r_base, h.n_nodes, c);
+        const int j = c - h.r_base[node];
+        const int ml = w.set_cnt[(int64_t)g * w.n_slots + h.l_slot[node]];
+        const int32_t *l_ids = w.set_ids + (int64_t)g * w.n + h.l_off[node];
+        const int b = w.set_ids[(int64_t)g * w.n + h.r_off[node] + j];
+        const T *pool_g = (const T *)pool.k + (int64_t)g * pool.P * pool.r;
+        const double *norm_g = pool.norm_k + (int64_t)g * pool.P;
+        const int cnt = w.cand_cnt[cidx];
+        double bv = -INFINITY;
+        int bi = 0x7FFFFFFF;
+        if (cnt <= w.cand_cap) {
+            int ci = 0x7FFFFFFF;
+            float cv = -INFINITY;
+            if (lane < cnt) {
+                ci = w.cand_idx[cidx * w.cand_cap + lane];
+                cv = w.cand_val[cidx * w.cand_cap + lane];
+            }
+            float smax = cv;
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1)
-            smax = fmaxf(smax, __shfl_xor(smax, off, 64));
-        const bool contender = lane < cnt && (double)cv >= (double)smax - 2.0 * band;
-        unsigned long long mask = __ballot(contender);
-        if (__popcll(mask) == 1 && (double)smax > thr + 2.0 * band) {
-            result = __shfl(ci, __ffsll((long long)mask) - 1, 64);
-        } else {
-            refined = 1;
-            double bv = -INFINITY;
-            int bi = 0x7FFFFFFF;
+            for (int off = 32; off >= 1; off >>= 1)
+                smax = fmaxf(smax, __shfl_xor(smax, off, 64));
+            unsigned long long mask = __ballot(lane < cnt && (double)cv >= (double)smax - 2.0 * band);
             while (mask) {
                 const int src = __ffsll((long long)mask) - 1;
                 mask &= mask - 1;
@@ -104,36 +143,25 @@ __global__ __launch_bounds__(256) void assign_decide_kernel(PoolDesc pool, WorkD
                     bi = i;
                 }
             }
-            if (bv > thr)
-                result = bi;
-            near = fabs(bv - thr) <= band;
-        }
-    } else if (cnt > w.cand_cap) {
-        // more screen candidates than slots: rescan the whole column in fp64 (ascending rows, strict '>')
-        overflow = 1;
-        refined = 1;
-        double bv = -INFINITY;
-        int bi = -1;
-        for (int i = 0; i < ml; ++i) {
-            const double cs = cosine_f64<T>(pool_g, pool.r, norm_g, l_ids[i], b, lane);
-            if (cs > bv) {
-                bv = cs;
-                bi = i;
+        } else {
+            // more screen candidates than slots: rescan the whole column (ascending rows, strict '>')
+            for (int i = 0; i < ml; ++i) {
+                const double cs = cosine_f64<T>(pool_g, pool.r, norm_g, l_ids[i], b, lane);
+                if (cs > bv) {
+                    bv = cs;
+                    bi = i;
+                }
             }
         }
-        if (bv > thr)
-            result = bi;
-        near = fabs(bv - thr) <= band;
-    }
-    if (lane == 0) {
-        w.assign[cidx] = result;
-        int32_t *cn = w.counters + (int64_t)g * 8;
-        if (near)
-            atomicAdd(&cn[1], 1);
-        if (refined)
+        if (lane == 0) {
+            w.assign[cidx] = bv > thr ? bi : -1;
+            int32_t *cn = w.counters + (int64_t)g * 8;
+            if (fabs(bv - thr) <= band)
+                atomicAdd(&cn[1], 1);
             atomicAdd(&cn[2], 1);
-        if (overflow)
-            atomicAdd(&cn[3], 1);
+            if (cnt > w.cand_cap)
+                atomicAdd(&cn[3], 1);
+        }
     }
 }
 
@@ -272,13 +300,15 @@ __global__ __launch_bounds__(256) void assign_finalize_kernel(int P, TableDesc t
 void launch_assign(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, const WorkDesc &w, const HeightDesc &h,
                    int height, double thr, double band)
 {
-    const int64_t waves = (int64_t)w.G * h.total_r_cap;
-    if (waves > 0) {
-        const unsigned grid = (unsigned)((waves + 3) / 4);
+    const int64_t cols = (int64_t)w.G * h.total_r_cap;
+    assign_reset_kernel<<<1, 1, 0, s>>>(w, height);
+    if (cols > 0) {
+        assign_screen_kernel<<<(unsigned)((cols + 255) / 256), 256, 0, s>>>(w, h, height, thr, band);
+        const unsigned rgrid = (unsigned)(cols < 4096 ? (cols + 3) / 4 : 1024);
         if (pool.dtype == KVFUSE_BF16)
-            assign_decide_kernel<bf16_t><<<grid, 256, 0, s>>>(pool, w, h, height, thr, band);
+            assign_refine_kernel<bf16_t><<<rgrid, 256, 0, s>>>(pool, w, h, height, thr, band);
         else
-            assign_decide_kernel<float><<<grid, 256, 0, s>>>(pool, w, h, height, thr, band);
+            assign_refine_kernel<float><<<rgrid, 256, 0, s>>>(pool, w, h, height, thr, band);
     }
     if (w.G * h.n_nodes > 0)
         assign_finalize_kernel<<<(unsigned)(w.G * h.n_nodes), 256, 0, s>>>(pool.P, tab, w, h, height);

@@ -66,6 +66,8 @@ struct WorkDesc {
     int32_t *seg_members;// [G][r_stride]
     int32_t *active;     // [G * l_stride] packed g * l_stride + target index
     int32_t *n_active;   // [max_heights]
+    int32_t *refine;     // [G * r_stride] columns (g * r_stride + c) that need the fp64 re-check
+    int32_t *n_refine;   // [max_heights]
     int32_t *counters;   // [G][8]: 0 fused, 1 near-threshold, 2 refined, 3 candidate overflow, 4 invalid ids
 };
 

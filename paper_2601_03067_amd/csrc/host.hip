@@ -236,6 +236,8 @@ static void carve(Carver &cv, int G, int n, int n_slots, int max_r, int max_l, i
     w.seg_members = cv.take<int32_t>(R);
     w.active = cv.take<int32_t>(L);
     w.n_active = cv.take<int32_t>(kMaxHeights);
+    w.refine = cv.take<int32_t>(R);
+    w.n_refine = cv.take<int32_t>(kMaxHeights);
     w.counters = cv.take<int32_t>((size_t)G * 8);
     slot_init = cv.take<int32_t>(n_slots);
     for (HostHeight &h : hs) {
