@@ -231,9 +231,11 @@ __global__ __launch_bounds__(256) void assign_finalize_kernel(int P, TableDesc t
             lds_base = n_act > 0 ? atomicAdd(&w.n_active[height], n_act) : 0;
         __syncthreads();
         if (i < ml) {
-            seg_ptr[i] = (int)(run + (pre & 0xFFFFFFFFFFll));
+            const int start = (int)(run + (pre & 0xFFFFFFFFFFll));
+            seg_ptr[i] = start;
             if (cnt > 0)
-                w.active[lds_base + (int)(pre >> 40)] = g * w.l_stride + h.l_base[node] + i;
+                w.active[lds_base + (int)(pre >> 40)] =
+                    make_int4(g, l_ids[i], cnt, (int)((int64_t)g * w.r_stride + h.r_base[node] + start));
         }
         run += total & 0xFFFFFFFFFFll;
         __syncthreads();

@@ -74,14 +74,11 @@ __global__ __launch_bounds__(256) void merge_group_kernel(PoolDesc pool, WorkDes
         const bool live = it < n_items;
         const int itc = live ? it : 0;
         const int kv = itc & 1;
-        const int packed = n_items > 0 ? w.active[itc >> 1] : 0;
-        const int g = packed / w.l_stride;
-        const int ti = packed - g * w.l_stride;
-        const int node = find_base(h.l_base, h.n_nodes, ti);
-        const int a = w.set_ids[(int64_t)g * w.n + h.l_off[node] + (ti - h.l_base[node])];
-        const int cnt = live ? w.seg_cnt[(int64_t)g * w.l_stride + ti] : 0;
-        const int start = w.seg_ptr[(int64_t)g * w.l_stride + ti] - cnt;
-        const int32_t *members = w.seg_members + (int64_t)g * w.r_stride + h.r_base[node] + start;
+        const int4 rec = n_items > 0 ? w.active[itc >> 1] : make_int4(0, 0, 0, 0);
+        const int g = rec.x;
+        const int a = rec.y;
+        const int cnt = live ? rec.z : 0;
+        const int32_t *members = w.seg_members + rec.w;
         T *pool_g = (T *)(kv ? pool.v : pool.k) + (int64_t)g * pool.P * pool.r;
         double *norm_g = (kv ? pool.norm_v : pool.norm_k) + (int64_t)g * pool.P;
 
@@ -196,15 +193,11 @@ __global__ __launch_bounds__(256) void merge_kernel(PoolDesc pool, WorkDesc w, H
     const int chunks = pool.r / PER;
     const int n_act = w.n_active[height];
     for (int t = blockIdx.x; t < n_act; t += gridDim.x) {
-        const int packed = w.active[t];
-        const int g = packed / w.l_stride;
-        const int ti = packed - g * w.l_stride;
-        const int node = find_base(h.l_base, h.n_nodes, ti);
-        const int i = ti - h.l_base[node];
-        const int a = w.set_ids[(int64_t)g * w.n + h.l_off[node] + i];
-        const int cnt = w.seg_cnt[(int64_t)g * w.l_stride + ti];
-        const int start = w.seg_ptr[(int64_t)g * w.l_stride + ti] - cnt;
-        const int32_t *members = w.seg_members + (int64_t)g * w.r_stride + h.r_base[node] + start;
+        const int4 rec = w.active[t];
+        const int g = rec.x;
+        const int a = rec.y;
+        const int cnt = rec.z;
+        const int32_t *members = w.seg_members + rec.w;
 
         for (int kv = 0; kv < 2; ++kv) {
             T *pool_g = (T *)(kv ? pool.v : pool.k) + (int64_t)g * pool.P * pool.r;
