@@ -368,6 +368,359 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN * TM * TN >= 64 ? 1 : 2)) vo
     }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Big tile (256 x 256, 8 wavefronts of 64 x 128): LDS ring fed by direct global -> LDS loads.
+//
+// K is walked in 64-byte slices per row.  A ring of four stages (each 256 left + 256 right rows x 64 bytes = 32 KB)
+// is filled by global_load_lds_dwordx4: the data never passes through registers, so two slices can be in flight
+// while one is being multiplied and one is ready, with no staging registers at all.  Every wavefront issues four
+// such loads per slice (1 KB each: 16 rows x 64 bytes).  A load writes LDS at (wave-uniform base + lane * 16), so
+// the XOR swizzle that keeps the fragment reads conflict-free is applied on the global side: lane L covers row
+// L / 4 and fetches logical 16-byte chunk (L & 3) ^ ((row >> 2) & 3) of that row's slice.
+//
+// Fragment reads are ds_read_b128 in inline assembly.  The compiler cannot tell that they never touch a stage
+// that is still being filled and would otherwise wait for every outstanding global -> LDS load before each LDS
+// read.  Each read's destination registers are handed to the following wait statement as in/out operands, which
+// is what orders the MFMAs behind the wait.  Fragments are double buffered (one set per 32-byte half slice), and
+// the first half of slice j + 1 is read before the barrier that ends iteration j; that is legal because the loads
+// of slice j + 1 were completed before the previous barrier.
+//
+// Iteration j (slice j in stage j & 3):   read set1 <- slice j, second half;  8 MFMA on set0 + 2 loads of slice
+// j + 3;  wait set1;  read set0 <- slice j + 1, first half;  8 MFMA on set1 + 2 loads;  wait until only this
+// iteration's 4 loads are outstanding;  barrier.  The stage written in iteration j held slice j - 1, which every
+// wavefront finished reading before the previous barrier.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+template <typename T> struct MmaV;
+template <> struct MmaV<bf16_t> {
+    __device__ static __forceinline__ floatx16 run(const u32x4 a, const u32x4 b, floatx16 c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+};
+template <> struct MmaV<float> {
+    __device__ static __forceinline__ floatx16 run(const u32x4 a, const u32x4 b, floatx16 c)
+    {
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
+        return c;
+    }
+};
+
+constexpr int kRingRowTiles = 4;   // most row tiles of one work item (the host's tile table keeps to it)
+
+template <typename T, bool DENSE>
+__global__ __launch_bounds__(512, 1) void similarity_ring_kernel(
+    SimArgs A, const char *__restrict__ kpool, const float *__restrict__ inv_norm, const int32_t *__restrict__ set_ids,
+    const int32_t *__restrict__ set_cnt, const int32_t *__restrict__ item_node, const int32_t *__restrict__ item_col0,
+    const int32_t *__restrict__ item_row0, const int32_t *__restrict__ item_rows, const int32_t *__restrict__ l_off,
+    const int32_t *__restrict__ r_off, const int32_t *__restrict__ l_slot, const int32_t *__restrict__ r_slot,
+    const int32_t *__restrict__ r_base, const int32_t *__restrict__ r_cap, const int64_t *__restrict__ s_base,
+    unsigned long long *__restrict__ best_packed, int32_t *__restrict__ cand_cnt, int32_t *__restrict__ cand_idx,
+    float *__restrict__ cand_val, float *__restrict__ dense_s)
+{
+    constexpr int WN = 2, TM = 2, TN = 4, NT = 512, BM = 256, BN = 256;
+    constexpr int STAGE = (BM + BN) * 64;
+    constexpr int B_REGION = BM * 64;
+    constexpr int RT = kRingRowTiles;
+
+    __shared__ __attribute__((aligned(1024))) char ring[4 * STAGE];
+    __shared__ float lds_invl[RT * BM];      // inverse norms of all left rows of the item; NaN past the end
+    __shared__ float lds_invr[BN];
+    __shared__ float lds_tcol[BN];
+    __shared__ uint32_t lds_bkey[TN][NT];
+    __shared__ int lds_brt[TN][NT];
+    constexpr int MAXC = 512;
+    __shared__ int lds_ncand;
+    __shared__ int lds_cand_row[MAXC];
+    __shared__ int lds_cand_col[MAXC];
+    __shared__ float lds_cand_val[MAXC];
+
+    const int per_xcd = gridDim.x >> 3;
+    const long long v = (long long)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (v >= (long long)A.G * A.n_items)
+        return;
+    const int g = (int)(v / A.n_items);
+    const int item = (int)(v - (long long)g * A.n_items);
+    const int node = item_node[item];
+    const int col0 = item_col0[item];
+    const int row0 = item_row0[item];
+    const int ml = set_cnt[(int64_t)g * A.n_slots + l_slot[node]];
+    const int mr = set_cnt[(int64_t)g * A.n_slots + r_slot[node]];
+    if (col0 >= mr || row0 >= ml)
+        return;
+    const int row_end = min(ml, row0 + min(item_rows[item], RT * BM));
+    const int32_t *__restrict__ l_ids = set_ids + (int64_t)g * A.n + l_off[node];
+    const int32_t *__restrict__ r_ids = set_ids + (int64_t)g * A.n + r_off[node];
+    const int64_t cbase = (int64_t)g * A.r_stride + r_base[node];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int half = lane >> 5;
+    const int64_t row_bytes = A.row_bytes;
+    const int nk = A.row_bytes >> 6;                          // 64-byte slices per row
+    const int n_rt = (row_end - row0 + BM - 1) / BM;
+    const char *__restrict__ kg = kpool + (int64_t)g * A.P * row_bytes;
+    const float *__restrict__ inv_g = inv_norm + (int64_t)g * A.P;
+
+    // ---- global -> LDS loaders: this lane's row within a 128-row half tile and its (swizzled) chunk
+    const int ld_row = wave * 16 + (lane >> 2);
+    const int ld_chunk = ((lane & 3) ^ ((lane >> 4) & 3)) * 16;
+#define KVF_LID(t, i) l_ids[min(row0 + (t) * BM + (i) * 128 + ld_row, row_end - 1)]
+    const int ia00 = KVF_LID(0, 0), ia01 = KVF_LID(0, 1);
+    const int ia10 = KVF_LID(1, 0), ia11 = KVF_LID(1, 1);
+    const int ia20 = KVF_LID(2, 0), ia21 = KVF_LID(2, 1);
+    const int ia30 = KVF_LID(3, 0), ia31 = KVF_LID(3, 1);
+#undef KVF_LID
+    const char *pa0 = kg + (int64_t)ia00 * row_bytes + ld_chunk;
+    const char *pa1 = kg + (int64_t)ia01 * row_bytes + ld_chunk;
+    const char *pb0 = kg + (int64_t)r_ids[min(col0 + ld_row, mr - 1)] * row_bytes + ld_chunk;
+    const char *pb1 = kg + (int64_t)r_ids[min(col0 + 128 + ld_row, mr - 1)] * row_bytes + ld_chunk;
+    const int dma_a0 = wave * 16 * 64;                          // LDS byte offsets of this wavefront's four 1 KB pieces
+    const int dma_a1 = dma_a0 + 128 * 64;
+    const int dma_b0 = B_REGION + dma_a0;
+    const int dma_b1 = B_REGION + dma_a1;
+#define KVF_DMA(PTR, OFF)                                                                                          \
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(PTR),                        \
+                                     (__attribute__((address_space(3))) void *)(ring + (OFF)), 16, 0, 0)
+
+    // ---- fragment read addresses (LDS byte addresses)
+    const uint32_t ring_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)ring;
+    const int l31 = lane & 31;
+    const uint32_t frag = (uint32_t)(l31 * 64 + ((half ^ ((l31 >> 2) & 3)) * 16));   // first half; second half = ^ 32
+    const uint32_t fa_lo = ring_addr + wm * (TM * 32 * 64) + frag;
+    const uint32_t fb_lo = ring_addr + B_REGION + wn * (TN * 32 * 64) + frag;
+    const uint32_t fa_hi = fa_lo ^ 32u;
+    const uint32_t fb_hi = fb_lo ^ 32u;
+#define KVF_DS_READ(DST, ADDR, IMM) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(DST) : "v"(ADDR), "n"(IMM))
+#define KVF_WAIT_SET(S)                                                                                            \
+    asm volatile("s_waitcnt lgkmcnt(0)"                                                                           \
+                 : "+v"(fa0_##S), "+v"(fa1_##S), "+v"(fb0_##S), "+v"(fb1_##S), "+v"(fb2_##S), "+v"(fb3_##S))
+    // The dense-output instantiation (tests only) is short of registers in its epilogue; it waits for each set
+    // right away so that no register is ever moved or spilled while its data is still on the way.
+#define KVF_READ_SET(S, ADDR_A, ADDR_B)          \
+    KVF_DS_READ(fa0_##S, ADDR_A, 0);             \
+    KVF_DS_READ(fb0_##S, ADDR_B, 0);             \
+    KVF_DS_READ(fa1_##S, ADDR_A, 2048);          \
+    KVF_DS_READ(fb1_##S, ADDR_B, 2048);          \
+    KVF_DS_READ(fb2_##S, ADDR_B, 4096);          \
+    KVF_DS_READ(fb3_##S, ADDR_B, 6144);          \
+    if constexpr (DENSE) { KVF_WAIT_SET(S); }
+#define KVF_MMA(S, MT, NTI) acc[MT][NTI] = MmaV<T>::run(fa##MT##_##S, fb##NTI##_##S, acc[MT][NTI]);
+    u32x4 fa0_0, fa1_0, fb0_0, fb1_0, fb2_0, fb3_0;
+    u32x4 fa0_1, fa1_1, fb0_1, fb1_1, fb2_1, fb3_1;
+
+    // ---- epilogue state
+    constexpr uint32_t CODE_MASK = TM * 16 - 1;
+    for (int x = tid; x < BN; x += NT) {
+        const int col = col0 + x;
+        const float ir = col < mr ? inv_g[r_ids[col]] : 0.0f;
+        lds_invr[x] = ir;
+        lds_tcol[x] = col >= mr ? INFINITY : (ir > 0.0f ? A.thr_floor / ir : (A.thr_floor < 0.0f ? -INFINITY : INFINITY));
+    }
+    for (int x = tid; x < RT * BM; x += NT) {
+        const int row = row0 + x;
+        lds_invl[x] = row < row_end ? inv_g[l_ids[row]] : __uint_as_float(0x7FC00000u);
+    }
+#pragma unroll
+    for (int nt = 0; nt < TN; ++nt) {
+        lds_bkey[nt][tid] = 0u;
+        lds_brt[nt][tid] = 0;
+    }
+    if (tid == 0)
+        lds_ncand = 0;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < TN; ++nt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                acc[mt][nt][e] = 0.0f;
+
+    // ---- prologue: slices 0, 1, 2 on their way; 0 and 1 landed and visible before the first iteration
+    int pf_kt = 0, pf_rt = 0;
+#define KVF_DMA_ADVANCE()                                                                                          \
+    do {                                                                                                           \
+        pa0 += 64; pa1 += 64; pb0 += 64; pb1 += 64;                                                                \
+        if (++pf_kt == nk) {                                                                                       \
+            pf_kt = 0;                                                                                             \
+            ++pf_rt;                                                                                               \
+            const int na0 = pf_rt == 1 ? ia10 : (pf_rt == 2 ? ia20 : ia30);                                        \
+            const int na1 = pf_rt == 1 ? ia11 : (pf_rt == 2 ? ia21 : ia31);                                        \
+            pa0 = kg + (int64_t)na0 * row_bytes + ld_chunk;                                                        \
+            pa1 = kg + (int64_t)na1 * row_bytes + ld_chunk;                                                        \
+            pb0 -= row_bytes;                                                                                      \
+            pb1 -= row_bytes;                                                                                      \
+        }                                                                                                          \
+    } while (0)
+#pragma unroll 1
+    for (int p = 0; p < 3; ++p) {
+        const int so = p * STAGE;
+        KVF_DMA(pa0, so + dma_a0);
+        KVF_DMA(pa1, so + dma_a1);
+        KVF_DMA(pb0, so + dma_b0);
+        KVF_DMA(pb1, so + dma_b1);
+        KVF_DMA_ADVANCE();
+    }
+    asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    __syncthreads();
+    KVF_READ_SET(0, fa_lo, fb_lo)
+
+    int it = 0;
+    for (int rt = 0; rt < n_rt; ++rt) {
+#pragma unroll 1
+        for (int kt = 0; kt < nk; ++kt, ++it) {
+            const uint32_t cur = (uint32_t)(it & 3) * STAGE;
+            const uint32_t nxt = (uint32_t)((it + 1) & 3) * STAGE;
+            const int dst = ((it + 3) & 3) * STAGE;
+            const uint32_t ra1 = fa_hi + cur, rb1 = fb_hi + cur, ra0 = fa_lo + nxt, rb0 = fb_lo + nxt;
+            KVF_WAIT_SET(0);
+            KVF_READ_SET(1, ra1, rb1)
+            __builtin_amdgcn_sched_barrier(0);
+            KVF_MMA(0, 0, 0) KVF_MMA(0, 1, 0)
+            __builtin_amdgcn_sched_barrier(0);
+            KVF_DMA(pa0, dst + dma_a0);
+            __builtin_amdgcn_sched_barrier(0);
+            KVF_MMA(0, 0, 1) KVF_MMA(0, 1, 1) KVF_MMA(0, 0, 2) KVF_MMA(0, 1, 2)
+            __builtin_amdgcn_sched_barrier(0);
+            KVF_DMA(pa1, dst + dma_a1);
+            __builtin_amdgcn_sched_barrier(0);
+            KVF_MMA(0, 0, 3) KVF_MMA(0, 1, 3)
+            __builtin_amdgcn_sched_barrier(0);
+            KVF_WAIT_SET(1);
+            KVF_READ_SET(0, ra0, rb0)
+            __builtin_amdgcn_sched_barrier(0);
+            KVF_MMA(1, 0, 0) KVF_MMA(1, 1, 0)
+            __builtin_amdgcn_sched_barrier(0);
+            KVF_DMA(pb0, dst + dma_b0);
+            __builtin_amdgcn_sched_barrier(0);
+            KVF_MMA(1, 0, 1) KVF_MMA(1, 1, 1) KVF_MMA(1, 0, 2) KVF_MMA(1, 1, 2)
+            __builtin_amdgcn_sched_barrier(0);
+            KVF_DMA(pb1, dst + dma_b1);
+            __builtin_amdgcn_sched_barrier(0);
+            KVF_MMA(1, 0, 3) KVF_MMA(1, 1, 3)
+            __builtin_amdgcn_sched_barrier(0);
+            KVF_DMA_ADVANCE();
+            // all but this iteration's four loads have landed (slice it + 2), then everyone may read it
+            asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");
+        }
+        // the prefetched fragments of the next row tile's first slice must be in their registers before anything
+        // else may touch them
+        KVF_WAIT_SET(0);
+
+        // ---- epilogue of row tile rt
+        {
+            uint32_t kmax[TN];
+            float tcol[TN];
+#pragma unroll
+            for (int nt = 0; nt < TN; ++nt) {
+                kmax[nt] = 0u;
+                tcol[nt] = lds_tcol[(wn * TN + nt) * 32 + (lane & 31)];
+            }
+#pragma unroll
+            for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+                for (int eg = 0; eg < 4; ++eg) {
+                    const int rl0 = (wm * TM + mt) * 32 + eg * 8 + half * 4;
+                    const float4 il4 = *reinterpret_cast<const float4 *>(&lds_invl[rt * BM + rl0]);
+                    const float il[4] = {il4.x, il4.y, il4.z, il4.w};
+#pragma unroll
+                    for (int nt = 0; nt < TN; ++nt) {
+                        float t[4];
+                        bool hit = false;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            t[q] = acc[mt][nt][eg * 4 + q] * il[q];
+                            hit |= t[q] > tcol[nt];
+                            const uint32_t key = (__float_as_uint(fmaxf(t[q], 0.0f)) & ~CODE_MASK) |
+                                                 (CODE_MASK - (uint32_t)(mt * 16 + eg * 4 + q));
+                            kmax[nt] = max(kmax[nt], key);
+                        }
+                        if (hit) {      // rare: an entry clears the candidate floor
+                            const int cl = (wn * TN + nt) * 32 + (lane & 31);
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                if (t[q] > tcol[nt]) {
+                                    const int row = row0 + rt * BM + rl0 + q;
+                                    const float sv = t[q] * lds_invr[cl];
+                                    const int k = atomicAdd(&lds_ncand, 1);
+                                    if (k < MAXC) {
+                                        lds_cand_row[k] = row;
+                                        lds_cand_col[k] = cl;
+                                        lds_cand_val[k] = sv;
+                                    } else {
+                                        emit_candidate(cand_cnt, cand_idx, cand_val, cbase + col0 + cl, A.cand_cap, row, sv);
+                                    }
+                                }
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            if constexpr (DENSE) {
+#pragma unroll
+                for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < TN; ++nt)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            const int rl = (wm * TM + mt) * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
+                            const int row = row0 + rt * BM + rl;
+                            const int col = col0 + (wn * TN + nt) * 32 + (lane & 31);
+                            if (row < row_end && col < mr)
+                                dense_s[(int64_t)g * A.total_s + s_base[node] + (int64_t)row * r_cap[node] + col] =
+                                    acc[mt][nt][e] * lds_invl[rt * BM + rl] * lds_invr[(wn * TN + nt) * 32 + (lane & 31)];
+                        }
+            }
+#pragma unroll
+            for (int nt = 0; nt < TN; ++nt) {
+                if (kmax[nt] > lds_bkey[nt][tid]) {
+                    lds_bkey[nt][tid] = kmax[nt];
+                    lds_brt[nt][tid] = rt;
+                }
+#pragma unroll
+                for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        acc[mt][nt][e] = 0.0f;
+            }
+        }
+    }
+    // loads past the last slice are still on their way into the ring; nothing may leave before they land
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    {
+        const int nc = min(lds_ncand, MAXC);
+        for (int k = tid; k < nc; k += NT)
+            emit_candidate(cand_cnt, cand_idx, cand_val, cbase + col0 + lds_cand_col[k], A.cand_cap, lds_cand_row[k],
+                           lds_cand_val[k]);
+    }
+#pragma unroll
+    for (int nt = 0; nt < TN; ++nt) {
+        const int col = col0 + (wn * TN + nt) * 32 + (lane & 31);
+        const uint32_t bkey = lds_bkey[nt][tid];
+        const int code = (int)(CODE_MASK - (bkey & CODE_MASK));
+        const int row = min(row_end - 1, row0 + lds_brt[nt][tid] * BM + (wm * TM + (code >> 4)) * 32 + ((code & 15) >> 2) * 8 + half * 4 + (code & 3));
+        unsigned long long pk = bkey ? pack_best(__uint_as_float(bkey & ~CODE_MASK) * lds_invr[(wn * TN + nt) * 32 + (lane & 31)], row) : 0ull;
+        const unsigned long long other = __shfl_xor(pk, 32, 64);
+        pk = other > pk ? other : pk;
+        if (half == 0 && col < mr && pk)
+            atomicMax(&best_packed[cbase + col], pk);
+    }
+#undef KVF_DMA
+#undef KVF_DS_READ
+#undef KVF_READ_SET
+#undef KVF_WAIT_SET
+#undef KVF_MMA
+#undef KVF_DMA_ADVANCE
+}
+
 __global__ void similarity_clear_kernel(unsigned long long *__restrict__ best_packed, int32_t *__restrict__ cand_cnt,
                                         int64_t total)
 {
@@ -403,10 +756,31 @@ static void launch_cfg(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, c
 #undef KVF_SIM_LAUNCH
 }
 
-// Big tile: 256 x 256 as 4 x 2 wavefronts of 64 x 128 each (two wavefronts per SIMD, 128 accumulators each).
-#ifndef KVF_BIG_CFG
-#define KVF_BIG_CFG 4, 2, 2, 4
-#endif
+template <typename T>
+static void launch_ring(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const HeightDesc &h, const TileTable &tt,
+                        float thr_floor, float *dense_s)
+{
+    const int64_t total = (int64_t)w.G * tt.n_items;
+    if (total <= 0)
+        return;
+    SimArgs A;
+    A.G = w.G; A.n = w.n; A.n_slots = w.n_slots; A.r_stride = w.r_stride; A.cand_cap = w.cand_cap; A.P = pool.P;
+    A.n_items = tt.n_items;
+    A.row_bytes = pool.r * (int)sizeof(T);
+    A.thr_floor = thr_floor;
+    A.total_s = h.total_s;
+    const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
+#define KVF_SIM_LAUNCH(D)                                                                                              \
+    similarity_ring_kernel<T, D><<<grid, 512, 0, s>>>(                                                                 \
+        A, (const char *)pool.k, pool.inv_norm_k, w.set_ids, w.set_cnt, tt.node, tt.col0, tt.row0, tt.rows, h.l_off, h.r_off, \
+        h.l_slot, h.r_slot, h.r_base, h.r_cap, h.s_base, w.best_packed, w.cand_cnt, w.cand_idx, w.cand_val, dense_s)
+    if (dense_s)
+        KVF_SIM_LAUNCH(true);
+    else
+        KVF_SIM_LAUNCH(false);
+#undef KVF_SIM_LAUNCH
+}
+
 
 void launch_similarity(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const HeightDesc &h, float thr_floor,
                        float *dense_s)
@@ -417,12 +791,12 @@ void launch_similarity(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, c
     const bool big = h.use_big_tiles;
     if (pool.dtype == KVFUSE_BF16) {
         if (big)
-            launch_cfg<bf16_t, KVF_BIG_CFG>(s, pool, w, h, h.big, thr_floor, dense_s);
+            launch_ring<bf16_t>(s, pool, w, h, h.big, thr_floor, dense_s);
         else
             launch_cfg<bf16_t, 2, 2, 2, 2>(s, pool, w, h, h.small, thr_floor, dense_s);
     } else {
         if (big)
-            launch_cfg<float, KVF_BIG_CFG>(s, pool, w, h, h.big, thr_floor, dense_s);
+            launch_ring<float>(s, pool, w, h, h.big, thr_floor, dense_s);
         else
             launch_cfg<float, 2, 2, 2, 2>(s, pool, w, h, h.small, thr_floor, dense_s);
     }

@@ -61,10 +61,11 @@ def test_block_norms_match_oracle(kb, oracle, which):
 # ------------------------------------------------------------------------------------------ a2..a5 one node at a time
 
 def _two_leaf_case(kind):
-    """One tree node: left leaf and right leaf with planted duplicates, ragged against the 128 x 128 tiles."""
-    rng = np.random.default_rng(5 if kind == "f32" else 6)
-    ml, mr = (150, 201) if kind == "bf16" else (70, 45)
-    r = 256 if kind == "bf16" else 96
+    """One tree node: left leaf and right leaf with planted duplicates, ragged against the 128 x 128 tiles
+    (or, for the *_big kinds, against the 256 x 256 tiles with several row tiles and column panels)."""
+    rng = np.random.default_rng({"f32": 5, "bf16": 6, "f32_big": 7, "bf16_big": 8}[kind])
+    ml, mr = {"bf16": (150, 201), "f32": (70, 45), "bf16_big": (700, 530), "f32_big": (300, 290)}[kind]
+    r = 256 if kind.startswith("bf16") else 96
     n = ml + mr
     protos = rng.standard_normal((40, r))
     x = rng.standard_normal((n, r))
@@ -78,7 +79,7 @@ def _two_leaf_case(kind):
     x[11] = 0.0                           # zero blocks on both sides
     x[ml + 6] = 0.0
     y = rng.standard_normal((n, r))
-    dt = torch.bfloat16 if kind == "bf16" else torch.float32
+    dt = torch.bfloat16 if kind.startswith("bf16") else torch.float32
     K = torch.tensor(x, dtype=torch.float32).to(dt)[None].contiguous()
     V = torch.tensor(y, dtype=torch.float32).to(dt)[None].contiguous()
     perm = rng.permutation(n)
@@ -86,11 +87,11 @@ def _two_leaf_case(kind):
     Kp[0][perm] = K[0]
     Vp[0][perm] = V[0]
     bt = torch.tensor(perm, dtype=torch.int32)[None].contiguous()
-    t, d = (8, 32) if kind == "bf16" else (4, 24)
+    t, d = (8, 32) if kind.startswith("bf16") else (4, 24)
     return Kp, Vp, bt, ml, mr, t, d
 
 
-@pytest.mark.parametrize("kind", ["f32", "bf16"])
+@pytest.mark.parametrize("kind", ["f32", "bf16", "f32_big", "bf16_big"])
 @pytest.mark.parametrize("cand_cap", [16, 1])
 def test_single_node_steps_match_oracle(kb, oracle, kind, cand_cap):
     _say("single node", kind, "cand_cap", cand_cap)
