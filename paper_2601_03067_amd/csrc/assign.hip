@@ -207,6 +207,7 @@ __global__ __launch_bounds__(256) void assign_finalize_kernel(int P, TableDesc t
     int32_t *members = w.seg_members + (int64_t)g * w.r_stride + h.r_base[node];
     int32_t *seg_cnt = w.seg_cnt + (int64_t)g * w.l_stride + h.l_base[node];
     int32_t *seg_ptr = w.seg_ptr + (int64_t)g * w.l_stride + h.l_base[node];
+    int32_t *seg_slot = w.seg_slot + (int64_t)g * w.l_stride + h.l_base[node];
 
     // 1. members per target
     for (int i = tid; i < ml; i += 256)
@@ -234,8 +235,7 @@ __global__ __launch_bounds__(256) void assign_finalize_kernel(int P, TableDesc t
             const int start = (int)(run + (pre & 0xFFFFFFFFFFll));
             seg_ptr[i] = start;
             if (cnt > 0)
-                w.active[lds_base + (int)(pre >> 40)] =
-                    make_int4(g, l_ids[i], cnt, (int)((int64_t)g * w.r_stride + h.r_base[node] + start));
+                seg_slot[i] = lds_base + (int)(pre >> 40);
         }
         run += total & 0xFFFFFFFFFFll;
         __syncthreads();
@@ -271,6 +271,17 @@ __global__ __launch_bounds__(256) void assign_finalize_kernel(int P, TableDesc t
     for (int k = tid; k < (int)run; k += 256)
         members[k] = r_ids[members[k]];
     __syncthreads();
+    // work-list records: target, count, member list and the first two members themselves
+    for (int i = tid; i < ml; i += 256) {
+        const int cnt = ld_relaxed(&seg_cnt[i]);
+        if (cnt > 0) {
+            const int start = ld_relaxed(&seg_ptr[i]) - cnt;
+            const int a = l_ids[i];
+            int4 *rec = w.active + 2 * (int64_t)seg_slot[i];
+            rec[0] = make_int4(g, a, cnt, (int)((int64_t)g * w.r_stride + h.r_base[node] + start));
+            rec[1] = make_int4(members[start], cnt > 1 ? members[start + 1] : a, 0, 0);
+        }
+    }
 
     // 4. remap of evicted blocks and in-place compaction of the survivors behind the left set
     int kept = 0;

@@ -64,8 +64,10 @@ struct WorkDesc {
     int32_t *seg_cnt;    // [G][l_stride]
     int32_t *seg_ptr;    // [G][l_stride]
     int32_t *seg_members;// [G][r_stride]
-    int4 *active;        // [G * l_stride] merge work list: (group, target's physical id, member count, index of the
-                         // first member in seg_members) -- everything the merge kernel needs in one 16-byte load
+    int4 *active;        // [G * l_stride][2] merge work list, 32 bytes per target: (group, target's physical id,
+                         // member count, index of the first member in seg_members), (physical ids of the first
+                         // two members, unused, unused) -- the merge kernel starts its block loads straight from it
+    int32_t *seg_slot;   // [G][l_stride] position of a target in the work list
     int32_t *n_active;   // [max_heights]
     int32_t *refine;     // [G * r_stride] columns (g * r_stride + c) that need the fp64 re-check
     int32_t *n_refine;   // [max_heights]

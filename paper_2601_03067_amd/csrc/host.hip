@@ -236,7 +236,8 @@ static void carve(Carver &cv, int G, int n, int n_slots, int max_r, int max_l, i
     w.seg_cnt = cv.take<int32_t>(L);
     w.seg_ptr = cv.take<int32_t>(L);
     w.seg_members = cv.take<int32_t>(R);
-    w.active = cv.take<int4>(L);
+    w.active = cv.take<int4>(2 * L);
+    w.seg_slot = cv.take<int32_t>(L);
     w.n_active = cv.take<int32_t>(kMaxHeights);
     w.refine = cv.take<int32_t>(R);
     w.n_refine = cv.take<int32_t>(kMaxHeights);

@@ -15,14 +15,29 @@ namespace kvfuse {
 
 template <typename T> struct Store16;
 template <> struct Store16<bf16_t> {
+    // Eight fp64 values -> bfloat16, nearest even straight from fp64.  The common case is branch free: round to
+    // binary32 (nearest even), then to bfloat16 (nearest even); the two roundings agree with the direct one unless
+    // the binary32 value sits exactly on a bfloat16 rounding boundary or is zero / subnormal / non-finite.  Those
+    // cases (a few per million elements) send all eight values through the exact integer routine.
     __device__ static __forceinline__ uint4 pack(const double *u, double *back)
     {
         uint32_t h[8];
+        bool special = false;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            h[i] = f64_to_bf16_fast(u[i]);
-            back[i] = (double)__uint_as_float(h[i] << 16);
+            const uint32_t b = __float_as_uint((float)u[i]);
+            const uint32_t ex = (b >> 23) & 0xFFu;
+            special |= ex == 0u || ex == 0xFFu || (b & 0xFFFFu) == 0x8000u;
+            h[i] = (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
         }
+        if (special) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                h[i] = f64_to_bf16_rne(u[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            back[i] = (double)__uint_as_float(h[i] << 16);
         return make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
     }
 };
@@ -62,42 +77,59 @@ __global__ __launch_bounds__(256) void merge_group_kernel(PoolDesc pool, WorkDes
     constexpr int GT = 64 * GW;          // threads per item
     constexpr int GPW = 4 / GW;          // items per workgroup
     __shared__ double red[GPW][GW];
-    const int grp = threadIdx.x / GT;
+    const int grp = __builtin_amdgcn_readfirstlane(threadIdx.x / GT);     // wave-uniform
     const int tg = threadIdx.x % GT;
     const int wv = tg >> 6;
     const int chunks = pool.r / PER;
     const int n_items = 2 * w.n_active[height];
     const int stride = gridDim.x * GPW;
     const int n_iter = (n_items + stride - 1) / stride;      // same for every thread of the workgroup (barriers below)
+    // the record of the next item is fetched while the current one is being worked on
+    int4 nrec0 = make_int4(0, 0, 0, 0), nrec1 = make_int4(0, 0, 0, 0);
+    {
+        const int it = blockIdx.x * GPW + grp;
+        if (it < n_items) {
+            nrec0 = w.active[2 * (int64_t)(it >> 1)];
+            nrec1 = w.active[2 * (int64_t)(it >> 1) + 1];
+        }
+    }
     for (int k = 0; k < n_iter; ++k) {
         const int it = k * stride + blockIdx.x * GPW + grp;
         const bool live = it < n_items;
-        const int itc = live ? it : 0;
-        const int kv = itc & 1;
-        const int4 rec = n_items > 0 ? w.active[itc >> 1] : make_int4(0, 0, 0, 0);
-        const int g = rec.x;
-        const int a = rec.y;
-        const int cnt = live ? rec.z : 0;
-        const int32_t *members = w.seg_members + rec.w;
+        const int kv = it & 1;
+        // an item belongs to whole wavefronts, so its record is the same in every lane: keep it in scalar registers
+        const int g = __builtin_amdgcn_readfirstlane(nrec0.x);
+        const int a = __builtin_amdgcn_readfirstlane(nrec0.y);
+        const int cnt = live ? __builtin_amdgcn_readfirstlane(nrec0.z) : 0;
+        const int32_t *members = w.seg_members + __builtin_amdgcn_readfirstlane(nrec0.w);
+        const int m1 = __builtin_amdgcn_readfirstlane(nrec1.x), m2 = __builtin_amdgcn_readfirstlane(nrec1.y);
         T *pool_g = (T *)(kv ? pool.v : pool.k) + (int64_t)g * pool.P * pool.r;
         double *norm_g = (kv ? pool.norm_v : pool.norm_k) + (int64_t)g * pool.P;
 
-        // the target and the first two members are fetched together; further members (rare) follow one by one
-        const int b1 = cnt > 0 ? members[0] : a;
-        const int b2 = cnt > 1 ? members[1] : a;
+        // the target and the first two members are fetched together; further members (rare) follow one by one.
+        // Loads are unconditional (a lane past the end of the block re-reads its last chunk, an item past the end of
+        // the list reads block 0) and the surplus is masked afterwards: no divergent control flow around memory.
+        const int b1 = cnt > 0 ? m1 : a;
+        const int b2 = cnt > 1 ? m2 : a;
         const uint4 *sa = reinterpret_cast<const uint4 *>(pool_g + (int64_t)a * pool.r);
         const uint4 *s1 = reinterpret_cast<const uint4 *>(pool_g + (int64_t)b1 * pool.r);
         const uint4 *s2 = reinterpret_cast<const uint4 *>(pool_g + (int64_t)b2 * pool.r);
         uint4 xa[CPT], x1[CPT], x2[CPT];
 #pragma unroll
         for (int c = 0; c < CPT; ++c) {
-            const int ch = tg + GT * c;
-            const bool in = live && ch < chunks;
-            xa[c] = in ? sa[ch] : make_uint4(0, 0, 0, 0);
-            x1[c] = in ? s1[ch] : make_uint4(0, 0, 0, 0);
-            x2[c] = in ? s2[ch] : make_uint4(0, 0, 0, 0);
+            const int ch = min(tg + GT * c, chunks - 1);
+            xa[c] = sa[ch];
+            x1[c] = s1[ch];
+            x2[c] = s2[ch];
         }
         const double na = norm_g[a], n1 = norm_g[b1], n2 = norm_g[b2];
+        {
+            const int nit = it + stride;
+            if (nit < n_items) {
+                nrec0 = w.active[2 * (int64_t)(nit >> 1)];
+                nrec1 = w.active[2 * (int64_t)(nit >> 1) + 1];
+            }
+        }
         const double ia = na == 0.0 ? 0.0 : 1.0 / na;
         const double i1 = (cnt > 0 && n1 != 0.0) ? 1.0 / n1 : 0.0;
         const double i2 = (cnt > 1 && n2 != 0.0) ? 1.0 / n2 : 0.0;
@@ -108,9 +140,10 @@ __global__ __launch_bounds__(256) void merge_group_kernel(PoolDesc pool, WorkDes
             Elem<T>::widen(xa[c], ya);
             Elem<T>::widen(x1[c], y1);
             Elem<T>::widen(x2[c], y2);
+            const bool in = live && tg + GT * c < chunks;
 #pragma unroll
             for (int e = 0; e < PER; ++e)
-                acc[c][e] = fma(y2[e], i2, fma(y1[e], i1, ya[e] * ia));
+                acc[c][e] = in ? fma(y2[e], i2, fma(y1[e], i1, ya[e] * ia)) : 0.0;
         }
         for (int m = 2; m < cnt; ++m) {
             const int b = members[m];
@@ -193,7 +226,7 @@ __global__ __launch_bounds__(256) void merge_kernel(PoolDesc pool, WorkDesc w, H
     const int chunks = pool.r / PER;
     const int n_act = w.n_active[height];
     for (int t = blockIdx.x; t < n_act; t += gridDim.x) {
-        const int4 rec = w.active[t];
+        const int4 rec = w.active[2 * (int64_t)t];
         const int g = rec.x;
         const int a = rec.y;
         const int cnt = rec.z;

@@ -571,6 +571,7 @@ __global__ __launch_bounds__(512, 1) void similarity_ring_kernel(
     asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
     __syncthreads();
     KVF_READ_SET(0, fa_lo, fb_lo)
+    KVF_WAIT_SET(0);     // nothing but the loop body below runs while fragment reads are on their way
 
     int it = 0;
     for (int rt = 0; rt < n_rt; ++rt) {
