@@ -303,13 +303,14 @@ void launch_merge(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const 
     const int maxc = (chunks + 255) / 256;
     const int cpl = (chunks + 63) / 64;
     if (cpl <= 8) {
-        const unsigned wgrid = (unsigned)(want < 256 * 8 ? (want + 1) / 2 + 1 : 256 * 8);
-        // blocks of 4 or 8 chunks per lane are split over two wavefronts (fewer registers, more items in flight)
+        const unsigned wgrid = (unsigned)(want < 256 * 16 ? (want + 1) / 2 + 1 : 256 * 16);
+        // up to 4 chunks per lane (bfloat16) one wavefront holds the block and no barrier is needed; longer blocks
+        // and binary32 blocks of 4 chunks per lane are split over two wavefronts
 #define KVF_MERGE_G(T, C, W) merge_group_kernel<T, C, W><<<wgrid, 256, 0, s>>>(pool, w, h, height)
         if (pool.dtype == KVFUSE_BF16) {
             if (cpl <= 1) KVF_MERGE_G(bf16_t, 1, 1);
             else if (cpl <= 2) KVF_MERGE_G(bf16_t, 2, 1);
-            else if (cpl <= 4) KVF_MERGE_G(bf16_t, 2, 2);
+            else if (cpl <= 4) KVF_MERGE_G(bf16_t, 4, 1);
             else KVF_MERGE_G(bf16_t, 4, 2);
         } else {
             if (cpl <= 1) KVF_MERGE_G(float, 1, 1);
