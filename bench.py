@@ -141,6 +141,12 @@ def main():
         stats = st
         stage["norms"] += st.ms_norms; stage["similarity"] += st.ms_similarity; stage["assign"] += st.ms_assign
         stage["merge"] += st.ms_merge; stage["rewrite"] += st.ms_rewrite; stage["decode"] += dec
+    # what the machine sustains, measured with the library's own probes after the timed steps (they load the chip
+    # heavily and would otherwise warm it up for the steps): the MFMA instruction of the similarity kernel on
+    # random and on constant operands, and a plain device copy
+    probes = {"mfma_bf16_random_operands_TFLOPs": kb.probe_mfma_bf16(ctx, True, dev),
+              "mfma_bf16_constant_operands_TFLOPs": kb.probe_mfma_bf16(ctx, False, dev),
+              "copy_kernel_GBps": kb.probe_copy(ctx, K0, cache.K, repeats=3)}
     k = max(args.steps, 1)
     stage = {a: b / k for a, b in stage.items()}
     ms_step = sum(walls) / k
@@ -175,10 +181,14 @@ def main():
                    "logical_GBps": logi_bytes / (stage["decode"] * 1e-3) / 1e9, "hbm_peak_GBps": 8000.0,
                    "frac_of_hbm_peak_physical": phys_bytes / (stage["decode"] * 1e-3) / 1e9 / 8000.0},
         "norms": {"ms": stage["norms"], "GBps": logi_bytes / (stage["norms"] * 1e-3) / 1e9},
-        "roofline": {"kernel": "similarity_kernel", "bound": "mfma", "achieved": sim_tflops, "peak": peak,
+        "roofline": {"kernel": "similarity_ring_kernel (256 x 256 tiles) + similarity_kernel (128 x 128 tiles)",
+                     "bound": "mfma", "achieved": sim_tflops, "peak": peak,
                      "unit": "TFLOP/s", "frac": sim_tflops / peak, "traffic": traffic,
+                     "frac_of_measured_mfma_rate": (sim_tflops / probes["mfma_bf16_random_operands_TFLOPs"]
+                                                    if rec.dtype == torch.bfloat16 else None),
                      "launches_per_step": stats.n_heights,
                      "flops_per_step": stats.sim_flops, "ms_per_step": stage["similarity"]},
+        "machine_probes": probes,
         "generation_s": t_gen,
     }
     if not args.no_cpu_baseline:

@@ -222,6 +222,23 @@ int kvfuse_paged_decode_attn(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvf
                              const int32_t *ctx_len, int32_t B, int32_t Hq, int32_t max_blocks, float sm_scale,
                              void *workspace, size_t workspace_bytes, float *out);
 
+/* ---- machine probes (measurement aids; not part of the hot path) -------------------------------------- */
+
+#define KVFUSE_PROBE_SCRATCH_BYTES 65792
+
+/* Sustained rate of the bfloat16 MFMA instruction the similarity step uses (section 3.2's matrix product runs on
+ * it), over the whole GPU, with operands in registers and no memory traffic: the compute ceiling the similarity
+ * kernel can be held against besides the nominal peak.  random_operands = 0 multiplies a constant pattern,
+ * 1 multiplies pseudo-random values, which is what real caches look like to the multipliers -- the chip lowers
+ * its clock under that load, so the two differ.  scratch: device, >= KVFUSE_PROBE_SCRATCH_BYTES, overwritten.
+ * tflops: host.  Runs on the context's stream and waits for it (about 50 - 100 ms). */
+int kvfuse_probe_mfma_bf16(kvfuse_ctx *ctx, int32_t random_operands, void *scratch, size_t scratch_bytes, double *tflops);
+
+/* Rate of a plain device copy kernel (16 bytes per lane), read + write bytes per second: the HBM ceiling the
+ * bandwidth-bound steps (norms, merge, decode attention) can be held against.  src, dst: device, bytes each,
+ * not overlapping; gbps: host.  Waits for the stream. */
+int kvfuse_probe_copy(kvfuse_ctx *ctx, const void *src, void *dst, size_t bytes, int32_t repeats, double *gbps);
+
 #ifdef __cplusplus
 }
 #endif

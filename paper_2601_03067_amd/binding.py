@@ -85,6 +85,10 @@ lib.kvfuse_decode_workspace_bytes.argtypes = [_i32, _i32, _i32, _i32, _i32, _i32
 lib.kvfuse_paged_decode_attn.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _i32, _i32, _i32, _vp, _vp, _vp, _i32,
                                          _i32, _i32, _f32, _vp, C.c_size_t, _vp]
 
+lib.kvfuse_probe_mfma_bf16.argtypes = [_vp, _i32, _vp, C.c_size_t, C.POINTER(C.c_double)]
+lib.kvfuse_probe_copy.argtypes = [_vp, _vp, _vp, C.c_size_t, _i32, C.POINTER(C.c_double)]
+PROBE_SCRATCH_BYTES = 65792
+
 
 class KvfuseError(RuntimeError):
     def __init__(self, code, text):
@@ -276,6 +280,22 @@ def paged_decode_attn(ctx, cache, kv_heads, q, req_start, ctx_len, max_blocks, l
                                            _ptr(q), _ptr(req_start), _ptr(ctx_len), B, Hq, max_blocks, sm_scale,
                                            _ptr(workspace), workspace.numel(), _ptr(out)))
     return out
+
+
+def probe_mfma_bf16(ctx, random_operands=True, device="cuda:0"):
+    """Sustained bfloat16 MFMA rate of the whole GPU in TFLOP/s (operands in registers, no memory traffic)."""
+    scratch = torch.empty(PROBE_SCRATCH_BYTES, device=device, dtype=torch.uint8)
+    out = C.c_double(0.0)
+    ctx.check(lib.kvfuse_probe_mfma_bf16(ctx.h, 1 if random_operands else 0, _ptr(scratch), scratch.numel(), C.byref(out)))
+    return out.value
+
+
+def probe_copy(ctx, src, dst, repeats=3):
+    """Read + write GB/s of a plain device copy kernel from src to dst (same size, contiguous)."""
+    assert src.is_contiguous() and dst.is_contiguous() and src.numel() * src.element_size() == dst.numel() * dst.element_size()
+    out = C.c_double(0.0)
+    ctx.check(lib.kvfuse_probe_copy(ctx.h, _ptr(src), _ptr(dst), src.numel() * src.element_size(), repeats, C.byref(out)))
+    return out.value
 
 
 def unpack_best(packed):

@@ -113,6 +113,12 @@ int launch_decode(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, int
                   const void *q, const int32_t *req_start, const int32_t *ctx_len, int B, int Hq, int max_blocks,
                   float sm_scale, void *workspace, size_t workspace_bytes, float *out);
 
+// machine probes (probe.hip)
+constexpr size_t kProbeScratchBytes = 65536 + 256;     // 4096 operand chunks of 16 bytes + a sink word
+void launch_probe_fill(hipStream_t s, void *operands, int random_operands);
+void launch_probe_mfma(hipStream_t s, const void *operands, int workgroups, int iters, float *sink);
+void launch_probe_copy(hipStream_t s, const void *src, void *dst, size_t bytes);
+
 // ---------------------------------------------------------------------------------------------------
 // device side
 // ---------------------------------------------------------------------------------------------------

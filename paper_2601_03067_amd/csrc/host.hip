@@ -693,4 +693,68 @@ int kvfuse_paged_decode_attn(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvf
     return KVFUSE_OK;
 }
 
+int kvfuse_probe_mfma_bf16(kvfuse_ctx *ctx, int32_t random_operands, void *scratch, size_t scratch_bytes, double *tflops)
+{
+    if (!ctx)
+        return KVFUSE_EINVAL;
+    Ctx *c = &ctx->c;
+    if (!scratch || !tflops || scratch_bytes < kProbeScratchBytes)
+        return fail(c, KVFUSE_EINVAL, "probe: needs a device scratch buffer of KVFUSE_PROBE_SCRATCH_BYTES and an output");
+    hipDeviceProp_t prop;
+    KVF_HIP(c, hipGetDeviceProperties(&prop, c->device));
+    const int wgs = prop.multiProcessorCount * 4;      // four rounds of one 8-wavefront workgroup per compute unit
+    const int iters = 2000;
+    float *sink = reinterpret_cast<float *>(static_cast<char *>(scratch) + 65536);
+    hipEvent_t e0, e1;
+    KVF_HIP(c, hipEventCreate(&e0));
+    KVF_HIP(c, hipEventCreate(&e1));
+    launch_probe_fill(c->stream, scratch, random_operands);
+    launch_probe_mfma(c->stream, scratch, wgs, iters / 10, sink);     // warm-up
+    hipError_t err = hipEventRecord(e0, c->stream);
+    launch_probe_mfma(c->stream, scratch, wgs, iters, sink);
+    if (err == hipSuccess)
+        err = hipEventRecord(e1, c->stream);
+    if (err == hipSuccess)
+        err = hipEventSynchronize(e1);
+    float ms = 0.0f;
+    if (err == hipSuccess)
+        err = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    KVF_HIP(c, err);
+    KVF_HIP(c, hipGetLastError());
+    // per wavefront and iteration: 32 MFMAs of 2 * 32 * 32 * 16 flops
+    *tflops = ms > 0.0f ? (double)wgs * 8.0 * iters * 32.0 * 32768.0 / (ms * 1e-3) / 1e12 : 0.0;
+    return KVFUSE_OK;
+}
+
+int kvfuse_probe_copy(kvfuse_ctx *ctx, const void *src, void *dst, size_t bytes, int32_t repeats, double *gbps)
+{
+    if (!ctx)
+        return KVFUSE_EINVAL;
+    Ctx *c = &ctx->c;
+    if (!src || !dst || !gbps || bytes < 16 || repeats <= 0)
+        return fail(c, KVFUSE_EINVAL, "probe: null pointer, fewer than 16 bytes or no repeats");
+    hipEvent_t e0, e1;
+    KVF_HIP(c, hipEventCreate(&e0));
+    KVF_HIP(c, hipEventCreate(&e1));
+    launch_probe_copy(c->stream, src, dst, bytes);                      // warm-up
+    hipError_t err = hipEventRecord(e0, c->stream);
+    for (int i = 0; i < repeats; ++i)
+        launch_probe_copy(c->stream, src, dst, bytes);
+    if (err == hipSuccess)
+        err = hipEventRecord(e1, c->stream);
+    if (err == hipSuccess)
+        err = hipEventSynchronize(e1);
+    float ms = 0.0f;
+    if (err == hipSuccess)
+        err = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    KVF_HIP(c, err);
+    KVF_HIP(c, hipGetLastError());
+    *gbps = ms > 0.0f ? 2.0 * (double)(bytes / 16 * 16) * repeats / (ms * 1e-3) / 1e9 : 0.0;
+    return KVFUSE_OK;
+}
+
 }  // extern "C"

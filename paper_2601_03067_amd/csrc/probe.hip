@@ -1,0 +1,105 @@
+// Machine probes: what the MFMA units and the HBM sustain on this GPU, measured with the same instructions
+// the hot path uses.  Measurement aids only -- nothing on the hot path calls them.
+#include "common.h"
+
+namespace kvfuse {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// Every wavefront issues independent v_mfma_f32_32x32x16_bf16 on operands that stay in registers: eight
+// accumulators (as in the similarity kernel), two wavefronts per SIMD, no memory traffic inside the loop.
+__global__ __launch_bounds__(512, 1) void probe_mfma_kernel(const uint4 *__restrict__ operands, int iters, float *__restrict__ sink)
+{
+    const int tid = threadIdx.x;
+    uint4 a[4], b[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        a[q] = operands[(tid * 4 + q) & 4095];
+        b[q] = operands[(tid * 4 + q + 2048) & 4095];
+    }
+    floatx16 acc[8];
+#pragma unroll
+    for (int x = 0; x < 8; ++x)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            acc[x][e] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int x = 0; x < 8; ++x)
+                acc[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[(x + s) & 3]),
+                                                                 __builtin_bit_cast(bf16x8, b[(x * 3 + s) & 3]), acc[x], 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int x = 0; x < 8; ++x)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            s += acc[x][e];
+    if (s == 12345.678f)      // keeps the accumulators alive without a store in the common case
+        sink[0] = s;
+}
+
+__global__ void probe_fill_kernel(uint4 *__restrict__ operands, int random_operands)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= 4096)
+        return;
+    uint32_t w[4];
+    uint32_t st = 0x9E3779B9u * (uint32_t)(i + 1);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        uint32_t v = 0x3F803F80u;                      // two bfloat16 ones
+        if (random_operands) {
+            // two bfloat16 values with random sign and mantissa and exponents within a few binades of 1
+            st = st * 1664525u + 1013904223u;
+            const uint32_t lo = 0x3E00u + ((st >> 8) & 0x1FFu) + ((st >> 20) & 1u) * 0x8000u;
+            st = st * 1664525u + 1013904223u;
+            const uint32_t hi = 0x3E00u + ((st >> 8) & 0x1FFu) + ((st >> 20) & 1u) * 0x8000u;
+            v = lo | (hi << 16);
+        }
+        w[k] = v;
+    }
+    operands[i] = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// Each workgroup copies runs of 4 x 256 chunks of 16 bytes: four loads in flight per lane before the stores.
+__global__ __launch_bounds__(256) void probe_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n16)
+{
+    const size_t per_wg = 1024;
+    const size_t n_runs = (n16 + per_wg - 1) / per_wg;
+    for (size_t run = blockIdx.x; run < n_runs; run += gridDim.x) {
+        const size_t i0 = run * per_wg + threadIdx.x;
+        uint4 v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (i0 + 256 * q < n16)
+                v[q] = src[i0 + 256 * q];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (i0 + 256 * q < n16)
+                dst[i0 + 256 * q] = v[q];
+    }
+}
+
+void launch_probe_fill(hipStream_t s, void *operands, int random_operands)
+{
+    probe_fill_kernel<<<16, 256, 0, s>>>(reinterpret_cast<uint4 *>(operands), random_operands);
+}
+void launch_probe_mfma(hipStream_t s, const void *operands, int workgroups, int iters, float *sink)
+{
+    probe_mfma_kernel<<<workgroups, 512, 0, s>>>(reinterpret_cast<const uint4 *>(operands), iters, sink);
+}
+void launch_probe_copy(hipStream_t s, const void *src, void *dst, size_t bytes)
+{
+    const size_t n16 = bytes / 16;
+    if (n16 == 0)
+        return;
+    const size_t want = (n16 + 1023) / 1024;
+    probe_copy_kernel<<<(unsigned)(want < 256 * 64 ? want : 256 * 64), 256, 0, s>>>(reinterpret_cast<const uint4 *>(src),
+                                                                                  reinterpret_cast<uint4 *>(dst), n16);
+}
+
+}  // namespace kvfuse

@@ -355,3 +355,20 @@ def test_decode_matches_oracle(kb, oracle, case):
     _say("  max abs err", worst)
     assert worst <= 2e-2
     assert worst <= (1e-4 if rec.dtype == torch.float32 else 5e-3)
+
+
+# ------------------------------------------------------------------------------------------ machine probes
+
+def test_machine_probes_run_and_copy_is_exact(kb):
+    _say("machine probes")
+    ctx = kb.Context(DEV)
+    a = torch.arange(1 << 20, dtype=torch.int32, device=DEV)
+    b = torch.zeros_like(a)
+    gbps = kb.probe_copy(ctx, a, b, repeats=2)
+    assert gbps > 0 and torch.equal(a, b)
+    rnd = kb.probe_mfma_bf16(ctx, True, DEV)
+    const = kb.probe_mfma_bf16(ctx, False, DEV)
+    _say("  mfma bf16 TFLOP/s: random operands", round(rnd), "constant operands", round(const), "copy GB/s (small)", round(gbps))
+    assert 50 < rnd < 2600 and 50 < const < 2600      # below the nominal dense peak of 2500 plus timing slack
+    with pytest.raises(kb.KvfuseError):
+        kb.ctx_check = ctx.check(kb.lib.kvfuse_probe_copy(ctx.h, None, None, 0, 1, None))
