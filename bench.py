@@ -31,6 +31,8 @@ def make_recipe(wl, name):
         return wl.cff_long()
     if name == "tiny_bff":
         return wl.tiny_bff()
+    if name == "llama8b_bff_prefix75":       # same shape, three quarters of every request is the common prefix
+        return wl.llama8b_bff(prefix_tokens=1536)
     if name == "llama8b_bff_small":          # quick functional check, not a benchmark configuration
         return wl.llama8b_bff(n_req=16, layers=4)
     raise SystemExit(f"unknown workload {name}")
@@ -141,6 +143,24 @@ def main():
         stats = st
         stage["norms"] += st.ms_norms; stage["similarity"] += st.ms_similarity; stage["assign"] += st.ms_assign
         stage["merge"] += st.ms_merge; stage["rewrite"] += st.ms_rewrite; stage["decode"] += dec
+    # shared-block decode attention (the first "next" row): same outputs, blocks common to several requests read
+    # once per tile of requests.  Measured on the table the last step left, outside the timed steps.
+    t_plan = time.perf_counter()
+    splan = kb.SharedDecodePlan(ctx, cache, rec.kv_heads, rec.req_start, rec.ctx_len, rec.q_heads, min_cluster_blocks=4)
+    t_plan = time.perf_counter() - t_plan
+    out_sh = torch.empty_like(out)
+    kb.paged_decode_attn_shared(ctx, cache, splan, q, out=out_sh)
+    sev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    torch.cuda.synchronize()
+    sev[0].record()
+    for _ in range(3):
+        kb.paged_decode_attn_shared(ctx, cache, splan, q, out=out_sh)
+    sev[1].record()
+    torch.cuda.synchronize()
+    ms_shared = sev[0].elapsed_time(sev[1]) / 3
+    shared_diff = float((out_sh - out).abs().max())
+    si = splan.info
+
     # what the machine sustains, measured with the library's own probes after the timed steps (they load the chip
     # heavily and would otherwise warm it up for the steps): the MFMA instruction of the similarity kernel on
     # random and on constant operands, and a plain device copy
@@ -180,6 +200,11 @@ def main():
         "decode": {"ms": stage["decode"], "physical_GBps": phys_bytes / (stage["decode"] * 1e-3) / 1e9,
                    "logical_GBps": logi_bytes / (stage["decode"] * 1e-3) / 1e9, "hbm_peak_GBps": 8000.0,
                    "frac_of_hbm_peak_physical": phys_bytes / (stage["decode"] * 1e-3) / 1e9 / 8000.0},
+        "decode_shared_blocks": {"ms": ms_shared, "physical_GBps": phys_bytes / (ms_shared * 1e-3) / 1e9,
+                                 "max_abs_diff_vs_decode": shared_diff, "plan_build_s": t_plan, "clusters": si.clusters,
+                                 "logical_blocks": si.logical_blocks, "served_through_clusters": si.shared_instances,
+                                 "block_reads": si.cluster_block_reads + si.residual_block_reads,
+                                 "plan_device_MB": si.device_bytes / 1e6},
         "norms": {"ms": stage["norms"], "GBps": logi_bytes / (stage["norms"] * 1e-3) / 1e9},
         "roofline": {"kernel": "similarity_ring_kernel (256 x 256 tiles) + similarity_kernel (128 x 128 tiles)",
                      "bound": "mfma", "achieved": sim_tflops, "peak": peak,

@@ -222,6 +222,55 @@ int kvfuse_paged_decode_attn(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvf
                              const int32_t *ctx_len, int32_t B, int32_t Hq, int32_t max_blocks, float sm_scale,
                              void *workspace, size_t workspace_bytes, float *out);
 
+/* ---- shared-block decode attention -------------------------------------------------------------------- */
+
+/* The same attention as kvfuse_paged_decode_attn, organised around the blocks that fusion made common
+ * (motivation section: a fused representation allows one matrix-matrix product where there were several
+ * matrix-vector products; Algorithm 1 marks shared blocks for that purpose; the result for a request is the
+ * merge of the attention over its fused part and over its unique part, rescaled).
+ *
+ * A decode plan is built on the host from the current block table: within each group, physical blocks that are
+ * referenced by exactly the same set of requests form a cluster; a cluster of at least min_cluster_blocks blocks
+ * is walked once per tile of up to 16 / (Hq / kv_heads) sharing requests, whose query heads fill the rows of one
+ * MFMA tile, so its K and V blocks are read once per tile instead of once per request.  What is left of every
+ * request (unshared blocks, small clusters, the partial last block) is walked per request as before.  Partial
+ * softmax states (maximum, sum, weighted values) of all pieces of a request are merged at the end.  Where a
+ * request's blocks sit in its context does not matter, so clusters need not be prefixes or aligned.
+ *
+ * The plan depends on the table contents: rebuild it after every fusion or table edit.  Building copies the
+ * table of the covered groups to the host and synchronises the stream (milliseconds to a fraction of a second,
+ * a few times per fusion, never per decode step). */
+typedef struct kvfuse_decode_plan kvfuse_decode_plan;
+
+typedef struct kvfuse_decode_plan_info {
+    int64_t device_bytes;      /* workspace the plan needs on the device (tables + partial states) */
+    int64_t clusters;          /* clusters used, all groups */
+    int64_t shared_instances;  /* logical blocks served through clusters */
+    int64_t logical_blocks;    /* logical blocks in the contexts, all groups */
+    int64_t cluster_block_reads; /* K+V block reads of the cluster pass (blocks x request tiles) */
+    int64_t residual_block_reads; /* block reads of the per-request pass */
+    int64_t items_cluster, items_residual;
+} kvfuse_decode_plan_info;
+
+/* Step 1 (host only plus one device-to-host copy): analyse the table.  req_start, ctx_len: HOST arrays [B].
+ * min_cluster_blocks >= 1 (4 is a sensible value).  On success *plan is a host object to be finished by
+ * kvfuse_shared_decode_plan_upload and released with kvfuse_shared_decode_plan_destroy. */
+int kvfuse_shared_decode_plan_build(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table, int32_t kv_heads,
+                                    int32_t layer_begin, int32_t n_layers, const int32_t *req_start, const int32_t *ctx_len,
+                                    int32_t B, int32_t Hq, int32_t min_cluster_blocks, kvfuse_decode_plan **plan,
+                                    kvfuse_decode_plan_info *info);
+
+/* Step 2: place the plan's tables in workspace (device, >= info.device_bytes, owned by the caller, must stay
+ * alive and untouched while the plan is used).  Synchronises the stream. */
+int kvfuse_shared_decode_plan_upload(kvfuse_ctx *ctx, kvfuse_decode_plan *plan, void *workspace, size_t workspace_bytes);
+
+int kvfuse_shared_decode_plan_destroy(kvfuse_decode_plan *plan);
+
+/* One decode step through an uploaded plan; q and out as in kvfuse_paged_decode_attn, for the plan's layers,
+ * requests and context lengths.  Asynchronous on the context's stream. */
+int kvfuse_paged_decode_attn_shared(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table,
+                                    const kvfuse_decode_plan *plan, const void *q, float sm_scale, float *out);
+
 /* ---- machine probes (measurement aids; not part of the hot path) -------------------------------------- */
 
 #define KVFUSE_PROBE_SCRATCH_BYTES 65792

@@ -85,6 +85,19 @@ lib.kvfuse_decode_workspace_bytes.argtypes = [_i32, _i32, _i32, _i32, _i32, _i32
 lib.kvfuse_paged_decode_attn.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _i32, _i32, _i32, _vp, _vp, _vp, _i32,
                                          _i32, _i32, _f32, _vp, C.c_size_t, _vp]
 
+
+
+class DecodePlanInfo(C.Structure):
+    _fields_ = [("device_bytes", C.c_int64), ("clusters", C.c_int64), ("shared_instances", C.c_int64),
+                ("logical_blocks", C.c_int64), ("cluster_block_reads", C.c_int64), ("residual_block_reads", C.c_int64),
+                ("items_cluster", C.c_int64), ("items_residual", C.c_int64)]
+
+
+lib.kvfuse_shared_decode_plan_build.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _i32, _i32, _i32, _vp, _vp, _i32, _i32,
+                                                _i32, C.POINTER(_vp), C.POINTER(DecodePlanInfo)]
+lib.kvfuse_shared_decode_plan_upload.argtypes = [_vp, _vp, _vp, C.c_size_t]
+lib.kvfuse_shared_decode_plan_destroy.argtypes = [_vp]
+lib.kvfuse_paged_decode_attn_shared.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _vp, _vp, C.c_float, _vp]
 lib.kvfuse_probe_mfma_bf16.argtypes = [_vp, _i32, _vp, C.c_size_t, C.POINTER(C.c_double)]
 lib.kvfuse_probe_copy.argtypes = [_vp, _vp, _vp, C.c_size_t, _i32, C.POINTER(C.c_double)]
 PROBE_SCRATCH_BYTES = 65792
@@ -279,6 +292,45 @@ def paged_decode_attn(ctx, cache, kv_heads, q, req_start, ctx_len, max_blocks, l
     ctx.check(lib.kvfuse_paged_decode_attn(ctx.h, C.byref(cache.pool), C.byref(cache.table), kv_heads, layer_begin, n_layers,
                                            _ptr(q), _ptr(req_start), _ptr(ctx_len), B, Hq, max_blocks, sm_scale,
                                            _ptr(workspace), workspace.numel(), _ptr(out)))
+    return out
+
+
+class SharedDecodePlan:
+    """Decode plan for kvfuse_paged_decode_attn_shared, built from the cache's current table (rebuild after a fusion)."""
+
+    def __init__(self, ctx, cache, kv_heads, req_start, ctx_len, Hq, layer_begin=0, n_layers=None, min_cluster_blocks=4):
+        import numpy as np
+        self.ctx = ctx
+        self.h = _vp()
+        rs = np.ascontiguousarray(np.asarray(req_start.cpu() if hasattr(req_start, "cpu") else req_start, dtype=np.int32))
+        cl = np.ascontiguousarray(np.asarray(ctx_len.cpu() if hasattr(ctx_len, "cpu") else ctx_len, dtype=np.int32))
+        if n_layers is None:
+            n_layers = cache.pool.G // kv_heads - layer_begin
+        self.n_layers, self.B, self.Hq, self.kv_heads = n_layers, len(rs), Hq, kv_heads
+        self.info = DecodePlanInfo()
+        ctx.check(lib.kvfuse_shared_decode_plan_build(ctx.h, C.byref(cache.pool), C.byref(cache.table), kv_heads, layer_begin,
+                                                      n_layers, rs.ctypes.data_as(_vp), cl.ctypes.data_as(_vp), len(rs), Hq,
+                                                      min_cluster_blocks, C.byref(self.h), C.byref(self.info)))
+        self.workspace = torch.empty(int(self.info.device_bytes), device=cache.K.device, dtype=torch.uint8)
+        ctx.check(lib.kvfuse_shared_decode_plan_upload(ctx.h, self.h, _ptr(self.workspace), self.workspace.numel()))
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            lib.kvfuse_shared_decode_plan_destroy(self.h)
+            self.h = None
+
+
+def paged_decode_attn_shared(ctx, cache, plan, q, sm_scale=None, out=None):
+    """q [n_layers][B][Hq][d] (pool dtype) -> out [n_layers][B][Hq][d] float32, through a SharedDecodePlan."""
+    n_layers, B, Hq, d = q.shape
+    assert q.is_contiguous() and q.dtype == cache.K.dtype and d == cache.d
+    assert (n_layers, B, Hq) == (plan.n_layers, plan.B, plan.Hq)
+    if sm_scale is None:
+        sm_scale = 1.0 / float(d) ** 0.5
+    if out is None:
+        out = torch.empty(n_layers, B, Hq, d, device=q.device, dtype=torch.float32)
+    ctx.check(lib.kvfuse_paged_decode_attn_shared(ctx.h, C.byref(cache.pool), C.byref(cache.table), plan.h, _ptr(q), sm_scale,
+                                                  _ptr(out)))
     return out
 
 

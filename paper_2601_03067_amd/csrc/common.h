@@ -21,6 +21,9 @@ struct Ctx {
     std::string err;
     hipEvent_t ev[16] = {};
     bool ev_ready = false;
+    // second stream (default priority) and fork / join events for launches that may overlap; made on first use
+    hipStream_t aux = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
 };
 
 int fail(Ctx *c, int code, const std::string &msg);
@@ -31,6 +34,15 @@ int fail(Ctx *c, int code, const std::string &msg);
         if (e__ != hipSuccess)                                                                    \
             return ::kvfuse::fail((ctx), KVFUSE_EHIP, std::string(#expr) + ": " + hipGetErrorString(e__)); \
     } while (0)
+
+}  // namespace kvfuse
+
+// the opaque context of the C ABI
+struct kvfuse_ctx {
+    kvfuse::Ctx c;
+};
+
+namespace kvfuse {
 
 // Work items of the similarity launch of one height (device arrays, identical for every group): item k covers
 // right blocks [col0, col0 + BN) x left blocks [row0, row0 + rows) of node `node`.

@@ -314,9 +314,6 @@ template <typename T> static hipError_t upload(hipStream_t s, const T *dst, cons
 
 using namespace kvfuse;
 
-struct kvfuse_ctx {
-    Ctx c;
-};
 struct kvfuse_plan {
     Plan p;
 };
@@ -347,6 +344,12 @@ int kvfuse_destroy(kvfuse_ctx *ctx)
     if (ctx->c.ev_ready)
         for (hipEvent_t &e : ctx->c.ev)
             (void)hipEventDestroy(e);
+    if (ctx->c.aux) {
+        (void)hipStreamSynchronize(ctx->c.aux);
+        (void)hipEventDestroy(ctx->c.fork);
+        (void)hipEventDestroy(ctx->c.join);
+        (void)hipStreamDestroy(ctx->c.aux);
+    }
     delete ctx;
     return KVFUSE_OK;
 }

@@ -357,6 +357,73 @@ def test_decode_matches_oracle(kb, oracle, case):
     assert worst <= (1e-4 if rec.dtype == torch.float32 else 5e-3)
 
 
+# ------------------------------------------------------------------------------------------ shared-block decode attention
+
+def _decode_shared(kb, ctx, rec, cache, q, min_cluster_blocks):
+    plan = kb.SharedDecodePlan(ctx, cache, rec.kv_heads, rec.req_start, rec.ctx_len, rec.q_heads,
+                               min_cluster_blocks=min_cluster_blocks)
+    out = kb.paged_decode_attn_shared(ctx, cache, plan, q)
+    torch.cuda.synchronize()
+    return out.cpu().numpy().astype(np.float64), plan.info
+
+
+@pytest.mark.parametrize("case", ["bf16_prefix_gqa4", "bf16_d64_gqa8_t32", "bf16_one_request", "f32_ragged", "bf16_unfused"])
+@pytest.mark.parametrize("min_cluster_blocks", [1, 4])
+def test_shared_decode_matches_oracle_and_plain_decode(kb, oracle, case, min_cluster_blocks):
+    """Attention through the cluster plan equals the definition (the oracle's fp64 attention through the fused table)
+    to the same bound as the per-request kernel, and the per-request kernel's output closely: only the order in which
+    partial softmax states are merged differs."""
+    _say("shared decode case", case, "min_cluster_blocks", min_cluster_blocks)
+    thr = None
+    if case == "bf16_prefix_gqa4":          # a common prefix (cluster of all requests) plus scattered near duplicates
+        rec = wl.llama8b_bff(n_req=7, tokens=16 * 41, layers=2, kv_heads=2, prefix_tokens=16 * 9, near_pool=16)
+    elif case == "bf16_d64_gqa8_t32":       # 8 query heads per KV head: two requests fill the 16 rows
+        rec = wl.zipf_bff(n_req=5, tokens=32 * 9, layers=1, kv_heads=2, pool=30, t=32, d=64)
+    elif case == "bf16_one_request":        # chunks of one request: blocks shared inside a request never form a cluster
+        rec = wl.cff_long(tokens=16 * 300, chunk_tokens=16 * 50, layers=1, kv_heads=2)
+    elif case == "f32_ragged":              # partial last blocks, mixed lengths
+        rec = wl.mixed(n_req=6, min_tokens=20, max_tokens=700, chunk_tokens=256, layers=1, kv_heads=2, pool=40,
+                       dtype=torch.float32)
+    else:                                   # nothing fused: every block is private, the plan has no cluster
+        rec = wl.llama8b_bff(n_req=4, tokens=16 * 20, layers=1, kv_heads=2, prefix_tokens=64, near_pool=8)
+        thr = 1.5
+    mat = wl.materialise(rec, DEV, phys_perm=True)
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, thr=thr)
+    q = wl.queries(rec, DEV)
+    plain = _decode(kb, ctx, rec, cache, q)
+    shared, info = _decode_shared(kb, ctx, rec, cache, q, min_cluster_blocks)
+    _say("  clusters", info.clusters, "shared instances", info.shared_instances, "of", info.logical_blocks,
+         "block reads", info.cluster_block_reads, "+", info.residual_block_reads)
+    full_blocks = sum(int(c) // rec.t for c in rec.ctx_len) * rec.G
+    assert info.logical_blocks == sum((int(c) + rec.t - 1) // rec.t for c in rec.ctx_len) * rec.G
+    assert 0 <= info.shared_instances <= full_blocks
+    if case == "bf16_prefix_gqa4":
+        assert info.clusters >= rec.G and info.shared_instances >= rec.G * 7 * 9      # the common prefix at least
+        assert info.cluster_block_reads + info.residual_block_reads < info.logical_blocks
+    if case in ("bf16_unfused", "bf16_one_request"):
+        assert info.clusters == 0 and info.residual_block_reads == info.logical_blocks
+    worst = 0.0
+    for layer in range(rec.layers):
+        ref = _attn_oracle(oracle, rec, cache, q[layer], layer, rec.kv_heads)
+        worst = max(worst, float(np.abs(shared[layer] - ref).max()))
+    _say("  max abs err vs oracle", worst, " vs per-request kernel", float(np.abs(shared - plain).max()))
+    assert worst <= 2e-2
+    assert worst <= (1e-4 if rec.dtype == torch.float32 else 5e-3)
+    assert np.abs(shared - plain).max() <= (1e-5 if rec.dtype == torch.float32 else 2e-3)
+
+
+def test_shared_decode_rejects_bad_arguments(kb):
+    rec = wl.tiny_bff()
+    mat = wl.materialise(rec, DEV)
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat)
+    with pytest.raises(kb.KvfuseError):       # request runs past the table
+        kb.SharedDecodePlan(ctx, cache, rec.kv_heads, [rec.n - 1], [rec.t * 4], rec.q_heads)
+    with pytest.raises(kb.KvfuseError):       # query heads not a multiple of KV heads
+        kb.SharedDecodePlan(ctx, cache, rec.kv_heads, rec.req_start, rec.ctx_len, rec.q_heads + 1)
+    with pytest.raises(kb.KvfuseError):
+        kb.SharedDecodePlan(ctx, cache, rec.kv_heads, rec.req_start, rec.ctx_len, rec.q_heads, min_cluster_blocks=0)
+
+
 # ------------------------------------------------------------------------------------------ machine probes
 
 def test_machine_probes_run_and_copy_is_exact(kb):
