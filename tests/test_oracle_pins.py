@@ -456,3 +456,55 @@ def test_fusion_then_attention_satisfies_softmax_drift_bound(oracle):
     s1 = np.exp(z1 - z1.max()); s1 /= s1.sum()
     eps = np.abs(z1 - z0).max()
     assert eps > 0 and np.abs(s1 - s0).sum() <= math.exp(2 * eps) - 1 + 1e-12
+
+
+# ---------------------------------------------------------------- threshold control statistics (analysis section)
+
+def test_exceedance_rate_closed_forms_and_inverse():
+    from oracle import threshold as th
+    n, mu, sigma = 5000.0, 0.2, 0.1
+    assert th.exceedance_rate(n, mu, sigma, mu) == pytest.approx(n / 2, rel=1e-15)
+    # 1 - Phi(1), 1 - Phi(2), 1 - Phi(3): textbook values of the normal tail
+    for k, tail in ((1, 0.15865525393145707), (2, 0.022750131948179195), (3, 0.0013498980316300933)):
+        assert th.exceedance_rate(n, mu, sigma, mu + k * sigma) == pytest.approx(n * tail, rel=1e-12)
+        assert th.exceedance_rate(n, mu, sigma, mu - k * sigma) == pytest.approx(n * (1 - tail), rel=1e-12)
+    for u in (0.25, 0.4, 0.55):
+        lam = th.exceedance_rate(n, mu, sigma, u)
+        assert th.threshold_for_rate(n, mu, sigma, lam) == pytest.approx(u, abs=1e-10)
+    # degenerate spread: everything or nothing exceeds
+    assert th.exceedance_rate(n, 0.5, 0.0, 0.4) == n and th.exceedance_rate(n, 0.3, 0.0, 0.4) == 0.0
+
+
+def test_exceedance_rate_predicts_gaussian_counts():
+    from oracle import threshold as th
+    rng = np.random.default_rng(11)
+    x = rng.normal(0.3, 0.07, 200_000)
+    mu, var = th.moments(x)
+    assert mu == pytest.approx(x.mean(), rel=1e-12) and var == pytest.approx(x.var(), rel=1e-10)
+    for u in (0.45, 0.5, 0.55):
+        lam = th.exceedance_rate(len(x), mu, math.sqrt(var), u)
+        cnt = int((x > u).sum())
+        assert abs(cnt - lam) <= 4 * math.sqrt(lam) + 0.02 * lam
+
+
+def test_compression_corollary_closed_forms():
+    from oracle import threshold as th
+    cr, p0 = th.predicted_compression([10.0, 30.0], 100.0)        # 200 blocks, 40 expected fusions
+    assert cr == pytest.approx(200.0 / 160.0, rel=1e-15)
+    assert p0[0] == pytest.approx(math.exp(-10.0)) and p0[1] == pytest.approx(math.exp(-30.0))
+    cr, p0 = th.predicted_compression([math.log(2.0)], 50.0)
+    assert p0[0] == pytest.approx(0.5, rel=1e-15)
+    cr, p0 = th.predicted_compression([0.0, 0.0, 0.0], 64.0)
+    assert cr == 1.0 and (p0 == 1.0).all()
+
+
+def test_pair_cosines_and_feedback_direction():
+    from oracle import threshold as th
+    K = np.array([[1.0, 0.0], [1.2, 1.6], [0.0, 3.0], [0.0, 0.0], [2.0, 0.0]])
+    bt = np.array([4, 1, 2, 3, 0])             # logical -> physical
+    cos = th.pair_cosines(K, bt, np.array([[0, 1], [0, 2], [1, 2], [0, 4], [3, 1]]))
+    assert cos == pytest.approx([0.6, 0.0, 0.8, 1.0, 0.0], abs=1e-15)
+    assert th.feedback_step(0.9, 2.0, 1.5, 0.1, 0.5, 0.99) > 0.9       # too much compression: raise
+    assert th.feedback_step(0.9, 1.1, 1.5, 0.1, 0.5, 0.99) < 0.9       # too little: lower
+    assert th.feedback_step(0.9, 1.5, 1.5, 0.1, 0.5, 0.99) == 0.9
+    assert th.feedback_step(0.98, 9.0, 1.5, 0.5, 0.5, 0.99) == 0.99    # clamped
