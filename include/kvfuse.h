@@ -271,6 +271,44 @@ int kvfuse_shared_decode_plan_destroy(kvfuse_decode_plan *plan);
 int kvfuse_paged_decode_attn_shared(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table,
                                     const kvfuse_decode_plan *plan, const void *q, float sm_scale, float *out);
 
+/* ---- threshold control ------------------------------------------------------------------------------- */
+
+/* Analysis section: with a layer's block similarities approximately Gaussian (mean mu_l and variance sigma_l^2 =
+ * the sample moments of n similarities), the number of similarities above a threshold u is approximately Poisson
+ * with rate Lambda_l(u) = n (1 - Phi((u - mu_l) / sigma_l)); the corollary gives the compression ratio over L
+ * layers, L m / (L m - sum_l Lambda_l(u)) with m blocks per layer, and the probability that a layer fuses
+ * nothing, exp(-Lambda_l(u)), which allows skipping such layers.  Method section, remark on self-adjusting
+ * thresholds: feedback on the observed compression. */
+
+/* Cosines of sampled pairs of logical blocks (keys), through the block table, for every group of the pool.
+ *   pairs   device [n_pairs][2] int32 logical indices in [0, table.n), the same list for all groups (the caller
+ *           draws them; out-of-range indices are clamped)
+ *   cos_out device [G][n_pairs] double;  a pair with a zero block gives 0
+ * Needs pool.norm_k to be current (kvfuse_block_norms, or a finished fusion).  Asynchronous. */
+int kvfuse_pair_cosines(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table, const int32_t *pairs,
+                        int32_t n_pairs, double *cos_out);
+
+/* Per group, mean and (population) variance of its n_pairs cosines: moments device [G][2] double.  Fixed summation
+ * order.  Average the groups of a layer on the host for the per-layer figures of the paper.  Asynchronous. */
+int kvfuse_cosine_moments(kvfuse_ctx *ctx, const double *cos_in, int32_t G, int32_t n_pairs, double *moments);
+
+/* Host-only closed forms (no context, no device).  Lambda(u) for n similarities; the u that gives a wanted rate
+ * (NaN unless 0 < rate < n and sigma > 0); the corollary (p_no_fusion: host [n_layers] or NULL); one step of
+ * target-compression feedback, thr + gain * (observed - target) / target clamped to [lo, hi]: compression above
+ * the target raises the threshold. */
+double kvfuse_exceedance_rate(double n, double mu, double sigma, double u);
+double kvfuse_threshold_for_rate(double n, double mu, double sigma, double rate);
+int kvfuse_predict_compression(const double *rates, int32_t n_layers, double blocks_per_layer, double *compression_ratio,
+                               double *p_no_fusion);
+double kvfuse_threshold_feedback(double thr, double observed_cr, double target_cr, double gain, double lo, double hi);
+
+/* Switch groups off for the following kvfuse_similarity / kvfuse_fuse_tree calls on this plan: enable is a device
+ * array [G] of bytes (0 = skip: the group's similarity work items exit at once, its candidate lists stay empty and
+ * nothing in it fuses; the other steps run and leave the group as it is), or NULL for all groups.  The array is
+ * read during those calls and must stay alive; it is also copied to the host here for the statistics (this call
+ * waits for the stream). */
+int kvfuse_plan_set_group_mask(kvfuse_ctx *ctx, kvfuse_plan *plan, const uint8_t *enable);
+
 /* ---- machine probes (measurement aids; not part of the hot path) -------------------------------------- */
 
 #define KVFUSE_PROBE_SCRATCH_BYTES 65792

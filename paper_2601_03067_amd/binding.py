@@ -98,6 +98,16 @@ lib.kvfuse_shared_decode_plan_build.argtypes = [_vp, C.POINTER(Pool), C.POINTER(
 lib.kvfuse_shared_decode_plan_upload.argtypes = [_vp, _vp, _vp, C.c_size_t]
 lib.kvfuse_shared_decode_plan_destroy.argtypes = [_vp]
 lib.kvfuse_paged_decode_attn_shared.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _vp, _vp, C.c_float, _vp]
+lib.kvfuse_pair_cosines.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _vp, _i32, _vp]
+lib.kvfuse_cosine_moments.argtypes = [_vp, _vp, _i32, _i32, _vp]
+lib.kvfuse_exceedance_rate.argtypes = [_f64, _f64, _f64, _f64]
+lib.kvfuse_exceedance_rate.restype = _f64
+lib.kvfuse_threshold_for_rate.argtypes = [_f64, _f64, _f64, _f64]
+lib.kvfuse_threshold_for_rate.restype = _f64
+lib.kvfuse_predict_compression.argtypes = [C.POINTER(_f64), _i32, _f64, C.POINTER(_f64), C.POINTER(_f64)]
+lib.kvfuse_threshold_feedback.argtypes = [_f64] * 6
+lib.kvfuse_threshold_feedback.restype = _f64
+lib.kvfuse_plan_set_group_mask.argtypes = [_vp, _vp, _vp]
 lib.kvfuse_probe_mfma_bf16.argtypes = [_vp, _i32, _vp, C.c_size_t, C.POINTER(C.c_double)]
 lib.kvfuse_probe_copy.argtypes = [_vp, _vp, _vp, C.c_size_t, _i32, C.POINTER(C.c_double)]
 PROBE_SCRATCH_BYTES = 65792
@@ -293,6 +303,56 @@ def paged_decode_attn(ctx, cache, kv_heads, q, req_start, ctx_len, max_blocks, l
                                            _ptr(q), _ptr(req_start), _ptr(ctx_len), B, Hq, max_blocks, sm_scale,
                                            _ptr(workspace), workspace.numel(), _ptr(out)))
     return out
+
+
+def pair_cosines(ctx, cache, pairs, out=None):
+    """pairs: int32 tensor [n_pairs][2] of logical indices (device) -> float64 tensor [G][n_pairs] of key cosines."""
+    assert pairs.dtype == torch.int32 and pairs.is_contiguous() and pairs.dim() == 2 and pairs.shape[1] == 2
+    n_pairs = pairs.shape[0]
+    if out is None:
+        out = torch.empty(cache.pool.G, n_pairs, device=pairs.device, dtype=torch.float64)
+    ctx.check(lib.kvfuse_pair_cosines(ctx.h, C.byref(cache.pool), C.byref(cache.table), _ptr(pairs), n_pairs, _ptr(out)))
+    return out
+
+
+def cosine_moments(ctx, cos):
+    """float64 [G][n_pairs] -> float64 [G][2] (mean, population variance)."""
+    assert cos.dtype == torch.float64 and cos.is_contiguous() and cos.dim() == 2
+    out = torch.empty(cos.shape[0], 2, device=cos.device, dtype=torch.float64)
+    ctx.check(lib.kvfuse_cosine_moments(ctx.h, _ptr(cos), cos.shape[0], cos.shape[1], _ptr(out)))
+    return out
+
+
+def exceedance_rate(n, mu, sigma, u):
+    return lib.kvfuse_exceedance_rate(n, mu, sigma, u)
+
+
+def threshold_for_rate(n, mu, sigma, rate):
+    return lib.kvfuse_threshold_for_rate(n, mu, sigma, rate)
+
+
+def predict_compression(rates, blocks_per_layer):
+    """-> (compression ratio, [probability of no fusion per layer])."""
+    L = len(rates)
+    arr = (_f64 * L)(*[float(r) for r in rates])
+    p0 = (_f64 * L)()
+    cr = _f64(0.0)
+    rc = lib.kvfuse_predict_compression(arr, L, float(blocks_per_layer), C.byref(cr), p0)
+    if rc:
+        raise KvfuseError(rc, "kvfuse_predict_compression: bad arguments")
+    return cr.value, list(p0)
+
+
+def threshold_feedback(thr, observed_cr, target_cr, gain, lo, hi):
+    return lib.kvfuse_threshold_feedback(thr, observed_cr, target_cr, gain, lo, hi)
+
+
+def set_group_mask(ctx, plan, enable):
+    """enable: uint8 tensor [G] on the device (kept alive by the plan object), or None for all groups."""
+    if enable is not None:
+        assert enable.dtype == torch.uint8 and enable.is_contiguous() and enable.numel() == plan.cache.pool.G
+    plan.group_mask = enable
+    ctx.check(lib.kvfuse_plan_set_group_mask(ctx.h, plan.h, _ptr(enable) if enable is not None else None))
 
 
 class SharedDecodePlan:

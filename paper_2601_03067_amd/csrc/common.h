@@ -84,6 +84,7 @@ struct WorkDesc {
     int32_t *refine;     // [G * r_stride] columns (g * r_stride + c) that need the fp64 re-check
     int32_t *n_refine;   // [max_heights]
     int32_t *counters;   // [G][8]: 0 fused, 1 near-threshold, 2 refined, 3 candidate overflow, 4 invalid ids
+    const uint8_t *group_enable;   // [G] or null: groups with 0 are skipped by the similarity step (nothing fuses)
 };
 
 struct PoolDesc {
@@ -124,6 +125,11 @@ size_t decode_workspace_bytes(int n_layers, int B, int Hq, int kv_heads, int d, 
 int launch_decode(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, int kv_heads, int layer_begin, int n_layers,
                   const void *q, const int32_t *req_start, const int32_t *ctx_len, int B, int Hq, int max_blocks,
                   float sm_scale, void *workspace, size_t workspace_bytes, float *out);
+
+// threshold statistics (threshold.hip)
+void launch_pair_cosines(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, const int32_t *pairs, int n_pairs,
+                         double *cos_out);
+void launch_cosine_moments(hipStream_t s, const double *cos_in, int G, int n_pairs, double *moments);
 
 // machine probes (probe.hip)
 constexpr size_t kProbeScratchBytes = 65536 + 256;     // 4096 operand chunks of 16 bytes + a sink word

@@ -42,6 +42,7 @@ struct Plan {
     std::vector<HostHeight> heights;
     int32_t *slot_init = nullptr;   // device [n_slots]
     int max_r = 0, max_l = 0;
+    std::vector<uint8_t> group_enable_host;   // copy of the group mask for the statistics; empty = all groups
 };
 
 // Similarity tile shapes (must match the two kernel instantiations): big 256 x 256, small 128 x 128.
@@ -242,6 +243,7 @@ static void carve(Carver &cv, int G, int n, int n_slots, int max_r, int max_l, i
     w.refine = cv.take<int32_t>(R);
     w.n_refine = cv.take<int32_t>(kMaxHeights);
     w.counters = cv.take<int32_t>((size_t)G * 8);
+    w.group_enable = nullptr;
     slot_init = cv.take<int32_t>(n_slots);
     for (HostHeight &h : hs) {
         const size_t nn = h.l_off.size();
@@ -640,13 +642,14 @@ int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band
     KVF_TRY(hipMemcpy(cnt.data(), w.set_cnt, cnt.size() * 4, hipMemcpyDeviceToHost));
     int64_t invalid = 0;
     for (int g = 0; g < w.G; ++g) {
+        const bool on = p.group_enable_host.empty() || p.group_enable_host[(size_t)g] != 0;
         stats->fused += counters[(size_t)g * 8 + 0];
         stats->near_threshold += counters[(size_t)g * 8 + 1];
         stats->refined += counters[(size_t)g * 8 + 2];
         stats->cand_overflow += counters[(size_t)g * 8 + 3];
         invalid += counters[(size_t)g * 8 + 4];
         for (const Node &nd : p.nodes)
-            if (nd.left >= 0)
+            if (nd.left >= 0 && on)
                 stats->sim_flops += 2.0 * (double)cnt[(size_t)g * w.n_slots + nd.left] *
                                     (double)cnt[(size_t)g * w.n_slots + nd.right] * (double)p.pool.r;
     }
@@ -657,6 +660,24 @@ int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band
         return fail(c, KVFUSE_EINVAL, "block table holds " + std::to_string(invalid) + " ids outside [0, P)");
     return KVFUSE_OK;
 #undef KVF_TRY
+}
+
+int kvfuse_plan_set_group_mask(kvfuse_ctx *ctx, kvfuse_plan *plan, const uint8_t *enable)
+{
+    if (!ctx)
+        return KVFUSE_EINVAL;
+    Ctx *c = &ctx->c;
+    if (!plan)
+        return fail(c, KVFUSE_EINVAL, "group mask: null plan");
+    Plan &p = plan->p;
+    p.group_enable_host.clear();
+    p.work.group_enable = enable;
+    if (enable && p.work.G > 0) {
+        p.group_enable_host.resize((size_t)p.work.G);
+        KVF_HIP(c, hipStreamSynchronize(c->stream));
+        KVF_HIP(c, hipMemcpy(p.group_enable_host.data(), enable, (size_t)p.work.G, hipMemcpyDeviceToHost));
+    }
+    return KVFUSE_OK;
 }
 
 int kvfuse_decode_workspace_bytes(int32_t n_layers, int32_t B, int32_t Hq, int32_t kv_heads, int32_t d, int32_t max_blocks,

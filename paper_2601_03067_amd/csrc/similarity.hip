@@ -81,7 +81,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN * TM * TN >= 64 ? 1 : 2)) vo
     const int32_t *__restrict__ r_off, const int32_t *__restrict__ l_slot, const int32_t *__restrict__ r_slot,
     const int32_t *__restrict__ r_base, const int32_t *__restrict__ r_cap, const int64_t *__restrict__ s_base,
     unsigned long long *__restrict__ best_packed, int32_t *__restrict__ cand_cnt, int32_t *__restrict__ cand_idx,
-    float *__restrict__ cand_val, float *__restrict__ dense_s)
+    float *__restrict__ cand_val, float *__restrict__ dense_s, const uint8_t *__restrict__ group_enable)
 {
     constexpr int NT = 64 * WM * WN;
     constexpr int BM = WM * TM * 32;
@@ -117,6 +117,8 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN * TM * TN >= 64 ? 1 : 2)) vo
     if (v >= (long long)A.G * A.n_items)
         return;
     const int g = (int)(v / A.n_items);
+    if (group_enable && !group_enable[g])      // a switched-off group keeps empty candidate lists: nothing fuses
+        return;
     const int item = (int)(v - (long long)g * A.n_items);
     const int node = item_node[item];
     const int col0 = item_col0[item];
@@ -419,7 +421,7 @@ __global__ __launch_bounds__(512, 1) void similarity_ring_kernel(
     const int32_t *__restrict__ r_off, const int32_t *__restrict__ l_slot, const int32_t *__restrict__ r_slot,
     const int32_t *__restrict__ r_base, const int32_t *__restrict__ r_cap, const int64_t *__restrict__ s_base,
     unsigned long long *__restrict__ best_packed, int32_t *__restrict__ cand_cnt, int32_t *__restrict__ cand_idx,
-    float *__restrict__ cand_val, float *__restrict__ dense_s)
+    float *__restrict__ cand_val, float *__restrict__ dense_s, const uint8_t *__restrict__ group_enable)
 {
     constexpr int WN = 2, TM = 2, TN = 4, NT = 512, BM = 256, BN = 256;
     constexpr int STAGE = (BM + BN) * 64;
@@ -443,6 +445,8 @@ __global__ __launch_bounds__(512, 1) void similarity_ring_kernel(
     if (v >= (long long)A.G * A.n_items)
         return;
     const int g = (int)(v / A.n_items);
+    if (group_enable && !group_enable[g])      // a switched-off group keeps empty candidate lists: nothing fuses
+        return;
     const int item = (int)(v - (long long)g * A.n_items);
     const int node = item_node[item];
     const int col0 = item_col0[item];
@@ -749,7 +753,8 @@ static void launch_cfg(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, c
 #define KVF_SIM_LAUNCH(D)                                                                                              \
     similarity_kernel<T, WM, WN, TM, TN, D><<<grid, 64 * WM * WN, 0, s>>>(                                             \
         A, (const char *)pool.k, pool.inv_norm_k, w.set_ids, w.set_cnt, tt.node, tt.col0, tt.row0, tt.rows, h.l_off, h.r_off, \
-        h.l_slot, h.r_slot, h.r_base, h.r_cap, h.s_base, w.best_packed, w.cand_cnt, w.cand_idx, w.cand_val, dense_s)
+        h.l_slot, h.r_slot, h.r_base, h.r_cap, h.s_base, w.best_packed, w.cand_cnt, w.cand_idx, w.cand_val, dense_s,           \
+        w.group_enable)
     if (dense_s)
         KVF_SIM_LAUNCH(true);
     else
@@ -774,7 +779,8 @@ static void launch_ring(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, 
 #define KVF_SIM_LAUNCH(D)                                                                                              \
     similarity_ring_kernel<T, D><<<grid, 512, 0, s>>>(                                                                 \
         A, (const char *)pool.k, pool.inv_norm_k, w.set_ids, w.set_cnt, tt.node, tt.col0, tt.row0, tt.rows, h.l_off, h.r_off, \
-        h.l_slot, h.r_slot, h.r_base, h.r_cap, h.s_base, w.best_packed, w.cand_cnt, w.cand_idx, w.cand_val, dense_s)
+        h.l_slot, h.r_slot, h.r_base, h.r_cap, h.s_base, w.best_packed, w.cand_cnt, w.cand_idx, w.cand_val, dense_s,           \
+        w.group_enable)
     if (dense_s)
         KVF_SIM_LAUNCH(true);
     else

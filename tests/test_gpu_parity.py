@@ -424,6 +424,68 @@ def test_shared_decode_rejects_bad_arguments(kb):
         kb.SharedDecodePlan(ctx, cache, rec.kv_heads, rec.req_start, rec.ctx_len, rec.q_heads, min_cluster_blocks=0)
 
 
+# ------------------------------------------------------------------------------------------ threshold control
+
+@pytest.mark.parametrize("kind", ["bf16_fused", "f32_tiny"])
+def test_pair_cosines_and_moments_match_oracle(kb, kind):
+    """Sampled pair cosines through the (fused) table and their per-group moments against the definition."""
+    import oracle as oracle_pkg
+    from oracle import threshold as th
+    _say("pair cosines", kind)
+    rec = _small_bf16(n_req=5, tokens=640, kv_heads=2) if kind == "bf16_fused" else wl.tiny_bff()
+    mat = wl.materialise(rec, DEV, phys_perm=True)
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat)
+    assert stats.fused > 0
+    rng = np.random.default_rng(17)
+    n_pairs = 777
+    pairs_h = rng.integers(0, rec.n, size=(n_pairs, 2)).astype(np.int32)
+    pairs_h[0] = (3, 3)                                    # a block with itself
+    pairs = torch.tensor(pairs_h, device=DEV)
+    cos = kb.pair_cosines(ctx, cache, pairs)
+    mom = kb.cosine_moments(ctx, cos)
+    torch.cuda.synchronize()
+    cos_h, mom_h = cos.cpu().numpy(), mom.cpu().numpy()
+    for g in range(rec.G):
+        Kf = oracle_pkg.pool_to_f64(wl.to_numpy_pool(cache.K[g]))
+        want = th.pair_cosines(Kf.reshape(Kf.shape[0], -1), cache.bt[g].cpu().numpy(), pairs_h)
+        np.testing.assert_allclose(cos_h[g], want, rtol=1e-12, atol=1e-15)
+        assert cos_h[g][0] == pytest.approx(1.0, abs=1e-14)
+        mu, var = th.moments(want)
+        assert mom_h[g][0] == pytest.approx(mu, rel=1e-11, abs=1e-14) and mom_h[g][1] == pytest.approx(var, rel=1e-10)
+    # the library's rate on these moments equals the oracle's
+    mu, var = float(mom_h[0][0]), float(mom_h[0][1])
+    assert kb.exceedance_rate(1e6, mu, math.sqrt(var), rec.thr) == pytest.approx(th.exceedance_rate(1e6, mu, math.sqrt(var), rec.thr), rel=1e-12, abs=1e-300)
+
+
+def test_group_mask_skips_groups_and_leaves_the_rest_unchanged(kb, oracle):
+    """A switched-off group comes out of the tree untouched; the other groups are bit-identical to an unmasked run."""
+    _say("group mask")
+    rec = _small_bf16(n_req=6, tokens=800, kv_heads=4)
+    mat_a = wl.materialise(rec, DEV, phys_perm=True)
+    cache_a, plan_a, stats_a, ctx = gu.gpu_fuse(rec, mat_a)
+    mat_b = wl.materialise(rec, DEV, phys_perm=True)
+    K0, V0, bt0 = mat_b["K"].clone(), mat_b["V"].clone(), mat_b["bt"].clone()
+    cache_b = kb.Cache(mat_b["K"], mat_b["V"], mat_b["bt"], rec.t, rec.d)
+    plan_b = kb.Plan(ctx, cache_b, kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr, rec.group_size), 16)
+    mask = torch.tensor([1, 0, 1, 0], dtype=torch.uint8, device=DEV)
+    kb.set_group_mask(ctx, plan_b, mask)
+    stats_b = kb.fuse_tree(ctx, plan_b, rec.thr, want_stats=True)
+    torch.cuda.synchronize()
+    for g in range(rec.G):
+        if int(mask[g]):
+            assert torch.equal(cache_b.bt[g], cache_a.bt[g]) and torch.equal(cache_b.K[g], cache_a.K[g])
+            assert torch.equal(cache_b.V[g], cache_a.V[g]) and torch.equal(cache_b.scale_k[g], cache_a.scale_k[g])
+        else:
+            assert torch.equal(cache_b.bt[g], bt0[g]) and torch.equal(cache_b.K[g], K0[g]) and torch.equal(cache_b.V[g], V0[g])
+            assert bool((cache_b.scale_k[g] == 1).all()) and bool((cache_b.refcount[g][bt0[g].long()] == 1).all())
+    assert 0 < stats_b.fused < stats_a.fused and stats_b.sim_flops < stats_a.sim_flops
+    # and back to all groups
+    kb.set_group_mask(ctx, plan_b, None)
+    cache_b.K.copy_(K0); cache_b.V.copy_(V0); cache_b.bt.copy_(bt0)
+    stats_c = kb.fuse_tree(ctx, plan_b, rec.thr, want_stats=True)
+    assert stats_c.fused == stats_a.fused and torch.equal(cache_b.bt, cache_a.bt)
+
+
 # ------------------------------------------------------------------------------------------ machine probes
 
 def test_machine_probes_run_and_copy_is_exact(kb):
