@@ -374,10 +374,16 @@ class SharedDecodePlan:
         self.workspace = torch.empty(int(self.info.device_bytes), device=cache.K.device, dtype=torch.uint8)
         ctx.check(lib.kvfuse_shared_decode_plan_upload(ctx.h, self.h, _ptr(self.workspace), self.workspace.numel()))
 
-    def __del__(self):
+    def close(self):
         if getattr(self, "h", None):
             lib.kvfuse_shared_decode_plan_destroy(self.h)
             self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:       # interpreter shutdown: the module globals may already be gone
+            pass
 
 
 def paged_decode_attn_shared(ctx, cache, plan, q, sm_scale=None, out=None):

@@ -83,6 +83,65 @@ def test_llama8b_bff_full_size_sampled_groups_and_invariants(oracle):
     assert worst <= 2e-2
 
 
+@pytest.mark.timeout(600)
+def test_cff_long_full_size_sampled_groups_and_invariants(oracle):
+    """Config 3 at full size: one request of 32768 tokens in 16 chunk leaves, 256 groups.  Sampled groups exactly,
+    every group through invariants, the single long-context decode output of sampled layers against the oracle
+    (exercises the split path of the decode kernel at its real length)."""
+    kb = gu.load_binding()
+    rec = wl.cff_long()
+    print("materialise", rec.name, "G", rec.G, "n", rec.n, flush=True)
+    mat = wl.materialise(rec, DEV)
+    rng = np.random.default_rng(20260103 + 3)
+    sample = sorted({0, rec.G - 1, *rng.choice(rec.G, size=4, replace=False).tolist()})
+    host = {g: (wl.to_numpy_pool(mat["K"][g]), wl.to_numpy_pool(mat["V"][g]), mat["bt"][g].cpu().numpy().copy()) for g in sample}
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, cand_cap=16)
+    print("gpu fused", stats.fused, "CR", stats.compression_ratio, "refined", stats.refined, flush=True)
+    n, P = rec.n, rec.n
+    bt = cache.bt.cpu().numpy()
+    rc = cache.refcount.cpu().numpy()
+    remap = cache.remap.cpu().numpy()
+    n_phys = cache.n_phys.cpu().numpy()
+    n_free = cache.n_free.cpu().numpy()
+    sk = cache.scale_k.cpu().numpy()
+    assert stats.fused > 0 and (rc.sum(1) == n).all()
+    assert stats.physical_blocks == int(n_phys.sum()) and math.isclose(stats.compression_ratio, rec.G * n / n_phys.sum())
+    cb = int(rec.leaf_count[0])
+    for g in range(rec.G):
+        live = np.unique(bt[g])
+        assert len(live) == n_phys[g] and n_phys[g] + n_free[g] == P
+        assert (remap[g][live] == -1).all() and np.array_equal(np.bincount(bt[g], minlength=P), rc[g])
+        assert np.array_equal(bt[g][:cb], np.arange(cb))          # blocks of one leaf never fuse with each other (chunk 0)
+        assert (sk[g][rc[g][bt[g]] == 1] == 1.0).all()
+    print("oracle on groups", sample, flush=True)
+    res = gu.oracle_fuse(oracle, rec, ([host[g][0] for g in sample], [host[g][1] for g in sample], [host[g][2] for g in sample]),
+                         threads=len(sample))
+    safe = gu.check_ambiguity(res, "cff_long full size")
+    assert len(safe) >= len(sample) - 1
+    for i in safe:
+        gu.compare_group(res[i], _GroupView(cache, sample[i]), 0, False, f"cff full size group {sample[i]}")
+    print("sampled groups match", flush=True)
+    q = wl.queries(rec, DEV)
+    rs = torch.tensor(rec.req_start, dtype=torch.int32, device=DEV)
+    cl = torch.tensor(rec.ctx_len, dtype=torch.int32, device=DEV)
+    out = kb.paged_decode_attn(ctx, cache, rec.kv_heads, q, rs, cl, int(rec.req_blocks.max()))
+    splan = kb.SharedDecodePlan(ctx, cache, rec.kv_heads, rec.req_start, rec.ctx_len, rec.q_heads)
+    out_sh = kb.paged_decode_attn_shared(ctx, cache, splan, q)
+    torch.cuda.synchronize()
+    assert splan.info.clusters == 0                               # one request: nothing is shared between requests
+    assert float((out - out_sh).abs().max()) <= 1e-5
+    worst = 0.0
+    for layer in (0, 13, rec.layers - 1):
+        gs = [layer * rec.kv_heads + h for h in range(rec.kv_heads)]
+        ref = oracle.paged_decode_attention(
+            q[layer].float().cpu().numpy(), [wl.to_numpy_pool(cache.K[g]) for g in gs],
+            [wl.to_numpy_pool(cache.V[g]) for g in gs], [bt[g] for g in gs], [sk[g].astype(np.float64) for g in gs],
+            [cache.scale_v[g].cpu().numpy().astype(np.float64) for g in gs], rec.req_start, rec.ctx_len, rec.t, rec.d)
+        worst = max(worst, float(np.abs(out[layer].cpu().numpy() - ref).max()))
+    print("decode max abs err on sampled outputs", worst, flush=True)
+    assert worst <= 2e-2
+
+
 class _GroupView:
     """Presents group g of a big cache as group 0 to gu.compare_group."""
 
