@@ -165,11 +165,11 @@ def test_single_node_steps_match_oracle(kb, oracle, kind, cand_cap):
 
 # ------------------------------------------------------------------------------------------ whole tree
 
-def _run_tree_case(kb, oracle, rec, name, cand_cap=16, thr=None, phys_perm=True, group_size=None, groups=None):
+def _run_tree_case(kb, oracle, rec, name, cand_cap=16, thr=None, phys_perm=True, group_size=None, groups=None, band=1e-3):
     _say("tree case", name, "G", rec.G, "n", rec.n, "r", rec.r, "leaves", len(rec.leaf_start), "cand_cap", cand_cap)
     mat = wl.materialise(rec, DEV, groups=groups, phys_perm=phys_perm)
     host = gu.host_copy(mat)
-    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, thr=thr, cand_cap=cand_cap, group_size=group_size)
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, thr=thr, cand_cap=cand_cap, group_size=group_size, band=band)
     res = gu.oracle_fuse(oracle, rec, host, thr=thr, group_size=group_size)
     safe = gu.check_ambiguity(res, name)
     for g in safe:
@@ -242,6 +242,27 @@ def test_tree_zipf_many_near_ties(kb, oracle):
     rec = wl.zipf_bff(n_req=8, tokens=32 * 40, layers=1, kv_heads=2, pool=60, t=32, d=64, thr=0.9)
     cache, plan, stats, res, mat = _run_tree_case(kb, oracle, rec, "zipf_small", cand_cap=8)
     assert stats.refined > 20
+
+
+@pytest.mark.parametrize("shape", ["r4096_bf16", "r8192_bf16", "r2048_f32"])
+def test_tree_long_blocks(kb, oracle, shape):
+    """Block lengths beyond the bench shape: config 4's 32 x 128 blocks (8 KiB rows: 128 K-slices per row in the
+    similarity kernels, two-wavefront merge items), the longest supported block (t*d = 8192: workgroup-per-target
+    merge) and binary32 blocks of 8 KiB.  Sets are large enough for the 256 x 256 tiles at the upper heights."""
+    if shape == "r4096_bf16":
+        rec = wl.zipf_bff(n_req=6, tokens=32 * 150, layers=1, kv_heads=2, pool=400, t=32, d=128, thr=0.9)
+    elif shape == "r8192_bf16":
+        rec = wl.zipf_bff(n_req=4, tokens=64 * 90, layers=1, kv_heads=1, pool=200, t=64, d=128, thr=0.9)
+    else:
+        rec = wl.zipf_bff(n_req=4, tokens=16 * 150, layers=1, kv_heads=1, pool=300, t=16, d=128, thr=0.9, dtype=torch.float32)
+    # the screen's error bound grows with the block length: the band must be at least r * 2^-22
+    cache, plan, stats, res, mat = _run_tree_case(kb, oracle, rec, "long_blocks_" + shape, cand_cap=8,
+                                                  band=max(1e-3, 1.25 * rec.r * 2.0 ** -22))
+    assert stats.fused > 50
+    q = wl.queries(rec, DEV)
+    out = _decode(kb, ctx=kb.Context(DEV), rec=rec, cache=cache, q=q)
+    ref = _attn_oracle(oracle, rec, cache, q[0], 0, rec.kv_heads)
+    assert np.abs(out[0] - ref).max() <= (1e-4 if rec.dtype == torch.float32 else 5e-3)
 
 
 def test_tree_is_deterministic(kb):
