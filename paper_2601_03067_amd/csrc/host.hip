@@ -191,9 +191,9 @@ static void build_heights(const std::vector<Node> &nodes, std::vector<HostHeight
             const int n_rtile = (h.l_cap[k] + bm - 1) / bm;
             if (n_cp == 0 || n_rtile == 0)
                 continue;
-            // row tiles per work item: about 4 chunks per panel; the big-tile kernel keeps the row ids of one item
-            // in registers and takes at most 4 row tiles per item
-            const int rt = h.big ? std::min((n_rtile + 3) / 4, 4) : (n_rtile + 3) / 4;
+            // row tiles per work item: about 4 chunks per panel; the kernel keeps the row ids of one item in registers
+            // and takes at most 4 row tiles per item
+            const int rt = std::min((n_rtile + 3) / 4, 4);
             const int n_rc = (n_rtile + rt - 1) / rt;
             for (int cpg = 0; cpg < n_cp; cpg += 8)
                 for (int rc = 0; rc < n_rc; ++rc)

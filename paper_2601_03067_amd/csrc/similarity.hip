@@ -6,7 +6,7 @@
 // the fp32 accumulators by the two inverse norms, keeps the column maximum and appends every entry above the
 // candidate floor to the column's candidate list.
 //
-// Work decomposition.  A work item is (group, node, panel of BN right blocks, chunk of up to RT tiles of BM left
+// Work decomposition.  A work item is (group, node, panel of BN right blocks, chunk of up to 4 tiles of BM left
 // blocks); one workgroup per item.  Items are numbered so that consecutive ones form a 2-D patch of one node
 // (8 panels x several chunks), and hardware workgroup ids are renumbered so that each XCD walks a contiguous range
 // of items: the workgroups resident on one XCD then share both their left tiles and their right panels through
@@ -14,11 +14,29 @@
 // global memory through integer atomics only (64-bit max of (ordered cosine, inverted row), 32-bit slot counters),
 // so the outcome does not depend on scheduling.
 //
-// Tiling.  WM x WN wavefronts, each TM x TN MFMA tiles of 32 x 32 (v_mfma_f32_32x32x16_bf16, or 4 x
-// v_mfma_f32_32x32x2_f32 per 16-byte fragment for f32 pools).  K is walked in 128-byte slices per row, double
-// buffered in LDS with a 16-byte-chunk XOR swizzle (chunk ^ ((row >> 1) & 7)): the LDS has 64 four-byte banks, so
-// two 128-byte rows make one sweep over the banks, and with this swizzle both the 16-byte stores (16 lanes = 2 rows x
-// 8 chunks) and the MFMA fragment reads (16 lanes = 16 rows, one chunk) touch every bank exactly once.  Global loads of the next slice are in flight during the MFMAs.
+// Tiling.  WM x 2 wavefronts, each 2 x TN MFMA tiles of 32 x 32 (v_mfma_f32_32x32x16_bf16, or 4 x
+// v_mfma_f32_32x32x2_f32 per 16-byte fragment for f32 pools): 256 x 256 with 8 wavefronts, or 128 x 128 with 4 for
+// nodes whose sets are smaller than that.
+//
+// K is walked in 64-byte slices per row.  A ring of four LDS stages (each BM left + BN right rows x 64 bytes) is
+// filled by global_load_lds_dwordx4: the data never passes through registers, so two slices can be in flight
+// while one is being multiplied and one is ready, with no staging registers at all.  Every wavefront issues four
+// such loads per slice (1 KB each: 16 rows x 64 bytes).  A load writes LDS at (wave-uniform base + lane * 16), so
+// the XOR swizzle that keeps the fragment reads conflict-free (the LDS has 64 four-byte banks) is applied on the
+// global side: lane L covers row L / 4 and fetches logical 16-byte chunk (L & 3) ^ ((row >> 2) & 3) of that row's
+// slice.
+//
+// Fragment reads are ds_read_b128 in inline assembly.  The compiler cannot tell that they never touch a stage
+// that is still being filled and would otherwise wait for every outstanding global -> LDS load before each LDS
+// read.  Each read's destination registers are handed to the following wait statement as in/out operands, which
+// is what orders the MFMAs behind the wait.  Fragments are double buffered (one set per 32-byte half slice), and
+// the first half of slice j + 1 is read before the barrier that ends iteration j; that is legal because the loads
+// of slice j + 1 were completed before the previous barrier.
+//
+// Iteration j (slice j in stage j & 3):   read set1 <- slice j, second half;  MFMAs on set0 + 2 loads of slice
+// j + 3;  wait set1;  read set0 <- slice j + 1, first half;  MFMAs on set1 + 2 loads;  wait until only this
+// iteration's 4 loads are outstanding;  barrier.  The stage written in iteration j held slice j - 1, which every
+// wavefront finished reading before the previous barrier.
 #include "common.h"
 
 namespace kvfuse {
@@ -26,25 +44,6 @@ namespace kvfuse {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-template <typename T> struct Mma;
-template <> struct Mma<bf16_t> {
-    __device__ static __forceinline__ floatx16 run(const uint4 a, const uint4 b, floatx16 c)
-    {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    }
-};
-template <> struct Mma<float> {
-    // One 16-byte fragment holds 4 consecutive floats of a row; lane halves hold different chunks.  Element e of
-    // both operands pairs up, which is a valid k-assignment because A and B use the same one.
-    __device__ static __forceinline__ floatx16 run(const uint4 a, const uint4 b, floatx16 c)
-    {
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
-        return c;
-    }
-};
 
 // (cosine, row) packed so that an unsigned 64-bit max picks the larger cosine and, on equal cosines, the lower row.
 __device__ __forceinline__ unsigned long long pack_best(float s, int row)
@@ -73,324 +72,6 @@ struct SimArgs {
     int64_t total_s;
 };
 
-template <typename T, int WM, int WN, int TM, int TN, bool DENSE>
-__global__ __launch_bounds__(64 * WM * WN, (WM * WN * TM * TN >= 64 ? 1 : 2)) void similarity_kernel(
-    SimArgs A, const char *__restrict__ kpool, const float *__restrict__ inv_norm, const int32_t *__restrict__ set_ids,
-    const int32_t *__restrict__ set_cnt, const int32_t *__restrict__ item_node, const int32_t *__restrict__ item_col0,
-    const int32_t *__restrict__ item_row0, const int32_t *__restrict__ item_rows, const int32_t *__restrict__ l_off,
-    const int32_t *__restrict__ r_off, const int32_t *__restrict__ l_slot, const int32_t *__restrict__ r_slot,
-    const int32_t *__restrict__ r_base, const int32_t *__restrict__ r_cap, const int64_t *__restrict__ s_base,
-    unsigned long long *__restrict__ best_packed, int32_t *__restrict__ cand_cnt, int32_t *__restrict__ cand_idx,
-    float *__restrict__ cand_val, float *__restrict__ dense_s, const uint8_t *__restrict__ group_enable)
-{
-    constexpr int NT = 64 * WM * WN;
-    constexpr int BM = WM * TM * 32;
-    constexpr int BN = WN * TN * 32;
-    constexpr int LA = BM * 8 / NT;   // 16-byte chunks of the left tile per thread and K slice
-    constexpr int LB = BN * 8 / NT;
-    constexpr int RPP = NT / 8;       // rows covered by one pass of the loaders
-    static_assert((LA == 4 || LA == 8) && LA == LB, "the loaders below are written out for 4 + 4 or 8 + 8 chunks per thread");
-    constexpr bool L8 = LA == 8;
-
-    __shared__ uint4 lds_a[2][BM * 8];
-    __shared__ uint4 lds_b[2][BN * 8];
-    __shared__ float lds_invl[BM];
-    // Epilogue state lives in LDS, not in registers, so that the main loop has the register file to itself:
-    // per column of the panel the inverse norm and the candidate floor in accumulator units, per thread and
-    // column tile the running maximum (key, row tile).
-    __shared__ float lds_invr[BN];
-    __shared__ float lds_tcol[BN];
-    __shared__ uint32_t lds_bkey[TN][NT];
-    __shared__ int lds_brt[TN][NT];
-    // Candidates found by this workgroup are staged here (LDS atomics are cheap) and appended to the global lists
-    // in one parallel burst at the end; waiting for a global atomic's return value inside the epilogue would stall
-    // the wavefront for a memory round trip per candidate.
-    constexpr int MAXC = BM * BN / 64;
-    __shared__ int lds_ncand;
-    __shared__ int lds_cand_row[MAXC];
-    __shared__ int lds_cand_col[MAXC];
-    __shared__ float lds_cand_val[MAXC];
-
-    // hardware workgroup id -> item: XCD x (ids congruent x mod 8) walks items [x * per_xcd, (x + 1) * per_xcd)
-    const int per_xcd = gridDim.x >> 3;
-    const long long v = (long long)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (v >= (long long)A.G * A.n_items)
-        return;
-    const int g = (int)(v / A.n_items);
-    if (group_enable && !group_enable[g])      // a switched-off group keeps empty candidate lists: nothing fuses
-        return;
-    const int item = (int)(v - (long long)g * A.n_items);
-    const int node = item_node[item];
-    const int col0 = item_col0[item];
-    const int row0 = item_row0[item];
-    const int ml = set_cnt[(int64_t)g * A.n_slots + l_slot[node]];
-    const int mr = set_cnt[(int64_t)g * A.n_slots + r_slot[node]];
-    if (col0 >= mr || row0 >= ml)
-        return;
-    const int row_end = min(ml, row0 + item_rows[item]);
-    const int32_t *__restrict__ l_ids = set_ids + (int64_t)g * A.n + l_off[node];
-    const int32_t *__restrict__ r_ids = set_ids + (int64_t)g * A.n + r_off[node];
-    const int64_t cbase = (int64_t)g * A.r_stride + r_base[node];
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int wm = wave / WN, wn = wave % WN;
-    const int half = lane >> 5;
-    const int64_t row_bytes = A.row_bytes;
-    const int nk = A.row_bytes >> 7;                          // 128-byte slices per row
-    const int n_rt = (row_end - row0 + BM - 1) / BM;
-    const int total_it = n_rt * nk;
-    const char *__restrict__ kg = kpool + (int64_t)g * A.P * row_bytes;
-    const float *__restrict__ inv_g = inv_norm + (int64_t)g * A.P;
-
-    // loaders: 8 consecutive threads cover the 128-byte slice of one row
-    const int ld_c = tid & 7;
-    const int ld_r = tid >> 3;
-    // The staging registers are named scalars, not arrays: an array that is written under one `if` and read under
-    // another is left in scratch memory by the compiler, which doubles the memory traffic of the kernel.
-#define KVF_COL_PTR(P) (kg + (int64_t)r_ids[min(col0 + ld_r + RPP * (P), mr - 1)] * row_bytes + ld_c * 16)
-#define KVF_ROW_PTR(RT, P) (kg + (int64_t)l_ids[min(row0 + (RT) * BM + ld_r + RPP * (P), row_end - 1)] * row_bytes + ld_c * 16)
-#define KVF_LD(PTR, KO) (*reinterpret_cast<const uint4 *>((PTR) + (KO)))
-#define KVF_SLOT(P) ((ld_r + RPP * (P)) * 8 + (ld_c ^ (((ld_r + RPP * (P)) >> 1) & 7)))
-    // X(i) expands once per staged chunk i; chunks 4..7 exist only in the 8 + 8 configuration
-#define KVF_FOR4(X) X(0) X(1) X(2) X(3)
-#define KVF_FOR48(X) X(4) X(5) X(6) X(7)
-#define KVF_DECL(i)                                                  \
-    const char *pb##i = KVF_COL_PTR((i) < LA ? (i) : 0);             \
-    const char *pa##i = KVF_ROW_PTR(0, (i) < LA ? (i) : 0);          \
-    const int sl##i = KVF_SLOT((i) < LA ? (i) : 0);                  \
-    uint4 ra##i, rb##i;
-    KVF_FOR4(KVF_DECL)
-    KVF_FOR48(KVF_DECL)
-#define KVF_NEWROWS(i) pa##i = KVF_ROW_PTR(pf_rt, i);
-#define KVF_LOAD(i) ra##i = KVF_LD(pa##i, ko); rb##i = KVF_LD(pb##i, ko);
-#define KVF_STORE(i) na[sl##i] = ra##i; nb[sl##i] = rb##i;
-
-    // per-lane epilogue state: the lane holds column (lane & 31) of each of its TN tiles.  The column maximum is
-    // kept as an integer key: the bits of max(acc * inv_l, 0) with the low CODE_BITS replaced by (all ones - position
-    // in the wavefront's tile), so that one unsigned max per element tracks value and row; bkey_rt remembers the
-    // row tile.  The value therefore carries 23 - CODE_BITS mantissa bits, which is ample for a diagnostic; decisions
-    // are taken from the candidate lists, never from it.
-    constexpr uint32_t CODE_MASK = TM * 16 - 1;
-    for (int x = tid; x < BN; x += NT) {
-        const int col = col0 + x;
-        const float ir = col < mr ? inv_g[r_ids[col]] : 0.0f;
-        lds_invr[x] = ir;
-        // acc * inv_l > tcol  <=>  cosine > thr_floor.  A zero right block has cosine 0 with everything.
-        lds_tcol[x] = col >= mr ? INFINITY : (ir > 0.0f ? A.thr_floor / ir : (A.thr_floor < 0.0f ? -INFINITY : INFINITY));
-    }
-#pragma unroll
-    for (int nt = 0; nt < TN; ++nt) {
-        lds_bkey[nt][tid] = 0u;
-        lds_brt[nt][tid] = 0;
-    }
-    if (tid == 0)
-        lds_ncand = 0;
-
-    floatx16 acc[TM][TN];
-#pragma unroll
-    for (int mt = 0; mt < TM; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < TN; ++nt)
-#pragma unroll
-            for (int e = 0; e < 16; ++e)
-                acc[mt][nt][e] = 0.0f;
-
-    int pf_kt = 1, pf_rt = 0;
-    {   // first slice
-        const int64_t ko = 0;
-        uint4 *__restrict__ na = lds_a[0];
-        uint4 *__restrict__ nb = lds_b[0];
-        KVF_FOR4(KVF_LOAD)
-        if constexpr (L8) { KVF_FOR48(KVF_LOAD) }
-        KVF_FOR4(KVF_STORE)
-        if constexpr (L8) { KVF_FOR48(KVF_STORE) }
-    }
-    if (pf_kt == nk) {
-        pf_kt = 0;
-        pf_rt = 1;
-    }
-    __syncthreads();
-
-    for (int it = 0; it < total_it; ++it) {
-        const int cur = it & 1;
-        const int kt = it % nk;
-        const int rt = it / nk;
-        const bool more = it + 1 < total_it;
-        if (kt == 0) {
-            for (int x = tid; x < BM; x += NT) {
-                const int row = row0 + rt * BM + x;
-                lds_invl[x] = row < row_end ? inv_g[l_ids[row]] : __uint_as_float(0x7FC00000u);
-            }
-        }
-        if (more) {
-            if (pf_kt == 0) {      // the prefetch enters a new tile of left rows
-                KVF_FOR4(KVF_NEWROWS)
-                if constexpr (L8) { KVF_FOR48(KVF_NEWROWS) }
-            }
-            const int64_t ko = (int64_t)pf_kt * 128;
-            KVF_FOR4(KVF_LOAD)
-            if constexpr (L8) { KVF_FOR48(KVF_LOAD) }
-            if (++pf_kt == nk) {
-                pf_kt = 0;
-                ++pf_rt;
-            }
-        }
-        const uint4 *__restrict__ la = lds_a[cur];
-        const uint4 *__restrict__ lb = lds_b[cur];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            uint4 fa[TM], fb[TN];
-            const int chunk = 2 * s + half;
-#pragma unroll
-            for (int mt = 0; mt < TM; ++mt) {
-                const int row = (wm * TM + mt) * 32 + (lane & 31);
-                fa[mt] = la[row * 8 + (chunk ^ ((row >> 1) & 7))];
-            }
-#pragma unroll
-            for (int nt = 0; nt < TN; ++nt) {
-                const int row = (wn * TN + nt) * 32 + (lane & 31);
-                fb[nt] = lb[row * 8 + (chunk ^ ((row >> 1) & 7))];
-            }
-#pragma unroll
-            for (int mt = 0; mt < TM; ++mt)
-#pragma unroll
-                for (int nt = 0; nt < TN; ++nt)
-                    acc[mt][nt] = Mma<T>::run(fa[mt], fb[nt], acc[mt][nt]);
-        }
-        if (more) {
-            uint4 *__restrict__ na = lds_a[cur ^ 1];
-            uint4 *__restrict__ nb = lds_b[cur ^ 1];
-            KVF_FOR4(KVF_STORE)
-            if constexpr (L8) { KVF_FOR48(KVF_STORE) }
-        }
-        if (kt == nk - 1) {
-            __syncthreads();   // lds_invl of this row tile is visible even when nk == 1
-            uint32_t kmax[TN];
-            float tcol[TN];
-#pragma unroll
-            for (int nt = 0; nt < TN; ++nt) {
-                kmax[nt] = 0u;
-                tcol[nt] = lds_tcol[(wn * TN + nt) * 32 + (lane & 31)];
-            }
-            // Rows past the end of the set carry a NaN inverse norm: their products compare false against the
-            // candidate floor and turn into key 0, so the unrolled code needs no validity tests.
-#pragma unroll
-            for (int mt = 0; mt < TM; ++mt)
-#pragma unroll
-                for (int eg = 0; eg < 4; ++eg) {
-                    const int rl0 = (wm * TM + mt) * 32 + eg * 8 + half * 4;
-                    const float4 il4 = *reinterpret_cast<const float4 *>(&lds_invl[rl0]);   // 4 consecutive left rows
-                    const float il[4] = {il4.x, il4.y, il4.z, il4.w};
-#pragma unroll
-                    for (int nt = 0; nt < TN; ++nt) {
-                        float t[4];
-                        bool hit = false;
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            t[q] = acc[mt][nt][eg * 4 + q] * il[q];
-                            hit |= t[q] > tcol[nt];
-                            const uint32_t key = (__float_as_uint(fmaxf(t[q], 0.0f)) & ~CODE_MASK) |
-                                                 (CODE_MASK - (uint32_t)(mt * 16 + eg * 4 + q));
-                            kmax[nt] = max(kmax[nt], key);
-                        }
-                        if (hit) {      // rare: an entry clears the candidate floor
-                            const int cl = (wn * TN + nt) * 32 + (lane & 31);
-#pragma unroll
-                            for (int q = 0; q < 4; ++q)
-                                if (t[q] > tcol[nt]) {
-                                    const int row = row0 + rt * BM + rl0 + q;
-                                    const float sv = t[q] * lds_invr[cl];
-                                    const int k = atomicAdd(&lds_ncand, 1);
-                                    if (k < MAXC) {
-                                        lds_cand_row[k] = row;
-                                        lds_cand_col[k] = cl;
-                                        lds_cand_val[k] = sv;
-                                    } else {
-                                        emit_candidate(cand_cnt, cand_idx, cand_val, cbase + col0 + cl, A.cand_cap, row, sv);
-                                    }
-                                }
-                        }
-                    }
-                    __builtin_amdgcn_sched_barrier(0);   // keep the scheduler from widening live ranges across groups
-                }
-            if constexpr (DENSE) {      // separate instantiation for tests: writes every screened cosine
-#pragma unroll
-                for (int mt = 0; mt < TM; ++mt)
-#pragma unroll
-                    for (int nt = 0; nt < TN; ++nt)
-#pragma unroll
-                        for (int e = 0; e < 16; ++e) {
-                            const int rl = (wm * TM + mt) * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
-                            const int row = row0 + rt * BM + rl;
-                            const int col = col0 + (wn * TN + nt) * 32 + (lane & 31);
-                            if (row < row_end && col < mr)
-                                dense_s[(int64_t)g * A.total_s + s_base[node] + (int64_t)row * r_cap[node] + col] =
-                                    acc[mt][nt][e] * lds_invl[rl] * lds_invr[(wn * TN + nt) * 32 + (lane & 31)];
-                        }
-            }
-#pragma unroll
-            for (int nt = 0; nt < TN; ++nt) {
-                if (kmax[nt] > lds_bkey[nt][tid]) {
-                    lds_bkey[nt][tid] = kmax[nt];
-                    lds_brt[nt][tid] = rt;
-                }
-#pragma unroll
-                for (int mt = 0; mt < TM; ++mt)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e)
-                        acc[mt][nt][e] = 0.0f;
-            }
-        }
-        __syncthreads();
-    }
-
-    // staged candidates -> global lists (the loop's last barrier made the staging area visible)
-    {
-        const int nc = min(lds_ncand, MAXC);
-        for (int k = tid; k < nc; k += NT)
-            emit_candidate(cand_cnt, cand_idx, cand_val, cbase + col0 + lds_cand_col[k], A.cand_cap, lds_cand_row[k],
-                           lds_cand_val[k]);
-    }
-
-    // column maxima of this item: lane halves hold different rows of a column; all chunks of a panel and all
-    // wavefront rows meet in the packed 64-bit maximum
-#pragma unroll
-    for (int nt = 0; nt < TN; ++nt) {
-        const int col = col0 + (wn * TN + nt) * 32 + (lane & 31);
-        const uint32_t bkey = lds_bkey[nt][tid];
-        const int code = (int)(CODE_MASK - (bkey & CODE_MASK));
-        const int row = min(row_end - 1, row0 + lds_brt[nt][tid] * BM + (wm * TM + (code >> 4)) * 32 + ((code & 15) >> 2) * 8 + half * 4 + (code & 3));
-        unsigned long long pk = bkey ? pack_best(__uint_as_float(bkey & ~CODE_MASK) * lds_invr[(wn * TN + nt) * 32 + (lane & 31)], row) : 0ull;
-        const unsigned long long other = __shfl_xor(pk, 32, 64);
-        pk = other > pk ? other : pk;
-        if (half == 0 && col < mr && pk)
-            atomicMax(&best_packed[cbase + col], pk);
-    }
-}
-
-// ---------------------------------------------------------------------------------------------------
-// Big tile (256 x 256, 8 wavefronts of 64 x 128): LDS ring fed by direct global -> LDS loads.
-//
-// K is walked in 64-byte slices per row.  A ring of four stages (each 256 left + 256 right rows x 64 bytes = 32 KB)
-// is filled by global_load_lds_dwordx4: the data never passes through registers, so two slices can be in flight
-// while one is being multiplied and one is ready, with no staging registers at all.  Every wavefront issues four
-// such loads per slice (1 KB each: 16 rows x 64 bytes).  A load writes LDS at (wave-uniform base + lane * 16), so
-// the XOR swizzle that keeps the fragment reads conflict-free is applied on the global side: lane L covers row
-// L / 4 and fetches logical 16-byte chunk (L & 3) ^ ((row >> 2) & 3) of that row's slice.
-//
-// Fragment reads are ds_read_b128 in inline assembly.  The compiler cannot tell that they never touch a stage
-// that is still being filled and would otherwise wait for every outstanding global -> LDS load before each LDS
-// read.  Each read's destination registers are handed to the following wait statement as in/out operands, which
-// is what orders the MFMAs behind the wait.  Fragments are double buffered (one set per 32-byte half slice), and
-// the first half of slice j + 1 is read before the barrier that ends iteration j; that is legal because the loads
-// of slice j + 1 were completed before the previous barrier.
-//
-// Iteration j (slice j in stage j & 3):   read set1 <- slice j, second half;  8 MFMA on set0 + 2 loads of slice
-// j + 3;  wait set1;  read set0 <- slice j + 1, first half;  8 MFMA on set1 + 2 loads;  wait until only this
-// iteration's 4 loads are outstanding;  barrier.  The stage written in iteration j held slice j - 1, which every
-// wavefront finished reading before the previous barrier.
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 template <typename T> struct MmaV;
@@ -413,8 +94,10 @@ template <> struct MmaV<float> {
 
 constexpr int kRingRowTiles = 4;   // most row tiles of one work item (the host's tile table keeps to it)
 
-template <typename T, bool DENSE>
-__global__ __launch_bounds__(512, 1) void similarity_ring_kernel(
+// BIG: 256 x 256 tile, 8 wavefronts of 64 x 128, one workgroup per compute unit.  Otherwise 128 x 128, 4 wavefronts
+// of 64 x 64 and a 64 KB ring, two workgroups per compute unit: for nodes whose sets are smaller than a big tile.
+template <typename T, bool BIG, bool DENSE>
+__global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_kernel(
     SimArgs A, const char *__restrict__ kpool, const float *__restrict__ inv_norm, const int32_t *__restrict__ set_ids,
     const int32_t *__restrict__ set_cnt, const int32_t *__restrict__ item_node, const int32_t *__restrict__ item_col0,
     const int32_t *__restrict__ item_row0, const int32_t *__restrict__ item_rows, const int32_t *__restrict__ l_off,
@@ -423,7 +106,8 @@ __global__ __launch_bounds__(512, 1) void similarity_ring_kernel(
     unsigned long long *__restrict__ best_packed, int32_t *__restrict__ cand_cnt, int32_t *__restrict__ cand_idx,
     float *__restrict__ cand_val, float *__restrict__ dense_s, const uint8_t *__restrict__ group_enable)
 {
-    constexpr int WN = 2, TM = 2, TN = 4, NT = 512, BM = 256, BN = 256;
+    constexpr int WN = 2, TM = 2, TN = BIG ? 4 : 2, NT = BIG ? 512 : 256, BM = BIG ? 256 : 128, BN = BM;
+    constexpr int HALF = BM / 2;              // rows one pass of the loaders covers (16 per wavefront)
     constexpr int STAGE = (BM + BN) * 64;
     constexpr int B_REGION = BM * 64;
     constexpr int RT = kRingRowTiles;
@@ -471,10 +155,10 @@ __global__ __launch_bounds__(512, 1) void similarity_ring_kernel(
     const char *__restrict__ kg = kpool + (int64_t)g * A.P * row_bytes;
     const float *__restrict__ inv_g = inv_norm + (int64_t)g * A.P;
 
-    // ---- global -> LDS loaders: this lane's row within a 128-row half tile and its (swizzled) chunk
+    // ---- global -> LDS loaders: this lane's row within a half tile and its (swizzled) chunk
     const int ld_row = wave * 16 + (lane >> 2);
     const int ld_chunk = ((lane & 3) ^ ((lane >> 4) & 3)) * 16;
-#define KVF_LID(t, i) l_ids[min(row0 + (t) * BM + (i) * 128 + ld_row, row_end - 1)]
+#define KVF_LID(t, i) l_ids[min(row0 + (t) * BM + (i) * HALF + ld_row, row_end - 1)]
     const int ia00 = KVF_LID(0, 0), ia01 = KVF_LID(0, 1);
     const int ia10 = KVF_LID(1, 0), ia11 = KVF_LID(1, 1);
     const int ia20 = KVF_LID(2, 0), ia21 = KVF_LID(2, 1);
@@ -483,9 +167,9 @@ __global__ __launch_bounds__(512, 1) void similarity_ring_kernel(
     const char *pa0 = kg + (int64_t)ia00 * row_bytes + ld_chunk;
     const char *pa1 = kg + (int64_t)ia01 * row_bytes + ld_chunk;
     const char *pb0 = kg + (int64_t)r_ids[min(col0 + ld_row, mr - 1)] * row_bytes + ld_chunk;
-    const char *pb1 = kg + (int64_t)r_ids[min(col0 + 128 + ld_row, mr - 1)] * row_bytes + ld_chunk;
+    const char *pb1 = kg + (int64_t)r_ids[min(col0 + HALF + ld_row, mr - 1)] * row_bytes + ld_chunk;
     const int dma_a0 = wave * 16 * 64;                          // LDS byte offsets of this wavefront's four 1 KB pieces
-    const int dma_a1 = dma_a0 + 128 * 64;
+    const int dma_a1 = dma_a0 + HALF * 64;
     const int dma_b0 = B_REGION + dma_a0;
     const int dma_b1 = B_REGION + dma_a1;
 #define KVF_DMA(PTR, OFF)                                                                                          \
@@ -502,8 +186,13 @@ __global__ __launch_bounds__(512, 1) void similarity_ring_kernel(
     const uint32_t fb_hi = fb_lo ^ 32u;
 #define KVF_DS_READ(DST, ADDR, IMM) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(DST) : "v"(ADDR), "n"(IMM))
 #define KVF_WAIT_SET(S)                                                                                            \
-    asm volatile("s_waitcnt lgkmcnt(0)"                                                                           \
-                 : "+v"(fa0_##S), "+v"(fa1_##S), "+v"(fb0_##S), "+v"(fb1_##S), "+v"(fb2_##S), "+v"(fb3_##S))
+    do {                                                                                                           \
+        if constexpr (TN > 2)                                                                                      \
+            asm volatile("s_waitcnt lgkmcnt(0)"                                                                   \
+                         : "+v"(fa0_##S), "+v"(fa1_##S), "+v"(fb0_##S), "+v"(fb1_##S), "+v"(fb2_##S), "+v"(fb3_##S)); \
+        else                                                                                                       \
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(fa0_##S), "+v"(fa1_##S), "+v"(fb0_##S), "+v"(fb1_##S));     \
+    } while (0)
     // The dense-output instantiation (tests only) is short of registers in its epilogue; it waits for each set
     // right away so that no register is ever moved or spilled while its data is still on the way.
 #define KVF_READ_SET(S, ADDR_A, ADDR_B)          \
@@ -511,10 +200,14 @@ __global__ __launch_bounds__(512, 1) void similarity_ring_kernel(
     KVF_DS_READ(fb0_##S, ADDR_B, 0);             \
     KVF_DS_READ(fa1_##S, ADDR_A, 2048);          \
     KVF_DS_READ(fb1_##S, ADDR_B, 2048);          \
-    KVF_DS_READ(fb2_##S, ADDR_B, 4096);          \
-    KVF_DS_READ(fb3_##S, ADDR_B, 6144);          \
+    if constexpr (TN > 2) {                      \
+        KVF_DS_READ(fb2_##S, ADDR_B, 4096);      \
+        KVF_DS_READ(fb3_##S, ADDR_B, 6144);      \
+    }                                            \
     if constexpr (DENSE) { KVF_WAIT_SET(S); }
 #define KVF_MMA(S, MT, NTI) acc[MT][NTI] = MmaV<T>::run(fa##MT##_##S, fb##NTI##_##S, acc[MT][NTI]);
+    // column tiles 2 and 3 exist only in the big configuration
+#define KVF_MMA_HI(S, MT, NTI) if constexpr (TN > 2) { acc[MT][TN > 2 ? NTI : 0] = MmaV<T>::run(fa##MT##_##S, fb##NTI##_##S, acc[MT][TN > 2 ? NTI : 0]); }
     u32x4 fa0_0, fa1_0, fb0_0, fb1_0, fb2_0, fb3_0;
     u32x4 fa0_1, fa1_1, fb0_1, fb1_1, fb2_1, fb3_1;
 
@@ -592,11 +285,11 @@ __global__ __launch_bounds__(512, 1) void similarity_ring_kernel(
             __builtin_amdgcn_sched_barrier(0);
             KVF_DMA(pa0, dst + dma_a0);
             __builtin_amdgcn_sched_barrier(0);
-            KVF_MMA(0, 0, 1) KVF_MMA(0, 1, 1) KVF_MMA(0, 0, 2) KVF_MMA(0, 1, 2)
+            KVF_MMA(0, 0, 1) KVF_MMA(0, 1, 1) KVF_MMA_HI(0, 0, 2) KVF_MMA_HI(0, 1, 2)
             __builtin_amdgcn_sched_barrier(0);
             KVF_DMA(pa1, dst + dma_a1);
             __builtin_amdgcn_sched_barrier(0);
-            KVF_MMA(0, 0, 3) KVF_MMA(0, 1, 3)
+            KVF_MMA_HI(0, 0, 3) KVF_MMA_HI(0, 1, 3)
             __builtin_amdgcn_sched_barrier(0);
             KVF_WAIT_SET(1);
             KVF_READ_SET(0, ra0, rb0)
@@ -605,11 +298,11 @@ __global__ __launch_bounds__(512, 1) void similarity_ring_kernel(
             __builtin_amdgcn_sched_barrier(0);
             KVF_DMA(pb0, dst + dma_b0);
             __builtin_amdgcn_sched_barrier(0);
-            KVF_MMA(1, 0, 1) KVF_MMA(1, 1, 1) KVF_MMA(1, 0, 2) KVF_MMA(1, 1, 2)
+            KVF_MMA(1, 0, 1) KVF_MMA(1, 1, 1) KVF_MMA_HI(1, 0, 2) KVF_MMA_HI(1, 1, 2)
             __builtin_amdgcn_sched_barrier(0);
             KVF_DMA(pb1, dst + dma_b1);
             __builtin_amdgcn_sched_barrier(0);
-            KVF_MMA(1, 0, 3) KVF_MMA(1, 1, 3)
+            KVF_MMA_HI(1, 0, 3) KVF_MMA_HI(1, 1, 3)
             __builtin_amdgcn_sched_barrier(0);
             KVF_DMA_ADVANCE();
             // all but this iteration's four loads have landed (slice it + 2), then everyone may read it
@@ -723,6 +416,7 @@ __global__ __launch_bounds__(512, 1) void similarity_ring_kernel(
 #undef KVF_READ_SET
 #undef KVF_WAIT_SET
 #undef KVF_MMA
+#undef KVF_MMA_HI
 #undef KVF_DMA_ADVANCE
 }
 
@@ -736,33 +430,7 @@ __global__ void similarity_clear_kernel(unsigned long long *__restrict__ best_pa
     }
 }
 
-template <typename T, int WM, int WN, int TM, int TN>
-static void launch_cfg(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const HeightDesc &h, const TileTable &tt,
-                       float thr_floor, float *dense_s)
-{
-    const int64_t total = (int64_t)w.G * tt.n_items;
-    if (total <= 0)
-        return;
-    SimArgs A;
-    A.G = w.G; A.n = w.n; A.n_slots = w.n_slots; A.r_stride = w.r_stride; A.cand_cap = w.cand_cap; A.P = pool.P;
-    A.n_items = tt.n_items;
-    A.row_bytes = pool.r * (int)sizeof(T);
-    A.thr_floor = thr_floor;
-    A.total_s = h.total_s;
-    const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
-#define KVF_SIM_LAUNCH(D)                                                                                              \
-    similarity_kernel<T, WM, WN, TM, TN, D><<<grid, 64 * WM * WN, 0, s>>>(                                             \
-        A, (const char *)pool.k, pool.inv_norm_k, w.set_ids, w.set_cnt, tt.node, tt.col0, tt.row0, tt.rows, h.l_off, h.r_off, \
-        h.l_slot, h.r_slot, h.r_base, h.r_cap, h.s_base, w.best_packed, w.cand_cnt, w.cand_idx, w.cand_val, dense_s,           \
-        w.group_enable)
-    if (dense_s)
-        KVF_SIM_LAUNCH(true);
-    else
-        KVF_SIM_LAUNCH(false);
-#undef KVF_SIM_LAUNCH
-}
-
-template <typename T>
+template <typename T, bool BIG>
 static void launch_ring(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const HeightDesc &h, const TileTable &tt,
                         float thr_floor, float *dense_s)
 {
@@ -777,7 +445,7 @@ static void launch_ring(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, 
     A.total_s = h.total_s;
     const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
 #define KVF_SIM_LAUNCH(D)                                                                                              \
-    similarity_ring_kernel<T, D><<<grid, 512, 0, s>>>(                                                                 \
+    similarity_ring_kernel<T, BIG, D><<<grid, BIG ? 512 : 256, 0, s>>>(                                                                 \
         A, (const char *)pool.k, pool.inv_norm_k, w.set_ids, w.set_cnt, tt.node, tt.col0, tt.row0, tt.rows, h.l_off, h.r_off, \
         h.l_slot, h.r_slot, h.r_base, h.r_cap, h.s_base, w.best_packed, w.cand_cnt, w.cand_idx, w.cand_val, dense_s,           \
         w.group_enable)
@@ -798,14 +466,14 @@ void launch_similarity(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, c
     const bool big = h.use_big_tiles;
     if (pool.dtype == KVFUSE_BF16) {
         if (big)
-            launch_ring<bf16_t>(s, pool, w, h, h.big, thr_floor, dense_s);
+            launch_ring<bf16_t, true>(s, pool, w, h, h.big, thr_floor, dense_s);
         else
-            launch_cfg<bf16_t, 2, 2, 2, 2>(s, pool, w, h, h.small, thr_floor, dense_s);
+            launch_ring<bf16_t, false>(s, pool, w, h, h.small, thr_floor, dense_s);
     } else {
         if (big)
-            launch_ring<float>(s, pool, w, h, h.big, thr_floor, dense_s);
+            launch_ring<float, true>(s, pool, w, h, h.big, thr_floor, dense_s);
         else
-            launch_cfg<float, 2, 2, 2, 2>(s, pool, w, h, h.small, thr_floor, dense_s);
+            launch_ring<float, false>(s, pool, w, h, h.small, thr_floor, dense_s);
     }
 }
 
