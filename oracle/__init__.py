@@ -259,3 +259,42 @@ def paged_decode_attention(q, kpool, vpool, bt, scale_k, scale_v, req_start, ctx
             p /= p.sum()
             out[b, h] = p @ vt
     return out
+
+
+def causal_prefill_attention(q, q_pos, kpool, vpool, bt, scale_k, scale_v, req_start, t, d, sm_scale=None):
+    """Textbook causal softmax attention of a run of query tokens of ONE request over its paged context, fp64
+    (motivation section: chunked prefill over a cache whose table points several logical blocks at one stored
+    block; the query at position pos sees the tokens 0 .. pos of its own request).
+
+    q         [Nq][Hq][d]    queries of ONE layer, query i sits at absolute token position q_pos[i]
+    kpool     [H][P][t*d]    pool of that layer, one slab per KV head (float32 or bfloat16 bits)
+    bt        [H][n]         per-group block table; the request owns logical entries req_start, req_start + 1, ...
+    scale_*   [H][n]         per-logical-block rescale
+    Query head h reads KV head h // (Hq // H).  Token tau lives in logical block x = req_start + tau // t:
+    z_tau = sm_scale * scale_k[x] * <q, K[bt[x]][tau % t]>, out = sum_{tau <= pos} softmax(z)_tau * scale_v[x] * V[bt[x]][tau % t].
+    """
+    q = np.asarray(q, np.float64)
+    Nq, Hq, dd = q.shape
+    assert dd == d
+    H = len(kpool)
+    rep = Hq // H
+    if sm_scale is None:
+        sm_scale = 1.0 / np.sqrt(d)
+    q_pos = np.asarray(q_pos, np.int64)
+    T = int(q_pos.max()) + 1
+    nb = (T + t - 1) // t
+    out = np.zeros((Nq, Hq, d), np.float64)
+    for g in range(H):
+        xs = np.arange(req_start, req_start + nb)
+        phys = np.asarray(bt[g])[xs]
+        kt = (pool_to_f64(np.asarray(kpool[g])[phys]).reshape(nb, t, d) * np.asarray(scale_k[g], np.float64)[xs, None, None]).reshape(nb * t, d)
+        vt = (pool_to_f64(np.asarray(vpool[g])[phys]).reshape(nb, t, d) * np.asarray(scale_v[g], np.float64)[xs, None, None]).reshape(nb * t, d)
+        for i in range(Nq):
+            L = int(q_pos[i]) + 1
+            for h in range(g * rep, (g + 1) * rep):
+                z = sm_scale * (kt[:L] @ q[i, h])
+                z = z - z.max()
+                p = np.exp(z)
+                p /= p.sum()
+                out[i, h] = p @ vt[:L]
+    return out

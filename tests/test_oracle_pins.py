@@ -508,3 +508,38 @@ def test_pair_cosines_and_feedback_direction():
     assert th.feedback_step(0.9, 1.1, 1.5, 0.1, 0.5, 0.99) < 0.9       # too little: lower
     assert th.feedback_step(0.9, 1.5, 1.5, 0.1, 0.5, 0.99) == 0.9
     assert th.feedback_step(0.98, 9.0, 1.5, 0.5, 0.5, 0.99) == 0.99    # clamped
+
+
+# ---------------------------------------------------------------- causal prefill attention through the table
+
+def test_causal_prefill_attention_equals_library_causal_attention_and_decode(oracle):
+    """Nothing fused: the oracle must equal a library causal attention (torch SDPA with a causal mask, fp64);
+    with a fused table, the row of the query at position pos must equal the decode oracle with ctx_len = pos + 1."""
+    rng = np.random.default_rng(21)
+    H, Hq, t, d, N = 2, 4, 4, 8, 37
+    nb = (N + t - 1) // t
+    n = nb + 3
+    req_start = 2
+    K = rng.standard_normal((H, n, t * d)).astype(np.float32)
+    V = rng.standard_normal((H, n, t * d)).astype(np.float32)
+    bt = np.stack([rng.permutation(n) for _ in range(H)]).astype(np.int32)
+    one = np.ones((H, n))
+    q = rng.standard_normal((N, Hq, d))
+    out = oracle.causal_prefill_attention(q, np.arange(N), K, V, bt, one, one, req_start, t, d)
+    for h in range(Hq):
+        g = h // (Hq // H)
+        xs = bt[g][req_start: req_start + nb]
+        kt = torch.tensor(K[g][xs].reshape(-1, d)[:N], dtype=torch.float64)
+        vt = torch.tensor(V[g][xs].reshape(-1, d)[:N], dtype=torch.float64)
+        ref = torch.nn.functional.scaled_dot_product_attention(torch.tensor(q[:, h])[None], kt[None], vt[None], is_causal=True)[0]
+        assert np.allclose(out[:, h], ref.numpy(), atol=1e-12)
+    assert np.allclose(out[0, 0], V[0][bt[0][req_start]].reshape(t, d)[0], atol=1e-13)   # first token sees only itself
+    # fused table: two logical blocks share a stored block with different scales
+    bt2 = bt.copy()
+    bt2[:, req_start + 5] = bt2[:, req_start + 1]
+    sk, sv = rng.uniform(0.5, 2.0, (H, n)), rng.uniform(0.5, 2.0, (H, n))
+    pos = np.array([3, 22, 23, 36])
+    out2 = oracle.causal_prefill_attention(q[pos], pos, K, V, bt2, sk, sv, req_start, t, d)
+    for i, p in enumerate(pos):
+        dec = oracle.paged_decode_attention(q[p][None], K, V, bt2, sk, sv, np.array([req_start]), np.array([p + 1]), t, d)
+        assert np.allclose(out2[i], dec[0], atol=1e-13)
