@@ -271,6 +271,40 @@ int kvfuse_shared_decode_plan_destroy(kvfuse_decode_plan *plan);
 int kvfuse_paged_decode_attn_shared(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table,
                                     const kvfuse_decode_plan *plan, const void *q, float sm_scale, float *out);
 
+/* ---- chunked-prefill attention with reuse on fused blocks ----------------------------------------------- */
+
+/* Causal softmax attention of a run of query tokens of ONE request over its paged, fused context (motivation
+ * section: with chunked prefill, a softmax-attention computation that involves a fused block is reused for the
+ * later instances of that block; the result merges the fused part and the unique part with rescaling).
+ * The queries are the tokens [q_begin, q_end) of the chunk that starts at token chunk_begin (a multiple of t);
+ * the query at position pos sees tokens 0 .. pos.  Logical blocks that end before the chunk and point at the same
+ * stored block share one Q K^T product and one product with V; only the exponentials are per instance.  The blocks
+ * of the chunk itself are walked one by one with the causal mask.  reuse = 0 builds the same plan without merging
+ * instances (every logical block its own entry): the baseline the reuse is measured against; both give the
+ * same result up to summation order.  bfloat16 pools, d in {64, 128}, t a multiple of 16, Hq / kv_heads <= 16.
+ * The plan reads the table (ids and scales of the blocks before the chunk) once, on the host: rebuild it when the
+ * table changes.  Tokens at and after q_end are never read as visible; tokens of the last block beyond q_end may
+ * hold anything. */
+typedef struct kvfuse_prefill_plan kvfuse_prefill_plan;
+
+typedef struct kvfuse_prefill_plan_info {
+    int64_t device_bytes;                 /* workspace the plan needs on the device */
+    int64_t logical_blocks_before_chunk;  /* over all groups of the plan */
+    int64_t stored_blocks_before_chunk;   /* distinct stored blocks among them (= logical if reuse is off) */
+} kvfuse_prefill_plan_info;
+
+int kvfuse_prefill_plan_build(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table, int32_t kv_heads,
+                              int32_t layer_begin, int32_t n_layers, int32_t req_start, int32_t chunk_begin, int32_t q_begin,
+                              int32_t q_end, int32_t Hq, int32_t reuse, kvfuse_prefill_plan **plan,
+                              kvfuse_prefill_plan_info *info);
+/* workspace: device, >= info.device_bytes, 256-byte aligned, owned by the caller, alive while the plan is used. */
+int kvfuse_prefill_plan_upload(kvfuse_ctx *ctx, kvfuse_prefill_plan *plan, void *workspace, size_t workspace_bytes);
+int kvfuse_prefill_plan_destroy(kvfuse_prefill_plan *plan);
+
+/* q: device [n_layers][q_end - q_begin][Hq][d] bfloat16;  out: device, same shape, float.  Asynchronous. */
+int kvfuse_prefill_attn(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table, const kvfuse_prefill_plan *plan,
+                        const void *q, float sm_scale, float *out);
+
 /* ---- threshold control ------------------------------------------------------------------------------- */
 
 /* Analysis section: with a layer's block similarities approximately Gaussian (mean mu_l and variance sigma_l^2 =

@@ -98,6 +98,18 @@ lib.kvfuse_shared_decode_plan_build.argtypes = [_vp, C.POINTER(Pool), C.POINTER(
 lib.kvfuse_shared_decode_plan_upload.argtypes = [_vp, _vp, _vp, C.c_size_t]
 lib.kvfuse_shared_decode_plan_destroy.argtypes = [_vp]
 lib.kvfuse_paged_decode_attn_shared.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _vp, _vp, C.c_float, _vp]
+
+
+class PrefillPlanInfo(C.Structure):
+    _fields_ = [("device_bytes", C.c_int64), ("logical_blocks_before_chunk", C.c_int64),
+                ("stored_blocks_before_chunk", C.c_int64)]
+
+
+lib.kvfuse_prefill_plan_build.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32,
+                                          _i32, C.POINTER(_vp), C.POINTER(PrefillPlanInfo)]
+lib.kvfuse_prefill_plan_upload.argtypes = [_vp, _vp, _vp, C.c_size_t]
+lib.kvfuse_prefill_plan_destroy.argtypes = [_vp]
+lib.kvfuse_prefill_attn.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _vp, _vp, C.c_float, _vp]
 lib.kvfuse_pair_cosines.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _vp, _i32, _vp]
 lib.kvfuse_cosine_moments.argtypes = [_vp, _vp, _i32, _i32, _vp]
 lib.kvfuse_exceedance_rate.argtypes = [_f64, _f64, _f64, _f64]
@@ -302,6 +314,47 @@ def paged_decode_attn(ctx, cache, kv_heads, q, req_start, ctx_len, max_blocks, l
     ctx.check(lib.kvfuse_paged_decode_attn(ctx.h, C.byref(cache.pool), C.byref(cache.table), kv_heads, layer_begin, n_layers,
                                            _ptr(q), _ptr(req_start), _ptr(ctx_len), B, Hq, max_blocks, sm_scale,
                                            _ptr(workspace), workspace.numel(), _ptr(out)))
+    return out
+
+
+class PrefillPlan:
+    """Plan for kvfuse_prefill_attn: queries = tokens [q_begin, q_end) of the chunk starting at chunk_begin."""
+
+    def __init__(self, ctx, cache, kv_heads, Hq, req_start, chunk_begin, q_begin, q_end, layer_begin=0, n_layers=None,
+                 reuse=True):
+        self.ctx = ctx
+        self.h = _vp()
+        if n_layers is None:
+            n_layers = cache.pool.G // kv_heads - layer_begin
+        self.n_layers, self.Hq, self.nq = n_layers, Hq, q_end - q_begin
+        self.info = PrefillPlanInfo()
+        ctx.check(lib.kvfuse_prefill_plan_build(ctx.h, C.byref(cache.pool), C.byref(cache.table), kv_heads, layer_begin, n_layers,
+                                                int(req_start), int(chunk_begin), int(q_begin), int(q_end), Hq, 1 if reuse else 0,
+                                                C.byref(self.h), C.byref(self.info)))
+        self.workspace = torch.empty(int(self.info.device_bytes), device=cache.K.device, dtype=torch.uint8)
+        ctx.check(lib.kvfuse_prefill_plan_upload(ctx.h, self.h, _ptr(self.workspace), self.workspace.numel()))
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib.kvfuse_prefill_plan_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def prefill_attn(ctx, cache, plan, q, sm_scale=None, out=None):
+    """q [n_layers][Nq][Hq][d] bfloat16 -> out float32 of the same shape (causal attention through the table)."""
+    n_layers, nq, Hq, d = q.shape
+    assert q.is_contiguous() and q.dtype == cache.K.dtype and d == cache.d and (n_layers, nq, Hq) == (plan.n_layers, plan.nq, plan.Hq)
+    if sm_scale is None:
+        sm_scale = 1.0 / float(d) ** 0.5
+    if out is None:
+        out = torch.empty(n_layers, nq, Hq, d, device=q.device, dtype=torch.float32)
+    ctx.check(lib.kvfuse_prefill_attn(ctx.h, C.byref(cache.pool), C.byref(cache.table), plan.h, _ptr(q), sm_scale, _ptr(out)))
     return out
 
 

@@ -445,6 +445,69 @@ def test_shared_decode_rejects_bad_arguments(kb):
         kb.SharedDecodePlan(ctx, cache, rec.kv_heads, rec.req_start, rec.ctx_len, rec.q_heads, min_cluster_blocks=0)
 
 
+# ------------------------------------------------------------------------------------------ chunked prefill with reuse
+
+@pytest.mark.parametrize("case", ["d128_gqa4_last_chunk", "d64_gqa8_t32", "first_chunk_no_prefix", "unfused"])
+def test_prefill_attention_with_reuse_matches_oracle(kb, oracle, case):
+    """Causal attention of a ragged run of query tokens through a CFF-fused table: with reuse of fused blocks, and
+    without (every logical block on its own), against the fp64 definition; the two GPU results agree closely."""
+    _say("prefill case", case)
+    thr = None
+    if case == "d64_gqa8_t32":
+        rec = wl.cff_long(tokens=32 * 120, chunk_tokens=32 * 20, layers=1, kv_heads=2, t=32, d=64)
+        rec.q_heads = 8 * rec.kv_heads
+        chunk_begin, q_begin, q_end = 32 * 100, 32 * 100 + 13, 32 * 100 + 13 + 70
+    elif case == "first_chunk_no_prefix":
+        rec = wl.cff_long(tokens=16 * 200, chunk_tokens=16 * 50, layers=1, kv_heads=2)
+        chunk_begin, q_begin, q_end = 0, 0, 53
+    else:
+        rec = wl.cff_long(tokens=16 * 300, chunk_tokens=16 * 50, layers=2, kv_heads=2)
+        chunk_begin, q_begin, q_end = 16 * 250, 16 * 250 + 37, 16 * 250 + 37 + 45
+        thr = 1.5 if case == "unfused" else None
+    mat = wl.materialise(rec, DEV, phys_perm=True)
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, thr=thr)
+    assert (stats.fused > 0) == (case != "unfused")
+    nq = q_end - q_begin
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(77)
+    q = torch.randn(rec.layers, nq, rec.q_heads, rec.d, generator=gen).to(torch.bfloat16).to(DEV)
+    outs, infos = [], []
+    for reuse in (True, False):
+        pp = kb.PrefillPlan(ctx, cache, rec.kv_heads, rec.q_heads, int(rec.req_start[0]), chunk_begin, q_begin, q_end, reuse=reuse)
+        outs.append(kb.prefill_attn(ctx, cache, pp, q))
+        infos.append(pp.info)
+    torch.cuda.synchronize()
+    _say("  blocks before the chunk: logical", infos[0].logical_blocks_before_chunk, "stored", infos[0].stored_blocks_before_chunk)
+    assert infos[1].stored_blocks_before_chunk == infos[1].logical_blocks_before_chunk == rec.G * (chunk_begin // rec.t)
+    assert infos[0].stored_blocks_before_chunk <= infos[0].logical_blocks_before_chunk
+    if case in ("d128_gqa4_last_chunk", "d64_gqa8_t32"):
+        assert infos[0].stored_blocks_before_chunk < infos[0].logical_blocks_before_chunk      # something to reuse
+    worst = 0.0
+    for layer in range(rec.layers):
+        gs = [layer * rec.kv_heads + h for h in range(rec.kv_heads)]
+        ref = oracle.causal_prefill_attention(
+            q[layer].float().cpu().numpy(), np.arange(q_begin, q_end), [wl.to_numpy_pool(cache.K[g]) for g in gs],
+            [wl.to_numpy_pool(cache.V[g]) for g in gs], [cache.bt[g].cpu().numpy() for g in gs],
+            [cache.scale_k[g].cpu().numpy().astype(np.float64) for g in gs],
+            [cache.scale_v[g].cpu().numpy().astype(np.float64) for g in gs], int(rec.req_start[0]), rec.t, rec.d)
+        for o in outs:
+            worst = max(worst, float(np.abs(o[layer].cpu().numpy() - ref).max()))
+    diff = float((outs[0] - outs[1]).abs().max())
+    _say("  max abs err vs oracle", worst, " reuse vs no reuse", diff)
+    assert worst <= 2e-2 and worst <= 5e-3 and diff <= 1e-4
+
+
+def test_prefill_rejects_bad_arguments(kb):
+    rec = wl.cff_long(tokens=16 * 64, chunk_tokens=16 * 16, layers=1, kv_heads=2)
+    mat = wl.materialise(rec, DEV)
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat)
+    for args in ((0, 8, 8, 40), (0, 16, 8, 40), (0, 16, 40, 30), (0, 16 * 32, 16 * 32, 16 * 64 + 1), (-1, 0, 0, 8)):
+        with pytest.raises(kb.KvfuseError):
+            kb.PrefillPlan(ctx, cache, rec.kv_heads, rec.q_heads, *args)
+    with pytest.raises(kb.KvfuseError):
+        kb.PrefillPlan(ctx, cache, rec.kv_heads, rec.q_heads + 1, 0, 0, 0, 8)
+
+
 # ------------------------------------------------------------------------------------------ threshold control
 
 @pytest.mark.parametrize("kind", ["bf16_fused", "f32_tiny"])
