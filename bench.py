@@ -161,6 +161,44 @@ def main():
     shared_diff = float((out_sh - out).abs().max())
     si = splan.info
 
+    # chunked-prefill attention with reuse on fused blocks (a "next" row; one-request workloads only): the last chunk's
+    # queries over the fused context, 4 layers, with the reuse and with every logical block on its own
+    prefill = None
+    if rec.B == 1 and rec.dtype == torch.bfloat16:
+        chunk_tokens = int(rec.leaf_count[-1]) * rec.t
+        total = int(rec.ctx_len[0])
+        cb = (total - 1) // chunk_tokens * chunk_tokens
+        pl_layers = min(4, rec.layers)
+        gen = torch.Generator(device="cpu")
+        gen.manual_seed(wl.MASTER_SEED + 7)
+        qp = torch.randn(pl_layers, total - cb, rec.q_heads, rec.d, generator=gen).to(rec.dtype).to(dev)
+        outp = torch.empty(pl_layers, total - cb, rec.q_heads, rec.d, device=dev, dtype=torch.float32)
+        prefill = {"layers": pl_layers, "query_tokens": total - cb, "context_tokens": total}
+        ref_out = None
+        for reuse in (True, False):
+            pp = kb.PrefillPlan(ctx, cache, rec.kv_heads, rec.q_heads, int(rec.req_start[0]), cb, cb, total, n_layers=pl_layers,
+                                reuse=reuse)
+            kb.prefill_attn(ctx, cache, pp, qp, out=outp)
+            torch.cuda.synchronize()
+            sev[0].record()
+            for _ in range(2):
+                kb.prefill_attn(ctx, cache, pp, qp, out=outp)
+            sev[1].record()
+            torch.cuda.synchronize()
+            ms_p = sev[0].elapsed_time(sev[1]) / 2
+            # algorithmic flops: every query row against every logical token it sees, Q.K and P.V
+            seen = sum(range(cb + 1, total + 1))
+            flops = 4.0 * rec.d * seen * rec.q_heads * pl_layers
+            key = "reuse" if reuse else "no_reuse"
+            prefill[key] = {"ms": ms_p, "TFLOPs_algorithmic": flops / (ms_p * 1e-3) / 1e12,
+                            "stored_blocks_before_chunk": pp.info.stored_blocks_before_chunk,
+                            "logical_blocks_before_chunk": pp.info.logical_blocks_before_chunk}
+            if ref_out is None:
+                ref_out = outp.clone()
+            else:
+                prefill["max_abs_diff_reuse_vs_no_reuse"] = float((outp - ref_out).abs().max())
+        prefill["speedup_from_reuse"] = prefill["no_reuse"]["ms"] / prefill["reuse"]["ms"]
+
     # threshold-control statistics (another "next" row): key cosines of sampled logical pairs on the unfused cache,
     # their moments, and the analysis section's Gaussian exceedance rate at the workload's threshold
     restore()
@@ -225,6 +263,7 @@ def main():
                                  "logical_blocks": si.logical_blocks, "served_through_clusters": si.shared_instances,
                                  "block_reads": si.cluster_block_reads + si.residual_block_reads,
                                  "plan_device_MB": si.device_bytes / 1e6},
+        "prefill_with_reuse": prefill,
         "threshold_stats": {"pairs_per_group": n_pairs, "pair_cosines_ms": ms_pairs,
                             "pair_cosines_GBps": rec.G * n_pairs * 2 * blk_bytes / (ms_pairs * 1e-3) / 1e9,
                             "mean_cosine": mu_s, "sigma_cosine": sigma_s,
