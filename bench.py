@@ -33,6 +33,8 @@ def make_recipe(wl, name):
         return wl.tiny_bff()
     if name == "llama8b_bff_prefix75":       # same shape, three quarters of every request is the common prefix
         return wl.llama8b_bff(prefix_tokens=1536)
+    if name == "zipf_bff_slab":              # config 4's shape, a slab of 4 of its 80 layers (the whole does not fit HBM un-fused)
+        return wl.zipf_bff(layers=4)
     if name == "llama8b_bff_small":          # quick functional check, not a benchmark configuration
         return wl.llama8b_bff(n_req=16, layers=4)
     raise SystemExit(f"unknown workload {name}")
@@ -68,7 +70,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="llama8b_bff")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cand-cap", type=int, default=16)
+    ap.add_argument("--cand-cap", type=int, default=64)
     ap.add_argument("--thr", type=float, default=None, help="override the workload's similarity threshold")
     ap.add_argument("--calib-copy-gib", type=float, default=0.0,
                     help="also run a plain device copy of this many GiB (3 times) so that rocprofv3 --pmc FETCH_SIZE / "

@@ -213,7 +213,7 @@ def tree_spec(leaf_start, leaf_count, unit_leaf_ptr, group_size=0):
     return spec
 
 
-def workspace_bytes(G, n, spec, cand_cap=16):
+def workspace_bytes(G, n, spec, cand_cap=64):
     out = C.c_size_t(0)
     rc = lib.kvfuse_workspace_bytes(G, n, C.byref(spec), cand_cap, C.byref(out))
     if rc:
@@ -224,7 +224,7 @@ def workspace_bytes(G, n, spec, cand_cap=16):
 class Plan:
     """kvfuse_plan_create over a caller-allocated (torch) workspace."""
 
-    def __init__(self, ctx: Context, cache: Cache, spec: TreeSpec, cand_cap: int = 16):
+    def __init__(self, ctx: Context, cache: Cache, spec: TreeSpec, cand_cap: int = 64):
         self.ctx, self.cache, self.spec, self.cand_cap = ctx, cache, spec, cand_cap
         nbytes = workspace_bytes(cache.G, cache.n, spec, cand_cap)
         self.workspace = torch.empty(nbytes + 256, device=cache.K.device, dtype=torch.uint8)

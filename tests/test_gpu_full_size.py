@@ -142,6 +142,62 @@ def test_cff_long_full_size_sampled_groups_and_invariants(oracle):
     assert worst <= 2e-2
 
 
+@pytest.mark.timeout(600)
+def test_zipf_bff_one_layer_of_config_4_invariants_and_decode(oracle):
+    """Config 4's shape for one of its 80 layers (8 groups x 32768 blocks of 32 x 128, 256 requests): the oracle
+    cannot walk a group of this size, so the fused table is checked through invariants and determinism, and the
+    decode attention through it (GQA 8, 32-token blocks) on sampled requests against the oracle."""
+    kb = gu.load_binding()
+    rec = wl.zipf_bff(layers=1)
+    print("materialise", rec.name, "G", rec.G, "n", rec.n, "r", rec.r, flush=True)
+    mat = wl.materialise(rec, DEV)
+    K0, V0, bt0 = mat["K"].clone(), mat["V"].clone(), mat["bt"].clone()
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, cand_cap=64)
+    print("gpu fused", stats.fused, "CR", stats.compression_ratio, "refined", stats.refined, "overflow", stats.cand_overflow, flush=True)
+    n, P = rec.n, rec.n
+    bt = cache.bt.cpu().numpy()
+    rc = cache.refcount.cpu().numpy()
+    remap = cache.remap.cpu().numpy()
+    n_phys = cache.n_phys.cpu().numpy()
+    n_free = cache.n_free.cpu().numpy()
+    sk = cache.scale_k.cpu().numpy()
+    nk = cache.norm_k.cpu().numpy()
+    assert stats.compression_ratio > 3 and (rc.sum(1) == n).all()
+    assert stats.physical_blocks == int(n_phys.sum()) and stats.logical_blocks == rec.G * n
+    p = int(rec.req_blocks[0])
+    for g in range(rec.G):
+        live = np.unique(bt[g])
+        assert len(live) == n_phys[g] and n_phys[g] + n_free[g] == P
+        assert (remap[g][live] == -1).all() and np.array_equal(np.bincount(bt[g], minlength=P), rc[g])
+        assert np.array_equal(bt[g][:p], np.arange(p))              # the first leaf is the left-most set: never evicted
+        fused = live[rc[g][live] > 1]
+        assert np.abs(nk[g][fused] - 1.0).max() < 3e-3
+        assert (sk[g][rc[g][bt[g]] == 1] == 1.0).all()
+    # determinism: the same input gives the same table and pool bit for bit
+    bt_a, K_a = cache.bt.clone(), cache.K.clone()
+    cache.K.copy_(K0); cache.V.copy_(V0); cache.bt.copy_(bt0)
+    stats2 = kb.fuse_tree(ctx, plan, rec.thr, want_stats=True)
+    torch.cuda.synchronize()
+    assert stats2.fused == stats.fused and torch.equal(cache.bt, bt_a) and torch.equal(cache.K, K_a)
+    # decode on sampled requests
+    q = wl.queries(rec, DEV)
+    rs = torch.tensor(rec.req_start, dtype=torch.int32, device=DEV)
+    cl = torch.tensor(rec.ctx_len, dtype=torch.int32, device=DEV)
+    out = kb.paged_decode_attn(ctx, cache, rec.kv_heads, q, rs, cl, int(rec.req_blocks.max()))
+    torch.cuda.synchronize()
+    worst = 0.0
+    gs = list(range(rec.kv_heads))
+    pools = ([wl.to_numpy_pool(cache.K[g]) for g in gs], [wl.to_numpy_pool(cache.V[g]) for g in gs])
+    for b in (0, 101, rec.B - 1):
+        ref = oracle.paged_decode_attention(
+            q[0, b: b + 1].float().cpu().numpy(), pools[0], pools[1], [bt[g] for g in gs], [sk[g].astype(np.float64) for g in gs],
+            [cache.scale_v[g].cpu().numpy().astype(np.float64) for g in gs], rec.req_start[b: b + 1], rec.ctx_len[b: b + 1],
+            rec.t, rec.d)
+        worst = max(worst, float(np.abs(out[0, b].cpu().numpy() - ref[0]).max()))
+    print("decode max abs err on sampled requests", worst, flush=True)
+    assert worst <= 2e-2
+
+
 class _GroupView:
     """Presents group g of a big cache as group 0 to gu.compare_group."""
 
