@@ -35,6 +35,8 @@ def make_recipe(wl, name):
         return wl.llama8b_bff(prefix_tokens=1536)
     if name == "zipf_bff_slab":              # config 4's shape, a slab of 4 of its 80 layers (the whole does not fit HBM un-fused)
         return wl.zipf_bff(layers=4)
+    if name == "mixed_slab":                 # config 5's shape, one of its 32 layers (292 GB un-fused as a whole)
+        return wl.mixed(layers=1)
     if name == "llama8b_bff_small":          # quick functional check, not a benchmark configuration
         return wl.llama8b_bff(n_req=16, layers=4)
     raise SystemExit(f"unknown workload {name}")

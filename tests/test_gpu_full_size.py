@@ -143,12 +143,14 @@ def test_cff_long_full_size_sampled_groups_and_invariants(oracle):
 
 
 @pytest.mark.timeout(600)
-def test_zipf_bff_one_layer_of_config_4_invariants_and_decode(oracle):
-    """Config 4's shape for one of its 80 layers (8 groups x 32768 blocks of 32 x 128, 256 requests): the oracle
-    cannot walk a group of this size, so the fused table is checked through invariants and determinism, and the
-    decode attention through it (GQA 8, 32-token blocks) on sampled requests against the oracle."""
+@pytest.mark.parametrize("config", ["config4_zipf", "config5_mixed"])
+def test_one_layer_of_the_large_configs_invariants_and_decode(oracle, config):
+    """One layer of config 4 (8 groups x 32768 blocks of 32 x 128, 256 requests, GQA 8) and of config 5 (8 groups x
+    about 141 k blocks, 512 ragged requests of 1 - 4 chunks each, chunk sub-trees below the request tree): the
+    oracle cannot walk groups of this size, so the fused table is checked through invariants and bit-for-bit
+    determinism, and the decode attention through it on sampled requests against the oracle."""
     kb = gu.load_binding()
-    rec = wl.zipf_bff(layers=1)
+    rec = wl.zipf_bff(layers=1) if config == "config4_zipf" else wl.mixed(layers=1)
     print("materialise", rec.name, "G", rec.G, "n", rec.n, "r", rec.r, flush=True)
     mat = wl.materialise(rec, DEV)
     K0, V0, bt0 = mat["K"].clone(), mat["V"].clone(), mat["bt"].clone()
@@ -162,9 +164,9 @@ def test_zipf_bff_one_layer_of_config_4_invariants_and_decode(oracle):
     n_free = cache.n_free.cpu().numpy()
     sk = cache.scale_k.cpu().numpy()
     nk = cache.norm_k.cpu().numpy()
-    assert stats.compression_ratio > 3 and (rc.sum(1) == n).all()
+    assert stats.compression_ratio > (3 if config == "config4_zipf" else 1.3) and (rc.sum(1) == n).all()
     assert stats.physical_blocks == int(n_phys.sum()) and stats.logical_blocks == rec.G * n
-    p = int(rec.req_blocks[0])
+    p = int(rec.leaf_count[0])
     for g in range(rec.G):
         live = np.unique(bt[g])
         assert len(live) == n_phys[g] and n_phys[g] + n_free[g] == P
