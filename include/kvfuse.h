@@ -21,7 +21,10 @@
  *   - All work is enqueued on the context's stream and is asynchronous unless stated otherwise.
  *   - A group g is one (layer, KV head): g = layer * kv_heads + kv_head.  Groups are independent.
  *   - Pool layout: [G][P][t][d] elements, one block (r = t*d elements) contiguous.  dtype bf16 or f32.
- *     r * sizeof(element) must be a multiple of 128 bytes and r <= 8192 (KVFUSE_ESHAPE otherwise).
+ *     r * sizeof(element) must be a multiple of 128 bytes and at most 32 KiB (KVFUSE_ESHAPE otherwise).
+ *     The fusion steps never look inside a block, so the paper's own vector -- one per block over all KV heads
+ *     of a layer (method section: r = t*h*d, one table per layer) -- is the same call with G = layers,
+ *     d := h*d and the pool laid out [layers][P][t][h][d]; the attention entry points need the per-head layout.
  *   - Representation (method section: "a single unit vector and a norm (scalar) per block"): logical block
  *     x of group g stands for  scale[g][x] * stored(bt[g][x]).  Blocks that were never fused stay as they
  *     were written (scale exactly 1); a fused representative is stored as a unit vector rounded to the

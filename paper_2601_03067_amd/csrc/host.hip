@@ -292,8 +292,8 @@ static int check_pool(Ctx *ctx, const kvfuse_pool *p)
         return fail(ctx, KVFUSE_ESHAPE, "pool: dtype must be KVFUSE_BF16 or KVFUSE_F32");
     const int64_t r = (int64_t)p->t * p->d;
     const int64_t bytes = r * (p->dtype == KVFUSE_BF16 ? 2 : 4);
-    if (bytes % 128 != 0 || r > 8192)
-        return fail(ctx, KVFUSE_ESHAPE, "pool: t*d*sizeof(element) must be a multiple of 128 bytes and t*d <= 8192");
+    if (bytes % 128 != 0 || bytes > 32768)
+        return fail(ctx, KVFUSE_ESHAPE, "pool: t*d*sizeof(element) must be a multiple of 128 bytes and at most 32 KiB");
     return KVFUSE_OK;
 }
 

@@ -325,7 +325,8 @@ void launch_merge(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const 
     if (pool.dtype == KVFUSE_BF16) {
         if (maxc <= 1) KVF_MERGE(bf16_t, 1);
         else if (maxc <= 2) KVF_MERGE(bf16_t, 2);
-        else KVF_MERGE(bf16_t, 4);
+        else if (maxc <= 4) KVF_MERGE(bf16_t, 4);
+        else KVF_MERGE(bf16_t, 8);
     } else {
         if (maxc <= 1) KVF_MERGE(float, 1);
         else if (maxc <= 2) KVF_MERGE(float, 2);

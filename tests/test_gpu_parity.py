@@ -244,7 +244,7 @@ def test_tree_zipf_many_near_ties(kb, oracle):
     assert stats.refined > 20
 
 
-@pytest.mark.parametrize("shape", ["r4096_bf16", "r8192_bf16", "r2048_f32"])
+@pytest.mark.parametrize("shape", ["r4096_bf16", "r8192_bf16", "r2048_f32", "r16384_bf16_all_heads", "r8192_f32"])
 def test_tree_long_blocks(kb, oracle, shape):
     """Block lengths beyond the bench shape: config 4's 32 x 128 blocks (8 KiB rows: 128 K-slices per row in the
     similarity kernels, two-wavefront merge items), the longest supported block (t*d = 8192: workgroup-per-target
@@ -253,12 +253,20 @@ def test_tree_long_blocks(kb, oracle, shape):
         rec = wl.zipf_bff(n_req=6, tokens=32 * 150, layers=1, kv_heads=2, pool=400, t=32, d=128, thr=0.9)
     elif shape == "r8192_bf16":
         rec = wl.zipf_bff(n_req=4, tokens=64 * 90, layers=1, kv_heads=1, pool=200, t=64, d=128, thr=0.9)
+    elif shape == "r16384_bf16_all_heads":
+        # the paper's own vector: one per block over all 8 KV heads of a layer (t = 16, h * d = 1024), one table per
+        # layer -- for the fusion steps simply a pool with G = layers and d := h * d
+        rec = wl.zipf_bff(n_req=4, tokens=16 * 90, layers=2, kv_heads=1, pool=200, t=16, d=1024, thr=0.9)
+    elif shape == "r8192_f32":
+        rec = wl.zipf_bff(n_req=3, tokens=64 * 100, layers=1, kv_heads=1, pool=150, t=64, d=128, thr=0.9, dtype=torch.float32)
     else:
         rec = wl.zipf_bff(n_req=4, tokens=16 * 150, layers=1, kv_heads=1, pool=300, t=16, d=128, thr=0.9, dtype=torch.float32)
     # the screen's error bound grows with the block length: the band must be at least r * 2^-22
     cache, plan, stats, res, mat = _run_tree_case(kb, oracle, rec, "long_blocks_" + shape, cand_cap=8,
                                                   band=max(1e-3, 1.25 * rec.r * 2.0 ** -22))
     assert stats.fused > 50
+    if rec.d > 128:
+        return                      # the attention kernels need the per-head layout
     q = wl.queries(rec, DEV)
     out = _decode(kb, ctx=kb.Context(DEV), rec=rec, cache=cache, q=q)
     ref = _attn_oracle(oracle, rec, cache, q[0], 0, rec.kv_heads)
