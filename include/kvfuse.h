@@ -87,7 +87,8 @@ typedef struct kvfuse_table {
  * fused over its own leaves the same way.  With one unit this is CFF over its chunks; with one leaf per
  * unit it is BFF.  group_size > 0 applies the method's "every N requests or chunks": consecutive runs of
  * N units (N leaves when there is a single unit) form independent trees; <= 0 means one tree.
- * Leaves must be in ascending, non-overlapping logical order. */
+ * Leaves must not overlap; the order of the lists is the order of the tree, whatever the logical positions (see
+ * kvfuse_tree_spec_shortest_first). */
 typedef struct kvfuse_tree_spec {
     int32_t n_leaves;
     const int32_t *leaf_start;    /* host [n_leaves] */
@@ -177,7 +178,8 @@ int kvfuse_similarity(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t height, double
 /* ---- a3: assignment (Algorithm 1: indices where sim > thr, one target per right block) ---------- */
 
 /* Right block j fuses into the left row with the largest cosine, lowest row on exact ties, iff that cosine
- * is > thr (strict).  Cosines that decide are fp64.  Then, per node: members grouped by target (ascending j),
+ * is > thr (strict); under KVFUSE_RULE_FIRST_ROW (kvfuse_plan_set_assign_rule) into the lowest row whose cosine
+ * is > thr.  Cosines that decide are fp64.  Then, per node: members grouped by target (ascending j),
  * evicted blocks entered in table.remap, the surviving set cat(left, non-fused right in order) written in
  * place, and the list of targets to rebuild handed to kvfuse_merge. */
 int kvfuse_assign(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t height, double thr, double band);
@@ -345,6 +347,44 @@ double kvfuse_threshold_feedback(double thr, double observed_cr, double target_c
  * read during those calls and must stay alive; it is also copied to the host here for the statistics (this call
  * waits for the stream). */
 int kvfuse_plan_set_group_mask(kvfuse_ctx *ctx, kvfuse_plan *plan, const uint8_t *enable);
+
+/* ---- variants of the method ---------------------------------------------------------------------------- */
+
+/* Algorithm 1 loops over the rows of sim, collects for each row the right blocks above the threshold and evicts
+ * them.  A right block that clears the threshold for several rows can go to one of them only.
+ * KVFUSE_RULE_ARGMAX (the default) gives it to the most similar row; KVFUSE_RULE_FIRST_ROW follows the loop
+ * literally: the block is gone once the first such row has taken it, so the lowest row with cosine > thr wins.
+ * Applies to the following kvfuse_assign / kvfuse_fuse_tree calls on this plan.  Under FIRST_ROW the
+ * near_threshold statistic counts columns whose deciding cosine (the taker's; the column maximum when no row
+ * takes the block) lies within band of thr. */
+enum { KVFUSE_RULE_ARGMAX = 0, KVFUSE_RULE_FIRST_ROW = 1 };
+int kvfuse_plan_set_assign_rule(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t rule);
+
+/* Method section, remark on the order of requests: requests with fewer blocks are better placed on the left of
+ * the tree.  Host only.  Writes the spec's lists reordered so that units come in ascending number of blocks
+ * (stable; the leaves of a unit keep their order); with a single unit its leaves are sorted instead.
+ *   leaf_start, leaf_count host [n_leaves] out;  unit_leaf_ptr host [n_units + 1] out (may alias the inputs)
+ *   order  host [n_units] (or [n_leaves] when n_units == 1) out, may be NULL: position k holds the unit (leaf)
+ *          that was at index order[k]
+ * The logical layout of the table is untouched: only the tree changes. */
+int kvfuse_tree_spec_shortest_first(const kvfuse_tree_spec *spec, int32_t *leaf_start, int32_t *leaf_count,
+                                    int32_t *unit_leaf_ptr, int32_t *order);
+
+/* Results section, first evaluation mode ("fuse and replicate the rescaled cache across all fused blocks, without
+ * freeing blocks"): every logical entry x gets the block it had before fusion back, orig_bt[x], filled with
+ * scale[x] * stored(bt[x]) rounded once to the pool dtype (K with scale_k, V with scale_v), so that an attention
+ * kernel that knows nothing of fusion sees what the fused cache stands for.  On return the table is orig_bt again
+ * with unit scales, one reference per block, nothing evicted, and the pool's norms are those of the rewritten
+ * blocks, exactly as after kvfuse_block_norms on the new contents.
+ *   orig_bt  device [G][n] int32: the table as it was before kvfuse_fuse_tree (injective per group; the caller
+ *            keeps a copy, the library does not).  Entries with an id outside [0, P) are left alone.
+ * Asynchronous. */
+int kvfuse_replicate_rescaled(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table, const int32_t *orig_bt);
+
+/* Results section, second evaluation mode ("fusing and freeing blocks, without rescaling"): the fused table and
+ * the freed blocks stay as they are and every scale_k / scale_v becomes 1, so each logical block reads its shared
+ * representative as stored.  Asynchronous. */
+int kvfuse_drop_rescale(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table);
 
 /* ---- machine probes (measurement aids; not part of the hot path) -------------------------------------- */
 

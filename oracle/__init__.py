@@ -116,6 +116,16 @@ def assign(S: np.ndarray, thr: float):
     return a, best, second
 
 
+def assign_first_row(S: np.ndarray, thr: float):
+    """Threshold line of Algorithm 1 in row order: the first row above thr takes the block -> assign[mr]."""
+    lib = _load()
+    S = np.ascontiguousarray(S, np.float64)
+    ml, mr = S.shape
+    a = np.full(mr, -1, np.int32)
+    lib.ora_assign_first_row(_ptr(S, _f64p), ml, mr, ctypes.c_double(thr), _ptr(a, _i32p))
+    return a
+
+
 def merge(pool: np.ndarray, norm: np.ndarray, L, R, assign_) -> None:
     """Fusion lines of Algorithm 1 for one pool tensor, in place (pool rows and norm of targets)."""
     lib = _load()
@@ -161,8 +171,11 @@ class GroupResult:
 
 
 def fuse_group(kpool: np.ndarray, vpool: np.ndarray, bt: np.ndarray, leaf_start, leaf_count, unit_leaf_ptr,
-               thr: float, group_size: int = 0, band: float = 1e-3, want_trace: bool = False) -> GroupResult:
-    """Run Algorithm 1 on one group.  Inputs are copied; the result holds the fused pool and table."""
+               thr: float, group_size: int = 0, band: float = 1e-3, want_trace: bool = False,
+               rule: str = "argmax") -> GroupResult:
+    """Run Algorithm 1 on one group.  Inputs are copied; the result holds the fused pool and table.
+    rule: "argmax" (one target per right block, the most similar row) or "first_row" (the row loop taken
+    literally: the first row above the threshold takes the block)."""
     lib = _load()
     eb = _elem_bytes(kpool)
     assert kpool.shape == vpool.shape and kpool.dtype == vpool.dtype
@@ -195,7 +208,8 @@ def fuse_group(kpool: np.ndarray, vpool: np.ndarray, bt: np.ndarray, leaf_start,
         _ptr(res.orig_norm_k, _f64p), _ptr(res.orig_norm_v, _f64p), _ptr(res.norm_k, _f64p),
         _ptr(res.norm_v, _f64p), _ptr(res.scale_k, _f64p), _ptr(res.scale_v, _f64p),
         _ptr(res.refcount, _i32p), _ptr(free_list, _i32p), ctypes.byref(n_free), _ptr(res.stats, _f64p),
-        _ptr(trace, _i32p) if want_trace else None, ctypes.c_int64(trace_cap), ctypes.byref(trace_len))
+        _ptr(trace, _i32p) if want_trace else None, ctypes.c_int64(trace_cap), ctypes.byref(trace_len),
+        {"argmax": 0, "first_row": 1}[rule])
     if rc != 0:
         raise ValueError(f"ora_fuse_group failed with code {rc}")
     res.free_list = free_list[: n_free.value].copy()
@@ -204,16 +218,62 @@ def fuse_group(kpool: np.ndarray, vpool: np.ndarray, bt: np.ndarray, leaf_start,
 
 
 def fuse_groups(kpools, vpools, bts, leaf_start, leaf_count, unit_leaf_ptr, thr, group_size=0, band=1e-3,
-                threads: int = 1):
+                threads: int = 1, rule: str = "argmax"):
     """Independent groups on ``threads`` host threads (ctypes drops the GIL inside the C call)."""
     def one(g):
         return fuse_group(kpools[g], vpools[g], bts[g], leaf_start, leaf_count, unit_leaf_ptr, thr,
-                          group_size, band)
+                          group_size, band, rule=rule)
     G = len(kpools)
     if threads <= 1:
         return [one(g) for g in range(G)]
     with ThreadPoolExecutor(max_workers=threads) as ex:
         return list(ex.map(one, range(G)))
+
+
+# ----------------------------------------------------------------------
+# variants: order of the requests, the two evaluation modes
+# ----------------------------------------------------------------------
+
+def shortest_first(leaf_start, leaf_count, unit_leaf_ptr):
+    """Remark after Algorithm 1: requests with fewer blocks go to the left of the tree.  Units in ascending
+    number of blocks, ties in their given order, each unit keeping its leaves; with one unit its leaves are
+    ordered instead.  -> (leaf_start, leaf_count, unit_leaf_ptr, order)."""
+    ls, lc, up = (np.asarray(a, np.int64) for a in (leaf_start, leaf_count, unit_leaf_ptr))
+    n_units = len(up) - 1
+    if n_units == 1:
+        order = sorted(range(len(ls)), key=lambda l: (lc[l], l))
+        return ls[order].astype(np.int32), lc[order].astype(np.int32), up.astype(np.int32), np.asarray(order, np.int32)
+    size = [int(lc[up[u]:up[u + 1]].sum()) for u in range(n_units)]
+    order = sorted(range(n_units), key=lambda u: (size[u], u))
+    out_s, out_c, out_p = [], [], [0]
+    for u in order:
+        out_s += list(ls[up[u]:up[u + 1]])
+        out_c += list(lc[up[u]:up[u + 1]])
+        out_p.append(len(out_s))
+    return (np.asarray(out_s, np.int32), np.asarray(out_c, np.int32), np.asarray(out_p, np.int32),
+            np.asarray(order, np.int32))
+
+
+def _round_to_pool(x: np.ndarray, like: np.ndarray) -> np.ndarray:
+    """fp64 -> the pool's storage type, nearest even, one rounding."""
+    lib = _load()
+    flat = np.ascontiguousarray(x, np.float64).ravel()
+    out = np.empty(flat.shape, like.dtype)
+    lib.ora_store_array(_ptr(out), _elem_bytes(like), _ptr(flat, _f64p), ctypes.c_size_t(flat.size))
+    return out.reshape(x.shape)
+
+
+def replicate_rescaled(pool: np.ndarray, bt0: np.ndarray, bt: np.ndarray, scale: np.ndarray) -> np.ndarray:
+    """First evaluation mode of the results section for one pool tensor of one group: every logical block x gets
+    the block it had before fusion, bt0[x], filled with scale[x] * stored(bt[x]) in the pool's type; nothing is
+    freed.  The scale is the binary32 number the table holds.  Returns the new pool [P][r]; blocks that no entry
+    of bt0 names are unchanged."""
+    src = pool_to_f64(pool)
+    out = np.array(pool, copy=True)
+    for x in range(len(bt0)):
+        s = float(np.float32(scale[x]))
+        out[bt0[x]] = _round_to_pool(s * src[bt[x]], pool)
+    return out
 
 
 # ----------------------------------------------------------------------

@@ -93,6 +93,13 @@ static void ora_store(void *base, int elem_bytes, size_t idx, double x)
 /* exported so that tests can pin the rounding rule on its own */
 double ora_test_round_bf16(double x) { return ora_round_to_bf16(x); }
 
+/* n doubles -> n values of the pool's storage type (float, or bfloat16 bit patterns), one rounding each */
+void ora_store_array(void *dst, int elem_bytes, const double *x, size_t n)
+{
+    for (size_t i = 0; i < n; ++i)
+        ora_store(dst, elem_bytes, i, x[i]);
+}
+
 /* ------------------------------------------------------------------ */
 /* the steps of one tree node                                          */
 /* ------------------------------------------------------------------ */
@@ -158,6 +165,24 @@ void ora_assign(const double *S, int ml, int mr, double thr, int32_t *assign, do
         if (second)
             second[j] = s2;
     }
+}
+
+/* Threshold line of Algorithm 1 under the row-order reading (the loop over
+ * the rows of sim, taken literally): rows are visited in ascending order; a
+ * row takes every right block whose cosine with it is > thr and that no
+ * earlier row has taken, and a taken block is evicted at once, so later rows
+ * no longer see it.  assign[j] = the row that took j, or -1. */
+void ora_assign_first_row(const double *S, int ml, int mr, double thr, int32_t *assign)
+{
+    for (int j = 0; j < mr; ++j)
+        assign[j] = -1;
+    for (int i = 0; i < ml; ++i)
+        for (int j = 0; j < mr; ++j) {
+            if (assign[j] >= 0)
+                continue; /* evicted by an earlier row */
+            if (S[(size_t)i * mr + j] > thr)
+                assign[j] = i;
+        }
 }
 
 /* Fusion lines of Algorithm 1 for one pool tensor (call once for K, once for
@@ -248,6 +273,7 @@ typedef struct {
     int32_t *bt;
     const int32_t *leaf_start, *leaf_count;
     double thr, band;
+    int rule; /* 0: one target per right block by arg-max; 1: row order, the first row above thr takes the block */
     double *orig_norm_k, *orig_norm_v, *norm_k, *norm_v, *scale_k, *scale_v;
     int32_t *refcount, *free_list, *n_free;
     /* decision statistics */
@@ -276,6 +302,13 @@ static ora_set ora_node(ora_ctx *c, ora_set Ls, ora_set Rs)
             col[i] = ora_cosine(c->kpool, c->elem_bytes, c->r, c->norm_k, Ls.id[i], Rs.id[j]);
         double best, second;
         ora_assign(col, ml, 1, c->thr, &assign[j], &best, &second);
+        if (c->rule == 1) {
+            /* the column seen by the row loop; the value that decided it is the taker's cosine, or the column
+             * maximum when no row took it */
+            ora_assign_first_row(col, ml, 1, c->thr, &assign[j]);
+            if (assign[j] >= 0)
+                best = col[assign[j]];
+        }
         /* statistics only; they never feed back into a decision */
         if (ml > 0) {
             c->n_decisions++;
@@ -286,7 +319,9 @@ static ora_set ora_node(ora_ctx *c, ora_set Ls, ora_set Rs)
                 c->n_near_thr++;
             if (assign[j] >= 0) {
                 c->n_fused++;
-                if (best == second)
+                if (c->rule == 1)
+                    ; /* ties between rows play no part in the row-order reading */
+                else if (best == second)
                     c->n_exact_tie++;
                 else if (best - second < c->min_tie_gap)
                     c->min_tie_gap = best - second;
@@ -364,6 +399,7 @@ static ora_set ora_ff_units(ora_ctx *c, const int32_t *unit_leaf_ptr, int lo, in
  *                 independent trees; <= 0 means one tree over everything
  *   outputs       orig_norm_* [n], norm_* [P], scale_* [n], refcount [P],
  *                 free_list [P] + *n_free, stats[8], optional trace
+ *   rule          0 = arg-max reading of the threshold line, 1 = row-order reading
  * stats: 0 decisions, 1 fused, 2 near-threshold (|best-thr| <= band),
  *        3 exact ties among fused, 4 min |best-thr|, 5 min positive tie gap,
  *        6 distinct physical blocks after fusion, 7 compression ratio n/distinct
@@ -373,7 +409,7 @@ int ora_fuse_group(int elem_bytes, int r, int P, int n, void *kpool, void *vpool
                    const int32_t *unit_leaf_ptr, int n_units, int group_size, double thr, double band,
                    double *orig_norm_k, double *orig_norm_v, double *norm_k, double *norm_v,
                    double *scale_k, double *scale_v, int32_t *refcount, int32_t *free_list,
-                   int32_t *n_free, double *stats, int32_t *trace, int64_t trace_cap, int64_t *trace_len)
+                   int32_t *n_free, double *stats, int32_t *trace, int64_t trace_cap, int64_t *trace_len, int rule)
 {
     if ((elem_bytes != 2 && elem_bytes != 4) || r <= 0 || P <= 0 || n < 0)
         return -1;
@@ -382,7 +418,7 @@ int ora_fuse_group(int elem_bytes, int r, int P, int n, void *kpool, void *vpool
     c.elem_bytes = elem_bytes; c.r = r; c.P = P; c.n = n;
     c.kpool = kpool; c.vpool = vpool; c.bt = bt;
     c.leaf_start = leaf_start; c.leaf_count = leaf_count;
-    c.thr = thr; c.band = band;
+    c.thr = thr; c.band = band; c.rule = rule;
     c.orig_norm_k = orig_norm_k; c.orig_norm_v = orig_norm_v;
     c.norm_k = norm_k; c.norm_v = norm_v; c.scale_k = scale_k; c.scale_v = scale_v;
     c.refcount = refcount; c.free_list = free_list; c.n_free = n_free;

@@ -120,6 +120,11 @@ lib.kvfuse_predict_compression.argtypes = [C.POINTER(_f64), _i32, _f64, C.POINTE
 lib.kvfuse_threshold_feedback.argtypes = [_f64] * 6
 lib.kvfuse_threshold_feedback.restype = _f64
 lib.kvfuse_plan_set_group_mask.argtypes = [_vp, _vp, _vp]
+lib.kvfuse_plan_set_assign_rule.argtypes = [_vp, _vp, _i32]
+lib.kvfuse_tree_spec_shortest_first.argtypes = [C.POINTER(TreeSpec), _vp, _vp, _vp, _vp]
+lib.kvfuse_replicate_rescaled.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _vp]
+lib.kvfuse_drop_rescale.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table)]
+RULE_ARGMAX, RULE_FIRST_ROW = 0, 1
 lib.kvfuse_probe_mfma_bf16.argtypes = [_vp, _i32, _vp, C.c_size_t, C.POINTER(C.c_double)]
 lib.kvfuse_probe_copy.argtypes = [_vp, _vp, _vp, C.c_size_t, _i32, C.POINTER(C.c_double)]
 PROBE_SCRATCH_BYTES = 65792
@@ -406,6 +411,34 @@ def set_group_mask(ctx, plan, enable):
         assert enable.dtype == torch.uint8 and enable.is_contiguous() and enable.numel() == plan.cache.pool.G
     plan.group_mask = enable
     ctx.check(lib.kvfuse_plan_set_group_mask(ctx.h, plan.h, _ptr(enable) if enable is not None else None))
+
+
+def set_assign_rule(ctx, plan, rule):
+    ctx.check(lib.kvfuse_plan_set_assign_rule(ctx.h, plan.h, int(rule)))
+
+
+def tree_spec_shortest_first(spec: TreeSpec):
+    """-> (reordered TreeSpec, order): units (leaves, when there is one unit) in ascending number of blocks."""
+    ls = np.zeros(max(spec.n_leaves, 1), np.int32)
+    lc = np.zeros(max(spec.n_leaves, 1), np.int32)
+    up = np.zeros(spec.n_units + 1, np.int32)
+    order = np.zeros(max(spec.n_leaves if spec.n_units == 1 else spec.n_units, 1), np.int32)
+    rc = lib.kvfuse_tree_spec_shortest_first(C.byref(spec), ls.ctypes.data, lc.ctypes.data, up.ctypes.data,
+                                             order.ctypes.data)
+    if rc:
+        raise KvfuseError(rc, "kvfuse_tree_spec_shortest_first failed")
+    n_order = spec.n_leaves if spec.n_units == 1 else spec.n_units
+    return tree_spec(ls[:spec.n_leaves], lc[:spec.n_leaves], up, spec.group_size), order[:n_order].copy()
+
+
+def replicate_rescaled(ctx, cache, orig_bt):
+    """orig_bt: int32 tensor [G][n] on the device, the table before fusion."""
+    assert orig_bt.dtype == torch.int32 and orig_bt.is_contiguous() and orig_bt.shape == cache.bt.shape
+    ctx.check(lib.kvfuse_replicate_rescaled(ctx.h, C.byref(cache.pool), C.byref(cache.table), _ptr(orig_bt)))
+
+
+def drop_rescale(ctx, cache):
+    ctx.check(lib.kvfuse_drop_rescale(ctx.h, C.byref(cache.pool), C.byref(cache.table)))
 
 
 class SharedDecodePlan:

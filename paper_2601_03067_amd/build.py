@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvfuse.so")
-SOURCES = ["host.hip", "norms.hip", "similarity.hip", "assign.hip", "merge.hip", "rewrite.hip", "decode.hip", "decode_shared.hip", "prefill.hip", "threshold.hip", "probe.hip"]
+SOURCES = ["host.hip", "norms.hip", "similarity.hip", "assign.hip", "merge.hip", "rewrite.hip", "decode.hip", "decode_shared.hip", "prefill.hip", "threshold.hip", "variants.hip", "probe.hip"]
 # packed-fp32 instructions are switched off for every device object of this library
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"]

@@ -1,6 +1,11 @@
 // a3: thresholded arg-max assignment (Algorithm 1: "indices where sim(row) > thr", read as one target per right
 // block: the left row with the largest cosine, lowest row on exact ties, strict '>').
 //
+// The other reading of the same line (rule KVFUSE_RULE_FIRST_ROW) follows the row loop literally: the first left row
+// whose cosine is > thr takes the block.  It uses the same candidate lists: a listed row whose screened cosine is
+// above thr + 2*band certainly qualifies, an unlisted one certainly does not, and only listed rows below the first
+// certain one need the fp64 re-check, in ascending row order.
+//
 // Three kernels per height:
 //   screen   one thread per right block.  The MFMA screen has left a short candidate list per column.  A column
 //            with no candidate cannot fuse.  A column whose best candidate is clear of the threshold and of every
@@ -57,7 +62,8 @@ __global__ void assign_reset_kernel(WorkDesc w, int height)
 
 // One THREAD per right block: everything the screen settles on its own (no candidate; or one candidate clear of the
 // threshold and of all others by more than 2 * band).  Columns it cannot settle go to the re-check list.
-__global__ __launch_bounds__(256) void assign_screen_kernel(WorkDesc w, HeightDesc h, int height, double thr, double band)
+__global__ __launch_bounds__(256) void assign_screen_kernel(WorkDesc w, HeightDesc h, int height, double thr, double band,
+                                                            int rule)
 {
     const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (id >= (int64_t)w.G * h.total_r_cap)
@@ -74,7 +80,21 @@ __global__ __launch_bounds__(256) void assign_screen_kernel(WorkDesc w, HeightDe
     const int cnt = ml > 0 ? w.cand_cnt[cidx] : 0;
     int result = -1;
     bool recheck = cnt > w.cand_cap;
-    if (cnt > 0 && !recheck) {
+    if (cnt > 0 && !recheck && rule == KVFUSE_RULE_FIRST_ROW) {
+        // lowest row that certainly clears the threshold; open = some undecided row comes before it
+        int i_def = 0x7FFFFFFF;
+        for (int k = 0; k < cnt; ++k)
+            if ((double)w.cand_val[cidx * w.cand_cap + k] > thr + 2.0 * band)
+                i_def = min(i_def, w.cand_idx[cidx * w.cand_cap + k]);
+        bool open = false;
+        for (int k = 0; k < cnt; ++k)
+            open |= !((double)w.cand_val[cidx * w.cand_cap + k] > thr + 2.0 * band) &&
+                    w.cand_idx[cidx * w.cand_cap + k] < i_def;
+        if (open)
+            recheck = true;
+        else
+            result = i_def;      // every list entry is either certain or open, so i_def is a row here
+    } else if (cnt > 0 && !recheck) {
         float smax = -INFINITY;
         int imax = -1;
         for (int k = 0; k < cnt; ++k) {
@@ -102,7 +122,7 @@ __global__ __launch_bounds__(256) void assign_screen_kernel(WorkDesc w, HeightDe
 // overflowed), strict '>' against thr, lowest row on exact ties.
 template <typename T>
 __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkDesc w, HeightDesc h, int height, double thr,
-                                                            double band)
+                                                            double band, int rule)
 {
     const int lane = threadIdx.x & 63;
     const int n_items = w.n_refine[height];
@@ -121,7 +141,53 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
         const int cnt = w.cand_cnt[cidx];
         double bv = -INFINITY;
         int bi = 0x7FFFFFFF;
-        if (cnt <= w.cand_cap) {
+        if (rule == KVFUSE_RULE_FIRST_ROW) {
+            // bv ends as the cosine that decided the column: the taker's, or the largest one seen when no row takes it
+            int win = -1;
+            if (cnt <= w.cand_cap) {
+                int ci = 0x7FFFFFFF;
+                float cv = -INFINITY;
+                if (lane < cnt) {
+                    ci = w.cand_idx[cidx * w.cand_cap + lane];
+                    cv = w.cand_val[cidx * w.cand_cap + lane];
+                }
+                const bool certain = lane < cnt && (double)cv > thr + 2.0 * band;
+                int i_def = certain ? ci : 0x7FFFFFFF;
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1)
+                    i_def = min(i_def, __shfl_xor(i_def, off, 64));
+                unsigned long long open = __ballot(lane < cnt && !certain && ci < i_def);
+                while (open) {
+                    int i = ((open >> lane) & 1ull) ? ci : 0x7FFFFFFF;     // the lowest open row comes first
+#pragma unroll
+                    for (int off = 32; off >= 1; off >>= 1)
+                        i = min(i, __shfl_xor(i, off, 64));
+                    open &= ~__ballot(ci == i);
+                    const double cs = cosine_f64<T>(pool_g, pool.r, norm_g, l_ids[i], b, lane);
+                    if (cs > thr) {
+                        win = i;
+                        bv = cs;
+                        break;
+                    }
+                    bv = fmax(bv, cs);
+                }
+                if (win < 0 && i_def != 0x7FFFFFFF) {
+                    win = i_def;
+                    bv = INFINITY;      // certain rows are more than band above thr
+                }
+            } else {
+                for (int i = 0; i < ml; ++i) {
+                    const double cs = cosine_f64<T>(pool_g, pool.r, norm_g, l_ids[i], b, lane);
+                    if (cs > thr) {
+                        win = i;
+                        bv = cs;
+                        break;
+                    }
+                    bv = fmax(bv, cs);
+                }
+            }
+            bi = win;                   // no taker: every cosine seen was <= thr, so the store below writes -1
+        } else if (cnt <= w.cand_cap) {
             int ci = 0x7FFFFFFF;
             float cv = -INFINITY;
             if (lane < cnt) {
@@ -154,7 +220,7 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
             }
         }
         if (lane == 0) {
-            w.assign[cidx] = bv > thr ? bi : -1;
+            w.assign[cidx] = (bv > thr && bi != 0x7FFFFFFF) ? bi : -1;
             int32_t *cn = w.counters + (int64_t)g * 8;
             if (fabs(bv - thr) <= band)
                 atomicAdd(&cn[1], 1);
@@ -311,17 +377,17 @@ __global__ __launch_bounds__(256) void assign_finalize_kernel(int P, TableDesc t
 }
 
 void launch_assign(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, const WorkDesc &w, const HeightDesc &h,
-                   int height, double thr, double band)
+                   int height, double thr, double band, int rule)
 {
     const int64_t cols = (int64_t)w.G * h.total_r_cap;
     assign_reset_kernel<<<1, 1, 0, s>>>(w, height);
     if (cols > 0) {
-        assign_screen_kernel<<<(unsigned)((cols + 255) / 256), 256, 0, s>>>(w, h, height, thr, band);
+        assign_screen_kernel<<<(unsigned)((cols + 255) / 256), 256, 0, s>>>(w, h, height, thr, band, rule);
         const unsigned rgrid = (unsigned)(cols < 4096 ? (cols + 3) / 4 : 1024);
         if (pool.dtype == KVFUSE_BF16)
-            assign_refine_kernel<bf16_t><<<rgrid, 256, 0, s>>>(pool, w, h, height, thr, band);
+            assign_refine_kernel<bf16_t><<<rgrid, 256, 0, s>>>(pool, w, h, height, thr, band, rule);
         else
-            assign_refine_kernel<float><<<rgrid, 256, 0, s>>>(pool, w, h, height, thr, band);
+            assign_refine_kernel<float><<<rgrid, 256, 0, s>>>(pool, w, h, height, thr, band, rule);
     }
     if (w.G * h.n_nodes > 0)
         assign_finalize_kernel<<<(unsigned)(w.G * h.n_nodes), 256, 0, s>>>(pool.P, tab, w, h, height);

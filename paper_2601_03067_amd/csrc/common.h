@@ -85,6 +85,7 @@ struct WorkDesc {
     int32_t *n_refine;   // [max_heights]
     int32_t *counters;   // [G][8]: 0 fused, 1 near-threshold, 2 refined, 3 candidate overflow, 4 invalid ids
     const uint8_t *group_enable;   // [G] or null: groups with 0 are skipped by the similarity step (nothing fuses)
+    int32_t *leaf_src;   // [n] position in a set_ids row -> logical entry the leaf step fills it from, -1 = none
 };
 
 struct PoolDesc {
@@ -117,7 +118,7 @@ void launch_leaf_sets(hipStream_t s, const WorkDesc &w, const TableDesc &tab, in
 void launch_similarity(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const HeightDesc &h, float thr_floor,
                        float *dense_s);
 void launch_assign(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, const WorkDesc &w, const HeightDesc &h,
-                   int height, double thr, double band);
+                   int height, double thr, double band, int rule);
 void launch_merge(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const HeightDesc &h, int height);
 void launch_rewrite(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, int32_t *free_list, int32_t *n_free,
                     int32_t *n_phys);

@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstring>
 #include <new>
+#include <utility>
 
 #include "common.h"
 
@@ -21,6 +22,7 @@ int fail(Ctx *c, int code, const std::string &msg)
 struct Node {
     int left = -1, right = -1;   // children (node indices) or -1 for a leaf
     int off = 0;                 // start of the node's region in a set_ids row
+    int src = 0;                 // leaves: first logical entry of the leaf
     int cap = 0;                 // size of the surviving set if nothing fuses
     int height = 0;
 };
@@ -43,6 +45,7 @@ struct Plan {
     int32_t *slot_init = nullptr;   // device [n_slots]
     int max_r = 0, max_l = 0;
     std::vector<uint8_t> group_enable_host;   // copy of the group mask for the statistics; empty = all groups
+    int assign_rule = KVFUSE_RULE_ARGMAX;
 };
 
 // Similarity tile shapes (must match the two kernel instantiations): big 256 x 256, small 128 x 128.
@@ -52,12 +55,16 @@ constexpr int kMaxHeights = 64;
 struct TreeBuilder {
     const kvfuse_tree_spec *spec;
     std::vector<Node> nodes;
+    int next_off = 0;   // set regions are handed out in the order the recursion meets the leaves, whatever their
+                        // logical positions: the region of an inner node is then its children's, left then right
 
     int leaf(int l)
     {
         Node n;
-        n.off = spec->leaf_start[l];
+        n.off = next_off;
+        n.src = spec->leaf_start[l];
         n.cap = spec->leaf_count[l];
+        next_off += n.cap;
         nodes.push_back(n);
         return (int)nodes.size() - 1;
     }
@@ -82,10 +89,10 @@ struct TreeBuilder {
         const int b = over_leaves(mid, hi);
         return join(a, b);
     }
-    int empty_leaf(int off)
+    int empty_leaf()
     {
         Node n;
-        n.off = off;
+        n.off = next_off;
         n.cap = 0;
         nodes.push_back(n);
         return (int)nodes.size() - 1;
@@ -96,7 +103,7 @@ struct TreeBuilder {
         if (hi - lo == 1) {
             const int a = spec->unit_leaf_ptr[lo], b = spec->unit_leaf_ptr[lo + 1];
             if (a == b)
-                return empty_leaf(a < spec->n_leaves ? spec->leaf_start[a] : 0);
+                return empty_leaf();
             return over_leaves(a, b);
         }
         const int mid = lo + (hi - lo) / 2;
@@ -111,12 +118,17 @@ static int check_spec(Ctx *ctx, int n, const kvfuse_tree_spec *s)
     if (!s || s->n_leaves < 0 || s->n_units < 0 || (s->n_leaves > 0 && (!s->leaf_start || !s->leaf_count)) ||
         (s->n_units > 0 && !s->unit_leaf_ptr))
         return fail(ctx, KVFUSE_EINVAL, "tree spec: null or negative field");
-    int end = 0;
+    std::vector<std::pair<int64_t, int64_t>> runs;   // (start, end) of the non-empty leaves
     for (int l = 0; l < s->n_leaves; ++l) {
-        if (s->leaf_count[l] < 0 || s->leaf_start[l] < end || (int64_t)s->leaf_start[l] + s->leaf_count[l] > n)
-            return fail(ctx, KVFUSE_EINVAL, "tree spec: leaves must be ascending, non-overlapping and inside the table");
-        end = s->leaf_start[l] + s->leaf_count[l];
+        if (s->leaf_count[l] < 0 || s->leaf_start[l] < 0 || (int64_t)s->leaf_start[l] + s->leaf_count[l] > n)
+            return fail(ctx, KVFUSE_EINVAL, "tree spec: leaves must lie inside the table");
+        if (s->leaf_count[l] > 0)
+            runs.emplace_back(s->leaf_start[l], (int64_t)s->leaf_start[l] + s->leaf_count[l]);
     }
+    std::sort(runs.begin(), runs.end());
+    for (size_t k = 1; k < runs.size(); ++k)
+        if (runs[k].first < runs[k - 1].second)
+            return fail(ctx, KVFUSE_EINVAL, "tree spec: leaves must not overlap");
     if (s->n_units > 0) {
         if (s->unit_leaf_ptr[0] != 0 || s->unit_leaf_ptr[s->n_units] != s->n_leaves)
             return fail(ctx, KVFUSE_EINVAL, "tree spec: unit_leaf_ptr must run from 0 to n_leaves");
@@ -244,6 +256,7 @@ static void carve(Carver &cv, int G, int n, int n_slots, int max_r, int max_l, i
     w.n_refine = cv.take<int32_t>(kMaxHeights);
     w.counters = cv.take<int32_t>((size_t)G * 8);
     w.group_enable = nullptr;
+    w.leaf_src = cv.take<int32_t>((size_t)std::max(n, 1));
     slot_init = cv.take<int32_t>(n_slots);
     for (HostHeight &h : hs) {
         const size_t nn = h.l_off.size();
@@ -423,6 +436,13 @@ int kvfuse_plan_create(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_ta
     for (size_t k = 0; k < p.nodes.size(); ++k)
         init[k] = p.nodes[k].left < 0 ? p.nodes[k].cap : 0;
     hipError_t e = upload(c->stream, p.slot_init, init);
+    // position in a set_ids row -> logical entry it is filled from (-1: not part of any leaf)
+    std::vector<int32_t> leaf_src((size_t)std::max(table->n, 1), -1);
+    for (const Node &nd : p.nodes)
+        if (nd.left < 0)
+            for (int i = 0; i < nd.cap; ++i)
+                leaf_src[(size_t)nd.off + i] = nd.src + i;
+    if (e == hipSuccess) e = upload(c->stream, p.work.leaf_src, leaf_src);
     for (HostHeight &h : p.heights) {
         const HeightDesc &d = h.dev;
         if (e == hipSuccess) e = upload(c->stream, d.l_off, h.l_off);
@@ -531,7 +551,8 @@ int kvfuse_assign(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t height, double thr
     const int rc = check_step(ctx, plan, height, thr, band, true);
     if (rc)
         return rc;
-    launch_assign(ctx->c.stream, plan->p.pool, plan->p.tab, plan->p.work, plan->p.heights[height].dev, height, thr, band);
+    launch_assign(ctx->c.stream, plan->p.pool, plan->p.tab, plan->p.work, plan->p.heights[height].dev, height, thr, band,
+                  plan->p.assign_rule);
     KVF_HIP(&ctx->c, hipGetLastError());
     return KVFUSE_OK;
 }
@@ -604,7 +625,7 @@ int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band
         const HeightDesc &d = p.heights[hgt].dev;
         launch_similarity(c->stream, p.pool, p.work, d, floor_f, nullptr);
         KVF_TRY(mark());
-        launch_assign(c->stream, p.pool, p.tab, p.work, d, hgt, thr, band);
+        launch_assign(c->stream, p.pool, p.tab, p.work, d, hgt, thr, band, p.assign_rule);
         KVF_TRY(mark());
         launch_merge(c->stream, p.pool, p.work, d, hgt);
         KVF_TRY(mark());
@@ -677,6 +698,18 @@ int kvfuse_plan_set_group_mask(kvfuse_ctx *ctx, kvfuse_plan *plan, const uint8_t
         KVF_HIP(c, hipStreamSynchronize(c->stream));
         KVF_HIP(c, hipMemcpy(p.group_enable_host.data(), enable, (size_t)p.work.G, hipMemcpyDeviceToHost));
     }
+    return KVFUSE_OK;
+}
+
+int kvfuse_plan_set_assign_rule(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t rule)
+{
+    if (!ctx)
+        return KVFUSE_EINVAL;
+    if (!plan)
+        return fail(&ctx->c, KVFUSE_EINVAL, "assign rule: null plan");
+    if (rule != KVFUSE_RULE_ARGMAX && rule != KVFUSE_RULE_FIRST_ROW)
+        return fail(&ctx->c, KVFUSE_EINVAL, "assign rule: must be KVFUSE_RULE_ARGMAX or KVFUSE_RULE_FIRST_ROW");
+    plan->p.assign_rule = rule;
     return KVFUSE_OK;
 }
 

@@ -88,8 +88,9 @@ void launch_block_norms(hipStream_t s, const PoolDesc &pool, const TableDesc &ta
         table_init_kernel<<<(unsigned)((ne + 255) / 256), 256, 0, s>>>(tab, pool.G, pool.P, pool.norm_k, pool.norm_v);
 }
 
-// Leaf sets = physical ids of the leaves' logical entries.  An id outside [0, P) (a caller error) is clamped
-// so that no later kernel can read out of range, and counted in counters[g][4].
+// Leaf sets = physical ids of the leaves' logical entries, each leaf at the region the plan gave it (leaf_src maps
+// a set position back to its logical entry).  An id outside [0, P) (a caller error) is clamped so that no later
+// kernel can read out of range, and counted in counters[g][4].
 __global__ void leaf_sets_kernel(WorkDesc w, int P, const int32_t *__restrict__ bt, const int32_t *__restrict__ slot_init)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -97,7 +98,9 @@ __global__ void leaf_sets_kernel(WorkDesc w, int P, const int32_t *__restrict__ 
     if (i < (int64_t)w.G * 8)
         w.counters[i] = 0;
     if (i < ne) {
-        int p = bt[i];
+        const int64_t g = i / w.n;
+        const int src = w.leaf_src[i - g * w.n];
+        int p = src >= 0 ? bt[g * w.n + src] : 0;
         if (p < 0 || p >= P)
             p = p < 0 ? 0 : P - 1;
         w.set_ids[i] = p;

@@ -10,25 +10,33 @@ def load_binding():
     return binding
 
 
-def gpu_fuse(rec, mat, thr=None, cand_cap=16, band=1e-3, group_size=None, timing=False):
+def gpu_fuse(rec, mat, thr=None, cand_cap=16, band=1e-3, group_size=None, timing=False, rule=None, shortest_first=False):
     """Whole pipeline on the GPU for the materialised groups.  Returns (cache, plan, stats, ctx)."""
     kb = load_binding()
     ctx = kb.Context(mat["K"].device)
     cache = kb.Cache(mat["K"], mat["V"], mat["bt"], rec.t, rec.d)
     spec = kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr, rec.group_size if group_size is None else group_size)
+    if shortest_first:
+        spec, _ = kb.tree_spec_shortest_first(spec)
     plan = kb.Plan(ctx, cache, spec, cand_cap)
+    if rule is not None:
+        kb.set_assign_rule(ctx, plan, {"argmax": kb.RULE_ARGMAX, "first_row": kb.RULE_FIRST_ROW}[rule])
     stats = kb.fuse_tree(ctx, plan, rec.thr if thr is None else thr, band, want_stats=True, want_timing=timing)
     torch.cuda.synchronize()
     return cache, plan, stats, ctx
 
 
-def oracle_fuse(oracle, rec, mat_host, thr=None, group_size=None, threads=8, groups=None):
+def oracle_fuse(oracle, rec, mat_host, thr=None, group_size=None, threads=8, groups=None, rule="argmax",
+                shortest_first=False):
     """Oracle on host copies of the same inputs (mat_host: numpy pools and tables per group)."""
     Ks, Vs, bts = mat_host
     idx = range(len(Ks)) if groups is None else groups
-    return oracle.fuse_groups([Ks[g] for g in idx], [Vs[g] for g in idx], [bts[g] for g in idx], rec.leaf_start,
-                              rec.leaf_count, rec.unit_leaf_ptr, rec.thr if thr is None else thr,
-                              rec.group_size if group_size is None else group_size, threads=threads)
+    ls, lc, up = rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr
+    if shortest_first:
+        ls, lc, up, _ = oracle.shortest_first(ls, lc, up)
+    return oracle.fuse_groups([Ks[g] for g in idx], [Vs[g] for g in idx], [bts[g] for g in idx], ls, lc, up,
+                              rec.thr if thr is None else thr,
+                              rec.group_size if group_size is None else group_size, threads=threads, rule=rule)
 
 
 def host_copy(mat):

@@ -88,3 +88,49 @@ def test_threshold_closed_forms_match_the_oracle(lib):
     assert cr.value == pytest.approx(want_cr, rel=1e-15) and list(p0) == pytest.approx(list(want_p0), rel=1e-15)
     for args in ((0.9, 2.0, 1.5, 0.1, 0.5, 0.99), (0.9, 1.1, 1.5, 0.1, 0.5, 0.99), (0.98, 9.0, 1.5, 0.5, 0.5, 0.99), (0.6, 1.0, 3.0, 0.5, 0.5, 0.99)):
         assert lib.kvfuse_threshold_feedback(*args) == pytest.approx(th.feedback_step(*args), rel=1e-15)
+
+
+class _Spec(ctypes.Structure):
+    _fields_ = [("n_leaves", ctypes.c_int32), ("leaf_start", ctypes.c_void_p), ("leaf_count", ctypes.c_void_p),
+                ("n_units", ctypes.c_int32), ("unit_leaf_ptr", ctypes.c_void_p), ("group_size", ctypes.c_int32)]
+
+
+def _shortest_first(lib, ls, lc, up):
+    ls, lc, up = (np.ascontiguousarray(a, np.int32) for a in (ls, lc, up))
+    spec = _Spec(len(ls), ls.ctypes.data, lc.ctypes.data, len(up) - 1, up.ctypes.data, 0)
+    o_ls, o_lc, o_up = np.zeros_like(ls), np.zeros_like(lc), np.zeros_like(up)
+    order = np.zeros(len(ls) if len(up) == 2 else len(up) - 1, np.int32)
+    lib.kvfuse_tree_spec_shortest_first.argtypes = [ctypes.POINTER(_Spec)] + [ctypes.c_void_p] * 4
+    rc = lib.kvfuse_tree_spec_shortest_first(ctypes.byref(spec), o_ls.ctypes.data, o_lc.ctypes.data, o_up.ctypes.data,
+                                             order.ctypes.data)
+    return rc, o_ls, o_lc, o_up, order
+
+
+def test_shortest_first_order_matches_the_oracle(lib):
+    """Host-only entry point (remark on the order of requests): compared with the oracle's ordering on random specs,
+    with and without several leaves per unit, and on the one-unit case."""
+    import oracle
+    rng = np.random.default_rng(41)
+    for case in range(60):
+        n_units = 1 if case % 5 == 0 else int(rng.integers(2, 12))
+        per_unit = rng.integers(0 if n_units > 1 else 1, 4, size=n_units)
+        lc = rng.integers(0, 6, size=int(per_unit.sum())).astype(np.int32)      # ties and empty leaves on purpose
+        ls = np.concatenate([[0], np.cumsum(lc)[:-1]]).astype(np.int32) if len(lc) else np.zeros(0, np.int32)
+        up = np.concatenate([[0], np.cumsum(per_unit)]).astype(np.int32)
+        rc, o_ls, o_lc, o_up, order = _shortest_first(lib, ls, lc, up)
+        assert rc == 0
+        w_ls, w_lc, w_up, w_order = oracle.shortest_first(ls, lc, up)
+        assert o_ls.tolist() == w_ls.tolist() and o_lc.tolist() == w_lc.tolist() and o_up.tolist() == w_up.tolist()
+        assert order.tolist() == w_order.tolist()
+        # a permutation of the same leaves, sizes non-decreasing
+        assert sorted(zip(o_ls.tolist(), o_lc.tolist())) == sorted(zip(ls.tolist(), lc.tolist()))
+        if n_units > 1:
+            sizes = [int(o_lc[o_up[u]:o_up[u + 1]].sum()) for u in range(n_units)]
+            assert sizes == sorted(sizes)
+    assert lib.kvfuse_tree_spec_shortest_first(None, None, None, None, None) != 0
+
+
+def test_variant_entry_points_reject_null_arguments(lib):
+    assert lib.kvfuse_plan_set_assign_rule(None, None, 1) != 0
+    assert lib.kvfuse_replicate_rescaled(None, None, None, None) != 0
+    assert lib.kvfuse_drop_rescale(None, None, None) != 0

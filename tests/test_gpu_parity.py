@@ -4,6 +4,7 @@ Bars: block tables, assignments, reference counts, free lists and fused pool byt
 relative (fp64 sums in a different order); scales 2e-7 relative (fp32 storage); screened cosines within the
 screen's stated error band; attention within 2e-2 max-abs (checked much tighter where fp32 allows).
 """
+import ctypes as C
 import math
 
 import numpy as np
@@ -165,12 +166,15 @@ def test_single_node_steps_match_oracle(kb, oracle, kind, cand_cap):
 
 # ------------------------------------------------------------------------------------------ whole tree
 
-def _run_tree_case(kb, oracle, rec, name, cand_cap=16, thr=None, phys_perm=True, group_size=None, groups=None, band=1e-3):
-    _say("tree case", name, "G", rec.G, "n", rec.n, "r", rec.r, "leaves", len(rec.leaf_start), "cand_cap", cand_cap)
+def _run_tree_case(kb, oracle, rec, name, cand_cap=16, thr=None, phys_perm=True, group_size=None, groups=None, band=1e-3,
+                   rule="argmax", shortest_first=False):
+    _say("tree case", name, "G", rec.G, "n", rec.n, "r", rec.r, "leaves", len(rec.leaf_start), "cand_cap", cand_cap,
+         "rule", rule, "shortest_first", shortest_first)
     mat = wl.materialise(rec, DEV, groups=groups, phys_perm=phys_perm)
     host = gu.host_copy(mat)
-    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, thr=thr, cand_cap=cand_cap, group_size=group_size, band=band)
-    res = gu.oracle_fuse(oracle, rec, host, thr=thr, group_size=group_size)
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, thr=thr, cand_cap=cand_cap, group_size=group_size, band=band, rule=rule,
+                                          shortest_first=shortest_first)
+    res = gu.oracle_fuse(oracle, rec, host, thr=thr, group_size=group_size, rule=rule, shortest_first=shortest_first)
     safe = gu.check_ambiguity(res, name)
     for g in safe:
         gu.compare_group(res[g], cache, g, rec.dtype == torch.float32, name)
@@ -242,6 +246,133 @@ def test_tree_zipf_many_near_ties(kb, oracle):
     rec = wl.zipf_bff(n_req=8, tokens=32 * 40, layers=1, kv_heads=2, pool=60, t=32, d=64, thr=0.9)
     cache, plan, stats, res, mat = _run_tree_case(kb, oracle, rec, "zipf_small", cand_cap=8)
     assert stats.refined > 20
+
+
+def test_tree_zipf_threshold_in_the_thick_of_the_cosines(kb, oracle):
+    """The same structure with the threshold at the cosine two noisy copies of one base have, 1 / (1 + sigma^2):
+    most decisions lie within the screen's band of the threshold and are settled by the fp64 re-check."""
+    sigma = 0.05
+    rec = wl.zipf_bff(n_req=8, tokens=32 * 40, layers=1, kv_heads=2, pool=60, t=32, d=64, sigma=sigma,
+                      thr=1.0 / (1.0 + sigma * sigma))
+    cache, plan, stats, res, mat = _run_tree_case(kb, oracle, rec, "zipf_at_threshold", cand_cap=16)
+    assert stats.refined > 100 and stats.near_threshold > 100
+
+
+@pytest.mark.parametrize("cand_cap", [16, 2])
+@pytest.mark.parametrize("which", ["zipf_small", "small_bf16", "mixed_small_f32", "zipf_at_threshold"])
+def test_tree_first_row_rule(kb, oracle, which, cand_cap):
+    """Algorithm 1's row loop taken literally (the lowest row above the threshold takes the block), on inputs where
+    many right blocks clear the threshold for several left rows; two candidate slots force the full-column path."""
+    if which == "zipf_small":
+        rec = wl.zipf_bff(n_req=8, tokens=32 * 40, layers=1, kv_heads=2, pool=60, t=32, d=64, thr=0.9)
+    elif which == "zipf_at_threshold":
+        # two noisy copies base + N(0, sigma) of one base have cosine 1 / (1 + sigma^2) up to O(sigma^2 / sqrt(r)): with
+        # the threshold there, most listed rows are undecided by the screen and the fp64 re-check walks them in row order
+        sigma = 0.05
+        rec = wl.zipf_bff(n_req=8, tokens=32 * 40, layers=1, kv_heads=2, pool=60, t=32, d=64, sigma=sigma,
+                          thr=1.0 / (1.0 + sigma * sigma))
+    elif which == "small_bf16":
+        rec = _small_bf16()
+    else:
+        rec = wl.mixed(n_req=9, min_tokens=40, max_tokens=900, chunk_tokens=256, layers=1, kv_heads=2, pool=48, t=8, d=32,
+                       dtype=torch.float32)
+    cache, plan, stats, res, mat = _run_tree_case(kb, oracle, rec, which + "_first_row", cand_cap=cand_cap, rule="first_row")
+    if which == "zipf_at_threshold":
+        assert stats.refined > 100 and stats.near_threshold > 100
+        if cand_cap == 16:
+            assert stats.cand_overflow < stats.refined
+    # the case has power only if the two readings disagree somewhere
+    other = gu.oracle_fuse(oracle, rec, gu.host_copy(wl.materialise(rec, DEV, phys_perm=True)))
+    differ = sum(int((a.bt != b.bt).sum()) for a, b in zip(res, other))
+    _say("  logical blocks whose target differs between the two readings:", differ)
+    if which != "small_bf16":
+        assert differ > 0
+    assert sum(r.n_physical for r in res) == stats.physical_blocks
+
+
+@pytest.mark.parametrize("which", ["mixed_small", "bff_ragged_lengths", "cff_short_tail"])
+def test_tree_shortest_first_order(kb, oracle, which):
+    """Remark on the order of requests: the tree is built over the units in ascending number of blocks while the
+    table keeps its layout, so leaves are no longer in logical order."""
+    if which == "mixed_small":
+        rec = wl.mixed(n_req=9, min_tokens=40, max_tokens=900, chunk_tokens=256, layers=1, kv_heads=2, pool=48, t=8, d=32)
+    elif which == "bff_ragged_lengths":
+        rec = wl.mixed(n_req=7, min_tokens=64, max_tokens=1500, chunk_tokens=1 << 20, layers=1, kv_heads=2, pool=40, t=8, d=32)
+    else:
+        rec = wl.cff_long(tokens=8 * 580, chunk_tokens=8 * 75, layers=1, kv_heads=2, t=8, d=32)
+    spec = kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr, rec.group_size)
+    new_spec, order = kb.tree_spec_shortest_first(spec)
+    ls, lc, up, want = oracle.shortest_first(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr)
+    assert order.tolist() == want.tolist() and order.tolist() != sorted(order.tolist())
+    assert np.array_equal(np.ctypeslib.as_array((C.c_int32 * len(ls)).from_address(new_spec.leaf_start)), ls)
+    cache, plan, stats, res, mat = _run_tree_case(kb, oracle, rec, which + "_shortest_first", shortest_first=True)
+    given = gu.oracle_fuse(oracle, rec, gu.host_copy(wl.materialise(rec, DEV, phys_perm=True)))
+    _say("  physical blocks: given order", sum(r.n_physical for r in given), "shortest first", stats.physical_blocks)
+    assert stats.fused > 20
+
+
+@pytest.mark.parametrize("kind", ["bf16", "f32"])
+def test_replicate_rescaled_and_drop_rescale_match_oracle(kb, oracle, kind):
+    """The two evaluation modes of the results section.  Replicate: every logical block gets the block it had before
+    fusion back, holding scale * representative in the pool type (bit-exact against the oracle), the table returns to
+    the original one, and plain decode attention over the result agrees with the oracle's.  Drop: unit scales."""
+    rec = wl.llama8b_bff(n_req=5, tokens=16 * 60, layers=1, kv_heads=2, prefix_tokens=96, near_pool=16, t=16, d=64,
+                         dtype=torch.bfloat16 if kind == "bf16" else torch.float32)
+    mat = wl.materialise(rec, DEV, phys_perm=True)
+    host = gu.host_copy(mat)
+    bt0 = mat["bt"].clone()
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat)
+    res = gu.oracle_fuse(oracle, rec, host)
+    assert stats.fused > 20 and stats.fused == sum(int(r.stats[1]) for r in res)
+    for g in range(rec.G):
+        gu.compare_group(res[g], cache, g, kind == "f32", "replicate/fused")
+    # drop-rescale on a copy of the table state: scales become one, nothing else moves
+    sk, sv, btf = cache.scale_k.clone(), cache.scale_v.clone(), cache.bt.clone()
+    kb.drop_rescale(ctx, cache)
+    torch.cuda.synchronize()
+    assert (cache.scale_k == 1).all() and (cache.scale_v == 1).all() and torch.equal(cache.bt, btf)
+    assert not (sk == 1).all()
+    cache.scale_k.copy_(sk)
+    cache.scale_v.copy_(sv)
+    # replicate
+    _say("replicate", kind, "G", rec.G, "n", rec.n, "fused", stats.fused)
+    kb.replicate_rescaled(ctx, cache, bt0)
+    torch.cuda.synchronize()
+    assert torch.equal(cache.bt, bt0)
+    assert (cache.scale_k == 1).all() and (cache.scale_v == 1).all() and (cache.remap == -1).all()
+    Kr, Vr = [], []
+    for g in range(rec.G):
+        Kr.append(oracle.replicate_rescaled(res[g].kpool, host[2][g], res[g].bt, res[g].scale_k))
+        Vr.append(oracle.replicate_rescaled(res[g].vpool, host[2][g], res[g].bt, res[g].scale_v))
+        assert np.array_equal(wl.to_numpy_pool(cache.K[g]), Kr[g]), f"group {g}: replicated K differs"
+        assert np.array_equal(wl.to_numpy_pool(cache.V[g]), Vr[g]), f"group {g}: replicated V differs"
+        assert np.array_equal(cache.refcount[g].cpu().numpy(), np.bincount(host[2][g], minlength=cache.P))
+        np.testing.assert_allclose(cache.norm_k[g].cpu().numpy(), oracle.block_norms(Kr[g]), rtol=1e-13)
+        np.testing.assert_allclose(cache.orig_norm_v[g].cpu().numpy(), oracle.block_norms(Vr[g])[host[2][g]], rtol=1e-13)
+    q = wl.queries(rec, DEV)
+    out = _decode(kb, ctx, rec, cache, q)
+    one = np.ones((rec.G, rec.n))
+    want = oracle.paged_decode_attention(q[0].float().cpu().numpy().astype(np.float64), Kr, Vr, host[2], one, one,
+                                         rec.req_start, rec.ctx_len, rec.t, rec.d)
+    err = np.abs(out[0] - want).max() / np.abs(want).max()
+    _say("  decode over the replicated cache: max rel err", err)
+    assert err < (2e-3 if kind == "bf16" else 1e-5)
+
+
+def test_variant_entry_points_reject_bad_arguments(kb):
+    rec = wl.tiny_bff()
+    mat = wl.materialise(rec, DEV)
+    ctx = kb.Context(DEV)
+    cache = kb.Cache(mat["K"], mat["V"], mat["bt"], rec.t, rec.d)
+    plan = kb.Plan(ctx, cache, kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr, 0), 16)
+    with pytest.raises(kb.KvfuseError):
+        kb.set_assign_rule(ctx, plan, 7)
+    with pytest.raises(kb.KvfuseError):
+        ctx.check(kb.lib.kvfuse_replicate_rescaled(ctx.h, C.byref(cache.pool), C.byref(cache.table), None))
+    # overlapping leaves are refused whatever their order; disjoint leaves in any order are accepted
+    with pytest.raises(kb.KvfuseError):
+        kb.Plan(ctx, cache, kb.tree_spec([8, 0, 4], [8, 8, 8], [0, 1, 2, 3], 0), 16)
+    kb.Plan(ctx, cache, kb.tree_spec([16, 0, 8], [8, 8, 8], [0, 1, 2, 3], 0), 16)
 
 
 @pytest.mark.parametrize("shape", ["r4096_bf16", "r8192_bf16", "r2048_f32", "r16384_bf16_all_heads", "r8192_f32"])

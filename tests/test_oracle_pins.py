@@ -243,7 +243,7 @@ def _widen(p):
     return wl_to_f64(p) if p.dtype == np.uint16 else p.astype(np.float64)
 
 
-def _brute_force(K, V, bt, leaves_of_units, thr, kind):
+def _brute_force(K, V, bt, leaves_of_units, thr, kind, rule="argmax"):
     """Dense, list-based restatement of Algorithm 1 written independently of the C oracle."""
     K, V, bt = K.copy(), V.copy(), bt.copy()
     n = len(bt)
@@ -259,6 +259,11 @@ def _brute_force(K, V, bt, leaves_of_units, thr, kind):
         sim = (kl @ kr.T) / np.outer(np.where(nl == 0, np.inf, nl), np.where(nr == 0, np.inf, nr))
         tgt = {}
         for j in range(len(Rs)):
+            if rule == "first_row":                 # lowest row above the threshold
+                above = np.nonzero(sim[:, j] > thr)[0]
+                if len(above):
+                    tgt.setdefault(int(above[0]), []).append(j)
+                continue
             i = int(np.argmax(sim[:, j]))           # numpy argmax: first maximum
             if sim[i, j] > thr:
                 tgt.setdefault(i, []).append(j)
@@ -298,9 +303,10 @@ def _brute_force(K, V, bt, leaves_of_units, thr, kind):
     return K, V, bt, safe(orig_k, nk[bt]), safe(orig_v, nv[bt]), sorted(freed)
 
 
+@pytest.mark.parametrize("rule", ["argmax", "first_row"])
 @pytest.mark.parametrize("kind", ["f32", "bf16"])
 @pytest.mark.parametrize("leaves", [[5, 3, 4, 6, 2], [4, 4, 4, 4], [7, 1, 1, 6, 3, 2, 5]])
-def test_oracle_equals_dense_brute_force(oracle, kind, leaves):
+def test_oracle_equals_dense_brute_force(oracle, kind, leaves, rule):
     rng = np.random.default_rng(sum(leaves) + len(kind))
     n, r = sum(leaves), 40
     protos = rng.standard_normal((6, r))
@@ -319,8 +325,8 @@ def test_oracle_equals_dense_brute_force(oracle, kind, leaves):
     ls = np.concatenate([[0], np.cumsum(lc)[:-1]]).astype(np.int32)
     up = np.arange(len(leaves) + 1, dtype=np.int32)
     thr = 0.8
-    res = oracle.fuse_group(Kp, Vp, perm, ls, lc, up, thr=thr)
-    bK, bV, bbt, bsk, bsv, bfreed = _brute_force(Kp, Vp, perm, [[(int(s), int(c))] for s, c in zip(ls, lc)], thr, kind)
+    res = oracle.fuse_group(Kp, Vp, perm, ls, lc, up, thr=thr, rule=rule)
+    bK, bV, bbt, bsk, bsv, bfreed = _brute_force(Kp, Vp, perm, [[(int(s), int(c))] for s, c in zip(ls, lc)], thr, kind, rule)
     assert res.stats[1] >= 3, "test input should actually fuse something"
     assert np.array_equal(res.bt, bbt)
     assert np.array_equal(res.kpool, bK) and np.array_equal(res.vpool, bV)
@@ -456,6 +462,125 @@ def test_fusion_then_attention_satisfies_softmax_drift_bound(oracle):
     s1 = np.exp(z1 - z1.max()); s1 /= s1.sum()
     eps = np.abs(z1 - z0).max()
     assert eps > 0 and np.abs(s1 - s0).sum() <= math.exp(2 * eps) - 1 + 1e-12
+
+
+# ---------------------------------------------------------------- variants: row-order rule, request order, evaluation modes
+
+def test_first_row_rule_hand_example_and_relation_to_argmax(oracle):
+    """Algorithm 1's loop over the rows of sim taken literally: a row takes every block above thr that is still
+    there.  Column 0: rows 0 (0.9) and 1 (0.95) both clear 0.7 -> row 0 was first; the arg-max reading gives row 1."""
+    S = np.array([[0.90, 0.20, 0.95, 0.70],
+                  [0.95, 0.80, 0.10, 0.70],
+                  [0.10, 0.85, 0.97, 0.6999]])
+    assert oracle.assign_first_row(S, 0.7).tolist() == [0, 1, 0, -1]     # 0.7 > 0.7 is false
+    assert oracle.assign(S, 0.7)[0].tolist() == [1, 2, 2, -1]
+    assert oracle.assign_first_row(S, 1.5).tolist() == [-1, -1, -1, -1]
+    rng = np.random.default_rng(23)
+    for _ in range(50):
+        ml, mr = rng.integers(1, 9), rng.integers(1, 9)
+        S = rng.random((ml, mr))
+        u = float(rng.uniform(0.3, 0.95))
+        a1 = oracle.assign_first_row(S, u)
+        a0 = oracle.assign(S, u)[0]
+        above = S > u
+        want = np.where(above.any(0), above.argmax(0), -1)               # first True per column
+        assert a1.tolist() == want.tolist()
+        assert ((a1 >= 0) == (a0 >= 0)).all()                            # the same blocks fuse, maybe elsewhere
+        single = above.sum(0) <= 1
+        assert (a1[single] == a0[single]).all()                          # the readings differ only on contested blocks
+
+
+def test_first_row_rule_changes_contested_blocks_only(oracle):
+    """Left leaf {a, a'} with a' a near copy of a, right leaf {b} nearest to a': arg-max sends b to a', the row
+    loop to a (the first row above the threshold)."""
+    e = np.eye(4)
+    a, a2, b = e[0], e[0] + 0.10 * e[1], e[0] + 0.12 * e[1]
+    K = np.stack([a, a2, b]).astype(np.float32)
+    V = np.stack([e[2], e[3], e[2] + e[3]]).astype(np.float32)
+    bt, ls, lc, up = _identity_setup(K, V, [2, 1])
+    r0 = oracle.fuse_group(K, V, bt, ls, lc, up, thr=0.9)
+    r1 = oracle.fuse_group(K, V, bt, ls, lc, up, thr=0.9, rule="first_row")
+    assert r0.bt.tolist() == [0, 1, 1] and r1.bt.tolist() == [0, 1, 0]
+    assert r0.n_physical == r1.n_physical == 2
+    assert np.array_equal(r1.kpool[1], K[1]) and not np.array_equal(r1.kpool[0], K[0])
+
+
+def test_shortest_first_order_and_the_remark_best_case(oracle):
+    """Remark after Algorithm 1: shorter requests on the left; in the best case every block of the right tree
+    is unified into the left tree.  Short request {x, y}, long request {x, y, x, y, x, y}: blocks of one request
+    are never compared with each other, so long-first keeps all six blocks of the long request, short-first
+    keeps two."""
+    ls, lc, up, order = oracle.shortest_first([0, 5, 8, 12], [5, 3, 4, 3], [0, 1, 2, 3, 4])
+    assert order.tolist() == [1, 3, 2, 0] and ls.tolist() == [5, 12, 8, 0] and lc.tolist() == [3, 3, 4, 5]
+    assert up.tolist() == [0, 1, 2, 3, 4]
+    # units with several leaves move as a whole and keep their chunk order
+    ls, lc, up, order = oracle.shortest_first([0, 4, 8, 10], [4, 4, 2, 3], [0, 2, 3, 4])
+    assert order.tolist() == [1, 2, 0] and ls.tolist() == [8, 10, 0, 4] and lc.tolist() == [2, 3, 4, 4]
+    assert up.tolist() == [0, 1, 2, 4]
+    # one unit: its leaves are ordered
+    ls, lc, up, order = oracle.shortest_first([0, 4, 8], [4, 4, 1], [0, 3])
+    assert order.tolist() == [2, 0, 1] and ls.tolist() == [8, 0, 4] and up.tolist() == [0, 3]
+
+    rng = np.random.default_rng(29)
+    x, y = rng.standard_normal(16), rng.standard_normal(16)
+    K = np.stack([x, y, x, y, x, y, x, y]).astype(np.float32)       # long request first in the table, then the short one
+    K *= rng.uniform(0.5, 2.0, size=(8, 1)).astype(np.float32)      # same directions, different norms
+    V = rng.standard_normal((8, 16)).astype(np.float32)
+    bt = np.arange(8, dtype=np.int32)
+    given = ([0, 6], [6, 2], [0, 1, 2])
+    long_first = oracle.fuse_group(K, V, bt, *given, thr=0.99)
+    ls, lc, up, order = oracle.shortest_first(*given)
+    assert order.tolist() == [1, 0] and ls.tolist() == [6, 0]
+    short_first = oracle.fuse_group(K, V, bt, ls, lc, up, thr=0.99)
+    assert long_first.n_physical == 6 and short_first.n_physical == 2
+    assert short_first.compression_ratio == 4.0
+    assert set(short_first.bt.tolist()) == {6, 7}                   # everything points into the short request's blocks
+    assert np.allclose(short_first.scale_k * short_first.norm_k[short_first.bt], np.linalg.norm(K.astype(np.float64), axis=1), rtol=1e-6)
+
+
+@pytest.mark.parametrize("kind", ["f32", "bf16"])
+def test_replicate_rescaled_closed_form_and_attention_equivalence(oracle, kind):
+    """First evaluation mode of the results section: every logical block gets its own block back, holding
+    scale * representative."""
+    # closed form (two-block bisector case): rep = (2, 1)/sqrt5, scales 1 and 2.5
+    K = np.array([[1.0, 0.0], [1.5, 2.0]], np.float32)
+    V = np.array([[0.0, 3.0], [4.0, 0.0]], np.float32)
+    bt0, ls, lc, up = _identity_setup(K, V, [1, 1])
+    res = oracle.fuse_group(K, V, bt0, ls, lc, up, thr=0.5)
+    Kr = oracle.replicate_rescaled(res.kpool, bt0, res.bt, res.scale_k)
+    Vr = oracle.replicate_rescaled(res.vpool, bt0, res.bt, res.scale_v)
+    assert np.allclose(Kr, [[2 / math.sqrt(5), 1 / math.sqrt(5)], [5 / math.sqrt(5), 2.5 / math.sqrt(5)]], rtol=3e-7)
+    assert np.allclose(Vr, [[3 / math.sqrt(2), 3 / math.sqrt(2)], [4 / math.sqrt(2), 4 / math.sqrt(2)]], rtol=3e-7)
+
+    # a fused workload: attention over the replicated cache with the original table and no scales equals
+    # attention through the fused table, up to the rounding of scale * representative into the pool type
+    rec = wl.llama8b_bff(n_req=4, tokens=256, layers=1, kv_heads=2, prefix_tokens=64, near_pool=8, d=32,
+                         dtype=torch.float32 if kind == "f32" else torch.bfloat16)
+    m = wl.materialise(rec, "cpu", phys_perm=True)
+    H = rec.G
+    Ks = [wl.to_numpy_pool(m["K"][g]) for g in range(H)]
+    Vs = [wl.to_numpy_pool(m["V"][g]) for g in range(H)]
+    bts = [m["bt"][g].numpy().copy() for g in range(H)]
+    res = [oracle.fuse_group(Ks[g], Vs[g], bts[g], rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr, thr=rec.thr) for g in range(H)]
+    assert sum(int(r.stats[1]) for r in res) > 20
+    Kr = [oracle.replicate_rescaled(res[g].kpool, bts[g], res[g].bt, res[g].scale_k) for g in range(H)]
+    Vr = [oracle.replicate_rescaled(res[g].vpool, bts[g], res[g].bt, res[g].scale_v) for g in range(H)]
+    for g in range(H):
+        untouched = [x for x in range(rec.n) if res[g].bt[x] == bts[g][x] and res[g].scale_k[x] == 1.0]
+        assert len(untouched) > 10
+        assert all(np.array_equal(Kr[g][bts[g][x]], Ks[g][bts[g][x]]) for x in untouched)   # never-fused blocks: byte for byte
+        # every element is the storage value nearest to the product, by the test's own rounding
+        x = next(x for x in range(rec.n) if res[g].bt[x] != bts[g][x])
+        prod = float(np.float32(res[g].scale_k[x])) * oracle.pool_to_f64(res[g].kpool[res[g].bt[x]])
+        assert np.array_equal(Kr[g][bts[g][x]], _round_store(prod, kind))
+    q = np.random.default_rng(31).standard_normal((rec.B, 4, rec.d))
+    one = np.ones((H, rec.n))
+    fused = oracle.paged_decode_attention(q, [r.kpool for r in res], [r.vpool for r in res], [r.bt for r in res],
+                                          [r.scale_k for r in res], [r.scale_v for r in res], rec.req_start, rec.ctx_len, rec.t, rec.d)
+    repl = oracle.paged_decode_attention(q, Kr, Vr, bts, one, one, rec.req_start, rec.ctx_len, rec.t, rec.d)
+    tol = 2e-6 if kind == "f32" else 2e-2
+    assert np.abs(fused - repl).max() <= tol * np.abs(fused).max()
+    assert np.abs(fused - repl).max() > 0
 
 
 # ---------------------------------------------------------------- threshold control statistics (analysis section)
