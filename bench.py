@@ -74,6 +74,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cand-cap", type=int, default=64)
     ap.add_argument("--thr", type=float, default=None, help="override the workload's similarity threshold")
+    ap.add_argument("--assign-rule", choices=["argmax", "first_row"], default="argmax",
+                    help="reading of Algorithm 1's threshold line: most similar row, or first row above the threshold")
+    ap.add_argument("--shortest-first", action="store_true",
+                    help="build the tree over the requests in ascending number of blocks (remark on the order of requests)")
     ap.add_argument("--calib-copy-gib", type=float, default=0.0,
                     help="also run a plain device copy of this many GiB (3 times) so that rocprofv3 --pmc FETCH_SIZE / "
                          "WRITE_SIZE readings can be scaled by a kernel of known traffic")
@@ -100,7 +104,12 @@ def main():
 
     ctx = kb.Context(dev)
     cache = kb.Cache(mat["K"], mat["V"], mat["bt"], rec.t, rec.d)
-    plan = kb.Plan(ctx, cache, kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr, rec.group_size), args.cand_cap)
+    spec = kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr, rec.group_size)
+    if args.shortest_first:
+        spec, _ = kb.tree_spec_shortest_first(spec)
+    plan = kb.Plan(ctx, cache, spec, args.cand_cap)
+    rule = {"argmax": kb.RULE_ARGMAX, "first_row": kb.RULE_FIRST_ROW}[args.assign_rule]
+    kb.set_assign_rule(ctx, plan, rule)
     rs = torch.tensor(rec.req_start, dtype=torch.int32, device=dev)
     cl = torch.tensor(rec.ctx_len, dtype=torch.int32, device=dev)
     max_blocks = int(((rec.ctx_len + rec.t - 1) // rec.t).max())
@@ -223,6 +232,31 @@ def main():
     mu_s, sigma_s = float(mom[0]), float(mom[1]) ** 0.5
     cross_pairs = (rec.n * rec.n - int((rec.leaf_count.astype("int64") ** 2).sum())) / 2
 
+    # variants of the method, outside the timed steps: the row-order reading of the threshold line, the tree over
+    # the requests in ascending length (only where that changes the order), and the "replicate" evaluation mode
+    variants = {}
+    todo = [("first_row" if rule == kb.RULE_ARGMAX else "argmax", kb.RULE_FIRST_ROW if rule == kb.RULE_ARGMAX else kb.RULE_ARGMAX, plan)]
+    sf_spec, sf_order = kb.tree_spec_shortest_first(spec)
+    if sf_order.tolist() != sorted(sf_order.tolist()):
+        todo.append(("shortest_first", rule, kb.Plan(ctx, cache, sf_spec, args.cand_cap)))
+    for name, vrule, vplan in todo:
+        restore()
+        kb.set_assign_rule(ctx, vplan, vrule)
+        vst = kb.fuse_tree(ctx, vplan, rec.thr, want_stats=True, want_timing=True)
+        variants[name] = {"fuse_ms": vst.ms_total, "similarity_ms": vst.ms_similarity, "assign_ms": vst.ms_assign,
+                          "merge_ms": vst.ms_merge, "compression_ratio": vst.compression_ratio, "fused": vst.fused,
+                          "refined_fp64": vst.refined}
+        del vplan
+    kb.set_assign_rule(ctx, plan, rule)
+    restore()
+    kb.fuse_tree(ctx, plan, rec.thr, want_stats=True)
+    sev[0].record()
+    kb.replicate_rescaled(ctx, cache, bt0)
+    sev[1].record()
+    torch.cuda.synchronize()
+    variants["replicate_rescaled"] = {"ms": sev[0].elapsed_time(sev[1]), "blocks_rewritten_at_least": stats.fused,
+                                      "includes": "scatter of scale * representative for K and V, table restore, norm pass"}
+
     # what the machine sustains, measured with the library's own probes after the timed steps (they load the chip
     # heavily and would otherwise warm it up for the steps): the MFMA instruction of the similarity kernel on
     # random and on constant operands, and a plain device copy
@@ -257,7 +291,8 @@ def main():
                    "groups": rec.G, "logical_blocks": blocks, "physical_blocks_after": stats.physical_blocks,
                    "compression_ratio": stats.compression_ratio, "fused": stats.fused,
                    "near_threshold": stats.near_threshold, "refined_fp64": stats.refined,
-                   "cand_overflow": stats.cand_overflow, "tree_heights": stats.n_heights},
+                   "cand_overflow": stats.cand_overflow, "tree_heights": stats.n_heights,
+                   "assign_rule": args.assign_rule, "shortest_first": bool(args.shortest_first)},
         "stages_ms": stage,
         "decode": {"ms": stage["decode"], "physical_GBps": phys_bytes / (stage["decode"] * 1e-3) / 1e9,
                    "logical_GBps": logi_bytes / (stage["decode"] * 1e-3) / 1e9, "hbm_peak_GBps": 8000.0,
@@ -274,8 +309,9 @@ def main():
                             "gaussian_exceedance_rate_per_group_at_thr": kb.exceedance_rate(cross_pairs, mu_s, sigma_s, rec.thr),
                             "note": "the synthetic cache plants exact and near duplicates, which a Gaussian fit of the "
                                     "bulk does not see; the rate is shown for the mechanism, not as a forecast"},
+        "variants": variants,
         "norms": {"ms": stage["norms"], "GBps": logi_bytes / (stage["norms"] * 1e-3) / 1e9},
-        "roofline": {"kernel": "similarity_ring_kernel (256 x 256 tiles) + similarity_kernel (128 x 128 tiles)",
+        "roofline": {"kernel": "similarity_ring_kernel (256 x 256 tile instance on the upper heights, 128 x 128 on the lowest)",
                      "bound": "mfma", "achieved": sim_tflops, "peak": peak,
                      "unit": "TFLOP/s", "frac": sim_tflops / peak, "traffic": traffic,
                      "frac_of_measured_mfma_rate": (sim_tflops / probes["mfma_bf16_random_operands_TFLOPs"]
