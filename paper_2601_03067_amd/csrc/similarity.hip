@@ -16,7 +16,9 @@
 //
 // Tiling.  WM x 2 wavefronts, each 2 x TN MFMA tiles of 32 x 32 (v_mfma_f32_32x32x16_bf16, or 4 x
 // v_mfma_f32_32x32x2_f32 per 16-byte fragment for f32 pools): 256 x 256 with 8 wavefronts, or 128 x 128 with 4 for
-// nodes whose sets are smaller than that.
+// nodes whose sets are smaller than that.  The MFMA tiles of a wavefront are not adjacent: tile (mt, nt) of every
+// wavefront lies in the same 128-row band and 64-column band of the workgroup tile, so on a ragged tile (set sizes
+// are data dependent and rarely multiples of 256) all wavefronts drop the same MFMA tiles and finish together.
 //
 // K is walked in 64-byte slices per row.  A ring of four LDS stages (each BM left + BN right rows x 64 bytes) is
 // filled by global_load_lds_dwordx4: the data never passes through registers, so two slices can be in flight
@@ -107,6 +109,12 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
     float *__restrict__ cand_val, float *__restrict__ dense_s, const uint8_t *__restrict__ group_enable)
 {
     constexpr int WN = 2, TM = 2, TN = BIG ? 4 : 2, NT = BIG ? 512 : 256, BM = BIG ? 256 : 128, BN = BM;
+    constexpr int WM = NT / 64 / WN;          // wavefronts along the rows
+    // MFMA tile (mt, nt) of wavefront (wm, wn) covers rows mt * WM * 32 + wm * 32 .. + 31 and columns
+    // nt * WN * 32 + wn * 32 .. + 31 of the workgroup tile: the tiles of one index are spread over all wavefronts, so
+    // when the valid part of a ragged tile ends early every wavefront can drop the same MFMA tiles and the whole
+    // workgroup gets shorter, not just some of its wavefronts.
+    constexpr int MT_STRIDE = WM * 32, NT_STRIDE = WN * 32;
     constexpr int HALF = BM / 2;              // rows one pass of the loaders covers (16 per wavefront)
     constexpr int STAGE = (BM + BN) * 64;
     constexpr int B_REGION = BM * 64;
@@ -180,8 +188,8 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
     const uint32_t ring_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)ring;
     const int l31 = lane & 31;
     const uint32_t frag = (uint32_t)(l31 * 64 + ((half ^ ((l31 >> 2) & 3)) * 16));   // first half; second half = ^ 32
-    const uint32_t fa_lo = ring_addr + wm * (TM * 32 * 64) + frag;
-    const uint32_t fb_lo = ring_addr + B_REGION + wn * (TN * 32 * 64) + frag;
+    const uint32_t fa_lo = ring_addr + wm * (32 * 64) + frag;
+    const uint32_t fb_lo = ring_addr + B_REGION + wn * (32 * 64) + frag;
     const uint32_t fa_hi = fa_lo ^ 32u;
     const uint32_t fb_hi = fb_lo ^ 32u;
 #define KVF_DS_READ(DST, ADDR, IMM) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(DST) : "v"(ADDR), "n"(IMM))
@@ -198,11 +206,11 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
 #define KVF_READ_SET(S, ADDR_A, ADDR_B)          \
     KVF_DS_READ(fa0_##S, ADDR_A, 0);             \
     KVF_DS_READ(fb0_##S, ADDR_B, 0);             \
-    KVF_DS_READ(fa1_##S, ADDR_A, 2048);          \
-    KVF_DS_READ(fb1_##S, ADDR_B, 2048);          \
+    KVF_DS_READ(fa1_##S, ADDR_A, MT_STRIDE * 64); \
+    KVF_DS_READ(fb1_##S, ADDR_B, NT_STRIDE * 64); \
     if constexpr (TN > 2) {                      \
-        KVF_DS_READ(fb2_##S, ADDR_B, 4096);      \
-        KVF_DS_READ(fb3_##S, ADDR_B, 6144);      \
+        KVF_DS_READ(fb2_##S, ADDR_B, 2 * NT_STRIDE * 64); \
+        KVF_DS_READ(fb3_##S, ADDR_B, 3 * NT_STRIDE * 64); \
     }                                            \
     if constexpr (DENSE) { KVF_WAIT_SET(S); }
 #define KVF_MMA(S, MT, NTI) acc[MT][NTI] = MmaV<T>::run(fa##MT##_##S, fb##NTI##_##S, acc[MT][NTI]);
@@ -270,43 +278,65 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
     KVF_READ_SET(0, fa_lo, fb_lo)
     KVF_WAIT_SET(0);     // nothing but the loop body below runs while fragment reads are on their way
 
+    // One K slice.  M and MH stand for the MFMA statements: the plain ones, or the ones that test whether their
+    // tile lies inside the valid part of a ragged workgroup tile.
+#define KVF_SLICE(M, MH)                                                                                           \
+    do {                                                                                                           \
+        const uint32_t cur = (uint32_t)(it & 3) * STAGE;                                                           \
+        const uint32_t nxt = (uint32_t)((it + 1) & 3) * STAGE;                                                     \
+        const int dst = ((it + 3) & 3) * STAGE;                                                                    \
+        const uint32_t ra1 = fa_hi + cur, rb1 = fb_hi + cur, ra0 = fa_lo + nxt, rb0 = fb_lo + nxt;                 \
+        KVF_WAIT_SET(0);                                                                                           \
+        KVF_READ_SET(1, ra1, rb1)                                                                                  \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        M(0, 0, 0) M(0, 1, 0)                                                                                      \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        KVF_DMA(pa0, dst + dma_a0);                                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        M(0, 0, 1) M(0, 1, 1) MH(0, 0, 2) MH(0, 1, 2)                                                              \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        KVF_DMA(pa1, dst + dma_a1);                                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        MH(0, 0, 3) MH(0, 1, 3)                                                                                    \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        KVF_WAIT_SET(1);                                                                                           \
+        KVF_READ_SET(0, ra0, rb0)                                                                                  \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        M(1, 0, 0) M(1, 1, 0)                                                                                      \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        KVF_DMA(pb0, dst + dma_b0);                                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        M(1, 0, 1) M(1, 1, 1) MH(1, 0, 2) MH(1, 1, 2)                                                              \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        KVF_DMA(pb1, dst + dma_b1);                                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        MH(1, 0, 3) MH(1, 1, 3)                                                                                    \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        KVF_DMA_ADVANCE();                                                                                         \
+        /* all but this iteration's four loads have landed (slice it + 2), then everyone may read it */            \
+        asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");                                             \
+    } while (0)
+    // MFMA tiles that lie wholly outside the valid part are dropped (their accumulators stay zero, which the epilogue
+    // treats like any entry below the candidate floor).  Fragment reads and loads stay as they are: every wavefront
+    // keeps issuing four loads per slice, which is what the vmcnt arithmetic counts on (leaving out the loads of
+    // a wholly invalid half tile as well, with waits that count what was issued, measured slower: the tests and
+    // wait variants cost more than the loads).
+    const int vcols = mr - col0;
+    const bool act_n[4] = {true, vcols > NT_STRIDE, vcols > 2 * NT_STRIDE, vcols > 3 * NT_STRIDE};
+#define KVF_MMA_IF(S, MT, NTI) if ((MT == 0 || act_m1) && act_n[NTI]) { KVF_MMA(S, MT, NTI) }
+#define KVF_MMA_HI_IF(S, MT, NTI) if ((MT == 0 || act_m1) && act_n[NTI]) { KVF_MMA_HI(S, MT, NTI) }
+
     int it = 0;
     for (int rt = 0; rt < n_rt; ++rt) {
+        const bool act_m1 = row_end - (row0 + rt * BM) > MT_STRIDE;
+        if (act_m1 && act_n[TN - 1]) {
 #pragma unroll 1
-        for (int kt = 0; kt < nk; ++kt, ++it) {
-            const uint32_t cur = (uint32_t)(it & 3) * STAGE;
-            const uint32_t nxt = (uint32_t)((it + 1) & 3) * STAGE;
-            const int dst = ((it + 3) & 3) * STAGE;
-            const uint32_t ra1 = fa_hi + cur, rb1 = fb_hi + cur, ra0 = fa_lo + nxt, rb0 = fb_lo + nxt;
-            KVF_WAIT_SET(0);
-            KVF_READ_SET(1, ra1, rb1)
-            __builtin_amdgcn_sched_barrier(0);
-            KVF_MMA(0, 0, 0) KVF_MMA(0, 1, 0)
-            __builtin_amdgcn_sched_barrier(0);
-            KVF_DMA(pa0, dst + dma_a0);
-            __builtin_amdgcn_sched_barrier(0);
-            KVF_MMA(0, 0, 1) KVF_MMA(0, 1, 1) KVF_MMA_HI(0, 0, 2) KVF_MMA_HI(0, 1, 2)
-            __builtin_amdgcn_sched_barrier(0);
-            KVF_DMA(pa1, dst + dma_a1);
-            __builtin_amdgcn_sched_barrier(0);
-            KVF_MMA_HI(0, 0, 3) KVF_MMA_HI(0, 1, 3)
-            __builtin_amdgcn_sched_barrier(0);
-            KVF_WAIT_SET(1);
-            KVF_READ_SET(0, ra0, rb0)
-            __builtin_amdgcn_sched_barrier(0);
-            KVF_MMA(1, 0, 0) KVF_MMA(1, 1, 0)
-            __builtin_amdgcn_sched_barrier(0);
-            KVF_DMA(pb0, dst + dma_b0);
-            __builtin_amdgcn_sched_barrier(0);
-            KVF_MMA(1, 0, 1) KVF_MMA(1, 1, 1) KVF_MMA_HI(1, 0, 2) KVF_MMA_HI(1, 1, 2)
-            __builtin_amdgcn_sched_barrier(0);
-            KVF_DMA(pb1, dst + dma_b1);
-            __builtin_amdgcn_sched_barrier(0);
-            KVF_MMA_HI(1, 0, 3) KVF_MMA_HI(1, 1, 3)
-            __builtin_amdgcn_sched_barrier(0);
-            KVF_DMA_ADVANCE();
-            // all but this iteration's four loads have landed (slice it + 2), then everyone may read it
-            asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");
+            for (int kt = 0; kt < nk; ++kt, ++it)
+                KVF_SLICE(KVF_MMA, KVF_MMA_HI);
+        } else {
+#pragma unroll 1
+            for (int kt = 0; kt < nk; ++kt, ++it)
+                KVF_SLICE(KVF_MMA_IF, KVF_MMA_HI_IF);
         }
         // the prefetched fragments of the next row tile's first slice must be in their registers before anything
         // else may touch them
@@ -319,13 +349,13 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
 #pragma unroll
             for (int nt = 0; nt < TN; ++nt) {
                 kmax[nt] = 0u;
-                tcol[nt] = lds_tcol[(wn * TN + nt) * 32 + (lane & 31)];
+                tcol[nt] = lds_tcol[nt * NT_STRIDE + wn * 32 + (lane & 31)];
             }
 #pragma unroll
             for (int mt = 0; mt < TM; ++mt)
 #pragma unroll
                 for (int eg = 0; eg < 4; ++eg) {
-                    const int rl0 = (wm * TM + mt) * 32 + eg * 8 + half * 4;
+                    const int rl0 = mt * MT_STRIDE + wm * 32 + eg * 8 + half * 4;
                     const float4 il4 = *reinterpret_cast<const float4 *>(&lds_invl[rt * BM + rl0]);
                     const float il[4] = {il4.x, il4.y, il4.z, il4.w};
 #pragma unroll
@@ -341,7 +371,7 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
                             kmax[nt] = max(kmax[nt], key);
                         }
                         if (hit) {      // rare: an entry clears the candidate floor
-                            const int cl = (wn * TN + nt) * 32 + (lane & 31);
+                            const int cl = nt * NT_STRIDE + wn * 32 + (lane & 31);
 #pragma unroll
                             for (int q = 0; q < 4; ++q)
                                 if (t[q] > tcol[nt]) {
@@ -367,12 +397,12 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
                     for (int nt = 0; nt < TN; ++nt)
 #pragma unroll
                         for (int e = 0; e < 16; ++e) {
-                            const int rl = (wm * TM + mt) * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
+                            const int rl = mt * MT_STRIDE + wm * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
                             const int row = row0 + rt * BM + rl;
-                            const int col = col0 + (wn * TN + nt) * 32 + (lane & 31);
+                            const int col = col0 + nt * NT_STRIDE + wn * 32 + (lane & 31);
                             if (row < row_end && col < mr)
                                 dense_s[(int64_t)g * A.total_s + s_base[node] + (int64_t)row * r_cap[node] + col] =
-                                    acc[mt][nt][e] * lds_invl[rt * BM + rl] * lds_invr[(wn * TN + nt) * 32 + (lane & 31)];
+                                    acc[mt][nt][e] * lds_invl[rt * BM + rl] * lds_invr[nt * NT_STRIDE + wn * 32 + (lane & 31)];
                         }
             }
 #pragma unroll
@@ -401,11 +431,11 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
     }
 #pragma unroll
     for (int nt = 0; nt < TN; ++nt) {
-        const int col = col0 + (wn * TN + nt) * 32 + (lane & 31);
+        const int col = col0 + nt * NT_STRIDE + wn * 32 + (lane & 31);
         const uint32_t bkey = lds_bkey[nt][tid];
         const int code = (int)(CODE_MASK - (bkey & CODE_MASK));
-        const int row = min(row_end - 1, row0 + lds_brt[nt][tid] * BM + (wm * TM + (code >> 4)) * 32 + ((code & 15) >> 2) * 8 + half * 4 + (code & 3));
-        unsigned long long pk = bkey ? pack_best(__uint_as_float(bkey & ~CODE_MASK) * lds_invr[(wn * TN + nt) * 32 + (lane & 31)], row) : 0ull;
+        const int row = min(row_end - 1, row0 + lds_brt[nt][tid] * BM + (code >> 4) * MT_STRIDE + wm * 32 + ((code & 15) >> 2) * 8 + half * 4 + (code & 3));
+        unsigned long long pk = bkey ? pack_best(__uint_as_float(bkey & ~CODE_MASK) * lds_invr[nt * NT_STRIDE + wn * 32 + (lane & 31)], row) : 0ull;
         const unsigned long long other = __shfl_xor(pk, 32, 64);
         pk = other > pk ? other : pk;
         if (half == 0 && col < mr && pk)
@@ -418,6 +448,9 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
 #undef KVF_MMA
 #undef KVF_MMA_HI
 #undef KVF_DMA_ADVANCE
+#undef KVF_SLICE
+#undef KVF_MMA_IF
+#undef KVF_MMA_HI_IF
 }
 
 __global__ void similarity_clear_kernel(unsigned long long *__restrict__ best_packed, int32_t *__restrict__ cand_cnt,
