@@ -221,7 +221,8 @@ int kvfuse_decode_workspace_bytes(int32_t n_layers, int32_t B, int32_t Hq, int32
  *   req_start device [B] int32: first logical entry of request b;  ctx_len device [B] int32 tokens
  *   max_blocks = max over b of ceil(ctx_len[b] / t) (host value, sizes the launch)
  *   out      device [n_layers][B][Hq][d] float
- * Supported: t a multiple of 16, d in {64, 128}, Hq / kv_heads <= 16. */
+ * Supported: t a multiple of 16, d in {64, 128}, Hq / kv_heads <= 16.  A request with ctx_len 0 gets zeros;
+ * B == 0 or n_layers == 0 returns at once. */
 int kvfuse_paged_decode_attn(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table, int32_t kv_heads,
                              int32_t layer_begin, int32_t n_layers, const void *q, const int32_t *req_start,
                              const int32_t *ctx_len, int32_t B, int32_t Hq, int32_t max_blocks, float sm_scale,

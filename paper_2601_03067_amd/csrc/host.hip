@@ -730,6 +730,8 @@ int kvfuse_paged_decode_attn(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvf
     if (!ctx)
         return KVFUSE_EINVAL;
     Ctx *c = &ctx->c;
+    if (B == 0 || n_layers == 0)
+        return KVFUSE_OK;       // nothing to compute; the (empty) arrays may be null
     if (!pool || !pool->k || !pool->v || !table || !table->bt || !table->scale_k || !table->scale_v || !q || !req_start ||
         !ctx_len || !out)
         return fail(c, KVFUSE_EINVAL, "decode: null pointer");

@@ -404,6 +404,113 @@ def test_tree_long_blocks(kb, oracle, shape):
     assert np.abs(out[0] - ref).max() <= (1e-4 if rec.dtype == torch.float32 else 5e-3)
 
 
+def _direct_case(kb, oracle, K, V, leaf_start, leaf_count, unit_leaf_ptr, thr, name, t=8, d=32, cand_cap=16, rule="argmax"):
+    """Pools given as float arrays [G][n][r]; identity table.  Runs both sides and compares every group exactly."""
+    G, n, r = K.shape
+    assert r == t * d
+    dt = torch.bfloat16
+    Kd = torch.from_numpy(K).to(DEV).to(dt).contiguous()
+    Vd = torch.from_numpy(V).to(DEV).to(dt).contiguous()
+    bt = torch.arange(n, dtype=torch.int32, device=DEV).repeat(G, 1).contiguous()
+    Kh = [wl.to_numpy_pool(Kd[g]) for g in range(G)]
+    Vh = [wl.to_numpy_pool(Vd[g]) for g in range(G)]
+    _say("direct case", name, "G", G, "n", n, "leaves", list(leaf_count))
+    ctx = kb.Context(DEV)
+    cache = kb.Cache(Kd, Vd, bt, t, d)
+    plan = kb.Plan(ctx, cache, kb.tree_spec(leaf_start, leaf_count, unit_leaf_ptr, 0), cand_cap)
+    if rule != "argmax":
+        kb.set_assign_rule(ctx, plan, kb.RULE_FIRST_ROW)
+    stats = kb.fuse_tree(ctx, plan, thr, want_stats=True)
+    torch.cuda.synchronize()
+    res = [oracle.fuse_group(Kh[g], Vh[g], np.arange(n, dtype=np.int32), leaf_start, leaf_count, unit_leaf_ptr, thr, rule=rule)
+           for g in range(G)]
+    for g in range(G):
+        gu.compare_group(res[g], cache, g, False, name)
+    assert stats.fused == sum(int(x.stats[1]) for x in res)
+    return cache, plan, stats, res
+
+
+def test_tree_degenerate_inputs(kb, oracle):
+    """Edges of the input space: one leaf (no tree at all), empty leaves and an empty unit among real ones, a table
+    with no leaves, every block identical (all cosines exactly 1: every decision is a tie between all left rows and
+    goes to the lowest), an all-zero pool (zero blocks never fuse), and two identical requests (the right one vanishes)."""
+    rng = np.random.default_rng(77)
+    t, d, G = 8, 32, 2
+    r = t * d
+    # one request, one leaf: nothing to compare
+    K = rng.standard_normal((G, 12, r)).astype(np.float32)
+    V = rng.standard_normal((G, 12, r)).astype(np.float32)
+    cache, plan, stats, res = _direct_case(kb, oracle, K, V, [0], [12], [0, 1], 0.5, "one_leaf")
+    assert plan.n_heights == 0 and stats.fused == 0 and stats.compression_ratio == 1.0
+    # no leaves at all: norms and table initialisation only
+    cache, plan, stats, res = _direct_case(kb, oracle, K, V, [], [], [0], 0.5, "no_leaves")
+    assert stats.fused == 0 and (cache.refcount == 1).all()
+    # empty leaves and an empty unit between real ones (units: [leaf0], [], [leaf1(empty), leaf2], [leaf3])
+    K = np.tile(rng.standard_normal((1, 5, r)).astype(np.float32), (G, 3, 1))[:, :12] + \
+        0.02 * rng.standard_normal((G, 12, r)).astype(np.float32)
+    V = rng.standard_normal((G, 12, r)).astype(np.float32)
+    cache, plan, stats, res = _direct_case(kb, oracle, K, V, [0, 4, 4, 8], [4, 0, 4, 4], [0, 1, 1, 3, 4], 0.9, "empty_leaves")
+    assert stats.fused > 0
+    # every block identical
+    one = rng.standard_normal((1, 1, r)).astype(np.float32)
+    K = np.tile(one, (G, 20, 1))
+    V = np.tile(one[:, :, ::-1], (G, 20, 1))
+    for rule in ("argmax", "first_row"):
+        cache, plan, stats, res = _direct_case(kb, oracle, K, V, [0, 5, 10, 15], [5, 5, 5, 5], [0, 1, 2, 3, 4], 0.9,
+                                               "all_identical_" + rule, cand_cap=4, rule=rule)
+        assert stats.fused == G * 15
+        if rule == "first_row":
+            assert (cache.bt[:, 5:] == 0).all() and (cache.refcount[:, 0] == 16).all()
+        else:
+            # at the top node the raw blocks 11 .. 14 are exactly equal to the raw left rows 1 .. 4 but only almost
+            # equal to row 0, which by then holds a rounded representative: the most similar row is row 1
+            assert (cache.bt[:, 11:15] == 1).all() and (cache.bt[:, 5:11] == 0).all() and (cache.bt[:, 15:] == 0).all()
+    # all-zero pool
+    Z = np.zeros((G, 16, r), np.float32)
+    cache, plan, stats, res = _direct_case(kb, oracle, Z, Z, [0, 8], [8, 8], [0, 1, 2], 0.0, "all_zero")
+    assert stats.fused == 0 and (cache.scale_k == 1).all() and (cache.norm_k == 0).all()
+    # two identical requests, random inside: block j of the right one goes to block j of the left one
+    half = rng.standard_normal((G, 9, r)).astype(np.float32)
+    K = np.concatenate([half, half], 1)
+    V = np.concatenate([half[:, :, ::-1], half[:, :, ::-1]], 1).copy()
+    cache, plan, stats, res = _direct_case(kb, oracle, K, V, [0, 9], [9, 9], [0, 1, 2], 0.99, "twin_requests")
+    assert stats.fused == G * 9 and torch.equal(cache.bt[:, 9:], cache.bt[:, :9]) and stats.compression_ratio == 2.0
+
+
+def test_decode_empty_and_minimal_requests(kb, oracle):
+    """Requests with no context, with one token, and a call with no request at all."""
+    rng = np.random.default_rng(78)
+    t, d, H, Hq = 16, 64, 2, 8
+    ctx_len = np.array([0, 1, 16, 17, 0, 40], np.int32)
+    blocks = np.maximum((ctx_len + t - 1) // t, 0)
+    req_start = np.concatenate([[0], np.cumsum(blocks)[:-1]]).astype(np.int32)
+    n = max(int(blocks.sum()), 1)
+    Kd = torch.from_numpy(rng.standard_normal((H, n, t * d)).astype(np.float32)).to(DEV).to(torch.bfloat16)
+    Vd = torch.from_numpy(rng.standard_normal((H, n, t * d)).astype(np.float32)).to(DEV).to(torch.bfloat16)
+    bt = torch.arange(n, dtype=torch.int32, device=DEV).repeat(H, 1).contiguous()
+    ctx = kb.Context(DEV)
+    cache = kb.Cache(Kd, Vd, bt, t, d)
+    cache.identity_scales()
+    q = torch.from_numpy(rng.standard_normal((1, len(ctx_len), Hq, d)).astype(np.float32)).to(DEV).to(torch.bfloat16)
+    rs = torch.tensor(req_start, dtype=torch.int32, device=DEV)
+    cl = torch.tensor(ctx_len, dtype=torch.int32, device=DEV)
+    out = kb.paged_decode_attn(ctx, cache, H, q, rs, cl, int(blocks.max()))
+    torch.cuda.synchronize()
+    one = np.ones((H, n))
+    want = oracle.paged_decode_attention(q[0].float().cpu().numpy().astype(np.float64), [wl.to_numpy_pool(Kd[g]) for g in range(H)],
+                                         [wl.to_numpy_pool(Vd[g]) for g in range(H)], [np.arange(n)] * H, one, one, req_start,
+                                         ctx_len, t, d)
+    got = out[0].cpu().numpy()
+    assert np.abs(got - want).max() <= 5e-3
+    assert (got[0] == 0).all() and (got[4] == 0).all()                      # no context: zero output, not NaN
+    assert np.allclose(got[1], np.repeat(Vd[:, req_start[1], :d].float().cpu().numpy(), Hq // H, 0), atol=1e-6)   # one token: its value
+    # no request at all
+    q0 = torch.empty(1, 0, Hq, d, device=DEV, dtype=torch.bfloat16)
+    out0 = kb.paged_decode_attn(ctx, cache, H, q0, rs[:0], cl[:0], 0)
+    torch.cuda.synchronize()
+    assert out0.shape == (1, 0, Hq, d)
+
+
 def test_tree_is_deterministic(kb):
     rec = _small_bf16(n_req=5, tokens=480, kv_heads=2)
     outs = []
