@@ -54,6 +54,37 @@ __device__ __forceinline__ double cosine_f64(const T *__restrict__ pool_g, int r
     return (na == 0.0 || nb == 0.0) ? 0.0 : dot / (na * nb);
 }
 
+// The same cosine with the right block already in registers (raw 16-byte chunks, chunk c of this lane = chunk
+// lane + 64 * c of the block): the re-check evaluates many left rows against one right block, and re-reading that
+// block for every row doubled the traffic through L2.  Same order of operations as cosine_f64, so the two give
+// bit-identical results.
+template <typename T, int CPL>
+__device__ __forceinline__ double cosine_f64_reg(const T *__restrict__ pool_g, int r, const double *__restrict__ norm_g,
+                                                 int a, const uint4 *braw, double nb, int lane)
+{
+    const double na = norm_g[a];
+    const uint4 *pa = reinterpret_cast<const uint4 *>(pool_g + (int64_t)a * r);
+    const int chunks = r / Elem<T>::PER16;
+    uint4 araw[CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c)
+        araw[c] = pa[min(lane + 64 * c, chunks - 1)];
+    double dot = 0.0;
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        if (lane + 64 * c < chunks) {
+            double x[Elem<T>::PER16], y[Elem<T>::PER16];
+            Elem<T>::widen(araw[c], x);
+            Elem<T>::widen(braw[c], y);
+#pragma unroll
+            for (int i = 0; i < Elem<T>::PER16; ++i)
+                dot = fma(x[i], y[i], dot);
+        }
+    }
+    dot = wave_sum(dot);
+    return (na == 0.0 || nb == 0.0) ? 0.0 : dot / (na * nb);
+}
+
 __global__ void assign_reset_kernel(WorkDesc w, int height)
 {
     w.n_active[height] = 0;   // the finalize kernel appends to this list
@@ -120,7 +151,9 @@ __global__ __launch_bounds__(256) void assign_screen_kernel(WorkDesc w, HeightDe
 
 // One WAVEFRONT per listed column: fp64 cosines of the contenders (or of the whole column when the candidate list
 // overflowed), strict '>' against thr, lowest row on exact ties.
-template <typename T>
+// CPL = 16-byte chunks of a block per lane when the right block is kept in registers (blocks up to 8 KiB), 0 = blocks
+// too long for that: both operands are streamed.
+template <typename T, int CPL>
 __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkDesc w, HeightDesc h, int height, double thr,
                                                             double band, int rule)
 {
@@ -139,6 +172,22 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
         const T *pool_g = (const T *)pool.k + (int64_t)g * pool.P * pool.r;
         const double *norm_g = pool.norm_k + (int64_t)g * pool.P;
         const int cnt = w.cand_cnt[cidx];
+        uint4 braw[CPL > 0 ? CPL : 1];
+        double nb = 0.0;
+        if constexpr (CPL > 0) {
+            const uint4 *pb = reinterpret_cast<const uint4 *>(pool_g + (int64_t)b * pool.r);
+            const int chunks = pool.r / Elem<T>::PER16;
+#pragma unroll
+            for (int q = 0; q < CPL; ++q)
+                braw[q] = pb[min(lane + 64 * q, chunks - 1)];
+            nb = norm_g[b];
+        }
+        auto cosine = [&](int a) __attribute__((always_inline)) {
+            if constexpr (CPL > 0)
+                return cosine_f64_reg<T, CPL>(pool_g, pool.r, norm_g, a, braw, nb, lane);
+            else
+                return cosine_f64<T>(pool_g, pool.r, norm_g, a, b, lane);
+        };
         double bv = -INFINITY;
         int bi = 0x7FFFFFFF;
         if (rule == KVFUSE_RULE_FIRST_ROW) {
@@ -163,7 +212,7 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
                     for (int off = 32; off >= 1; off >>= 1)
                         i = min(i, __shfl_xor(i, off, 64));
                     open &= ~__ballot(ci == i);
-                    const double cs = cosine_f64<T>(pool_g, pool.r, norm_g, l_ids[i], b, lane);
+                    const double cs = cosine(l_ids[i]);
                     if (cs > thr) {
                         win = i;
                         bv = cs;
@@ -177,7 +226,7 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
                 }
             } else {
                 for (int i = 0; i < ml; ++i) {
-                    const double cs = cosine_f64<T>(pool_g, pool.r, norm_g, l_ids[i], b, lane);
+                    const double cs = cosine(l_ids[i]);
                     if (cs > thr) {
                         win = i;
                         bv = cs;
@@ -203,7 +252,7 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
                 const int src = __ffsll((long long)mask) - 1;
                 mask &= mask - 1;
                 const int i = __shfl(ci, src, 64);
-                const double cs = cosine_f64<T>(pool_g, pool.r, norm_g, l_ids[i], b, lane);
+                const double cs = cosine(l_ids[i]);
                 if (cs > bv || (cs == bv && i < bi)) {
                     bv = cs;
                     bi = i;
@@ -212,7 +261,7 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
         } else {
             // more screen candidates than slots: rescan the whole column (ascending rows, strict '>')
             for (int i = 0; i < ml; ++i) {
-                const double cs = cosine_f64<T>(pool_g, pool.r, norm_g, l_ids[i], b, lane);
+                const double cs = cosine(l_ids[i]);
                 if (cs > bv) {
                     bv = cs;
                     bi = i;
@@ -384,10 +433,22 @@ void launch_assign(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, co
     if (cols > 0) {
         assign_screen_kernel<<<(unsigned)((cols + 255) / 256), 256, 0, s>>>(w, h, height, thr, band, rule);
         const unsigned rgrid = (unsigned)(cols < 4096 ? (cols + 3) / 4 : 1024);
-        if (pool.dtype == KVFUSE_BF16)
-            assign_refine_kernel<bf16_t><<<rgrid, 256, 0, s>>>(pool, w, h, height, thr, band, rule);
-        else
-            assign_refine_kernel<float><<<rgrid, 256, 0, s>>>(pool, w, h, height, thr, band, rule);
+        const int cpl = (pool.r / (pool.dtype == KVFUSE_BF16 ? 8 : 4) + 63) / 64;     // 16-byte chunks per lane
+#define KVF_REFINE(T, C) assign_refine_kernel<T, C><<<rgrid, 256, 0, s>>>(pool, w, h, height, thr, band, rule)
+        if (pool.dtype == KVFUSE_BF16) {
+            if (cpl <= 1) KVF_REFINE(bf16_t, 1);
+            else if (cpl <= 2) KVF_REFINE(bf16_t, 2);
+            else if (cpl <= 4) KVF_REFINE(bf16_t, 4);
+            else if (cpl <= 8) KVF_REFINE(bf16_t, 8);
+            else KVF_REFINE(bf16_t, 0);
+        } else {
+            if (cpl <= 1) KVF_REFINE(float, 1);
+            else if (cpl <= 2) KVF_REFINE(float, 2);
+            else if (cpl <= 4) KVF_REFINE(float, 4);
+            else if (cpl <= 8) KVF_REFINE(float, 8);
+            else KVF_REFINE(float, 0);
+        }
+#undef KVF_REFINE
     }
     if (w.G * h.n_nodes > 0)
         assign_finalize_kernel<<<(unsigned)(w.G * h.n_nodes), 256, 0, s>>>(pool.P, tab, w, h, height);
