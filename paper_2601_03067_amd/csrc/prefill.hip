@@ -16,12 +16,21 @@
 // table.  With reuse switched off the plan lists every logical block as its own entry, which gives the baseline
 // the reuse is measured against.
 //
-// Kernel: a workgroup of 4 wavefronts takes 4 x (16 / rep) consecutive query positions of one KV head; a wavefront
-// owns (16 / rep) positions x rep query heads = the 16 rows of an MFMA tile and walks all blocks itself, so no
-// partial states are exchanged.  Logits by v_mfma_f32_16x16x32_bf16 (K fragments straight from global memory),
-// online softmax in fp32, P.V by v_mfma_f32_16x16x16_bf16 after transposing each 16 x 16 piece of V through one
-// MFMA against the identity, probabilities split into a bfloat16 head and remainder -- the same arithmetic as the
-// shared-block decode kernel.  bfloat16 pools only.
+// Kernel: a workgroup of 4 wavefronts takes 4 x (32 / rep) consecutive query positions of one KV head; a wavefront
+// owns (32 / rep) positions x rep query heads = 32 query rows.  The context is walked in tiles of 32 tokens (two
+// 16-token pieces, each from one stored block with its own instance list) that the workgroup stages in LDS, double
+// buffered, so every K and V byte is fetched once per workgroup.
+//   logits^T = K Q^T with v_mfma_f32_32x32x16_bf16: K rows are the A operand as they lie in LDS, the query fragments
+//   (B operand) stay in registers.  In the accumulator layout a lane then owns ONE query and 16 of the 32 tokens, so
+//   the online softmax (per instance: exponentials of the scaled logits, weights summed with the value scales) is
+//   lane-local up to one exchange with lane ^ 32, and so is every rescaling of the output.
+//   out^T += V^T P^T: the weights of a lane are already a B operand (the order of the tokens inside the summation
+//   index is free as long as both operands agree); V^T fragments come from the row-major V tile through the LDS
+//   transpose read ds_read_b64_tr_b16 (16 lanes x 4 values: lane i receives element i & 3 of the rows that lanes
+//   i >> 2, 4 + (i >> 2), 8 + (i >> 2), 12 + (i >> 2) point at -- so when source lane s points at 4 consecutive head
+//   elements 4 (s & 3) .. of token (s >> 2), lane i ends up with head element i of 4 consecutive tokens).
+//   Weights are split into a bfloat16 head and remainder (two MFMAs) as in the decode kernels.
+// bfloat16 pools only.
 #include "common.h"
 
 #include <algorithm>
@@ -30,9 +39,7 @@
 
 namespace kvfuse {
 
-typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef short short4v __attribute__((ext_vector_type(4)));
 
 struct PEntry {          // 16 bytes
     int32_t phys, inst_off, inst_cnt, pad;
@@ -52,14 +59,32 @@ struct PrefillArgs {
     float sm_scale;
 };
 
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+
+// One 16-token piece of the context: where its K and V rows are, whose scale pairs apply, and the absolute
+// position of its first token for the causal test (very negative = visible to every query).
+struct PPiece {
+    const bf16_t *k, *v;
+    const float2 *ip;       // instance list, or null: the single pair below
+    float2 single;
+    int n_inst;             // 0 = no such piece (past the end of the walk)
+    int tok_base;
+};
+
 template <int D>
-__global__ __launch_bounds__(256, 4) void prefill_attn_kernel(PrefillArgs A)
+__global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillArgs A)
 {
     typedef bf16_t T;
-    constexpr int NF = D / 32;             // 16-byte fragments per lane (a lane owns a quarter of a token row)
-    constexpr int NT = 2 * NF;             // 16-column accumulator tiles
+    constexpr int KS = D / 16;                 // MFMA steps along the head dimension for the logits
+    constexpr int DT = D / 32;                 // 32-row tiles of out^T
+    constexpr int KSTR = D * 2 + 16;           // bytes per token row of the K tile (pad: conflict-free 16-byte row reads)
+    constexpr int VSTR = D * 2 + 64;           // bytes per token row of the V tile (pad: conflict-free transpose reads)
+    constexpr int RCH = D / 8;                 // 16-byte chunks per token row
+    constexpr int LPT = 32 * RCH / 256;        // chunks per thread, per tensor and tile (2 for D = 128, 1 for D = 64)
 
-    __shared__ __attribute__((aligned(16))) float c_lds[4][16];   // per wave: a per-row factor on its way to the accumulator layout
+    __shared__ __attribute__((aligned(16))) char k_lds[2][32 * KSTR];
+    __shared__ __attribute__((aligned(16))) char v_lds[2][32 * VSTR];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -73,174 +98,232 @@ __global__ __launch_bounds__(256, 4) void prefill_attn_kernel(PrefillArgs A)
     const float *skg = A.scale_k + (int64_t)g * A.n;
     const float *svg = A.scale_v + (int64_t)g * A.n;
 
-    const int head = lane & 15, tg = lane >> 4;      // logits / P: row, token group;  K and V loads: token, row quarter
-    const int pos_first = A.q_begin + ((int)blockIdx.x * 4 + wave) * A.npw;    // first query position of this wavefront
-    if (pos_first >= A.q_end)
-        return;                                       // no barrier below: a whole wavefront may leave
+    // rows of this wavefront: lane & 31 = query row, lane >> 5 = which half of the tokens / head elements it holds
+    const int qrow = lane & 31, h2 = lane >> 5;
+    const int wg_first = A.q_begin + (int)blockIdx.x * 4 * A.npw;
+    const int pos_last_wg = min(A.q_end - 1, wg_first + 4 * A.npw - 1);
+    const int pos_first = wg_first + wave * A.npw;                // may lie past the end: such a wavefront only helps loading
+    const bool wave_live = pos_first < A.q_end;
     const int pos_last = min(A.q_end - 1, pos_first + A.npw - 1);
-    const int rs = head / A.rep_pad, hh = head - rs * A.rep_pad;
-    const bool row_used = pos_first + rs <= pos_last && hh < A.rep;
-    const int my_pos = min(pos_first + rs, pos_last);             // unused rows mask like the wavefront's last position
+    const int rs = qrow / A.rep_pad, hh = qrow - rs * A.rep_pad;
+    const bool row_used = wave_live && pos_first + rs <= pos_last && hh < A.rep;
+    const int my_pos = wave_live ? min(pos_first + rs, pos_last) : A.q_end - 1;   // unused rows mask like a real one
 
-    uint4 qf[NF];
+    uint4 qf[KS];                                     // B operand of step ks: head elements 16 ks + 8 h2 .. + 7 of the row
     {
         const int64_t qi = (int64_t)li * (A.q_end - A.q_begin) + (my_pos - A.q_begin);
-        const T *qrow = (const T *)A.q + (qi * A.Hq + (int64_t)kvh * A.rep + (row_used ? hh : 0)) * D + tg * (D / 4);
+        const T *qp = (const T *)A.q + (qi * A.Hq + (int64_t)kvh * A.rep + (row_used ? hh : 0)) * D + 8 * h2;
 #pragma unroll
-        for (int f = 0; f < NF; ++f)
-            qf[f] = row_used ? reinterpret_cast<const uint4 *>(qrow)[f] : make_uint4(0, 0, 0, 0);
+        for (int ks = 0; ks < KS; ++ks)
+            qf[ks] = row_used ? *reinterpret_cast<const uint4 *>(qp + 16 * ks) : make_uint4(0, 0, 0, 0);
     }
-    short4v ident;                                    // identity as a B operand: I[k = 4 * tg + i][n = head]
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-        ident[i] = (4 * tg + i == head) ? (short)0x3F80 : (short)0;
 
-    float m_run = -INFINITY, l_run = 0.0f;
-    floatx4 o[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-        o[nt] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
-
-    // One 16-token piece of a stored block: logits once, then every instance's probabilities, then one P.V.
-    //   n_inst instances with scale pairs inst_ptr[0 .. n_inst);  tok_base = absolute position of the piece's first
-    //   token for the causal test (a very negative value for pieces that are visible to everybody)
-    auto piece = [&](const T *kblk, const T *vblk, int sub, const float2 *inst_ptr, int n_inst, int tok_base, int n_valid)
-        __attribute__((always_inline)) {
-        const uint4 *krow = reinterpret_cast<const uint4 *>(kblk + (int64_t)(sub + head) * D + tg * (D / 4));
-        const uint4 *vrow = reinterpret_cast<const uint4 *>(vblk + (int64_t)(sub + head) * D + tg * (D / 4));
-        uint4 kf[NF], vf[NF];
-#pragma unroll
-        for (int f = 0; f < NF; ++f)
-            kf[f] = krow[f];
-#pragma unroll
-        for (int f = 0; f < NF; ++f)
-            vf[f] = vrow[f];
-        floatx4 z = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-        for (int f = 0; f < NF; ++f)
-            z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[f]), __builtin_bit_cast(bf16x8, qf[f]), z, 0, 0, 0);
-        // which of this lane's 4 tokens its row may see
-        bool vis[4];
-#pragma unroll
-        for (int v = 0; v < 4; ++v)
-            vis[v] = tok_base + 4 * tg + v <= my_pos && 4 * tg + v < n_valid;
-        // block maximum over all instances
-        float bmax = -INFINITY;
-        for (int i = 0; i < n_inst; ++i) {
-            const float zs = A.sm_scale * inst_ptr[i].x;
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-                bmax = fmaxf(bmax, vis[v] ? z[v] * zs : -INFINITY);
+    // ---- the walk: pieces of the part before the chunk (distinct stored blocks with their instances), then the
+    //      chunk's own blocks up to the last position of this workgroup
+    const int ppb = A.t / 16;                                     // pieces per block
+    const int e0 = A.entry_begin[gi], e1 = A.entry_begin[gi + 1];
+    const int n_pre = (e1 - e0) * ppb;
+    const int n_pieces = n_pre + (pos_last_wg - A.chunk_begin) / 16 + 1;
+    const int n_tiles = (n_pieces + 1) / 2;
+    auto piece_at = [&](int p) __attribute__((always_inline)) {
+        PPiece pc;
+        pc.k = kg; pc.v = vg; pc.ip = nullptr; pc.single = make_float2(0.0f, 0.0f); pc.n_inst = 0; pc.tok_base = 0;
+        if (p < n_pre) {
+            const PEntry en = A.entries[e0 + p / ppb];
+            const int sub = (p % ppb) * 16;
+            pc.k = kg + (int64_t)en.phys * r + (int64_t)sub * D;
+            pc.v = vg + (int64_t)en.phys * r + (int64_t)sub * D;
+            pc.ip = A.inst + en.inst_off;
+            pc.n_inst = en.inst_cnt;
+            pc.tok_base = -(1 << 30);
+        } else if (p < n_pieces) {
+            const int cp = p - n_pre;
+            const int tok = A.chunk_begin + cp * 16;
+            const int x = A.req_start + tok / A.t;
+            const int phys = min(max(btg[x], 0), A.P - 1);      // a bad id in the table must not leave the pool
+            const int sub = tok % A.t;
+            pc.k = kg + (int64_t)phys * r + (int64_t)sub * D;
+            pc.v = vg + (int64_t)phys * r + (int64_t)sub * D;
+            pc.single = make_float2(skg[x], svg[x]);
+            pc.n_inst = 1;
+            pc.tok_base = tok;
         }
-        bmax = fmaxf(bmax, __shfl_xor(bmax, 16, 64));
-        bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
-        const float m_new = fmaxf(m_run, bmax);
-        const float corr = m_new == -INFINITY ? 1.0f : __expf(m_run - m_new);     // 0 on the first visible piece
-        float psum = 0.0f;
-        float pw[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        for (int i = 0; i < n_inst; ++i) {
-            const float2 sc = inst_ptr[i];
-            const float zs = A.sm_scale * sc.x;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float pr = vis[v] ? __expf(z[v] * zs - m_new) : 0.0f;
-                psum += pr;
-                pw[v] = fmaf(pr, sc.y, pw[v]);
-            }
-        }
-        psum += __shfl_xor(psum, 16, 64);
-        psum += __shfl_xor(psum, 32, 64);
-        l_run = l_run * corr + psum;
-        m_run = m_new;
-        short4v p_hi, p_lo;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const uint32_t hb = __float_as_uint(pw[v]) & 0xFFFF0000u;            // bfloat16 head (truncated)
-            const float rest = pw[v] - __uint_as_float(hb);                       // exact
-            p_hi[v] = (short)(hb >> 16);
-            p_lo[v] = (short)((__float_as_uint(rest) + 0x8000u) >> 16);           // bfloat16 remainder (rounded)
-        }
-        if (tg == 0)
-            c_lds[wave][head] = corr;
-        __builtin_amdgcn_wave_barrier();
-        const float4 c4 = *reinterpret_cast<const float4 *>(&c_lds[wave][4 * tg]);   // rows 4 * tg .. + 3 of every tile
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            o[nt][0] *= c4.x; o[nt][1] *= c4.y; o[nt][2] *= c4.z; o[nt][3] *= c4.w;
-        }
-        // V rows that no row of this wavefront may see can hold anything (the tail of the last block): zero them
-        if (tok_base + head > pos_last || head >= n_valid) {
-#pragma unroll
-            for (int f = 0; f < NF; ++f)
-                vf[f] = make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int f = 0; f < NF; ++f) {
-#pragma unroll
-            for (int hs = 0; hs < 2; ++hs) {
-                const uint32_t w0 = hs ? vf[f].z : vf[f].x, w1 = hs ? vf[f].w : vf[f].y;
-                short4v va;
-                va[0] = (short)(w0 & 0xFFFFu); va[1] = (short)(w0 >> 16);
-                va[2] = (short)(w1 & 0xFFFFu); va[3] = (short)(w1 >> 16);
-                const floatx4 vt = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, ident, floatx4{0.0f, 0.0f, 0.0f, 0.0f}, 0, 0, 0);
-                short4v vb;
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    vb[i] = (short)(__float_as_uint(vt[i]) >> 16);
-                o[2 * f + hs] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, vb, o[2 * f + hs], 0, 0, 0);
-                o[2 * f + hs] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_lo, vb, o[2 * f + hs], 0, 0, 0);
-            }
-        }
-        __builtin_amdgcn_wave_barrier();
+        return pc;
     };
 
-    // ---- the part before the chunk: distinct stored blocks with their instances, visible to every query
-    {
-        const int e0 = A.entry_begin[gi], e1 = A.entry_begin[gi + 1];
-        for (int e = e0; e < e1; ++e) {
-            const PEntry en = A.entries[e];
-            const T *kblk = kg + (int64_t)en.phys * r;
-            const T *vblk = vg + (int64_t)en.phys * r;
-            for (int sub = 0; sub < A.t; sub += 16)
-                piece(kblk, vblk, sub, A.inst + en.inst_off, en.inst_cnt, -(1 << 30), 16);
+    // global -> registers -> LDS, LPT chunks per thread and tensor: chunk c of a tile = token c / RCH, row chunk c % RCH
+    // two register sets: the tile after next is already on its way while the next one waits to be written to LDS
+    uint4 kr0[LPT], vr0[LPT], kr1[LPT], vr1[LPT];
+    auto fetch = [&](int ti, uint4 (&kreg)[LPT], uint4 (&vreg)[LPT]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < LPT; ++u) {
+            const int c = tid + 256 * u;
+            const int tok = c / RCH, rc = c % RCH;                // token 0 .. 31 of the tile
+            const PPiece pc = piece_at(2 * ti + (tok >> 4));
+            const bool ok = pc.n_inst > 0;
+            // values of tokens that no query of this workgroup may see can be anything (tail of the last block): zero
+            const bool v_ok = ok && pc.tok_base + (tok & 15) <= pos_last_wg;
+            const int64_t off = (int64_t)(tok & 15) * D + rc * 8;
+            kreg[u] = ok ? *reinterpret_cast<const uint4 *>(pc.k + off) : make_uint4(0, 0, 0, 0);
+            vreg[u] = v_ok ? *reinterpret_cast<const uint4 *>(pc.v + off) : make_uint4(0, 0, 0, 0);
         }
-    }
-    // ---- the chunk itself, block by block with the causal mask
-    {
-        const int xb0 = A.chunk_begin / A.t, xb1 = pos_last / A.t;
-        for (int xb = xb0; xb <= xb1; ++xb) {
-            const int x = A.req_start + xb;
-            const int phys = btg[x];
-            const float2 sc = make_float2(skg[x], svg[x]);
-            const T *kblk = kg + (int64_t)phys * r;
-            const T *vblk = vg + (int64_t)phys * r;
-            for (int sub = 0; sub < A.t; sub += 16) {
-                if (xb * A.t + sub > pos_last)
-                    break;
-                piece(kblk, vblk, sub, &sc, 1, xb * A.t + sub, 16);
+    };
+    auto stash = [&](int buf, const uint4 (&kreg)[LPT], const uint4 (&vreg)[LPT]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < LPT; ++u) {
+            const int c = tid + 256 * u;
+            const int tok = c / RCH, rc = c % RCH;
+            *reinterpret_cast<uint4 *>(&k_lds[buf][tok * KSTR + rc * 16]) = kreg[u];
+            *reinterpret_cast<uint4 *>(&v_lds[buf][tok * VSTR + rc * 16]) = vreg[u];
+        }
+    };
+
+    float m_run = -INFINITY, l_run = 0.0f;       // running maximum in base-2 units, running sum
+    floatx16 o[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            o[dt][i] = 0.0f;
+
+    // this lane's addresses inside a tile: K row for the logits, V patch for the transpose reads
+    const int k_off = qrow * KSTR + h2 * 16;
+    const int l16 = lane & 15;
+    const int v_off = (4 * h2 + (l16 >> 2)) * VSTR + (16 * ((lane >> 4) & 1) + 4 * (l16 & 3)) * 2;
+
+    auto compute = [&](int ti, int buf) __attribute__((always_inline)) {
+        if (wave_live) {
+            // ---- logits^T of the tile: 32 tokens x 32 query rows
+            floatx16 z;
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                z[i] = 0.0f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const uint4 ka = *reinterpret_cast<const uint4 *>(&k_lds[buf][k_off + ks * 32]);
+                z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka), __builtin_bit_cast(bf16x8, qf[ks]), z, 0, 0, 0);
+            }
+            // accumulator i of this lane: token 8 (i / 4) + 4 h2 + i % 4 of the tile, i.e. piece i / 8
+            const PPiece pc0 = piece_at(2 * ti), pc1 = piece_at(2 * ti + 1);
+            // pieces before the chunk are visible to every query: no masks in that (common) case
+            const bool masked = pc0.tok_base >= 0 || pc1.tok_base >= 0 || pc1.n_inst == 0;
+            bool vis[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int tp = 8 * ((i >> 2) & 1) + 4 * h2 + (i & 3);
+                const PPiece &pc = i < 8 ? pc0 : pc1;
+                vis[i] = !masked || (pc.n_inst > 0 && pc.tok_base + tp <= my_pos);
+            }
+            // everything below works in base 2: exp(x) = exp2(x * log2(e)), and v_exp_f32 is an exp2
+            constexpr float LOG2E = 1.4426950408889634f;
+            float bmax = -INFINITY;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const PPiece &pc = half ? pc1 : pc0;
+                for (int q = 0; q < pc.n_inst; ++q) {
+                    const float zs = A.sm_scale * LOG2E * (pc.ip ? pc.ip[q].x : pc.single.x);
+#pragma unroll
+                    for (int i = 8 * half; i < 8 * half + 8; ++i)
+                        bmax = fmaxf(bmax, vis[i] ? z[i] * zs : -INFINITY);
+                }
+            }
+            bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
+            const float m_new = fmaxf(m_run, bmax);
+            const float corr = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first visible tile
+            float psum = 0.0f;
+            float pw[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                pw[i] = 0.0f;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const PPiece &pc = half ? pc1 : pc0;
+                for (int q = 0; q < pc.n_inst; ++q) {
+                    const float2 sc = pc.ip ? pc.ip[q] : pc.single;
+                    const float zs = A.sm_scale * LOG2E * sc.x;
+#pragma unroll
+                    for (int i = 8 * half; i < 8 * half + 8; ++i) {
+                        const float pr = vis[i] ? __builtin_amdgcn_exp2f(fmaf(z[i], zs, -m_new)) : 0.0f;
+                        psum += pr;
+                        pw[i] = fmaf(pr, sc.y, pw[i]);
+                    }
+                }
+            }
+            psum += __shfl_xor(psum, 32, 64);
+            l_run = l_run * corr + psum;
+            m_run = m_new;
+            if (__builtin_amdgcn_ballot_w64(corr != 1.0f)) {
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        o[dt][i] *= corr;
+            }
+            // weights as B operands: the 8 values of MFMA jj are accumulators 8 jj .. 8 jj + 7, as a bfloat16 head
+            // (nearest) plus the bfloat16 of what is left
+            bf16x8 p_hi[2], p_lo[2];
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float w = pw[8 * jj + e];
+                    const __bf16 hb = (__bf16)w;
+                    p_hi[jj][e] = hb;
+                    p_lo[jj][e] = (__bf16)(w - (float)hb);
+                }
+            // ---- out^T += V^T P^T
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj) {
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    const char *vp = &v_lds[buf][v_off + (16 * jj) * VSTR + dt * 64];
+                    const bf16x4 t0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                        (__attribute__((address_space(3))) bf16x4 *)(vp));
+                    const bf16x4 t1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                        (__attribute__((address_space(3))) bf16x4 *)(vp + 8 * VSTR));
+                    const bf16x8 va = __builtin_shufflevector(t0, t1, 0, 1, 2, 3, 4, 5, 6, 7);
+                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, p_hi[jj], o[dt], 0, 0, 0);
+                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, p_lo[jj], o[dt], 0, 0, 0);
+                }
             }
         }
+    };
+
+    fetch(0, kr0, vr0);
+    if (n_tiles > 1)
+        fetch(1, kr1, vr1);
+    stash(0, kr0, vr0);
+    __syncthreads();
+    for (int ti = 0; ti < n_tiles; ti += 2) {
+        // tile ti is in buffer 0, tile ti + 1 in register set 1
+        if (ti + 2 < n_tiles)
+            fetch(ti + 2, kr0, vr0);
+        compute(ti, 0);
+        if (ti + 1 < n_tiles)
+            stash(1, kr1, vr1);
+        __syncthreads();
+        if (ti + 1 >= n_tiles)
+            break;
+        // tile ti + 1 is in buffer 1, tile ti + 2 in register set 0
+        if (ti + 3 < n_tiles)
+            fetch(ti + 3, kr1, vr1);
+        compute(ti + 1, 1);
+        if (ti + 2 < n_tiles)
+            stash(0, kr0, vr0);
+        __syncthreads();
     }
 
-    // ---- normalise and store: this lane holds o[row 4 * tg + i][column slot head] of every tile
-    if (tg == 0)
-        c_lds[wave][head] = l_run > 0.0f ? 1.0f / l_run : 0.0f;
-    __builtin_amdgcn_wave_barrier();
-    const float4 inv4 = *reinterpret_cast<const float4 *>(&c_lds[wave][4 * tg]);
-    const float inv[4] = {inv4.x, inv4.y, inv4.z, inv4.w};
+    // ---- normalise and store: this lane holds out[row qrow][head element 32 dt + 8 (i / 4) + 4 h2 + i % 4]
+    if (row_used) {
+        const float inv = l_run > 0.0f ? 1.0f / l_run : 0.0f;
+        const int64_t qi = (int64_t)li * (A.q_end - A.q_begin) + (pos_first + rs - A.q_begin);
+        float *dst = A.out + (qi * A.Hq + (int64_t)kvh * A.rep + hh) * D + 4 * h2;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = 4 * tg + i;
-        const int rrs = row / A.rep_pad, rhh = row - rrs * A.rep_pad;
-        if (pos_first + rrs > pos_last || rhh >= A.rep)
-            continue;
-        const int64_t qi = (int64_t)li * (A.q_end - A.q_begin) + (pos_first + rrs - A.q_begin);
-        float *dst = A.out + (qi * A.Hq + (int64_t)kvh * A.rep + rhh) * D;
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int f = 0; f < NF; ++f)
-#pragma unroll
-            for (int hs = 0; hs < 2; ++hs)
-                dst[(D / 4) * (head >> 2) + 8 * f + 4 * hs + (head & 3)] = o[2 * f + hs][i] * inv[i];
+            for (int g4 = 0; g4 < 4; ++g4)
+                *reinterpret_cast<float4 *>(dst + 32 * dt + 8 * g4) =
+                    make_float4(o[dt][4 * g4] * inv, o[dt][4 * g4 + 1] * inv, o[dt][4 * g4 + 2] * inv, o[dt][4 * g4 + 3] * inv);
     }
 }
 
@@ -306,7 +389,7 @@ int kvfuse_prefill_plan_build(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kv
     pl->kv_heads = kv_heads; pl->layer_begin = layer_begin; pl->n_layers = n_layers; pl->Hq = Hq;
     pl->rep = Hq / kv_heads;
     pl->rep_pad = pad_pow2_p(pl->rep);
-    pl->npw = 16 / pl->rep_pad;
+    pl->npw = 32 / pl->rep_pad;
     pl->req_start = req_start; pl->q_begin = q_begin; pl->q_end = q_end; pl->chunk_begin = chunk_begin;
 
     const int Gsel = n_layers * kv_heads;
