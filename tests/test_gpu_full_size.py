@@ -18,7 +18,8 @@ DEV = "cuda:0"
 
 
 @pytest.mark.timeout(900)
-def test_llama8b_bff_full_size_sampled_groups_and_invariants(oracle):
+@pytest.mark.parametrize("rule", ["argmax", "first_row"])
+def test_llama8b_bff_full_size_sampled_groups_and_invariants(oracle, rule):
     kb = gu.load_binding()
     rec = wl.llama8b_bff()
     print("materialise", rec.name, "G", rec.G, "n", rec.n, flush=True)
@@ -26,8 +27,8 @@ def test_llama8b_bff_full_size_sampled_groups_and_invariants(oracle):
     rng = np.random.default_rng(20260103)
     sample = sorted({0, rec.G - 1, *rng.choice(rec.G, size=2, replace=False).tolist()})
     host = {g: (wl.to_numpy_pool(mat["K"][g]), wl.to_numpy_pool(mat["V"][g]), mat["bt"][g].cpu().numpy().copy()) for g in sample}
-    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, cand_cap=16)
-    print("gpu fused", stats.fused, "CR", stats.compression_ratio, "refined", stats.refined, flush=True)
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, cand_cap=64, rule=rule)       # bench.py's candidate slots
+    print("rule", rule, "gpu fused", stats.fused, "CR", stats.compression_ratio, "refined", stats.refined, flush=True)
 
     # ---- invariants on every group
     n, P = rec.n, rec.n
@@ -57,7 +58,7 @@ def test_llama8b_bff_full_size_sampled_groups_and_invariants(oracle):
     # ---- exact comparison on the sampled groups
     print("oracle on groups", sample, flush=True)
     res = gu.oracle_fuse(oracle, rec, ([host[g][0] for g in sample], [host[g][1] for g in sample], [host[g][2] for g in sample]),
-                         threads=len(sample))
+                         threads=len(sample), rule=rule)
     safe = gu.check_ambiguity(res, "llama8b_bff full size")
     assert len(safe) >= len(sample) - 1
     for i in safe:
@@ -95,7 +96,7 @@ def test_cff_long_full_size_sampled_groups_and_invariants(oracle):
     rng = np.random.default_rng(20260103 + 3)
     sample = sorted({0, rec.G - 1, *rng.choice(rec.G, size=4, replace=False).tolist()})
     host = {g: (wl.to_numpy_pool(mat["K"][g]), wl.to_numpy_pool(mat["V"][g]), mat["bt"][g].cpu().numpy().copy()) for g in sample}
-    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, cand_cap=16)
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, cand_cap=64)
     print("gpu fused", stats.fused, "CR", stats.compression_ratio, "refined", stats.refined, flush=True)
     n, P = rec.n, rec.n
     bt = cache.bt.cpu().numpy()
