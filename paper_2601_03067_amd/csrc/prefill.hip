@@ -205,47 +205,71 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillArgs A)
             }
             // accumulator i of this lane: token 8 (i / 4) + 4 h2 + i % 4 of the tile, i.e. piece i / 8
             const PPiece pc0 = piece_at(2 * ti), pc1 = piece_at(2 * ti + 1);
-            // pieces before the chunk are visible to every query: no masks in that (common) case
-            const bool masked = pc0.tok_base >= 0 || pc1.tok_base >= 0 || pc1.n_inst == 0;
-            bool vis[16];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int tp = 8 * ((i >> 2) & 1) + 4 * h2 + (i & 3);
-                const PPiece &pc = i < 8 ? pc0 : pc1;
-                vis[i] = !masked || (pc.n_inst > 0 && pc.tok_base + tp <= my_pos);
-            }
             // everything below works in base 2: exp(x) = exp2(x * log2(e)), and v_exp_f32 is an exp2
             constexpr float LOG2E = 1.4426950408889634f;
-            float bmax = -INFINITY;
-#pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                const PPiece &pc = half ? pc1 : pc0;
-                for (int q = 0; q < pc.n_inst; ++q) {
-                    const float zs = A.sm_scale * LOG2E * (pc.ip ? pc.ip[q].x : pc.single.x);
-#pragma unroll
-                    for (int i = 8 * half; i < 8 * half + 8; ++i)
-                        bmax = fmaxf(bmax, vis[i] ? z[i] * zs : -INFINITY);
-                }
-            }
-            bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
-            const float m_new = fmaxf(m_run, bmax);
-            const float corr = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first visible tile
-            float psum = 0.0f;
+            float bmax, m_new, corr, psum = 0.0f;
             float pw[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i)
                 pw[i] = 0.0f;
+            // The common tile: both pieces lie before the chunk (visible to every query) and stand for one logical
+            // block each.  No masks and no instance loops: the kernel is bound by instruction issue, and this is
+            // where most of its instructions went.
+            const bool plain = pc0.tok_base < 0 && pc1.tok_base < 0 && pc0.n_inst == 1 && pc1.n_inst == 1;
+            if (__builtin_amdgcn_readfirstlane((int)plain)) {
+                const float2 s0 = pc0.ip[0], s1 = pc1.ip[0];
+                const float zs0 = A.sm_scale * LOG2E * s0.x, zs1 = A.sm_scale * LOG2E * s1.x;
+                float t[16];
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                const PPiece &pc = half ? pc1 : pc0;
-                for (int q = 0; q < pc.n_inst; ++q) {
-                    const float2 sc = pc.ip ? pc.ip[q] : pc.single;
-                    const float zs = A.sm_scale * LOG2E * sc.x;
+                for (int i = 0; i < 16; ++i)
+                    t[i] = z[i] * (i < 8 ? zs0 : zs1);
+                bmax = fmaxf(fmaxf(fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3])), fmaxf(fmaxf(t[4], t[5]), fmaxf(t[6], t[7]))),
+                             fmaxf(fmaxf(fmaxf(t[8], t[9]), fmaxf(t[10], t[11])), fmaxf(fmaxf(t[12], t[13]), fmaxf(t[14], t[15]))));
+                bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
+                m_new = fmaxf(m_run, bmax);
+                corr = __builtin_amdgcn_exp2f(m_run - m_new);          // m_new is finite here; 0 on the very first tile
 #pragma unroll
-                    for (int i = 8 * half; i < 8 * half + 8; ++i) {
-                        const float pr = vis[i] ? __builtin_amdgcn_exp2f(fmaf(z[i], zs, -m_new)) : 0.0f;
-                        psum += pr;
-                        pw[i] = fmaf(pr, sc.y, pw[i]);
+                for (int i = 0; i < 16; ++i) {
+                    const float pr = __builtin_amdgcn_exp2f(t[i] - m_new);
+                    psum += pr;
+                    pw[i] = pr * (i < 8 ? s0.y : s1.y);
+                }
+            } else {
+                // pieces before the chunk are visible to every query: no masks in that (common) case
+                const bool masked = pc0.tok_base >= 0 || pc1.tok_base >= 0 || pc1.n_inst == 0;
+                bool vis[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int tp = 8 * ((i >> 2) & 1) + 4 * h2 + (i & 3);
+                    const PPiece &pc = i < 8 ? pc0 : pc1;
+                    vis[i] = !masked || (pc.n_inst > 0 && pc.tok_base + tp <= my_pos);
+                }
+                bmax = -INFINITY;
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const PPiece &pc = half ? pc1 : pc0;
+                    for (int q = 0; q < pc.n_inst; ++q) {
+                        const float zs = A.sm_scale * LOG2E * (pc.ip ? pc.ip[q].x : pc.single.x);
+#pragma unroll
+                        for (int i = 8 * half; i < 8 * half + 8; ++i)
+                            bmax = fmaxf(bmax, vis[i] ? z[i] * zs : -INFINITY);
+                    }
+                }
+                bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
+                m_new = fmaxf(m_run, bmax);
+                corr = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first visible tile
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const PPiece &pc = half ? pc1 : pc0;
+                    for (int q = 0; q < pc.n_inst; ++q) {
+                        const float2 sc = pc.ip ? pc.ip[q] : pc.single;
+                        const float zs = A.sm_scale * LOG2E * sc.x;
+#pragma unroll
+                        for (int i = 8 * half; i < 8 * half + 8; ++i) {
+                            const float pr = vis[i] ? __builtin_amdgcn_exp2f(fmaf(z[i], zs, -m_new)) : 0.0f;
+                            psum += pr;
+                            pw[i] = fmaf(pr, sc.y, pw[i]);
+                        }
                     }
                 }
             }

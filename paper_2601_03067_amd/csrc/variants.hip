@@ -99,8 +99,12 @@ int kvfuse_tree_spec_shortest_first(const kvfuse_tree_spec *spec, int32_t *leaf_
     if (!spec || spec->n_leaves < 0 || spec->n_units < 0 || (spec->n_leaves > 0 && (!spec->leaf_start || !spec->leaf_count)) ||
         (spec->n_units > 0 && !spec->unit_leaf_ptr) || (spec->n_leaves > 0 && (!leaf_start || !leaf_count)) || !unit_leaf_ptr)
         return KVFUSE_EINVAL;
-    if (spec->n_units == 0)
-        return spec->n_leaves == 0 ? (unit_leaf_ptr[0] = 0, KVFUSE_OK) : KVFUSE_EINVAL;
+    if (spec->n_units == 0) {
+        if (spec->n_leaves != 0)
+            return KVFUSE_EINVAL;       // leaves without units
+        unit_leaf_ptr[0] = 0;
+        return KVFUSE_OK;
+    }
     if (spec->unit_leaf_ptr[0] != 0 || spec->unit_leaf_ptr[spec->n_units] != spec->n_leaves)
         return KVFUSE_EINVAL;
     for (int u = 0; u < spec->n_units; ++u)
