@@ -234,6 +234,38 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(PrefillArgs A)
                     psum += pr;
                     pw[i] = pr * (i < 8 ? s0.y : s1.y);
                 }
+            } else if (__builtin_amdgcn_readfirstlane((int)(pc0.tok_base < 0 && pc1.tok_base < 0 && pc1.n_inst > 0))) {
+                // both pieces before the chunk, several logical blocks behind at least one of them: instance loops, no masks
+                bmax = -INFINITY;
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const PPiece &pc = half ? pc1 : pc0;
+                    const int ni = __builtin_amdgcn_readfirstlane(pc.n_inst);
+                    for (int q = 0; q < ni; ++q) {
+                        const float zs = A.sm_scale * LOG2E * pc.ip[q].x;
+#pragma unroll
+                        for (int i = 8 * half; i < 8 * half + 8; ++i)
+                            bmax = fmaxf(bmax, z[i] * zs);
+                    }
+                }
+                bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
+                m_new = fmaxf(m_run, bmax);
+                corr = __builtin_amdgcn_exp2f(m_run - m_new);
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const PPiece &pc = half ? pc1 : pc0;
+                    const int ni = __builtin_amdgcn_readfirstlane(pc.n_inst);
+                    for (int q = 0; q < ni; ++q) {
+                        const float2 sc = pc.ip[q];
+                        const float zs = A.sm_scale * LOG2E * sc.x;
+#pragma unroll
+                        for (int i = 8 * half; i < 8 * half + 8; ++i) {
+                            const float pr = __builtin_amdgcn_exp2f(fmaf(z[i], zs, -m_new));
+                            psum += pr;
+                            pw[i] = fmaf(pr, sc.y, pw[i]);
+                        }
+                    }
+                }
             } else {
                 // pieces before the chunk are visible to every query: no masks in that (common) case
                 const bool masked = pc0.tok_base >= 0 || pc1.tok_base >= 0 || pc1.n_inst == 0;
