@@ -311,6 +311,16 @@ def test_tree_shortest_first_order(kb, oracle, which):
     assert stats.fused > 20
 
 
+def test_tree_variants_combined(kb, oracle):
+    """Row-order rule, shortest-first tree and "every N requests" together, on ragged chunked requests in f32 and bf16."""
+    for dtype, gs in ((torch.float32, 4), (torch.bfloat16, 3)):
+        rec = wl.mixed(n_req=10, min_tokens=40, max_tokens=800, chunk_tokens=256, layers=1, kv_heads=2, pool=40, t=8, d=32,
+                       dtype=dtype)
+        cache, plan, stats, res, mat = _run_tree_case(kb, oracle, rec, f"variants_combined_{gs}", cand_cap=4, rule="first_row",
+                                                      shortest_first=True, group_size=gs)
+        assert stats.fused > 20
+
+
 @pytest.mark.parametrize("kind", ["bf16", "f32"])
 def test_replicate_rescaled_and_drop_rescale_match_oracle(kb, oracle, kind):
     """The two evaluation modes of the results section.  Replicate: every logical block gets the block it had before
