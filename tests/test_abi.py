@@ -134,3 +134,16 @@ def test_variant_entry_points_reject_null_arguments(lib):
     assert lib.kvfuse_plan_set_assign_rule(None, None, 1) != 0
     assert lib.kvfuse_replicate_rescaled(None, None, None, None) != 0
     assert lib.kvfuse_drop_rescale(None, None, None) != 0
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 (and as C++) on its own."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "include/kvfuse.h"\nint main(void) { kvfuse_stats s; (void)s; return KVFUSE_OK; }\n')
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-I", ROOT, str(src)])
+    if shutil.which("g++") is not None:
+        subprocess.check_call(["g++", "-std=c++17", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", "-I", ROOT, str(src)])
