@@ -60,7 +60,16 @@ def cpu_baseline(wl, seconds_hint=20.0):
     res = oracle.fuse_groups(Ks, Vs, bts, rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr, rec.thr, threads=cores)
     dt = time.perf_counter() - t0
     blocks = rec.G * rec.n
-    return {"value": blocks / dt, "unit": "blocks/s", "cores": cores, "kind": "oracle",
+    model = "unknown"
+    try:
+        for ln in open("/proc/cpuinfo"):
+            if ln.startswith("model name"):
+                model = ln.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    return {"value": blocks / dt, "unit": "blocks/s", "cores": cores, "kind": "oracle", "cpu_model": model,
+            "blocks_per_s_per_core": blocks / dt / cores,
             "sample": f"{rec.G} groups x 32 requests x 128 blocks of the llama8b_bff recipe (fusion only, {dt:.1f} s wall), "
                       f"CR {sum(len(r.bt) for r in res) / sum(r.n_physical for r in res):.3f}"}
 
@@ -257,6 +266,18 @@ def main():
     variants["replicate_rescaled"] = {"ms": sev[0].elapsed_time(sev[1]), "blocks_rewritten_at_least": stats.fused,
                                       "includes": "scatter of scale * representative for K and V, table restore, norm pass"}
 
+    # decode attention over the un-fused cache (logical = physical bytes): the clean HBM figure of the decode kernel
+    restore()
+    cache.identity_scales()
+    kb.paged_decode_attn(ctx, cache, rec.kv_heads, q, rs, cl, max_blocks, workspace=ws, out=out)
+    torch.cuda.synchronize()
+    sev[0].record()
+    for _ in range(3):
+        kb.paged_decode_attn(ctx, cache, rec.kv_heads, q, rs, cl, max_blocks, workspace=ws, out=out)
+    sev[1].record()
+    torch.cuda.synchronize()
+    ms_dec_unfused = sev[0].elapsed_time(sev[1]) / 3
+
     # what the machine sustains, measured with the library's own probes after the timed steps (they load the chip
     # heavily and would otherwise warm it up for the steps): the MFMA instruction of the similarity kernel on
     # random and on constant operands, and a plain device copy
@@ -266,6 +287,7 @@ def main():
     k = max(args.steps, 1)
     stage = {a: b / k for a, b in stage.items()}
     ms_step = sum(walls) / k
+    ms_median = sorted(walls)[len(walls) // 2] if walls else 0.0
     blocks = rec.G * rec.n
     elem = 2 if rec.dtype == torch.bfloat16 else 4
     blk_bytes = rec.r * elem
@@ -283,7 +305,9 @@ def main():
         "metric": "KV blocks fused/sec (+ % MFMA peak); fused-table decode attn HBM GB/s",
         "value": blocks / (ms_step * 1e-3),
         "unit": "blocks/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "ms_per_step_median": ms_median,
+        "request_level_blocks_per_s": blocks / (rec.layers * rec.kv_heads) / (ms_step * 1e-3),
+        "blocks_fused_per_s": stats.fused / (ms_step * 1e-3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if rec.dtype == torch.bfloat16 else "f32", "data": "synthetic",
         "config": {"workload": f"{rec.name}: {rec.layers} layers x {rec.kv_heads} KV heads, d {rec.d}, block {rec.t}, "
@@ -297,6 +321,9 @@ def main():
         "decode": {"ms": stage["decode"], "physical_GBps": phys_bytes / (stage["decode"] * 1e-3) / 1e9,
                    "logical_GBps": logi_bytes / (stage["decode"] * 1e-3) / 1e9, "hbm_peak_GBps": 8000.0,
                    "frac_of_hbm_peak_physical": phys_bytes / (stage["decode"] * 1e-3) / 1e9 / 8000.0},
+        "decode_unfused": {"ms": ms_dec_unfused, "GBps": logi_bytes / (ms_dec_unfused * 1e-3) / 1e9,
+                           "frac_of_hbm_peak": logi_bytes / (ms_dec_unfused * 1e-3) / 1e9 / 8000.0,
+                           "note": "same kernel and queries on the cache before fusion: logical = physical bytes"},
         "decode_shared_blocks": {"ms": ms_shared, "physical_GBps": phys_bytes / (ms_shared * 1e-3) / 1e9,
                                  "max_abs_diff_vs_decode": shared_diff, "plan_build_s": t_plan, "clusters": si.clusters,
                                  "logical_blocks": si.logical_blocks, "served_through_clusters": si.shared_instances,
