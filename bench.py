@@ -336,6 +336,10 @@ def main():
                             "gaussian_exceedance_rate_per_group_at_thr": kb.exceedance_rate(cross_pairs, mu_s, sigma_s, rec.thr),
                             "note": "the synthetic cache plants exact and near duplicates, which a Gaussian fit of the "
                                     "bulk does not see; the rate is shown for the mechanism, not as a forecast"},
+        "merge": {"ms": stage["merge"], "targets": stats.merge_targets, "members": stats.fused,
+                  "algorithmic_bytes": (2 * stats.merge_targets + stats.fused) * blk_bytes * 2,
+                  "GBps": (2 * stats.merge_targets + stats.fused) * blk_bytes * 2 / (stage["merge"] * 1e-3) / 1e9,
+                  "frac_of_hbm_peak": (2 * stats.merge_targets + stats.fused) * blk_bytes * 2 / (stage["merge"] * 1e-3) / 1e9 / 8000.0},
         "variants": variants,
         "norms": {"ms": stage["norms"], "GBps": logi_bytes / (stage["norms"] * 1e-3) / 1e9},
         "roofline": {"kernel": "similarity_ring_kernel (256 x 256 tile instance on the upper heights, 128 x 128 on the lowest)",

@@ -111,7 +111,7 @@ typedef struct kvfuse_stats {
     /* stage times in ms from HIP events on the context's stream; filled only when timing was requested */
     float ms_norms, ms_similarity, ms_assign, ms_merge, ms_rewrite, ms_total;
     int32_t n_heights;
-    int32_t reserved;
+    int32_t merge_targets;    /* left blocks rebuilt by kvfuse_merge, all heights (each reads itself and its members, is written once) */
 } kvfuse_stats;
 
 /* Device views of one height's intermediate results, for tests and tools.  Column c of a height is right

@@ -50,10 +50,10 @@ class Stats(C.Structure):
     _fields_ = [("logical_blocks", _i64), ("physical_blocks", _i64), ("fused", _i64), ("near_threshold", _i64),
                 ("refined", _i64), ("cand_overflow", _i64), ("compression_ratio", _f64), ("sim_flops", _f64),
                 ("ms_norms", _f32), ("ms_similarity", _f32), ("ms_assign", _f32), ("ms_merge", _f32),
-                ("ms_rewrite", _f32), ("ms_total", _f32), ("n_heights", _i32), ("reserved", _i32)]
+                ("ms_rewrite", _f32), ("ms_total", _f32), ("n_heights", _i32), ("merge_targets", _i32)]
 
     def as_dict(self):
-        return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved"}
+        return {k: getattr(self, k) for k, _ in self._fields_}
 
 
 class HeightView(C.Structure):

@@ -1,7 +1,9 @@
 // Host side of the kvfuse C ABI: contexts, Algorithm 1's recursion tree cut into heights (a6), workspace layout,
 // argument checks and the stage sequencing of the whole pipeline.  No device memory is allocated here.
 #include <algorithm>
+#include <climits>
 #include <cmath>
+#include <cstdint>
 #include <cstring>
 #include <new>
 #include <utility>
@@ -661,6 +663,14 @@ int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band
     std::vector<int32_t> counters((size_t)w.G * 8), cnt((size_t)w.G * w.n_slots);
     KVF_TRY(hipMemcpy(counters.data(), w.counters, counters.size() * 4, hipMemcpyDeviceToHost));
     KVF_TRY(hipMemcpy(cnt.data(), w.set_cnt, cnt.size() * 4, hipMemcpyDeviceToHost));
+    if (nh > 0) {
+        std::vector<int32_t> n_act((size_t)nh);
+        KVF_TRY(hipMemcpy(n_act.data(), w.n_active, (size_t)nh * 4, hipMemcpyDeviceToHost));
+        int64_t targets = 0;
+        for (int32_t x : n_act)
+            targets += x;
+        stats->merge_targets = (int32_t)std::min<int64_t>(targets, INT32_MAX);
+    }
     int64_t invalid = 0;
     for (int g = 0; g < w.G; ++g) {
         const bool on = p.group_enable_host.empty() || p.group_enable_host[(size_t)g] != 0;

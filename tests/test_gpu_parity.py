@@ -193,6 +193,7 @@ def test_tree_tiny_config_all_groups(kb, oracle):
     rec = wl.tiny_bff()
     cache, plan, stats, res, mat = _run_tree_case(kb, oracle, rec, "tiny_bff")
     assert stats.physical_blocks == 2 * 22 and stats.fused == 20 and stats.near_threshold == 0
+    assert stats.merge_targets == 20                      # ten disjoint pairs per group: one rebuilt block per fused one
     assert math.isclose(stats.compression_ratio, 32 / 22)
 
 
