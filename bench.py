@@ -281,9 +281,11 @@ def main():
     # what the machine sustains, measured with the library's own probes after the timed steps (they load the chip
     # heavily and would otherwise warm it up for the steps): the MFMA instruction of the similarity kernel on
     # random and on constant operands, and a plain device copy
+    blk_bytes_probe = rec.r * (2 if rec.dtype == torch.bfloat16 else 4)
     probes = {"mfma_bf16_random_operands_TFLOPs": kb.probe_mfma_bf16(ctx, True, dev),
               "mfma_bf16_constant_operands_TFLOPs": kb.probe_mfma_bf16(ctx, False, dev),
-              "copy_kernel_GBps": kb.probe_copy(ctx, K0, cache.K, repeats=3)}
+              "copy_kernel_GBps": kb.probe_copy(ctx, K0, cache.K, repeats=3),
+              "read2_write1_GBps": kb.probe_read2_write1(ctx, cache.K, blk_bytes_probe, repeats=3)}
     k = max(args.steps, 1)
     stage = {a: b / k for a, b in stage.items()}
     ms_step = sum(walls) / k
@@ -339,7 +341,9 @@ def main():
         "merge": {"ms": stage["merge"], "targets": stats.merge_targets, "members": stats.fused,
                   "algorithmic_bytes": (2 * stats.merge_targets + stats.fused) * blk_bytes * 2,
                   "GBps": (2 * stats.merge_targets + stats.fused) * blk_bytes * 2 / (stage["merge"] * 1e-3) / 1e9,
-                  "frac_of_hbm_peak": (2 * stats.merge_targets + stats.fused) * blk_bytes * 2 / (stage["merge"] * 1e-3) / 1e9 / 8000.0},
+                  "frac_of_hbm_peak": (2 * stats.merge_targets + stats.fused) * blk_bytes * 2 / (stage["merge"] * 1e-3) / 1e9 / 8000.0,
+                  "frac_of_read2_write1_probe": (2 * stats.merge_targets + stats.fused) * blk_bytes * 2 / (stage["merge"] * 1e-3) / 1e9
+                                                / probes["read2_write1_GBps"]},
         "variants": variants,
         "norms": {"ms": stage["norms"], "GBps": logi_bytes / (stage["norms"] * 1e-3) / 1e9},
         "roofline": {"kernel": "similarity_ring_kernel (256 x 256 tile instance on the upper heights, 128 x 128 on the lowest)",

@@ -404,6 +404,12 @@ int kvfuse_probe_mfma_bf16(kvfuse_ctx *ctx, int32_t random_operands, void *scrat
  * not overlapping; gbps: host.  Waits for the stream. */
 int kvfuse_probe_copy(kvfuse_ctx *ctx, const void *src, void *dst, size_t bytes, int32_t repeats, double *gbps);
 
+/* Rate of the merge step's access pattern without its arithmetic: one wavefront per item reads two blocks of
+ * block_bytes (a target and a member 128 blocks further on) and writes the first one back; bytes read + written per
+ * second.  This is the ceiling the merge step (two reads per write, Algorithm 1's fusion line) can be held against on a
+ * given machine.  buf: device, bytes >= 256 * block_bytes, overwritten; gbps: host.  Waits for the stream. */
+int kvfuse_probe_read2_write1(kvfuse_ctx *ctx, void *buf, size_t bytes, int32_t block_bytes, int32_t repeats, double *gbps);
+
 #ifdef __cplusplus
 }
 #endif

@@ -127,6 +127,7 @@ lib.kvfuse_drop_rescale.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table)]
 RULE_ARGMAX, RULE_FIRST_ROW = 0, 1
 lib.kvfuse_probe_mfma_bf16.argtypes = [_vp, _i32, _vp, C.c_size_t, C.POINTER(C.c_double)]
 lib.kvfuse_probe_copy.argtypes = [_vp, _vp, _vp, C.c_size_t, _i32, C.POINTER(C.c_double)]
+lib.kvfuse_probe_read2_write1.argtypes = [_vp, _vp, C.c_size_t, _i32, _i32, C.POINTER(C.c_double)]
 PROBE_SCRATCH_BYTES = 65792
 
 
@@ -499,6 +500,15 @@ def probe_copy(ctx, src, dst, repeats=3):
     assert src.is_contiguous() and dst.is_contiguous() and src.numel() * src.element_size() == dst.numel() * dst.element_size()
     out = C.c_double(0.0)
     ctx.check(lib.kvfuse_probe_copy(ctx.h, _ptr(src), _ptr(dst), src.numel() * src.element_size(), repeats, C.byref(out)))
+    return out.value
+
+
+def probe_read2_write1(ctx, buf, block_bytes, repeats=3):
+    """GB/s (read + written) of the merge step's access pattern on ``buf`` (overwritten)."""
+    assert buf.is_contiguous()
+    out = C.c_double(0.0)
+    ctx.check(lib.kvfuse_probe_read2_write1(ctx.h, _ptr(buf), buf.numel() * buf.element_size(), int(block_bytes), repeats,
+                                            C.byref(out)))
     return out.value
 
 

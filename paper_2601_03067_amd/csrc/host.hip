@@ -826,4 +826,40 @@ int kvfuse_probe_copy(kvfuse_ctx *ctx, const void *src, void *dst, size_t bytes,
     return KVFUSE_OK;
 }
 
+int kvfuse_probe_read2_write1(kvfuse_ctx *ctx, void *buf, size_t bytes, int32_t block_bytes, int32_t repeats, double *gbps)
+{
+    if (!ctx)
+        return KVFUSE_EINVAL;
+    Ctx *c = &ctx->c;
+    if (!buf || !gbps || block_bytes < 16 || block_bytes % 16 != 0 || repeats <= 0)
+        return fail(c, KVFUSE_EINVAL, "probe: null pointer, block size not a positive multiple of 16 bytes, or no repeats");
+    // stripes of 256 blocks: the first 32 are targets, their members lie 128 blocks further on (the distance between
+    // the same block of two neighbouring requests in the bench workload)
+    const int gap = 128, per_stripe = 32;
+    const size_t stripes = bytes / ((size_t)2 * gap * block_bytes);
+    if (stripes == 0 || stripes * per_stripe > (size_t)INT32_MAX)
+        return fail(c, KVFUSE_EINVAL, "probe: buffer smaller than one stripe of 256 blocks, or too large");
+    const int n_items = (int)(stripes * per_stripe);
+    hipEvent_t e0, e1;
+    KVF_HIP(c, hipEventCreate(&e0));
+    KVF_HIP(c, hipEventCreate(&e1));
+    launch_probe_rmw(c->stream, buf, n_items, block_bytes, gap, per_stripe);          // warm-up
+    hipError_t err = hipEventRecord(e0, c->stream);
+    for (int i = 0; i < repeats; ++i)
+        launch_probe_rmw(c->stream, buf, n_items, block_bytes, gap, per_stripe);
+    if (err == hipSuccess)
+        err = hipEventRecord(e1, c->stream);
+    if (err == hipSuccess)
+        err = hipEventSynchronize(e1);
+    float ms = 0.0f;
+    if (err == hipSuccess)
+        err = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    KVF_HIP(c, err);
+    KVF_HIP(c, hipGetLastError());
+    *gbps = ms > 0.0f ? 3.0 * (double)block_bytes * n_items * repeats / (ms * 1e-3) / 1e9 : 0.0;
+    return KVFUSE_OK;
+}
+
 }  // extern "C"

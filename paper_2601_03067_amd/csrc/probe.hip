@@ -84,6 +84,39 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const uint4 *__restrict
     }
 }
 
+// The merge step's access pattern without its arithmetic: one wavefront per item reads two blocks of block_bytes
+// (a target and, `gap` blocks further on, a member) and writes the first one back.  Items walk the buffer in
+// stripes of 2 * gap blocks, the first `per_stripe` blocks of each stripe being targets.
+__global__ __launch_bounds__(256) void probe_rmw_kernel(uint4 *__restrict__ buf, int n_items, int chunks, int gap, int per_stripe)
+{
+    const int lane = threadIdx.x & 63;
+    const int n_waves = gridDim.x * 4;
+    for (int it = blockIdx.x * 4 + (threadIdx.x >> 6); it < n_items; it += n_waves) {
+        const size_t a = ((size_t)(it / per_stripe) * 2 * gap + it % per_stripe) * chunks, b = a + (size_t)gap * chunks;
+        for (int c0 = 0; c0 < chunks; c0 += 256) {
+            uint4 xa[4], xb[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int c = min(c0 + lane + 64 * q, chunks - 1);
+                xa[q] = buf[a + c];
+                xb[q] = buf[b + c];
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int c = c0 + lane + 64 * q;
+                if (c < chunks)
+                    buf[a + c] = make_uint4(xa[q].x ^ xb[q].x, xa[q].y ^ xb[q].y, xa[q].z ^ xb[q].z, xa[q].w ^ xb[q].w);
+            }
+        }
+    }
+}
+
+void launch_probe_rmw(hipStream_t s, void *buf, int n_items, int block_bytes, int gap, int per_stripe)
+{
+    if (n_items > 0)
+        probe_rmw_kernel<<<4096, 256, 0, s>>>(reinterpret_cast<uint4 *>(buf), n_items, block_bytes / 16, gap, per_stripe);
+}
+
 void launch_probe_fill(hipStream_t s, void *operands, int random_operands)
 {
     probe_fill_kernel<<<16, 256, 0, s>>>(reinterpret_cast<uint4 *>(operands), random_operands);

@@ -840,5 +840,21 @@ def test_machine_probes_run_and_copy_is_exact(kb):
     const = kb.probe_mfma_bf16(ctx, False, DEV)
     _say("  mfma bf16 TFLOP/s: random operands", round(rnd), "constant operands", round(const), "copy GB/s (small)", round(gbps))
     assert 50 < rnd < 2600 and 50 < const < 2600      # below the nominal dense peak of 2500 plus timing slack
+    # the merge access pattern: item i of a 256-block stripe xors block i + 128 into block i (i < 32) and nothing else
+    # moves; the probe runs its kernel an even number of times here (warm-up + 1), which must restore the buffer
+    blk = 4096
+    buf = torch.randint(0, 2 ** 31 - 1, (3 * 256 + 7, blk // 4), dtype=torch.int32, device=DEV)   # three stripes and a bit
+    orig = buf.clone()
+    rate = kb.probe_read2_write1(ctx, buf, blk, repeats=1)
+    torch.cuda.synchronize()
+    assert rate > 0 and torch.equal(buf, orig)
+    kb.probe_read2_write1(ctx, buf, blk, repeats=2)               # three applications = one
+    torch.cuda.synchronize()
+    want = orig.clone()
+    for s0 in range(0, 3 * 256, 256):
+        want[s0:s0 + 32] ^= want[s0 + 128:s0 + 160]
+    assert torch.equal(buf, want)
+    with pytest.raises(kb.KvfuseError):
+        kb.probe_read2_write1(ctx, buf[:100], blk)                # smaller than one stripe
     with pytest.raises(kb.KvfuseError):
         kb.ctx_check = ctx.check(kb.lib.kvfuse_probe_copy(ctx.h, None, None, 0, 1, None))
