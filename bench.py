@@ -284,6 +284,8 @@ def main():
     blk_bytes_probe = rec.r * (2 if rec.dtype == torch.bfloat16 else 4)
     probes = {"mfma_bf16_random_operands_TFLOPs": kb.probe_mfma_bf16(ctx, True, dev),
               "mfma_bf16_constant_operands_TFLOPs": kb.probe_mfma_bf16(ctx, False, dev),
+              "tile_loop_bf16_TFLOPs": kb.probe_tile_loop_bf16(ctx, K0, True) if rec.dtype == torch.bfloat16 else None,
+              "tile_loop_bf16_no_loads_TFLOPs": kb.probe_tile_loop_bf16(ctx, K0, False) if rec.dtype == torch.bfloat16 else None,
               "copy_kernel_GBps": kb.probe_copy(ctx, K0, cache.K, repeats=3),
               "read2_write1_GBps": kb.probe_read2_write1(ctx, cache.K, blk_bytes_probe, repeats=3)}
     k = max(args.steps, 1)
@@ -350,6 +352,8 @@ def main():
                      "bound": "mfma", "achieved": sim_tflops, "peak": peak,
                      "unit": "TFLOP/s", "frac": sim_tflops / peak, "traffic": traffic,
                      "frac_of_measured_mfma_rate": (sim_tflops / probes["mfma_bf16_random_operands_TFLOPs"]
+                                                    if rec.dtype == torch.bfloat16 else None),
+                     "frac_of_stripped_tile_loop": (sim_tflops / probes["tile_loop_bf16_TFLOPs"]
                                                     if rec.dtype == torch.bfloat16 else None),
                      "launches_per_step": stats.n_heights,
                      "flops_per_step": stats.sim_flops, "ms_per_step": stage["similarity"]},

@@ -404,6 +404,16 @@ int kvfuse_probe_mfma_bf16(kvfuse_ctx *ctx, int32_t random_operands, void *scrat
  * not overlapping; gbps: host.  Waits for the stream. */
 int kvfuse_probe_copy(kvfuse_ctx *ctx, const void *src, void *dst, size_t bytes, int32_t repeats, double *gbps);
 
+/* Rate of the similarity kernel's inner loop without its gather, ragged tiles and epilogue: per compute unit 8
+ * wavefronts of 2 x 4 MFMA tiles per 256 x 256 x 32-element slice, fragments read from LDS one half slice ahead, a
+ * barrier per slice and, if with_loads, 32 KB of global -> LDS loads per slice from an L2-resident 4 MiB window of
+ * src.  The LDS operands are taken from src, so pass data like the cache's (the rate depends on how the operand bits
+ * toggle).  This is the ceiling of the kernel's tile organisation on a given machine, between the register-fed MFMA
+ * probe and the kernel itself.  src: device, >= 4 MiB, read only; sink: device, one float; tflops: host.  Waits for
+ * the stream (about 30 ms). */
+int kvfuse_probe_tile_loop_bf16(kvfuse_ctx *ctx, const void *src, size_t src_bytes, int32_t with_loads, float *sink,
+                                double *tflops);
+
 /* Rate of the merge step's access pattern without its arithmetic: one wavefront per item reads two blocks of
  * block_bytes (a target and a member 128 blocks further on) and writes the first one back; bytes read + written per
  * second.  This is the ceiling the merge step (two reads per write, Algorithm 1's fusion line) can be held against on a

@@ -127,6 +127,7 @@ lib.kvfuse_drop_rescale.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table)]
 RULE_ARGMAX, RULE_FIRST_ROW = 0, 1
 lib.kvfuse_probe_mfma_bf16.argtypes = [_vp, _i32, _vp, C.c_size_t, C.POINTER(C.c_double)]
 lib.kvfuse_probe_copy.argtypes = [_vp, _vp, _vp, C.c_size_t, _i32, C.POINTER(C.c_double)]
+lib.kvfuse_probe_tile_loop_bf16.argtypes = [_vp, _vp, C.c_size_t, _i32, _vp, C.POINTER(C.c_double)]
 lib.kvfuse_probe_read2_write1.argtypes = [_vp, _vp, C.c_size_t, _i32, _i32, C.POINTER(C.c_double)]
 PROBE_SCRATCH_BYTES = 65792
 
@@ -500,6 +501,16 @@ def probe_copy(ctx, src, dst, repeats=3):
     assert src.is_contiguous() and dst.is_contiguous() and src.numel() * src.element_size() == dst.numel() * dst.element_size()
     out = C.c_double(0.0)
     ctx.check(lib.kvfuse_probe_copy(ctx.h, _ptr(src), _ptr(dst), src.numel() * src.element_size(), repeats, C.byref(out)))
+    return out.value
+
+
+def probe_tile_loop_bf16(ctx, src, with_loads=True):
+    """TFLOP/s of the similarity kernel's stripped inner loop, LDS operands and loads taken from ``src`` (>= 4 MiB)."""
+    assert src.is_contiguous()
+    sink = torch.zeros(1, device=src.device, dtype=torch.float32)
+    out = C.c_double(0.0)
+    ctx.check(lib.kvfuse_probe_tile_loop_bf16(ctx.h, _ptr(src), src.numel() * src.element_size(), 1 if with_loads else 0,
+                                              _ptr(sink), C.byref(out)))
     return out.value
 
 

@@ -137,6 +137,7 @@ constexpr size_t kProbeScratchBytes = 65536 + 256;     // 4096 operand chunks of
 void launch_probe_fill(hipStream_t s, void *operands, int random_operands);
 void launch_probe_mfma(hipStream_t s, const void *operands, int workgroups, int iters, float *sink);
 void launch_probe_copy(hipStream_t s, const void *src, void *dst, size_t bytes);
+void launch_probe_tile_loop(hipStream_t s, const void *src, int with_loads, int workgroups, int iters, float *sink);
 void launch_probe_rmw(hipStream_t s, void *buf, int n_items, int block_bytes, int gap, int per_stripe);
 
 // ---------------------------------------------------------------------------------------------------

@@ -826,6 +826,39 @@ int kvfuse_probe_copy(kvfuse_ctx *ctx, const void *src, void *dst, size_t bytes,
     return KVFUSE_OK;
 }
 
+int kvfuse_probe_tile_loop_bf16(kvfuse_ctx *ctx, const void *src, size_t src_bytes, int32_t with_loads, float *sink,
+                                double *tflops)
+{
+    if (!ctx)
+        return KVFUSE_EINVAL;
+    Ctx *c = &ctx->c;
+    if (!src || !sink || !tflops || src_bytes < ((size_t)4 << 20))
+        return fail(c, KVFUSE_EINVAL, "probe: needs 4 MiB of bfloat16 data to read, a device word to write and an output");
+    hipDeviceProp_t prop;
+    KVF_HIP(c, hipGetDeviceProperties(&prop, c->device));
+    const int wgs = prop.multiProcessorCount * 4;
+    const int iters = 4000;
+    hipEvent_t e0, e1;
+    KVF_HIP(c, hipEventCreate(&e0));
+    KVF_HIP(c, hipEventCreate(&e1));
+    launch_probe_tile_loop(c->stream, src, with_loads, wgs, iters / 10, sink);      // warm-up
+    hipError_t err = hipEventRecord(e0, c->stream);
+    launch_probe_tile_loop(c->stream, src, with_loads, wgs, iters, sink);
+    if (err == hipSuccess)
+        err = hipEventRecord(e1, c->stream);
+    if (err == hipSuccess)
+        err = hipEventSynchronize(e1);
+    float ms = 0.0f;
+    if (err == hipSuccess)
+        err = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    KVF_HIP(c, err);
+    KVF_HIP(c, hipGetLastError());
+    *tflops = ms > 0.0f ? (double)wgs * iters * 2.0 * 256.0 * 256.0 * 32.0 / (ms * 1e-3) / 1e12 : 0.0;
+    return KVFUSE_OK;
+}
+
 int kvfuse_probe_read2_write1(kvfuse_ctx *ctx, void *buf, size_t bytes, int32_t block_bytes, int32_t repeats, double *gbps)
 {
     if (!ctx)

@@ -84,6 +84,77 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const uint4 *__restrict
     }
 }
 
+// The similarity kernel's inner loop without its gather, its ragged tiles and its epilogue: 8 wavefronts, each
+// 2 x 4 MFMA tiles per 256 x 256 x 32-element slice, fragments read from LDS one half slice ahead, one barrier per
+// slice and, if LOADS, 32 KB of global -> LDS loads per slice from a 4 MB window (L2 resident).  LDS holds real
+// (caller-supplied) bfloat16 data, because the rate depends on how the operand bits toggle.
+template <bool LOADS>
+__global__ __launch_bounds__(512, 1) void probe_tile_loop_kernel(const char *__restrict__ src, int iters, float *__restrict__ sink)
+{
+    __shared__ uint4 lds[2 * 2048 + 2048];     // two 32 KB operand stages + a 32 KB landing zone for the loads
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < 4096; i += 512)
+        lds[i] = reinterpret_cast<const uint4 *>(src)[((size_t)blockIdx.x * 4096 + i) & 262143];
+    __syncthreads();
+    floatx16 acc[2][4];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                acc[a][b][e] = 0.0f;
+    uint4 fa[2][2], fb[2][4];
+    auto rd = [&](int set, int stage) __attribute__((always_inline)) {
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+            fa[set][a] = lds[(stage & 1) * 2048 + ((wave * 7 + a * 64 + lane) & 2047)];
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+            fb[set][b] = lds[(stage & 1) * 2048 + ((wave * 13 + b * 64 + 1024 + lane) & 2047)];
+    };
+    rd(0, 0);
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            rd(s ^ 1, it + s + 1);                                  // fragments of the next half slice
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[s][a]),
+                                                                       __builtin_bit_cast(bf16x8, fb[s][b]), acc[a][b], 0, 0, 0);
+                    if (LOADS && b == 1)                            // four 1 KB loads per wavefront and slice
+                        __builtin_amdgcn_global_load_lds(
+                            (const __attribute__((address_space(1))) void *)(src + ((size_t)((((blockIdx.x * 8 + wave) * 8 + ((it * 4 + s * 2 + a) & 7)) & 4095) * 64 + lane)) * 16),
+                            (__attribute__((address_space(3))) void *)(lds + 4096 + (s * 2 + a) * 512 + wave * 64), 16, 0, 0);
+                }
+        }
+        if (LOADS)
+            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        asm volatile("s_barrier" ::: "memory");
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    float s = 0.0f;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                s += acc[a][b][e];
+    if (s == 12345.678f)
+        sink[0] = s;
+}
+
+void launch_probe_tile_loop(hipStream_t s, const void *src, int with_loads, int workgroups, int iters, float *sink)
+{
+    if (with_loads)
+        probe_tile_loop_kernel<true><<<workgroups, 512, 0, s>>>(static_cast<const char *>(src), iters, sink);
+    else
+        probe_tile_loop_kernel<false><<<workgroups, 512, 0, s>>>(static_cast<const char *>(src), iters, sink);
+}
+
 // The merge step's access pattern without its arithmetic: one wavefront per item reads two blocks of block_bytes
 // (a target and, `gap` blocks further on, a member) and writes the first one back.  Items walk the buffer in
 // stripes of 2 * gap blocks, the first `per_stripe` blocks of each stripe being targets.

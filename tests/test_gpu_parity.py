@@ -840,6 +840,13 @@ def test_machine_probes_run_and_copy_is_exact(kb):
     const = kb.probe_mfma_bf16(ctx, False, DEV)
     _say("  mfma bf16 TFLOP/s: random operands", round(rnd), "constant operands", round(const), "copy GB/s (small)", round(gbps))
     assert 50 < rnd < 2600 and 50 < const < 2600      # below the nominal dense peak of 2500 plus timing slack
+    data = torch.randn(4 << 20, device=DEV).to(torch.bfloat16)          # 8 MiB of cache-like values
+    loop = kb.probe_tile_loop_bf16(ctx, data, True)
+    loop0 = kb.probe_tile_loop_bf16(ctx, data, False)
+    _say("  stripped tile loop TFLOP/s: with loads", round(loop), "without", round(loop0))
+    assert 50 < loop < 2600 and 50 < loop0 < 2600
+    with pytest.raises(kb.KvfuseError):
+        kb.probe_tile_loop_bf16(ctx, data[:1000], True)                 # less than 4 MiB
     # the merge access pattern: item i of a 256-block stripe xors block i + 128 into block i (i < 32) and nothing else
     # moves; the probe runs its kernel an even number of times here (warm-up + 1), which must restore the buffer
     blk = 4096
