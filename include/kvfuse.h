@@ -124,7 +124,8 @@ typedef struct kvfuse_height_view {
     const int32_t *set_ids;    /* device [G][n]: surviving physical ids, node sets at their offsets */
     const int32_t *set_cnt;    /* device [G][n_slots] */
     const int32_t *assign;     /* device [G][r_stride]: target row i or -1 */
-    const unsigned long long *best_packed; /* device [G][r_stride]: column maximum of the screen, packed as
+    const unsigned long long *best_packed; /* device [G][r_stride]: a diagnostic, filled only by a kvfuse_similarity
+                                  call that asked for the dense matrix (0 otherwise): column maximum of the screen, packed as
                                   (ordered cosine bits << 32) | (0xFFFFFFFF - row); ordered bits = ~b if the float's
                                   sign bit is set, else b | 0x80000000; 0 = no left row */
     const int32_t *cand_cnt;   /* device [G][r_stride] */
@@ -169,8 +170,8 @@ int kvfuse_leaf_sets(kvfuse_ctx *ctx, kvfuse_plan *plan);
 
 /* For every node of `height` and every group: cosine of each left block with each right block on the
  * MFMA units (bf16 x bf16 -> fp32, or f32), normalised with inv_norm_k.  Per right block it records the
- * column maximum and its row, and the list of rows whose screened cosine exceeds thr - 2*band (at most
- * cand_cap kept; the count is exact).  dense_s, if not NULL, is device [G][total_s] float and receives
+ * list of rows whose screened cosine exceeds thr - 2*band (at most cand_cap kept; the count is exact) and, when
+ * the dense matrix is asked for, the column maximum and its row.  dense_s, if not NULL, is device [G][total_s] float and receives
  * every screened cosine: node k's matrix at s_base[k], row-major [l_cap][r_cap], entries beyond the
  * current set sizes untouched.  band must be >= r * 2^-22 (the bound assumed on the screen's error). */
 int kvfuse_similarity(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t height, double thr, double band, float *dense_s);

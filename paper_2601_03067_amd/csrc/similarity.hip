@@ -124,8 +124,12 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
     __shared__ float lds_invl[RT * BM];      // inverse norms of all left rows of the item; NaN past the end
     __shared__ float lds_invr[BN];
     __shared__ float lds_tcol[BN];
-    __shared__ uint32_t lds_bkey[TN][NT];
-    __shared__ int lds_brt[TN][NT];
+    // The column maximum (best_packed) is a diagnostic: the assignment step works from the candidate lists alone.  It
+    // is kept only in the instantiation that also writes the dense matrix; in the production one it cost four of
+    // the six vector instructions per accumulator in the epilogue, during which the MFMA units of the CU idle.
+    constexpr bool BEST = DENSE;
+    __shared__ uint32_t lds_bkey[BEST ? TN : 1][BEST ? NT : 1];
+    __shared__ int lds_brt[BEST ? TN : 1][BEST ? NT : 1];
     constexpr int MAXC = 512;
     __shared__ int lds_ncand;
     __shared__ int lds_cand_row[MAXC];
@@ -231,10 +235,12 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
         const int row = row0 + x;
         lds_invl[x] = row < row_end ? inv_g[l_ids[row]] : __uint_as_float(0x7FC00000u);
     }
+    if constexpr (BEST) {
 #pragma unroll
-    for (int nt = 0; nt < TN; ++nt) {
-        lds_bkey[nt][tid] = 0u;
-        lds_brt[nt][tid] = 0;
+        for (int nt = 0; nt < TN; ++nt) {
+            lds_bkey[nt][tid] = 0u;
+            lds_brt[nt][tid] = 0;
+        }
     }
     if (tid == 0)
         lds_ncand = 0;
@@ -366,9 +372,11 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
                         for (int q = 0; q < 4; ++q) {
                             t[q] = acc[mt][nt][eg * 4 + q] * il[q];
                             hit |= t[q] > tcol[nt];
-                            const uint32_t key = (__float_as_uint(fmaxf(t[q], 0.0f)) & ~CODE_MASK) |
-                                                 (CODE_MASK - (uint32_t)(mt * 16 + eg * 4 + q));
-                            kmax[nt] = max(kmax[nt], key);
+                            if constexpr (BEST) {
+                                const uint32_t key = (__float_as_uint(fmaxf(t[q], 0.0f)) & ~CODE_MASK) |
+                                                     (CODE_MASK - (uint32_t)(mt * 16 + eg * 4 + q));
+                                kmax[nt] = max(kmax[nt], key);
+                            }
                         }
                         if (hit) {      // rare: an entry clears the candidate floor
                             const int cl = nt * NT_STRIDE + wn * 32 + (lane & 31);
@@ -407,9 +415,11 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
             }
 #pragma unroll
             for (int nt = 0; nt < TN; ++nt) {
-                if (kmax[nt] > lds_bkey[nt][tid]) {
-                    lds_bkey[nt][tid] = kmax[nt];
-                    lds_brt[nt][tid] = rt;
+                if constexpr (BEST) {
+                    if (kmax[nt] > lds_bkey[nt][tid]) {
+                        lds_bkey[nt][tid] = kmax[nt];
+                        lds_brt[nt][tid] = rt;
+                    }
                 }
 #pragma unroll
                 for (int mt = 0; mt < TM; ++mt)
@@ -429,17 +439,19 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
             emit_candidate(cand_cnt, cand_idx, cand_val, cbase + col0 + lds_cand_col[k], A.cand_cap, lds_cand_row[k],
                            lds_cand_val[k]);
     }
+    if constexpr (BEST) {
 #pragma unroll
-    for (int nt = 0; nt < TN; ++nt) {
-        const int col = col0 + nt * NT_STRIDE + wn * 32 + (lane & 31);
-        const uint32_t bkey = lds_bkey[nt][tid];
-        const int code = (int)(CODE_MASK - (bkey & CODE_MASK));
-        const int row = min(row_end - 1, row0 + lds_brt[nt][tid] * BM + (code >> 4) * MT_STRIDE + wm * 32 + ((code & 15) >> 2) * 8 + half * 4 + (code & 3));
-        unsigned long long pk = bkey ? pack_best(__uint_as_float(bkey & ~CODE_MASK) * lds_invr[nt * NT_STRIDE + wn * 32 + (lane & 31)], row) : 0ull;
-        const unsigned long long other = __shfl_xor(pk, 32, 64);
-        pk = other > pk ? other : pk;
-        if (half == 0 && col < mr && pk)
-            atomicMax(&best_packed[cbase + col], pk);
+        for (int nt = 0; nt < TN; ++nt) {
+            const int col = col0 + nt * NT_STRIDE + wn * 32 + (lane & 31);
+            const uint32_t bkey = lds_bkey[nt][tid];
+            const int code = (int)(CODE_MASK - (bkey & CODE_MASK));
+            const int row = min(row_end - 1, row0 + lds_brt[nt][tid] * BM + (code >> 4) * MT_STRIDE + wm * 32 + ((code & 15) >> 2) * 8 + half * 4 + (code & 3));
+            unsigned long long pk = bkey ? pack_best(__uint_as_float(bkey & ~CODE_MASK) * lds_invr[nt * NT_STRIDE + wn * 32 + (lane & 31)], row) : 0ull;
+            const unsigned long long other = __shfl_xor(pk, 32, 64);
+            pk = other > pk ? other : pk;
+            if (half == 0 && col < mr && pk)
+                atomicMax(&best_packed[cbase + col], pk);
+        }
     }
 #undef KVF_DMA
 #undef KVF_DS_READ
