@@ -312,6 +312,36 @@ def test_tree_shortest_first_order(kb, oracle, which):
     assert stats.fused > 20
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3, 4, 5, 6, 10, 14, 20, 21])
+def test_tree_seeded_sweep(kb, oracle, seed):
+    """Seeded small workloads of all four structures with the variants mixed at random: assignment rule, request order,
+    request groups, candidate slots (1 slot = every multi-candidate column is rescanned), dtype."""
+    rng = np.random.default_rng(seed)
+    kind = seed % 4
+    dtype = torch.bfloat16 if seed % 3 else torch.float32
+    if kind == 0:
+        rec = wl.llama8b_bff(n_req=int(rng.integers(2, 9)), tokens=8 * int(rng.integers(20, 160)), layers=1, kv_heads=2,
+                             prefix_tokens=8 * int(rng.integers(0, 12)), near_pool=int(rng.integers(4, 40)), t=8, d=32,
+                             dtype=dtype, seed=seed)
+    elif kind == 1:
+        rec = wl.mixed(n_req=int(rng.integers(3, 12)), min_tokens=20, max_tokens=int(rng.integers(200, 1200)),
+                       chunk_tokens=int(rng.choice([128, 256, 512])), layers=1, kv_heads=2, pool=int(rng.integers(8, 60)),
+                       t=8, d=32, dtype=dtype, seed=seed)
+    elif kind == 2:
+        rec = wl.zipf_bff(n_req=int(rng.integers(3, 10)), tokens=16 * int(rng.integers(10, 50)), layers=1, kv_heads=2,
+                          pool=int(rng.integers(10, 80)), t=16, d=32, sigma=float(rng.choice([0.03, 0.05, 0.2])),
+                          thr=float(rng.choice([0.85, 0.9, 0.97, 0.9975])), dtype=dtype, seed=seed)
+    else:
+        rec = wl.cff_long(tokens=8 * int(rng.integers(200, 700)), chunk_tokens=8 * int(rng.integers(30, 100)), layers=1,
+                          kv_heads=2, t=8, d=32, dtype=dtype, seed=seed)
+    rule = "first_row" if seed % 2 else "argmax"
+    shortest_first = bool(seed % 5 == 0 or seed % 7 == 0)
+    group_size = int(rng.choice([0, 0, 2, 3]))
+    cand_cap = int(rng.choice([1, 3, 16, 64]))
+    _run_tree_case(kb, oracle, rec, f"sweep_{seed}", cand_cap=cand_cap, rule=rule, shortest_first=shortest_first,
+                   group_size=group_size)
+
+
 def test_tree_variants_combined(kb, oracle):
     """Row-order rule, shortest-first tree and "every N requests" together, on ragged chunked requests in f32 and bf16."""
     for dtype, gs in ((torch.float32, 4), (torch.bfloat16, 3)):
