@@ -229,6 +229,20 @@ int kvfuse_paged_decode_attn(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvf
                              const int32_t *ctx_len, int32_t B, int32_t Hq, int32_t max_blocks, float sm_scale,
                              void *workspace, size_t workspace_bytes, float *out);
 
+/* The same decode step for callers that cannot allocate device memory or provide a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation).  The split-KV partial states live in a static
+ * device array of KVFUSE_DECODE_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held until the process
+ * ends) instead of a workspace; the call allocates nothing and is otherwise kvfuse_paged_decode_attn, with the same
+ * arguments, limits and results.  A call whose partial states would not fit (kvfuse_decode_workspace_bytes greater
+ * than the constant) fails with KVFUSE_ENOMEM and a message that names both sizes.  All calls on one GPU share the
+ * array: two such calls that overlap in time on one GPU (different streams or threads) race; calls that follow each
+ * other on one stream do not, and nothing needs clearing between them. */
+#define KVFUSE_DECODE_STATIC_SCRATCH_BYTES (8u << 20)
+int kvfuse_paged_decode_attn_static(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table, int32_t kv_heads,
+                                    int32_t layer_begin, int32_t n_layers, const void *q, const int32_t *req_start,
+                                    const int32_t *ctx_len, int32_t B, int32_t Hq, int32_t max_blocks, float sm_scale,
+                                    float *out);
+
 /* ---- shared-block decode attention -------------------------------------------------------------------- */
 
 /* The same attention as kvfuse_paged_decode_attn, organised around the blocks that fusion made common

@@ -25,7 +25,7 @@ EXPORTS = [
     "kvfuse_create", "kvfuse_destroy", "kvfuse_last_error", "kvfuse_workspace_bytes", "kvfuse_plan_create",
     "kvfuse_plan_destroy", "kvfuse_plan_heights", "kvfuse_plan_view", "kvfuse_block_norms", "kvfuse_leaf_sets",
     "kvfuse_similarity", "kvfuse_assign", "kvfuse_merge", "kvfuse_rewrite_block_table", "kvfuse_fuse_tree",
-    "kvfuse_decode_workspace_bytes", "kvfuse_paged_decode_attn",
+    "kvfuse_decode_workspace_bytes", "kvfuse_paged_decode_attn", "kvfuse_paged_decode_attn_static",
 ]
 
 _vp, _i32, _i64, _f32, _f64 = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_double
@@ -84,6 +84,9 @@ lib.kvfuse_fuse_tree.argtypes = [_vp, _vp, _f64, _f64, _vp, _vp, _vp, C.POINTER(
 lib.kvfuse_decode_workspace_bytes.argtypes = [_i32, _i32, _i32, _i32, _i32, _i32, C.POINTER(C.c_size_t)]
 lib.kvfuse_paged_decode_attn.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _i32, _i32, _i32, _vp, _vp, _vp, _i32,
                                          _i32, _i32, _f32, _vp, C.c_size_t, _vp]
+lib.kvfuse_paged_decode_attn_static.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _i32, _i32, _i32, _vp, _vp, _vp, _i32,
+                                                _i32, _i32, _f32, _vp]
+DECODE_STATIC_SCRATCH_BYTES = 8 << 20
 
 
 
@@ -321,6 +324,19 @@ def paged_decode_attn(ctx, cache, kv_heads, q, req_start, ctx_len, max_blocks, l
     ctx.check(lib.kvfuse_paged_decode_attn(ctx.h, C.byref(cache.pool), C.byref(cache.table), kv_heads, layer_begin, n_layers,
                                            _ptr(q), _ptr(req_start), _ptr(ctx_len), B, Hq, max_blocks, sm_scale,
                                            _ptr(workspace), workspace.numel(), _ptr(out)))
+    return out
+
+
+def paged_decode_attn_static(ctx, cache, kv_heads, q, req_start, ctx_len, max_blocks, out, layer_begin=0, sm_scale=None):
+    """kvfuse_paged_decode_attn_static: the caller passes inputs and the output; nothing is allocated on the way."""
+    n_layers, B, Hq, d = q.shape
+    assert q.is_contiguous() and q.dtype == cache.K.dtype and d == cache.d
+    assert out.is_contiguous() and out.dtype == torch.float32 and tuple(out.shape) == (n_layers, B, Hq, d)
+    if sm_scale is None:
+        sm_scale = 1.0 / float(d) ** 0.5
+    ctx.check(lib.kvfuse_paged_decode_attn_static(ctx.h, C.byref(cache.pool), C.byref(cache.table), kv_heads, layer_begin,
+                                                  n_layers, _ptr(q), _ptr(req_start), _ptr(ctx_len), B, Hq, max_blocks,
+                                                  sm_scale, _ptr(out)))
     return out
 
 

@@ -11,6 +11,8 @@
 //   P.V     on the vector ALU with lanes owning 16-byte column slices of V rows (V's layout would need a transpose
 //           to feed the MFMA k-dimension); probabilities pass through a per-wave LDS tile.
 // Partial states of the 4 wavefronts are merged in LDS; with several splits a second kernel merges the splits.
+#include <mutex>
+
 #include "common.h"
 
 namespace kvfuse {
@@ -361,3 +363,74 @@ int launch_decode(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, int
 }
 
 }  // namespace kvfuse
+
+// ---- the same decode step for callers that cannot allocate -------------------------------------------------
+//
+// The split-KV partial states (the only device memory the decode kernels use besides their inputs and outputs) live in
+// a static device array instead of a caller workspace.  Each GPU that loads the library holds its own copy of the
+// array, at its own address, until the process ends; `scratch` below is only the host-side handle of the symbol, so
+// host code never passes it to a kernel: the device address is looked up once per device and used from then on.
+static __device__ __align__(256) unsigned char scratch[KVFUSE_DECODE_STATIC_SCRATCH_BYTES];
+
+namespace kvfuse {
+namespace {
+
+constexpr size_t kStaticScratchBytes = KVFUSE_DECODE_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[kMaxDevices] = {};
+
+// Device address of this device's copy of the array; looked up with that device current, kept afterwards.
+hipError_t static_scratch(int device, void **out)
+{
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[device]) {
+        int cur = -1;
+        hipError_t e = hipGetDevice(&cur);
+        if (e != hipSuccess)
+            return e;
+        if (cur != device && (e = hipSetDevice(device)) != hipSuccess)
+            return e;
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (cur != device)
+            (void)hipSetDevice(cur);
+        if (e != hipSuccess)
+            return e;
+        scratch_ptr[device] = p;
+    }
+    *out = scratch_ptr[device];
+    return hipSuccess;
+}
+
+}  // namespace
+
+}  // namespace kvfuse
+
+extern "C" int kvfuse_paged_decode_attn_static(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table,
+                                               int32_t kv_heads, int32_t layer_begin, int32_t n_layers, const void *q,
+                                               const int32_t *req_start, const int32_t *ctx_len, int32_t B, int32_t Hq,
+                                               int32_t max_blocks, float sm_scale, float *out)
+{
+    using namespace kvfuse;
+    if (!ctx)
+        return KVFUSE_EINVAL;
+    Ctx *c = &ctx->c;
+    if (B == 0 || n_layers == 0)
+        return KVFUSE_OK;
+    if (c->device < 0 || c->device >= kMaxDevices)
+        return fail(c, KVFUSE_EINVAL, "decode (static scratch): device index beyond 63");
+    if (!pool || B < 0 || n_layers < 0 || Hq <= 0 || kv_heads <= 0 || max_blocks < 0)
+        return fail(c, KVFUSE_EINVAL, "decode (static scratch): null pool or negative size");
+    const size_t need = decode_workspace_bytes(n_layers, B, Hq, kv_heads, pool->d, max_blocks);
+    if (need > kStaticScratchBytes)
+        return fail(c, KVFUSE_ENOMEM, "decode (static scratch): this call needs " + std::to_string(need) +
+                                          " bytes of split-KV state, the static array holds " +
+                                          std::to_string(kStaticScratchBytes) + "; use kvfuse_paged_decode_attn with a workspace");
+    void *ptr = nullptr;
+    KVF_HIP(c, static_scratch(c->device, &ptr));
+    // every partial state a call reads was written by that same call (empty splits write a neutral state), so
+    // nothing has to be cleared between calls
+    return kvfuse_paged_decode_attn(ctx, pool, table, kv_heads, layer_begin, n_layers, q, req_start, ctx_len, B, Hq, max_blocks,
+                                    sm_scale, ptr, kStaticScratchBytes, out);
+}
