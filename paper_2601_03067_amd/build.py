@@ -1,4 +1,5 @@
-"""Build libkvfuse.so (HIP, gfx950 only) in-tree with hipcc.  No JIT, no torch extension machinery."""
+"""Build libkvfuse.so (the product) and libkvfuse_probe.so (machine probes for benchmarks) in-tree with hipcc, for
+gfx950 only.  No JIT, no torch extension machinery."""
 from __future__ import annotations
 
 import os
@@ -9,7 +10,9 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvfuse.so")
-SOURCES = ["host.hip", "norms.hip", "similarity.hip", "assign.hip", "merge.hip", "rewrite.hip", "decode.hip", "decode_shared.hip", "prefill.hip", "threshold.hip", "variants.hip", "probe.hip"]
+PROBE_LIB = os.path.join(HERE, "libkvfuse_probe.so")
+SOURCES = ["host.hip", "norms.hip", "similarity.hip", "assign.hip", "merge.hip", "rewrite.hip", "decode.hip", "decode_shared.hip", "prefill.hip", "threshold.hip", "variants.hip"]
+PROBE_SOURCES = ["probe.hip"]
 # packed-fp32 instructions are switched off for every device object of this library
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"]
@@ -36,14 +39,15 @@ def build(verbose: bool = True, jobs: int = 8) -> str:
         return obj
 
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(one, SOURCES))
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
+        objs = list(ex.map(one, SOURCES + PROBE_SOURCES))
+    for lib, part in ((LIB, objs[:len(SOURCES)]), (PROBE_LIB, objs[len(SOURCES):])):
+        cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *part]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
     return LIB
 
 
 if __name__ == "__main__":
     build()
-    print("built", LIB)
+    print("built", LIB, PROBE_LIB)

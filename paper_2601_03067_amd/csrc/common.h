@@ -83,7 +83,7 @@ struct WorkDesc {
     int32_t *n_active;   // [max_heights]
     int32_t *refine;     // [G * r_stride] columns (g * r_stride + c) that need the fp64 re-check
     int32_t *n_refine;   // [max_heights]
-    int32_t *counters;   // [G][8]: 0 fused, 1 near-threshold, 2 refined, 3 candidate overflow, 4 invalid ids
+    int32_t *counters;   // [G][8]: 0 fused, 1 near-threshold, 2 refined, 3 candidate overflow, 4 invalid ids, 5 entries of shared blocks
     const uint8_t *group_enable;   // [G] or null: groups with 0 are skipped by the similarity step (nothing fuses)
     int32_t *leaf_src;   // [n] position in a set_ids row -> logical entry the leaf step fills it from, -1 = none
 };
@@ -131,14 +131,6 @@ int launch_decode(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, int
 void launch_pair_cosines(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, const int32_t *pairs, int n_pairs,
                          double *cos_out);
 void launch_cosine_moments(hipStream_t s, const double *cos_in, int G, int n_pairs, double *moments);
-
-// machine probes (probe.hip)
-constexpr size_t kProbeScratchBytes = 65536 + 256;     // 4096 operand chunks of 16 bytes + a sink word
-void launch_probe_fill(hipStream_t s, void *operands, int random_operands);
-void launch_probe_mfma(hipStream_t s, const void *operands, int workgroups, int iters, float *sink);
-void launch_probe_copy(hipStream_t s, const void *src, void *dst, size_t bytes);
-void launch_probe_tile_loop(hipStream_t s, const void *src, int with_loads, int workgroups, int iters, float *sink);
-void launch_probe_rmw(hipStream_t s, void *buf, int n_items, int block_bytes, int gap, int per_stripe);
 
 // ---------------------------------------------------------------------------------------------------
 // device side

@@ -1,8 +1,14 @@
-// Machine probes: what the MFMA units and the HBM sustain on this GPU, measured with the same instructions
-// the hot path uses.  Measurement aids only -- nothing on the hot path calls them.
-#include "common.h"
+// Machine probes (libkvfuse_probe.so): what the MFMA units and the HBM sustain on this GPU, measured with the same
+// instructions the hot path uses.  A library of its own for benchmarks; the product library neither contains nor
+// calls any of this.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
-namespace kvfuse {
+#include <string>
+
+#include "../../include/kvfuse_probe.h"
+
+namespace kvfuse_probe {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -206,4 +212,157 @@ void launch_probe_copy(hipStream_t s, const void *src, void *dst, size_t bytes)
                                                                                   reinterpret_cast<uint4 *>(dst), n16);
 }
 
-}  // namespace kvfuse
+
+static thread_local std::string last_error;
+
+static int fail(int code, const std::string &msg)
+{
+    last_error = msg;
+    return code;
+}
+
+#define PROBE_HIP(expr)                                                                                  \
+    do {                                                                                                 \
+        hipError_t e__ = (expr);                                                                         \
+        if (e__ != hipSuccess)                                                                           \
+            return fail(KVFUSE_PROBE_EHIP, std::string(#expr) + ": " + hipGetErrorString(e__));          \
+    } while (0)
+
+}  // namespace kvfuse_probe
+
+using namespace kvfuse_probe;
+
+extern "C" {
+
+const char *kvfuse_probe_last_error(void) { return last_error.c_str(); }
+
+int kvfuse_probe_mfma_bf16(void *hip_stream, int32_t random_operands, void *scratch, size_t scratch_bytes, double *tflops)
+{
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (!scratch || !tflops || scratch_bytes < (size_t)KVFUSE_PROBE_SCRATCH_BYTES)
+        return fail(KVFUSE_PROBE_EINVAL, "probe: needs a device scratch buffer of KVFUSE_PROBE_SCRATCH_BYTES and an output");
+    int device = 0;
+    PROBE_HIP(hipGetDevice(&device));
+    hipDeviceProp_t prop;
+    PROBE_HIP(hipGetDeviceProperties(&prop, device));
+    const int wgs = prop.multiProcessorCount * 4;      // four rounds of one 8-wavefront workgroup per compute unit
+    const int iters = 2000;
+    float *sink = reinterpret_cast<float *>(static_cast<char *>(scratch) + 65536);
+    hipEvent_t e0, e1;
+    PROBE_HIP(hipEventCreate(&e0));
+    PROBE_HIP(hipEventCreate(&e1));
+    launch_probe_fill(stream, scratch, random_operands);
+    launch_probe_mfma(stream, scratch, wgs, iters / 10, sink);     // warm-up
+    hipError_t err = hipEventRecord(e0, stream);
+    launch_probe_mfma(stream, scratch, wgs, iters, sink);
+    if (err == hipSuccess)
+        err = hipEventRecord(e1, stream);
+    if (err == hipSuccess)
+        err = hipEventSynchronize(e1);
+    float ms = 0.0f;
+    if (err == hipSuccess)
+        err = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    PROBE_HIP(err);
+    PROBE_HIP(hipGetLastError());
+    // per wavefront and iteration: 32 MFMAs of 2 * 32 * 32 * 16 flops
+    *tflops = ms > 0.0f ? (double)wgs * 8.0 * iters * 32.0 * 32768.0 / (ms * 1e-3) / 1e12 : 0.0;
+    return KVFUSE_PROBE_OK;
+}
+
+int kvfuse_probe_copy(void *hip_stream, const void *src, void *dst, size_t bytes, int32_t repeats, double *gbps)
+{
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (!src || !dst || !gbps || bytes < 16 || repeats <= 0)
+        return fail(KVFUSE_PROBE_EINVAL, "probe: null pointer, fewer than 16 bytes or no repeats");
+    hipEvent_t e0, e1;
+    PROBE_HIP(hipEventCreate(&e0));
+    PROBE_HIP(hipEventCreate(&e1));
+    launch_probe_copy(stream, src, dst, bytes);                      // warm-up
+    hipError_t err = hipEventRecord(e0, stream);
+    for (int i = 0; i < repeats; ++i)
+        launch_probe_copy(stream, src, dst, bytes);
+    if (err == hipSuccess)
+        err = hipEventRecord(e1, stream);
+    if (err == hipSuccess)
+        err = hipEventSynchronize(e1);
+    float ms = 0.0f;
+    if (err == hipSuccess)
+        err = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    PROBE_HIP(err);
+    PROBE_HIP(hipGetLastError());
+    *gbps = ms > 0.0f ? 2.0 * (double)(bytes / 16 * 16) * repeats / (ms * 1e-3) / 1e9 : 0.0;
+    return KVFUSE_PROBE_OK;
+}
+
+int kvfuse_probe_tile_loop_bf16(void *hip_stream, const void *src, size_t src_bytes, int32_t with_loads, float *sink,
+                                double *tflops)
+{
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (!src || !sink || !tflops || src_bytes < ((size_t)4 << 20))
+        return fail(KVFUSE_PROBE_EINVAL, "probe: needs 4 MiB of bfloat16 data to read, a device word to write and an output");
+    int device = 0;
+    PROBE_HIP(hipGetDevice(&device));
+    hipDeviceProp_t prop;
+    PROBE_HIP(hipGetDeviceProperties(&prop, device));
+    const int wgs = prop.multiProcessorCount * 4;
+    const int iters = 4000;
+    hipEvent_t e0, e1;
+    PROBE_HIP(hipEventCreate(&e0));
+    PROBE_HIP(hipEventCreate(&e1));
+    launch_probe_tile_loop(stream, src, with_loads, wgs, iters / 10, sink);      // warm-up
+    hipError_t err = hipEventRecord(e0, stream);
+    launch_probe_tile_loop(stream, src, with_loads, wgs, iters, sink);
+    if (err == hipSuccess)
+        err = hipEventRecord(e1, stream);
+    if (err == hipSuccess)
+        err = hipEventSynchronize(e1);
+    float ms = 0.0f;
+    if (err == hipSuccess)
+        err = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    PROBE_HIP(err);
+    PROBE_HIP(hipGetLastError());
+    *tflops = ms > 0.0f ? (double)wgs * iters * 2.0 * 256.0 * 256.0 * 32.0 / (ms * 1e-3) / 1e12 : 0.0;
+    return KVFUSE_PROBE_OK;
+}
+
+int kvfuse_probe_read2_write1(void *hip_stream, void *buf, size_t bytes, int32_t block_bytes, int32_t repeats, double *gbps)
+{
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (!buf || !gbps || block_bytes < 16 || block_bytes % 16 != 0 || repeats <= 0)
+        return fail(KVFUSE_PROBE_EINVAL, "probe: null pointer, block size not a positive multiple of 16 bytes, or no repeats");
+    // stripes of 256 blocks: the first 32 are targets, their members lie 128 blocks further on (the distance between
+    // the same block of two neighbouring requests in the bench workload)
+    const int gap = 128, per_stripe = 32;
+    const size_t stripes = bytes / ((size_t)2 * gap * block_bytes);
+    if (stripes == 0 || stripes * per_stripe > (size_t)INT32_MAX)
+        return fail(KVFUSE_PROBE_EINVAL, "probe: buffer smaller than one stripe of 256 blocks, or too large");
+    const int n_items = (int)(stripes * per_stripe);
+    hipEvent_t e0, e1;
+    PROBE_HIP(hipEventCreate(&e0));
+    PROBE_HIP(hipEventCreate(&e1));
+    launch_probe_rmw(stream, buf, n_items, block_bytes, gap, per_stripe);          // warm-up
+    hipError_t err = hipEventRecord(e0, stream);
+    for (int i = 0; i < repeats; ++i)
+        launch_probe_rmw(stream, buf, n_items, block_bytes, gap, per_stripe);
+    if (err == hipSuccess)
+        err = hipEventRecord(e1, stream);
+    if (err == hipSuccess)
+        err = hipEventSynchronize(e1);
+    float ms = 0.0f;
+    if (err == hipSuccess)
+        err = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    PROBE_HIP(err);
+    PROBE_HIP(hipGetLastError());
+    *gbps = ms > 0.0f ? 3.0 * (double)block_bytes * n_items * repeats / (ms * 1e-3) / 1e9 : 0.0;
+    return KVFUSE_PROBE_OK;
+}
+
+}  // extern "C"
