@@ -39,7 +39,7 @@ def build(force: bool = False) -> str:
     """Compile the C oracle with gcc.  No fast-math: fp64 order is the definition."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(
-            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fno-fast-math", "-ffp-contract=off",
+            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fno-fast-math", "-ffp-contract=off", "-fopenmp",
              "-o", _LIB, _SRC, "-lm"])
     return _LIB
 
@@ -215,6 +215,13 @@ def fuse_group(kpool: np.ndarray, vpool: np.ndarray, bt: np.ndarray, leaf_start,
     res.free_list = free_list[: n_free.value].copy()
     res.trace = trace[: trace_len.value].reshape(-1, 2).copy() if want_trace else None
     return res
+
+
+def set_column_threads(n: int) -> None:
+    """Host threads that share out the (independent) columns of one tree node; 1 = none.  For groups too large to
+    walk on one core in reasonable time.  Changes the run time only: every cosine stays one left-to-right fp64 sum.
+    Process-wide; do not combine with ``fuse_groups(threads > 1)``."""
+    _load().ora_set_column_threads(int(n))
 
 
 def fuse_groups(kpools, vpools, bts, leaf_start, leaf_count, unit_leaf_ptr, thr, group_size=0, band=1e-3,

@@ -104,7 +104,7 @@ void ora_store_array(void *dst, int elem_bytes, const double *x, size_t n)
 /* the steps of one tree node                                          */
 /* ------------------------------------------------------------------ */
 
-/* Method section: "The norm of each r is stored".  norm[b] = ||block b||_2 of
+/* Method section: every block vector keeps its norm.  norm[b] = ||block b||_2 of
  * the values as stored, for blocks 0..P-1 of one pool tensor [P][r]. */
 void ora_block_norms(const void *pool, int elem_bytes, int r, int P, double *norm)
 {
@@ -267,6 +267,11 @@ void ora_rewrite(int32_t *bt, int n, const int32_t *L, int ml, const int32_t *R,
 /* Algorithm 1: the recursion                                          */
 /* ------------------------------------------------------------------ */
 
+/* Host threads that share out the columns of one node (1 = none).  Set once before a run; it changes how long a run
+ * takes and nothing that it computes. */
+static int ora_column_threads = 1;
+void ora_set_column_threads(int n) { ora_column_threads = n > 1 ? n : 1; }
+
 typedef struct {
     int elem_bytes, r, P, n;
     void *kpool, *vpool;
@@ -295,21 +300,35 @@ static ora_set ora_node(ora_ctx *c, ora_set Ls, ora_set Rs)
 {
     int ml = Ls.m, mr = Rs.m;
     int32_t *assign = (int32_t *)malloc(sizeof(int32_t) * (size_t)(mr > 0 ? mr : 1));
-    double *col = (double *)malloc(sizeof(double) * (size_t)(ml > 0 ? ml : 1));
-    /* column by column so that the dense matrix need not be held */
-    for (int j = 0; j < mr; ++j) {
-        for (int i = 0; i < ml; ++i)
-            col[i] = ora_cosine(c->kpool, c->elem_bytes, c->r, c->norm_k, Ls.id[i], Rs.id[j]);
-        double best, second;
-        ora_assign(col, ml, 1, c->thr, &assign[j], &best, &second);
-        if (c->rule == 1) {
-            /* the column seen by the row loop; the value that decided it is the taker's cosine, or the column
-             * maximum when no row took it */
-            ora_assign_first_row(col, ml, 1, c->thr, &assign[j]);
-            if (assign[j] >= 0)
-                best = col[assign[j]];
+    double *best_of = (double *)malloc(sizeof(double) * (size_t)(mr > 0 ? mr : 1));
+    double *second_of = (double *)malloc(sizeof(double) * (size_t)(mr > 0 ? mr : 1));
+    /* Column by column so that the dense matrix need not be held.  The columns of a node are independent (sim is
+     * computed once, before any fusing), so they may be shared out over host threads; every cosine is still one
+     * left-to-right fp64 sum and every decision is taken on its own column, whatever the thread count. */
+#pragma omp parallel num_threads(ora_column_threads) if (ora_column_threads > 1 && mr > 1)
+    {
+        double *col = (double *)malloc(sizeof(double) * (size_t)(ml > 0 ? ml : 1));
+#pragma omp for schedule(dynamic, 8)
+        for (int j = 0; j < mr; ++j) {
+            for (int i = 0; i < ml; ++i)
+                col[i] = ora_cosine(c->kpool, c->elem_bytes, c->r, c->norm_k, Ls.id[i], Rs.id[j]);
+            double best, second;
+            ora_assign(col, ml, 1, c->thr, &assign[j], &best, &second);
+            if (c->rule == 1) {
+                /* the column seen by the row loop; the value that decided it is the taker's cosine, or the column
+                 * maximum when no row took it */
+                ora_assign_first_row(col, ml, 1, c->thr, &assign[j]);
+                if (assign[j] >= 0)
+                    best = col[assign[j]];
+            }
+            best_of[j] = best;
+            second_of[j] = second;
         }
-        /* statistics only; they never feed back into a decision */
+        free(col);
+    }
+    /* statistics and the optional trace, in column order; they never feed back into a decision */
+    for (int j = 0; j < mr; ++j) {
+        double best = best_of[j], second = second_of[j];
         if (ml > 0) {
             c->n_decisions++;
             double mg = fabs(best - c->thr);
@@ -332,6 +351,8 @@ static ora_set ora_node(ora_ctx *c, ora_set Ls, ora_set Rs)
             c->trace[c->trace_len++] = assign[j] >= 0 ? Ls.id[assign[j]] : -1;
         }
     }
+    free(best_of);
+    free(second_of);
     ora_merge(c->kpool, c->elem_bytes, c->r, c->norm_k, Ls.id, ml, Rs.id, mr, assign);
     ora_merge(c->vpool, c->elem_bytes, c->r, c->norm_v, Ls.id, ml, Rs.id, mr, assign);
     ora_rewrite(c->bt, c->n, Ls.id, ml, Rs.id, mr, assign, c->orig_norm_k, c->orig_norm_v,
@@ -345,7 +366,6 @@ static ora_set ora_node(ora_ctx *c, ora_set Ls, ora_set Rs)
         if (assign[j] < 0)
             out.id[out.m++] = Rs.id[j];
     free(assign);
-    free(col);
     free(Ls.id);
     free(Rs.id);
     return out;

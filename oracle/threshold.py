@@ -57,5 +57,7 @@ def predicted_compression(rates, blocks_per_layer: float):
 
 def feedback_step(thr: float, observed_cr: float, target_cr: float, gain: float, lo: float, hi: float) -> float:
     """One step of target-compression feedback: compression above the target raises the threshold, below lowers it;
-    proportional to the relative miss, clamped to [lo, hi]."""
+    proportional to the relative miss, clamped to [lo, hi].  Parity unpinned beyond direction and clamp: the paper
+    names no gain law, so the proportional form is the builder's own and only its sign and its limits can be held
+    against the paper."""
     return min(hi, max(lo, thr + gain * (observed_cr - target_cr) / target_cr))

@@ -138,6 +138,26 @@ def test_two_block_fusion_is_the_bisector(oracle):
     assert res2.scale_k.tolist() == [1.0, 1.0]
 
 
+def test_decisions_near_the_threshold_are_counted_by_their_distance_to_it(oracle):
+    """The "reported separately" counter: a decision is near the threshold when its best cosine lies within `band` of
+    thr, whichever side it is on.  One left block e1 against right blocks at known angles: cosines thr + 4e-4 and
+    thr - 4e-4 (near; the first fuses, the second does not), thr + 3e-3 and thr - 3e-3 (not near), and one exactly
+    orthogonal.  The counters and the smallest margin follow by hand."""
+    thr, band = 0.9, 1e-3
+    cosines = [thr + 4e-4, thr - 4e-4, thr + 3e-3, thr - 3e-3, 0.0]
+    K = np.array([[1.0, 0.0]] + [[c, math.sqrt(1.0 - c * c)] for c in cosines], np.float32)
+    V = K.copy()
+    bt, ls, lc, up = _identity_setup(K, V, [1, len(cosines)])
+    res = oracle.fuse_group(K, V, bt, ls, lc, up, thr=thr, band=band)
+    decisions, fused, near, ties, min_margin = (res.stats[i] for i in range(5))
+    assert (decisions, fused, near, ties) == (5, 2, 2, 0)
+    assert res.bt.tolist() == [0, 0, 2, 0, 4, 5]
+    assert abs(min_margin - 4e-4) < 1e-6                      # binary32 storage moves a cosine by ~1e-7 at most
+    # a wider band takes the +-3e-3 decisions in as well; a narrower one leaves none
+    assert oracle.fuse_group(K, V, bt, ls, lc, up, thr=thr, band=5e-3).stats[2] == 4
+    assert oracle.fuse_group(K, V, bt, ls, lc, up, thr=thr, band=1e-4).stats[2] == 0
+
+
 def test_sum_is_over_current_unit_representatives_not_member_mean(oracle):
     """Three leaves a | b | c with a,b fusing first (left subtree = [a], right = [b, c] split as b | c).
     With leaves [a],[b],[c] the tree is FF([a]) vs FF([b],[c]): b and c fuse first, then their unit rep meets a.
@@ -372,6 +392,25 @@ def test_chunks_then_requests_and_group_size(oracle):
     assert np.array_equal(res2.bt, b3bt) and np.array_equal(res2.kpool, b3K)
     first_half = set(range(int(ls[up[2]])))
     assert all((res2.bt[x] in first_half) == (x in first_half) for x in range(n))
+
+
+def test_sharing_the_columns_of_a_node_over_threads_changes_nothing(oracle):
+    """The oracle may spread the independent columns of a node over host threads (for the groups of tens of thousands
+    of blocks); tables, pools, scales, statistics and the decision trace must not depend on the thread count."""
+    rec = wl.zipf_bff(n_req=8, tokens=32 * 24, layers=1, kv_heads=1, pool=120)
+    mat = wl.materialise(rec, "cpu")
+    K, V, bt = wl.to_numpy_pool(mat["K"][0]), wl.to_numpy_pool(mat["V"][0]), mat["bt"][0].numpy().copy()
+    runs = []
+    try:
+        for threads in (1, 4):
+            oracle.set_column_threads(threads)
+            runs.append(oracle.fuse_group(K, V, bt, rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr, rec.thr, want_trace=True))
+    finally:
+        oracle.set_column_threads(1)
+    a, b = runs
+    assert a.stats[1] > 0
+    for field in ("bt", "kpool", "vpool", "refcount", "scale_k", "scale_v", "norm_k", "norm_v", "stats", "free_list", "trace"):
+        assert np.array_equal(getattr(a, field), getattr(b, field)), field
 
 
 def test_groups_are_independent_and_deterministic(oracle):
