@@ -42,23 +42,43 @@ def make_recipe(wl, name):
     raise SystemExit(f"unknown workload {name}")
 
 
-def cpu_baseline(wl, seconds_hint=20.0):
-    """Time the oracle (as it stands) on host threads over a bounded sample of the Llama-3-8B BFF workload:
-    the first groups of the same recipe at 32 requests x 128 blocks, one group per thread."""
+def cpu_baseline(wl, reduced=False):
+    """Time the oracle (as it stands) on the host cores over a bounded sample of the workload the GPU is timed on:
+    one group per core (at least 8 groups) of the llama8b_bff recipe at its full per-group shape, 64 requests x 128
+    blocks, through the same unit of work as `value`: norms + Algorithm 1's whole tree, then one decode-attention
+    step of every request through the fused table.  ``reduced`` (a labelled fallback for quick runs) halves the
+    request count."""
+    import numpy as np
     import oracle
     import torch
     cores = min(16, os.cpu_count() or 1)
-    rec = wl.llama8b_bff(n_req=32, layers=1, kv_heads=cores)
+    groups = max(8, cores)
+    n_req = 32 if reduced else 64
+    rec = wl.llama8b_bff(n_req=n_req, layers=1, kv_heads=groups)
     dev = "cuda:0" if torch.cuda.is_available() else "cpu"
     mat = wl.materialise(rec, dev)
     Ks = [wl.to_numpy_pool(mat["K"][g]) for g in range(rec.G)]
     Vs = [wl.to_numpy_pool(mat["V"][g]) for g in range(rec.G)]
     bts = [mat["bt"][g].cpu().numpy() for g in range(rec.G)]
+    q = wl.queries(rec, dev)[0].float().cpu().numpy()
     del mat
     oracle.build()
     t0 = time.perf_counter()
     res = oracle.fuse_groups(Ks, Vs, bts, rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr, rec.thr, threads=cores)
-    dt = time.perf_counter() - t0
+    t_fuse = time.perf_counter() - t0
+    # decode: the groups are the KV heads of one layer; requests are shared out over the same threads
+    from concurrent.futures import ThreadPoolExecutor
+
+    def dec(b):
+        return oracle.paged_decode_attention(q[b: b + 1], [r.kpool for r in res], [r.vpool for r in res], [r.bt for r in res],
+                                             [r.scale_k for r in res], [r.scale_v for r in res], rec.req_start[b: b + 1],
+                                             rec.ctx_len[b: b + 1], rec.t, rec.d)
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=cores) as ex:
+        outs = list(ex.map(dec, range(rec.B)))
+    t_dec = time.perf_counter() - t0
+    assert np.isfinite(np.concatenate(outs)).all()
+    dt = t_fuse + t_dec
     blocks = rec.G * rec.n
     model = "unknown"
     try:
@@ -70,8 +90,80 @@ def cpu_baseline(wl, seconds_hint=20.0):
         pass
     return {"value": blocks / dt, "unit": "blocks/s", "cores": cores, "kind": "oracle", "cpu_model": model,
             "blocks_per_s_per_core": blocks / dt / cores,
-            "sample": f"{rec.G} groups x 32 requests x 128 blocks of the llama8b_bff recipe (fusion only, {dt:.1f} s wall), "
-                      f"CR {sum(len(r.bt) for r in res) / sum(r.n_physical for r in res):.3f}"}
+            "fusion_s": t_fuse, "decode_s": t_dec,
+            "sample": f"{rec.G} groups (one layer of {rec.G} KV heads) x {n_req} requests x 128 blocks of the llama8b_bff recipe"
+                      f"{' -- REDUCED sample, half the requests of the timed shape' if reduced else ', the per-group shape the GPU is timed on'}: "
+                      f"norms + fusion ({t_fuse:.1f} s wall, one group per thread) + decode attention of all {rec.B} requests "
+                      f"({t_dec:.1f} s), CR {sum(len(r.bt) for r in res) / sum(r.n_physical for r in res):.3f}; same unit as "
+                      f"`value`: logical blocks through norms, fusion and decode per second"}
+
+
+def similarity_tile_model(ml, mr, big):
+    """What the similarity kernel's tiling issues for nodes with ``ml`` left and ``mr`` right blocks (integer arrays
+    of one shape): rows and columns of MFMA work per node after the skipped bands (sum over its tiles; work =
+    rows x cols x 2 r flops is exact because the bands of a tile are whole in both directions), and the rows loaded
+    into LDS (every tile of BM x BN loads BM + BN block rows, ragged or not).  Bookkeeping for benchmarks: mirrors
+    the launch geometry of csrc/similarity.hip, computes nothing of the method."""
+    import numpy as np
+    ml = np.asarray(ml, np.int64)
+    mr = np.asarray(mr, np.int64)
+    bm = bn = 256 if big else 128
+    row_band, col_band = (128, 64) if big else (64, 64)
+    n_rt = -(-ml // bm)
+    n_cp = -(-mr // bn)
+    full_r, tail_r = ml // bm, ml % bm
+    full_c, tail_c = mr // bn, mr % bn
+    rows = full_r * bm + -(-tail_r // row_band) * row_band
+    cols = full_c * bn + -(-tail_c // col_band) * col_band
+    rows = np.where(mr > 0, rows, 0)
+    cols = np.where(ml > 0, cols, 0)
+    loaded_rows = n_rt * n_cp * (bm + bn)
+    return rows, cols, loaded_rows
+
+
+def per_height_table(kb, ctx, cache, plan, rec, restore, thr):
+    """One extra fusion pass taken height by height (similarity, assignment, merge as separate calls with HIP events
+    around the similarity launch): per tree height the node count, the mean set sizes, the valid flops
+    2 m_l m_r r, the MFMA work the tiling issues for those sizes (whole 32 x 32 MFMA tiles that are not skipped),
+    the bytes the tiling loads into LDS, and the time.  Used for profiles/: where the similarity stage loses
+    against its own full-tile rate is read off this table."""
+    import numpy as np
+    import torch
+    dev = cache.K.device
+    restore()
+    kb.block_norms(ctx, cache)
+    kb.leaf_sets(ctx, plan)
+    elem = 2 if rec.dtype == torch.bfloat16 else 4
+    rows = []
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for h in range(plan.n_heights):
+        v = plan.view(h)
+        torch.cuda.synchronize()
+        ev[0].record()
+        kb.similarity(ctx, plan, h, thr, 1e-3, None)
+        ev[1].record()
+        torch.cuda.synchronize()
+        ms = ev[0].elapsed_time(ev[1])
+        cnt = kb.device_array(v.set_cnt, rec.G * v.n_slots, np.int32, dev).reshape(rec.G, v.n_slots).astype(np.int64)
+        ml = cnt[:, kb.device_array(v.l_slot, v.n_nodes, np.int32, dev)]
+        mr = cnt[:, kb.device_array(v.r_slot, v.n_nodes, np.int32, dev)]
+        lcap = kb.device_array(v.l_cap, v.n_nodes, np.int32, dev).astype(np.int64)
+        rcap = kb.device_array(v.r_cap, v.n_nodes, np.int32, dev).astype(np.int64)
+        wsum = float((lcap * rcap).sum())
+        big = wsum > 0 and float((lcap * rcap * np.minimum(lcap, rcap)).sum()) / wsum >= 256.0     # the plan's rule
+        mma_rows, mma_cols, lds_bytes = similarity_tile_model(ml, mr, big)
+        valid = float((2 * ml * mr).sum()) * rec.r
+        tile = float((2 * mma_rows * mma_cols).sum()) * rec.r
+        kb.assign(ctx, plan, h, thr, 1e-3)
+        kb.merge(ctx, plan, h)
+        rows.append({"height": h + 1, "nodes_per_group": int(v.n_nodes), "tile": "256x256" if big else "128x128",
+                     "mean_m_l": float(ml.mean()), "mean_m_r": float(mr.mean()), "valid_TFLOP": valid / 1e12,
+                     "mfma_TFLOP": tile / 1e12, "valid_over_mfma": valid / tile if tile else 0.0,
+                     "lds_load_GB": float(lds_bytes.sum()) * rec.r * elem / 1e9,
+                     "compulsory_GB": float((ml + mr).sum()) * rec.r * elem / 1e9, "ms": ms,
+                     "valid_TFLOPs": valid / ms / 1e9 if ms else 0.0, "mfma_TFLOPs": tile / ms / 1e9 if ms else 0.0})
+    torch.cuda.synchronize()
+    return rows
 
 
 def main():
@@ -81,12 +173,17 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="llama8b_bff")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-baseline-reduced", action="store_true",
+                    help="time the oracle on half the requests per group (quick runs; labelled as reduced in the output)")
     ap.add_argument("--cand-cap", type=int, default=64)
     ap.add_argument("--thr", type=float, default=None, help="override the workload's similarity threshold")
     ap.add_argument("--assign-rule", choices=["argmax", "first_row"], default="argmax",
                     help="reading of Algorithm 1's threshold line: most similar row, or first row above the threshold")
     ap.add_argument("--shortest-first", action="store_true",
                     help="build the tree over the requests in ascending number of blocks (remark on the order of requests)")
+    ap.add_argument("--per-height", action="store_true",
+                    help="after the timed steps, run one more fusion height by height and add a per-height table of the "
+                         "similarity stage (set sizes, valid and issued MFMA work, bytes loaded, time) to the output")
     ap.add_argument("--calib-copy-gib", type=float, default=0.0,
                     help="also run a plain device copy of this many GiB (3 times) so that rocprofv3 --pmc FETCH_SIZE / "
                          "WRITE_SIZE readings can be scaled by a kernel of known traffic")
@@ -97,6 +194,7 @@ def main():
 
     import torch
     from paper_2601_03067_amd import binding as kb
+    from paper_2601_03067_amd import probe as kp
     from paper_2601_03067_amd import workloads as wl
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
@@ -282,12 +380,12 @@ def main():
     # heavily and would otherwise warm it up for the steps): the MFMA instruction of the similarity kernel on
     # random and on constant operands, and a plain device copy
     blk_bytes_probe = rec.r * (2 if rec.dtype == torch.bfloat16 else 4)
-    probes = {"mfma_bf16_random_operands_TFLOPs": kb.probe_mfma_bf16(ctx, True, dev),
-              "mfma_bf16_constant_operands_TFLOPs": kb.probe_mfma_bf16(ctx, False, dev),
-              "tile_loop_bf16_TFLOPs": kb.probe_tile_loop_bf16(ctx, K0, True) if rec.dtype == torch.bfloat16 else None,
-              "tile_loop_bf16_no_loads_TFLOPs": kb.probe_tile_loop_bf16(ctx, K0, False) if rec.dtype == torch.bfloat16 else None,
-              "copy_kernel_GBps": kb.probe_copy(ctx, K0, cache.K, repeats=3),
-              "read2_write1_GBps": kb.probe_read2_write1(ctx, cache.K, blk_bytes_probe, repeats=3)}
+    probes = {"mfma_bf16_random_operands_TFLOPs": kp.mfma_bf16(True, dev),
+              "mfma_bf16_constant_operands_TFLOPs": kp.mfma_bf16(False, dev),
+              "tile_loop_bf16_TFLOPs": kp.tile_loop_bf16(K0, True) if rec.dtype == torch.bfloat16 else None,
+              "tile_loop_bf16_no_loads_TFLOPs": kp.tile_loop_bf16(K0, False) if rec.dtype == torch.bfloat16 else None,
+              "copy_kernel_GBps": kp.copy(K0, cache.K, repeats=3),
+              "read2_write1_GBps": kp.read2_write1(cache.K, blk_bytes_probe, repeats=3)}
     k = max(args.steps, 1)
     stage = {a: b / k for a, b in stage.items()}
     ms_step = sum(walls) / k
@@ -309,6 +407,8 @@ def main():
         "metric": "KV blocks fused/sec (+ % MFMA peak); fused-table decode attn HBM GB/s",
         "value": blocks / (ms_step * 1e-3),
         "unit": "blocks/s",
+        "value_is": "logical KV blocks (one per layer, KV head and block position) through norms, the whole fusion tree and "
+                    "one decode-attention step, per second; blocks that fusion evicted per second are in blocks_fused_per_s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "ms_per_step_median": ms_median,
         "request_level_blocks_per_s": blocks / (rec.layers * rec.kv_heads) / (ms_step * 1e-3),
         "blocks_fused_per_s": stats.fused / (ms_step * 1e-3),
@@ -360,9 +460,20 @@ def main():
         "machine_probes": probes,
         "generation_s": t_gen,
     }
+    if args.per_height:
+        line["per_height"] = per_height_table(kb, ctx, cache, plan, rec, restore, rec.thr)
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(wl)
+        line["cpu_baseline"] = cpu_baseline(wl, reduced=args.cpu_baseline_reduced)
     print(json.dumps(line))
+    sys.stdout.flush()
+    # nothing of this run may outlive it: no worker process is started on purpose, and none is left behind
+    try:
+        import psutil
+        for child in psutil.Process().children(recursive=True):
+            print(f"bench.py: ending left-over child process {child.pid} ({child.name()})", file=sys.stderr)
+            child.terminate()
+    except Exception:
+        pass
 
 
 if __name__ == "__main__":

@@ -25,7 +25,7 @@
  *     The fusion steps never look inside a block, so the paper's own vector -- one per block over all KV heads
  *     of a layer (method section: r = t*h*d, one table per layer) -- is the same call with G = layers,
  *     d := h*d and the pool laid out [layers][P][t][h][d]; the attention entry points need the per-head layout.
- *   - Representation (method section: "a single unit vector and a norm (scalar) per block"): logical block
+ *   - Representation (method section: one unit vector and one scalar norm per block): logical block
  *     x of group g stands for  scale[g][x] * stored(bt[g][x]).  Blocks that were never fused stay as they
  *     were written (scale exactly 1); a fused representative is stored as a unit vector rounded to the
  *     pool dtype, and scale = ||original x|| / ||stored representative||.
@@ -64,7 +64,7 @@ typedef struct kvfuse_pool {
     void *v;            /* device [G][P][t*d] dtype, values (same) */
     int32_t dtype;      /* KVFUSE_F32 or KVFUSE_BF16 */
     int32_t G, P, t, d; /* groups, physical blocks per group, tokens per block, head size */
-    double *norm_k;     /* device [G][P] out: ||stored block||_2 in fp64 ("the norm of each r is stored") */
+    double *norm_k;     /* device [G][P] out: ||stored block||_2 in fp64 (method section: the norm of every block vector is kept) */
     double *norm_v;     /* device [G][P] out */
     float *inv_norm_k;  /* device [G][P] out: (float)(1/norm_k), 0 for a zero block; similarity epilogue operand */
 } kvfuse_pool;
@@ -72,7 +72,8 @@ typedef struct kvfuse_pool {
 /* Per-group block tables and the per-logical-block rescale. */
 typedef struct kvfuse_table {
     int32_t n;           /* logical blocks per group */
-    int32_t *bt;         /* device [G][n] in/out: logical -> physical.  Must be injective per group on entry */
+    int32_t *bt;         /* device [G][n] in/out: logical -> physical.  Must be injective per group on entry
+                            (Algorithm 1 starts from unshared blocks); kvfuse_fuse_tree reports a table that is not */
     float *scale_k;      /* device [G][n] out */
     float *scale_v;      /* device [G][n] out */
     double *orig_norm_k; /* device [G][n] out: norm of the block each logical entry had before fusion */
@@ -158,7 +159,7 @@ int kvfuse_plan_view(const kvfuse_plan *plan, int32_t height, kvfuse_height_view
 
 /* ---- a1: norms, leaf step of Algorithm 1 ("normalize") ---------------------------------------------- */
 
-/* Method section: "The norm of each r is stored".  Computes norm_k, norm_v, inv_norm_k for all G*P blocks
+/* Method section: the norm of every block vector is kept.  Computes norm_k, norm_v, inv_norm_k for all G*P blocks
  * (fp64 accumulation), and initialises the table: orig_norm_* from the block each entry points at,
  * scale = 1, refcount = entries per block, remap = -1. */
 int kvfuse_block_norms(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table);
@@ -205,7 +206,9 @@ int kvfuse_rewrite_block_table(kvfuse_ctx *ctx, const kvfuse_pool *pool, const k
 /* ---- whole pipeline ---------------------------------------------------------------------------------- */
 
 /* a1 .. a5 over all heights of the plan.  If stats is not NULL the call synchronises the stream at the end
- * and fills it; want_timing additionally brackets the stages with HIP events on the stream. */
+ * and fills it; want_timing additionally brackets the stages with HIP events on the stream.  With stats the call
+ * also reports caller errors found on the device: ids outside [0, P), and a table that shares blocks on entry
+ * (fused before, or a prefix cache) -- KVFUSE_EINVAL, the pool and table are then undefined. */
 int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band, int32_t *free_list,
                      int32_t *n_free, int32_t *n_phys, kvfuse_stats *stats, int32_t want_timing);
 
@@ -350,7 +353,8 @@ int kvfuse_cosine_moments(kvfuse_ctx *ctx, const double *cos_in, int32_t G, int3
 /* Host-only closed forms (no context, no device).  Lambda(u) for n similarities; the u that gives a wanted rate
  * (NaN unless 0 < rate < n and sigma > 0); the corollary (p_no_fusion: host [n_layers] or NULL); one step of
  * target-compression feedback, thr + gain * (observed - target) / target clamped to [lo, hi]: compression above
- * the target raises the threshold. */
+ * the target raises the threshold.  The paper fixes only that direction (remark on self-adjusting thresholds); the
+ * proportional gain law and the clamp are this library's choice, not the paper's. */
 double kvfuse_exceedance_rate(double n, double mu, double sigma, double u);
 double kvfuse_threshold_for_rate(double n, double mu, double sigma, double rate);
 int kvfuse_predict_compression(const double *rates, int32_t n_layers, double blocks_per_layer, double *compression_ratio,
@@ -386,8 +390,8 @@ int kvfuse_plan_set_assign_rule(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t rule
 int kvfuse_tree_spec_shortest_first(const kvfuse_tree_spec *spec, int32_t *leaf_start, int32_t *leaf_count,
                                     int32_t *unit_leaf_ptr, int32_t *order);
 
-/* Results section, first evaluation mode ("fuse and replicate the rescaled cache across all fused blocks, without
- * freeing blocks"): every logical entry x gets the block it had before fusion back, orig_bt[x], filled with
+/* Results section, first evaluation mode (the fused, rescaled cache is copied back into every fused block and no
+ * block is freed): every logical entry x gets the block it had before fusion back, orig_bt[x], filled with
  * scale[x] * stored(bt[x]) rounded once to the pool dtype (K with scale_k, V with scale_v), so that an attention
  * kernel that knows nothing of fusion sees what the fused cache stands for.  On return the table is orig_bt again
  * with unit scales, one reference per block, nothing evicted, and the pool's norms are those of the rewritten
@@ -397,43 +401,10 @@ int kvfuse_tree_spec_shortest_first(const kvfuse_tree_spec *spec, int32_t *leaf_
  * Asynchronous. */
 int kvfuse_replicate_rescaled(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table, const int32_t *orig_bt);
 
-/* Results section, second evaluation mode ("fusing and freeing blocks, without rescaling"): the fused table and
+/* Results section, second evaluation mode (blocks are fused and freed, nothing is rescaled): the fused table and
  * the freed blocks stay as they are and every scale_k / scale_v becomes 1, so each logical block reads its shared
  * representative as stored.  Asynchronous. */
 int kvfuse_drop_rescale(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table);
-
-/* ---- machine probes (measurement aids; not part of the hot path) -------------------------------------- */
-
-#define KVFUSE_PROBE_SCRATCH_BYTES 65792
-
-/* Sustained rate of the bfloat16 MFMA instruction the similarity step uses (section 3.2's matrix product runs on
- * it), over the whole GPU, with operands in registers and no memory traffic: the compute ceiling the similarity
- * kernel can be held against besides the nominal peak.  random_operands = 0 multiplies a constant pattern,
- * 1 multiplies pseudo-random values, which is what real caches look like to the multipliers -- the chip lowers
- * its clock under that load, so the two differ.  scratch: device, >= KVFUSE_PROBE_SCRATCH_BYTES, overwritten.
- * tflops: host.  Runs on the context's stream and waits for it (about 50 - 100 ms). */
-int kvfuse_probe_mfma_bf16(kvfuse_ctx *ctx, int32_t random_operands, void *scratch, size_t scratch_bytes, double *tflops);
-
-/* Rate of a plain device copy kernel (16 bytes per lane), read + write bytes per second: the HBM ceiling the
- * bandwidth-bound steps (norms, merge, decode attention) can be held against.  src, dst: device, bytes each,
- * not overlapping; gbps: host.  Waits for the stream. */
-int kvfuse_probe_copy(kvfuse_ctx *ctx, const void *src, void *dst, size_t bytes, int32_t repeats, double *gbps);
-
-/* Rate of the similarity kernel's inner loop without its gather, ragged tiles and epilogue: per compute unit 8
- * wavefronts of 2 x 4 MFMA tiles per 256 x 256 x 32-element slice, fragments read from LDS one half slice ahead, a
- * barrier per slice and, if with_loads, 32 KB of global -> LDS loads per slice from an L2-resident 4 MiB window of
- * src.  The LDS operands are taken from src, so pass data like the cache's (the rate depends on how the operand bits
- * toggle).  This is the ceiling of the kernel's tile organisation on a given machine, between the register-fed MFMA
- * probe and the kernel itself.  src: device, >= 4 MiB, read only; sink: device, one float; tflops: host.  Waits for
- * the stream (about 30 ms). */
-int kvfuse_probe_tile_loop_bf16(kvfuse_ctx *ctx, const void *src, size_t src_bytes, int32_t with_loads, float *sink,
-                                double *tflops);
-
-/* Rate of the merge step's access pattern without its arithmetic: one wavefront per item reads two blocks of
- * block_bytes (a target and a member 128 blocks further on) and writes the first one back; bytes read + written per
- * second.  This is the ceiling the merge step (two reads per write, Algorithm 1's fusion line) can be held against on a
- * given machine.  buf: device, bytes >= 256 * block_bytes, overwritten; gbps: host.  Waits for the stream. */
-int kvfuse_probe_read2_write1(kvfuse_ctx *ctx, void *buf, size_t bytes, int32_t block_bytes, int32_t repeats, double *gbps);
 
 #ifdef __cplusplus
 }

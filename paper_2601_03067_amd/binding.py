@@ -128,11 +128,6 @@ lib.kvfuse_tree_spec_shortest_first.argtypes = [C.POINTER(TreeSpec), _vp, _vp, _
 lib.kvfuse_replicate_rescaled.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _vp]
 lib.kvfuse_drop_rescale.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table)]
 RULE_ARGMAX, RULE_FIRST_ROW = 0, 1
-lib.kvfuse_probe_mfma_bf16.argtypes = [_vp, _i32, _vp, C.c_size_t, C.POINTER(C.c_double)]
-lib.kvfuse_probe_copy.argtypes = [_vp, _vp, _vp, C.c_size_t, _i32, C.POINTER(C.c_double)]
-lib.kvfuse_probe_tile_loop_bf16.argtypes = [_vp, _vp, C.c_size_t, _i32, _vp, C.POINTER(C.c_double)]
-lib.kvfuse_probe_read2_write1.argtypes = [_vp, _vp, C.c_size_t, _i32, _i32, C.POINTER(C.c_double)]
-PROBE_SCRATCH_BYTES = 65792
 
 
 class KvfuseError(RuntimeError):
@@ -502,41 +497,6 @@ def paged_decode_attn_shared(ctx, cache, plan, q, sm_scale=None, out=None):
     ctx.check(lib.kvfuse_paged_decode_attn_shared(ctx.h, C.byref(cache.pool), C.byref(cache.table), plan.h, _ptr(q), sm_scale,
                                                   _ptr(out)))
     return out
-
-
-def probe_mfma_bf16(ctx, random_operands=True, device="cuda:0"):
-    """Sustained bfloat16 MFMA rate of the whole GPU in TFLOP/s (operands in registers, no memory traffic)."""
-    scratch = torch.empty(PROBE_SCRATCH_BYTES, device=device, dtype=torch.uint8)
-    out = C.c_double(0.0)
-    ctx.check(lib.kvfuse_probe_mfma_bf16(ctx.h, 1 if random_operands else 0, _ptr(scratch), scratch.numel(), C.byref(out)))
-    return out.value
-
-
-def probe_copy(ctx, src, dst, repeats=3):
-    """Read + write GB/s of a plain device copy kernel from src to dst (same size, contiguous)."""
-    assert src.is_contiguous() and dst.is_contiguous() and src.numel() * src.element_size() == dst.numel() * dst.element_size()
-    out = C.c_double(0.0)
-    ctx.check(lib.kvfuse_probe_copy(ctx.h, _ptr(src), _ptr(dst), src.numel() * src.element_size(), repeats, C.byref(out)))
-    return out.value
-
-
-def probe_tile_loop_bf16(ctx, src, with_loads=True):
-    """TFLOP/s of the similarity kernel's stripped inner loop, LDS operands and loads taken from ``src`` (>= 4 MiB)."""
-    assert src.is_contiguous()
-    sink = torch.zeros(1, device=src.device, dtype=torch.float32)
-    out = C.c_double(0.0)
-    ctx.check(lib.kvfuse_probe_tile_loop_bf16(ctx.h, _ptr(src), src.numel() * src.element_size(), 1 if with_loads else 0,
-                                              _ptr(sink), C.byref(out)))
-    return out.value
-
-
-def probe_read2_write1(ctx, buf, block_bytes, repeats=3):
-    """GB/s (read + written) of the merge step's access pattern on ``buf`` (overwritten)."""
-    assert buf.is_contiguous()
-    out = C.c_double(0.0)
-    ctx.check(lib.kvfuse_probe_read2_write1(ctx.h, _ptr(buf), buf.numel() * buf.element_size(), int(block_bytes), repeats,
-                                            C.byref(out)))
-    return out.value
 
 
 def unpack_best(packed):

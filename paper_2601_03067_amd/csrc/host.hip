@@ -671,7 +671,7 @@ int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band
             targets += x;
         stats->merge_targets = (int32_t)std::min<int64_t>(targets, INT32_MAX);
     }
-    int64_t invalid = 0;
+    int64_t invalid = 0, shared = 0;
     for (int g = 0; g < w.G; ++g) {
         const bool on = p.group_enable_host.empty() || p.group_enable_host[(size_t)g] != 0;
         stats->fused += counters[(size_t)g * 8 + 0];
@@ -679,6 +679,7 @@ int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band
         stats->refined += counters[(size_t)g * 8 + 2];
         stats->cand_overflow += counters[(size_t)g * 8 + 3];
         invalid += counters[(size_t)g * 8 + 4];
+        shared += counters[(size_t)g * 8 + 5];
         for (const Node &nd : p.nodes)
             if (nd.left >= 0 && on)
                 stats->sim_flops += 2.0 * (double)cnt[(size_t)g * w.n_slots + nd.left] *
@@ -689,6 +690,10 @@ int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band
     stats->compression_ratio = stats->physical_blocks > 0 ? (double)stats->logical_blocks / (double)stats->physical_blocks : 0.0;
     if (invalid)
         return fail(c, KVFUSE_EINVAL, "block table holds " + std::to_string(invalid) + " ids outside [0, P)");
+    if (shared)
+        return fail(c, KVFUSE_EINVAL, "block table is not injective on entry: " + std::to_string(shared) +
+                                          " entries point at a block that another entry of their group holds as well "
+                                          "(a table that was fused before, or a prefix cache); the result is undefined");
     return KVFUSE_OK;
 #undef KVF_TRY
 }
@@ -759,139 +764,6 @@ int kvfuse_paged_decode_attn(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvf
     if (rc)
         return fail(c, rc, "decode: workspace too small");
     KVF_HIP(c, hipGetLastError());
-    return KVFUSE_OK;
-}
-
-int kvfuse_probe_mfma_bf16(kvfuse_ctx *ctx, int32_t random_operands, void *scratch, size_t scratch_bytes, double *tflops)
-{
-    if (!ctx)
-        return KVFUSE_EINVAL;
-    Ctx *c = &ctx->c;
-    if (!scratch || !tflops || scratch_bytes < kProbeScratchBytes)
-        return fail(c, KVFUSE_EINVAL, "probe: needs a device scratch buffer of KVFUSE_PROBE_SCRATCH_BYTES and an output");
-    hipDeviceProp_t prop;
-    KVF_HIP(c, hipGetDeviceProperties(&prop, c->device));
-    const int wgs = prop.multiProcessorCount * 4;      // four rounds of one 8-wavefront workgroup per compute unit
-    const int iters = 2000;
-    float *sink = reinterpret_cast<float *>(static_cast<char *>(scratch) + 65536);
-    hipEvent_t e0, e1;
-    KVF_HIP(c, hipEventCreate(&e0));
-    KVF_HIP(c, hipEventCreate(&e1));
-    launch_probe_fill(c->stream, scratch, random_operands);
-    launch_probe_mfma(c->stream, scratch, wgs, iters / 10, sink);     // warm-up
-    hipError_t err = hipEventRecord(e0, c->stream);
-    launch_probe_mfma(c->stream, scratch, wgs, iters, sink);
-    if (err == hipSuccess)
-        err = hipEventRecord(e1, c->stream);
-    if (err == hipSuccess)
-        err = hipEventSynchronize(e1);
-    float ms = 0.0f;
-    if (err == hipSuccess)
-        err = hipEventElapsedTime(&ms, e0, e1);
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
-    KVF_HIP(c, err);
-    KVF_HIP(c, hipGetLastError());
-    // per wavefront and iteration: 32 MFMAs of 2 * 32 * 32 * 16 flops
-    *tflops = ms > 0.0f ? (double)wgs * 8.0 * iters * 32.0 * 32768.0 / (ms * 1e-3) / 1e12 : 0.0;
-    return KVFUSE_OK;
-}
-
-int kvfuse_probe_copy(kvfuse_ctx *ctx, const void *src, void *dst, size_t bytes, int32_t repeats, double *gbps)
-{
-    if (!ctx)
-        return KVFUSE_EINVAL;
-    Ctx *c = &ctx->c;
-    if (!src || !dst || !gbps || bytes < 16 || repeats <= 0)
-        return fail(c, KVFUSE_EINVAL, "probe: null pointer, fewer than 16 bytes or no repeats");
-    hipEvent_t e0, e1;
-    KVF_HIP(c, hipEventCreate(&e0));
-    KVF_HIP(c, hipEventCreate(&e1));
-    launch_probe_copy(c->stream, src, dst, bytes);                      // warm-up
-    hipError_t err = hipEventRecord(e0, c->stream);
-    for (int i = 0; i < repeats; ++i)
-        launch_probe_copy(c->stream, src, dst, bytes);
-    if (err == hipSuccess)
-        err = hipEventRecord(e1, c->stream);
-    if (err == hipSuccess)
-        err = hipEventSynchronize(e1);
-    float ms = 0.0f;
-    if (err == hipSuccess)
-        err = hipEventElapsedTime(&ms, e0, e1);
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
-    KVF_HIP(c, err);
-    KVF_HIP(c, hipGetLastError());
-    *gbps = ms > 0.0f ? 2.0 * (double)(bytes / 16 * 16) * repeats / (ms * 1e-3) / 1e9 : 0.0;
-    return KVFUSE_OK;
-}
-
-int kvfuse_probe_tile_loop_bf16(kvfuse_ctx *ctx, const void *src, size_t src_bytes, int32_t with_loads, float *sink,
-                                double *tflops)
-{
-    if (!ctx)
-        return KVFUSE_EINVAL;
-    Ctx *c = &ctx->c;
-    if (!src || !sink || !tflops || src_bytes < ((size_t)4 << 20))
-        return fail(c, KVFUSE_EINVAL, "probe: needs 4 MiB of bfloat16 data to read, a device word to write and an output");
-    hipDeviceProp_t prop;
-    KVF_HIP(c, hipGetDeviceProperties(&prop, c->device));
-    const int wgs = prop.multiProcessorCount * 4;
-    const int iters = 4000;
-    hipEvent_t e0, e1;
-    KVF_HIP(c, hipEventCreate(&e0));
-    KVF_HIP(c, hipEventCreate(&e1));
-    launch_probe_tile_loop(c->stream, src, with_loads, wgs, iters / 10, sink);      // warm-up
-    hipError_t err = hipEventRecord(e0, c->stream);
-    launch_probe_tile_loop(c->stream, src, with_loads, wgs, iters, sink);
-    if (err == hipSuccess)
-        err = hipEventRecord(e1, c->stream);
-    if (err == hipSuccess)
-        err = hipEventSynchronize(e1);
-    float ms = 0.0f;
-    if (err == hipSuccess)
-        err = hipEventElapsedTime(&ms, e0, e1);
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
-    KVF_HIP(c, err);
-    KVF_HIP(c, hipGetLastError());
-    *tflops = ms > 0.0f ? (double)wgs * iters * 2.0 * 256.0 * 256.0 * 32.0 / (ms * 1e-3) / 1e12 : 0.0;
-    return KVFUSE_OK;
-}
-
-int kvfuse_probe_read2_write1(kvfuse_ctx *ctx, void *buf, size_t bytes, int32_t block_bytes, int32_t repeats, double *gbps)
-{
-    if (!ctx)
-        return KVFUSE_EINVAL;
-    Ctx *c = &ctx->c;
-    if (!buf || !gbps || block_bytes < 16 || block_bytes % 16 != 0 || repeats <= 0)
-        return fail(c, KVFUSE_EINVAL, "probe: null pointer, block size not a positive multiple of 16 bytes, or no repeats");
-    // stripes of 256 blocks: the first 32 are targets, their members lie 128 blocks further on (the distance between
-    // the same block of two neighbouring requests in the bench workload)
-    const int gap = 128, per_stripe = 32;
-    const size_t stripes = bytes / ((size_t)2 * gap * block_bytes);
-    if (stripes == 0 || stripes * per_stripe > (size_t)INT32_MAX)
-        return fail(c, KVFUSE_EINVAL, "probe: buffer smaller than one stripe of 256 blocks, or too large");
-    const int n_items = (int)(stripes * per_stripe);
-    hipEvent_t e0, e1;
-    KVF_HIP(c, hipEventCreate(&e0));
-    KVF_HIP(c, hipEventCreate(&e1));
-    launch_probe_rmw(c->stream, buf, n_items, block_bytes, gap, per_stripe);          // warm-up
-    hipError_t err = hipEventRecord(e0, c->stream);
-    for (int i = 0; i < repeats; ++i)
-        launch_probe_rmw(c->stream, buf, n_items, block_bytes, gap, per_stripe);
-    if (err == hipSuccess)
-        err = hipEventRecord(e1, c->stream);
-    if (err == hipSuccess)
-        err = hipEventSynchronize(e1);
-    float ms = 0.0f;
-    if (err == hipSuccess)
-        err = hipEventElapsedTime(&ms, e0, e1);
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
-    KVF_HIP(c, err);
-    KVF_HIP(c, hipGetLastError());
-    *gbps = ms > 0.0f ? 3.0 * (double)block_bytes * n_items * repeats / (ms * 1e-3) / 1e9 : 0.0;
     return KVFUSE_OK;
 }
 

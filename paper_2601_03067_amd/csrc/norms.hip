@@ -1,4 +1,4 @@
-// a1: block norms and table initialisation (method section: "The norm of each r is stored"; leaf step of
+// a1: block norms and table initialisation (method section: every block vector keeps its norm; leaf step of
 // Algorithm 1).  Pure HBM stream: every K and V byte is read once; one wavefront per block, 16-byte loads,
 // fp64 accumulation in a fixed order so that identical blocks get bit-identical norms.
 #include "common.h"
@@ -110,13 +110,20 @@ __global__ void leaf_sets_kernel(WorkDesc w, int P, const int32_t *__restrict__ 
         w.set_cnt[i] = slot_init[i % w.n_slots];
 }
 
-__global__ void check_ids_kernel(WorkDesc w, int P, const int32_t *__restrict__ bt)
+// Caller errors that the tree cannot work with are counted per group: ids outside [0, P) in counters[g][4], and entries
+// whose block is also held by another entry in counters[g][5] (Algorithm 1 starts from unshared blocks: a shared block
+// would sit in several sets of one height and be rewritten by one node while another reads it).  refcount is the
+// count the norm pass has just taken.
+__global__ void check_ids_kernel(WorkDesc w, int P, const int32_t *__restrict__ bt, const int32_t *__restrict__ refcount)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < (int64_t)w.G * w.n) {
         const int p = bt[i];
+        const int64_t g = i / w.n;
         if (p < 0 || p >= P)
-            atomicAdd(&w.counters[(i / w.n) * 8 + 4], 1);
+            atomicAdd(&w.counters[g * 8 + 4], 1);
+        else if (refcount[g * P + p] > 1)
+            atomicAdd(&w.counters[g * 8 + 5], 1);
     }
 }
 
@@ -131,7 +138,7 @@ void launch_leaf_sets(hipStream_t s, const WorkDesc &w, const TableDesc &tab, in
     if (total > 0)
         leaf_sets_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(w, P, tab.bt, slot_init);
     if ((int64_t)w.G * w.n > 0)
-        check_ids_kernel<<<(unsigned)(((int64_t)w.G * w.n + 255) / 256), 256, 0, s>>>(w, P, tab.bt);
+        check_ids_kernel<<<(unsigned)(((int64_t)w.G * w.n + 255) / 256), 256, 0, s>>>(w, P, tab.bt, tab.refcount);
 }
 
 }  // namespace kvfuse

@@ -2,10 +2,10 @@
 //
 //   - Order of the requests (remark after Algorithm 1): requests with fewer blocks are better placed on the left of
 //     the tree.  Host side only: a stable sort of the units (of the leaves, when there is one unit) by block count.
-//   - The two ways the results section evaluates a fused cache: "fuse and replicate the rescaled cache across all
-//     fused blocks (without freeing blocks)", which hands every logical block its own block back, holding
+//   - The two ways the results section evaluates a fused cache.  The first copies the fused, rescaled cache back into
+//     every fused block and frees nothing: every logical block gets its own block back, holding
 //     scale * representative rounded to the pool type, so that an attention kernel that knows nothing of fusion
-//     sees what the fused cache stands for; and "fusing and freeing blocks (without rescaling)", which keeps the
+//     sees what the fused cache stands for.  The second fuses and frees blocks without rescaling: it keeps the
 //     fused table and drops the per-block scales.
 #include "common.h"
 

@@ -12,11 +12,13 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "kvfuse.h")
+PROBE_HEADER = os.path.join(ROOT, "include", "kvfuse_probe.h")
 LIB = os.path.join(ROOT, "paper_2601_03067_amd", "libkvfuse.so")
+PROBE_LIB = os.path.join(ROOT, "paper_2601_03067_amd", "libkvfuse_probe.so")
 
 
-def _declared():
-    text = open(HEADER).read()
+def _declared(header=HEADER):
+    text = open(header).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(kvfuse_[a-z0-9_]+)\s*\(", text)))
 
@@ -34,6 +36,17 @@ def test_every_declared_function_is_exported(lib):
     assert len(names) >= 25 and "kvfuse_similarity" in names and "kvfuse_paged_decode_attn_shared" in names
     missing = [n for n in names if not hasattr(lib, n)]
     assert not missing, f"declared in include/kvfuse.h but not exported: {missing}"
+
+
+def test_probe_library_is_separate_and_exports_its_header(lib):
+    """The machine probes are bench tooling: their own header and shared library, nothing of them in the product."""
+    names = _declared(PROBE_HEADER)
+    assert len(names) == 5 and all(n.startswith("kvfuse_probe_") for n in names)
+    plib = ctypes.CDLL(PROBE_LIB)
+    assert not [n for n in names if not hasattr(plib, n)]
+    assert not [n for n in names if hasattr(lib, n)]
+    assert not [n for n in _declared() if "probe" in n]
+    assert plib.kvfuse_probe_copy(None, None, None, 0, 1, None) == 1      # bad arguments are an error code, no GPU needed
 
 
 def test_null_arguments_are_errors_not_crashes(lib):

@@ -25,7 +25,7 @@ def test_llama8b_bff_full_size_sampled_groups_and_invariants(oracle, rule):
     print("materialise", rec.name, "G", rec.G, "n", rec.n, flush=True)
     mat = wl.materialise(rec, DEV)
     rng = np.random.default_rng(20260103)
-    sample = sorted({0, rec.G - 1, *rng.choice(rec.G, size=2, replace=False).tolist()})
+    sample = sorted({0, rec.G - 1, *rng.choice(rec.G, size=7, replace=False).tolist()})[:9]
     host = {g: (wl.to_numpy_pool(mat["K"][g]), wl.to_numpy_pool(mat["V"][g]), mat["bt"][g].cpu().numpy().copy()) for g in sample}
     cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, cand_cap=64, rule=rule)       # bench.py's candidate slots
     print("rule", rule, "gpu fused", stats.fused, "CR", stats.compression_ratio, "refined", stats.refined, flush=True)
@@ -60,7 +60,7 @@ def test_llama8b_bff_full_size_sampled_groups_and_invariants(oracle, rule):
     res = gu.oracle_fuse(oracle, rec, ([host[g][0] for g in sample], [host[g][1] for g in sample], [host[g][2] for g in sample]),
                          threads=len(sample), rule=rule)
     safe = gu.check_ambiguity(res, "llama8b_bff full size")
-    assert len(safe) >= len(sample) - 1
+    assert len(safe) == len(sample)
     for i in safe:
         gu.compare_group(res[i], _GroupView(cache, sample[i]), 0, False, f"full size group {sample[i]}")
     print("sampled groups match", flush=True)
@@ -118,7 +118,7 @@ def test_cff_long_full_size_sampled_groups_and_invariants(oracle):
     res = gu.oracle_fuse(oracle, rec, ([host[g][0] for g in sample], [host[g][1] for g in sample], [host[g][2] for g in sample]),
                          threads=len(sample))
     safe = gu.check_ambiguity(res, "cff_long full size")
-    assert len(safe) >= len(sample) - 1
+    assert len(safe) == len(sample)
     for i in safe:
         gu.compare_group(res[i], _GroupView(cache, sample[i]), 0, False, f"cff full size group {sample[i]}")
     print("sampled groups match", flush=True)
@@ -199,6 +199,50 @@ def test_one_layer_of_the_large_configs_invariants_and_decode(oracle, config):
         worst = max(worst, float(np.abs(out[0, b].cpu().numpy() - ref[0]).max()))
     print("decode max abs err on sampled requests", worst, flush=True)
     assert worst <= 2e-2
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("config", ["config4_zipf_group_of_32768_blocks", "config5_mixed_128_requests"])
+def test_large_config_groups_match_the_oracle_exactly(oracle, config, capsys):
+    """Oracle parity at the group sizes of the two large configurations.
+
+    Config 4: one whole group at its real size (256 requests x 128 blocks of 32 x 128 = 32768 blocks, 8 heights,
+    every block a noisy copy of a Zipf-drawn base: hundreds of near-tied contenders per column, half of all decisions
+    through the fp64 re-check).  Config 5: its recipe (ragged requests of 1 - 4 chunks, partial tail blocks, chunk
+    sub-trees below the request tree) at 128 of its 512 requests, about 33 k blocks per group: the largest request
+    count whose oracle run stays near two minutes on the host cores (the run time grows with the square of the
+    request count; the full 141 k-block group would take over half an hour and is checked through invariants and
+    determinism only, in the test above).  Tables, pools, reference counts, free lists, scales and norms are
+    compared element by element.  The oracle shares the independent columns of a node out over the host threads."""
+    import os
+    import time
+    kb = gu.load_binding()
+    if config.startswith("config4"):
+        rec = wl.zipf_bff(layers=1, kv_heads=1)
+    else:
+        rec = wl.mixed(layers=1, kv_heads=1, n_req=128)
+    with capsys.disabled():
+        print(f"\n  {config}: materialise G {rec.G} n {rec.n} r {rec.r} requests {rec.B}", flush=True)
+    mat = wl.materialise(rec, DEV)
+    host = gu.host_copy(mat)
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, cand_cap=64)
+    with capsys.disabled():
+        print(f"  gpu: fused {stats.fused} CR {stats.compression_ratio:.4f} refined {stats.refined} overflow {stats.cand_overflow} "
+              f"heights {stats.n_heights}; oracle running on the host threads", flush=True)
+    threads = min(16, os.cpu_count() or 1)
+    t0 = time.perf_counter()
+    oracle.set_column_threads(threads)
+    try:
+        res = gu.oracle_fuse(oracle, rec, host, threads=1)
+    finally:
+        oracle.set_column_threads(1)
+    with capsys.disabled():
+        print(f"  oracle: {time.perf_counter() - t0:.0f} s on {threads} threads, decisions {int(res[0].stats[0])} fused "
+              f"{int(res[0].stats[1])} exact ties {int(res[0].stats[3])} smallest gap to the runner-up {res[0].stats[5]:.2e}", flush=True)
+    assert gu.check_ambiguity(res, config) == [0]
+    gu.compare_group(res[0], cache, 0, False, config)
+    assert stats.fused == int(res[0].stats[1]) and stats.physical_blocks == res[0].n_physical
+    assert stats.near_threshold == int(res[0].stats[2])
 
 
 class _GroupView:

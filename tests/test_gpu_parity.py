@@ -176,9 +176,9 @@ def _run_tree_case(kb, oracle, rec, name, cand_cap=16, thr=None, phys_perm=True,
                                           shortest_first=shortest_first)
     res = gu.oracle_fuse(oracle, rec, host, thr=thr, group_size=group_size, rule=rule, shortest_first=shortest_first)
     safe = gu.check_ambiguity(res, name)
+    assert len(safe) == len(res)
     for g in safe:
         gu.compare_group(res[g], cache, g, rec.dtype == torch.float32, name)
-    assert len(safe) >= max(1, len(res) - 1)
     if len(safe) == len(res):
         assert stats.fused == sum(int(r.stats[1]) for r in res)
         assert stats.near_threshold == sum(int(r.stats[2]) for r in res)
@@ -591,6 +591,16 @@ def test_bad_arguments_are_reported_not_crashed(kb):
         kb.fuse_tree(ctx, plan2, 0.95)
     assert e.value.code == kb.EINVAL
     torch.cuda.synchronize()
+    # a table that already shares a block (a second fusion over a fused table, a prefix cache) is refused as well:
+    # Algorithm 1 starts from unshared blocks
+    mat3 = wl.materialise(rec, DEV)
+    mat3["bt"][1, 20] = mat3["bt"][1, 2]
+    cache3 = kb.Cache(mat3["K"], mat3["V"], mat3["bt"], rec.t, rec.d)
+    plan3 = kb.Plan(ctx, cache3, kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr))
+    with pytest.raises(kb.KvfuseError) as e:
+        kb.fuse_tree(ctx, plan3, 0.95)
+    assert e.value.code == kb.EINVAL and "not injective" in str(e.value)
+    torch.cuda.synchronize()
 
 
 # ------------------------------------------------------------------------------------------ a7 decode attention
@@ -859,39 +869,40 @@ def test_group_mask_skips_groups_and_leaves_the_rest_unchanged(kb, oracle):
 
 # ------------------------------------------------------------------------------------------ machine probes
 
-def test_machine_probes_run_and_copy_is_exact(kb):
+def test_machine_probes_run_and_copy_is_exact():
+    """The probe library (its own .so and header, used by bench.py only): every probe runs, the copy is exact, the
+    read-two-write-one pattern touches what it says, bad arguments come back as errors."""
+    from paper_2601_03067_amd import probe as kp
     _say("machine probes")
-    ctx = kb.Context(DEV)
     a = torch.arange(1 << 20, dtype=torch.int32, device=DEV)
     b = torch.zeros_like(a)
-    gbps = kb.probe_copy(ctx, a, b, repeats=2)
+    gbps = kp.copy(a, b, repeats=2)
     assert gbps > 0 and torch.equal(a, b)
-    rnd = kb.probe_mfma_bf16(ctx, True, DEV)
-    const = kb.probe_mfma_bf16(ctx, False, DEV)
+    rnd = kp.mfma_bf16(True, DEV)
+    const = kp.mfma_bf16(False, DEV)
     _say("  mfma bf16 TFLOP/s: random operands", round(rnd), "constant operands", round(const), "copy GB/s (small)", round(gbps))
     assert 50 < rnd < 2600 and 50 < const < 2600      # below the nominal dense peak of 2500 plus timing slack
     data = torch.randn(4 << 20, device=DEV).to(torch.bfloat16)          # 8 MiB of cache-like values
-    loop = kb.probe_tile_loop_bf16(ctx, data, True)
-    loop0 = kb.probe_tile_loop_bf16(ctx, data, False)
+    loop = kp.tile_loop_bf16(data, True)
+    loop0 = kp.tile_loop_bf16(data, False)
     _say("  stripped tile loop TFLOP/s: with loads", round(loop), "without", round(loop0))
     assert 50 < loop < 2600 and 50 < loop0 < 2600
-    with pytest.raises(kb.KvfuseError):
-        kb.probe_tile_loop_bf16(ctx, data[:1000], True)                 # less than 4 MiB
+    with pytest.raises(kp.ProbeError):
+        kp.tile_loop_bf16(data[:1000], True)                 # less than 4 MiB
     # the merge access pattern: item i of a 256-block stripe xors block i + 128 into block i (i < 32) and nothing else
     # moves; the probe runs its kernel an even number of times here (warm-up + 1), which must restore the buffer
     blk = 4096
     buf = torch.randint(0, 2 ** 31 - 1, (3 * 256 + 7, blk // 4), dtype=torch.int32, device=DEV)   # three stripes and a bit
     orig = buf.clone()
-    rate = kb.probe_read2_write1(ctx, buf, blk, repeats=1)
+    rate = kp.read2_write1(buf, blk, repeats=1)
     torch.cuda.synchronize()
     assert rate > 0 and torch.equal(buf, orig)
-    kb.probe_read2_write1(ctx, buf, blk, repeats=2)               # three applications = one
+    kp.read2_write1(buf, blk, repeats=2)               # three applications = one
     torch.cuda.synchronize()
     want = orig.clone()
     for s0 in range(0, 3 * 256, 256):
         want[s0:s0 + 32] ^= want[s0 + 128:s0 + 160]
     assert torch.equal(buf, want)
-    with pytest.raises(kb.KvfuseError):
-        kb.probe_read2_write1(ctx, buf[:100], blk)                # smaller than one stripe
-    with pytest.raises(kb.KvfuseError):
-        kb.ctx_check = ctx.check(kb.lib.kvfuse_probe_copy(ctx.h, None, None, 0, 1, None))
+    with pytest.raises(kp.ProbeError):
+        kp.read2_write1(buf[:100], blk)                # smaller than one stripe
+    assert kp.lib.kvfuse_probe_copy(None, None, None, 0, 1, None) == 1      # KVFUSE_PROBE_EINVAL
