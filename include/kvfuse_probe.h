@@ -35,9 +35,9 @@ const char *kvfuse_probe_last_error(void);
  * tflops: host.  About 50 - 100 ms. */
 int kvfuse_probe_mfma_bf16(void *hip_stream, int32_t random_operands, void *scratch, size_t scratch_bytes, double *tflops);
 
-/* Rate of a plain device copy kernel (16 bytes per lane), read + write bytes per second: the HBM ceiling the
- * bandwidth-bound steps (norms, merge, decode attention) can be held against.  src, dst: device, bytes each,
- * not overlapping; gbps: host. */
+/* Rate of a plain device copy kernel (one 16-byte chunk per lane, one workgroup per 4 KB, workgroups handed out in
+ * address order), read + write bytes per second: the HBM ceiling for one read per write.  src, dst: device, bytes each
+ * (below 8 TiB), not overlapping; gbps: host. */
 int kvfuse_probe_copy(void *hip_stream, const void *src, void *dst, size_t bytes, int32_t repeats, double *gbps);
 
 /* Rate of the similarity kernel's inner loop without its gather, ragged tiles and epilogue: per compute unit 8

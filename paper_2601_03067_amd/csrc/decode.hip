@@ -64,11 +64,8 @@ struct DecodeArgs {
     float *part;   // [tuples][nsplit][REP][D + 2] : o, then m, l
     float *out;    // [n_layers][B][Hq][D]
     int32_t P, n, t, kv_heads, layer_begin, B, Hq, rep, nsplit, blocks_per_split;
-    int32_t walk_by_id;   // 1: each workgroup visits its blocks in ascending physical id (see decode_kernel)
     float sm_scale;
 };
-
-constexpr int kMaxSortedWalk = 512;   // longest run of blocks a workgroup sorts; longer runs are walked in table order
 
 template <typename T, int D, int REP>
 __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs A)
@@ -83,7 +80,6 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs A)
     __shared__ float c_lds[4][16];         // per wave: rescale factor per head
     __shared__ float w_m[4][16], w_l[4][16];
     __shared__ float w_o[4][REP][D];
-    __shared__ unsigned long long walk[kMaxSortedWalk];   // (physical id << 32) | position in the split, sorted
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int split = blockIdx.x;
@@ -125,39 +121,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs A)
         for (int e = 0; e < PER; ++e)
             o[h][e] = 0.0f;
 
-    // Softmax attention does not depend on the order in which the context is visited, so the blocks are taken in
-    // ascending physical id instead of table order.  After fusion many requests of a group point at the same stored
-    // blocks, at different places of their contexts; their workgroups run side by side on one XCD (consecutive
-    // workgroups of a launch differ in the KV head first, and there are as many XCDs as KV heads in the usual
-    // shapes), and walking by id makes them reach a shared block at about the same time, while it is still in that
-    // XCD's L2, instead of each fetching it from HBM when its own table gets there.
-    const int n_walk = max(blk_hi - blk_lo, 0);
-    const bool by_id = A.walk_by_id && n_walk > 1 && n_walk <= kMaxSortedWalk;
-    if (by_id) {
-        int n2 = 2;
-        while (n2 < n_walk)
-            n2 <<= 1;
-        for (int i = tid; i < n2; i += 256)
-            walk[i] = i < n_walk ? ((unsigned long long)(uint32_t)btg[x0 + blk_lo + i] << 32) | (unsigned long long)i : ~0ull;
-        __syncthreads();
-        for (int k = 2; k <= n2; k <<= 1)
-            for (int j = k >> 1; j > 0; j >>= 1) {
-                for (int i = tid; i < n2; i += 256) {
-                    const int p = i ^ j;
-                    if (p > i) {
-                        const unsigned long long a = walk[i], b = walk[p];
-                        if ((a > b) == ((i & k) == 0)) {
-                            walk[i] = b;
-                            walk[p] = a;
-                        }
-                    }
-                }
-                __syncthreads();
-            }
-    }
-
-    for (int wi = wave; wi < n_walk; wi += 4) {
-        const int xb = blk_lo + (by_id ? (int)(uint32_t)walk[wi] : wi);
+    for (int xb = blk_lo + wave; xb < blk_hi; xb += 4) {
         const int x = x0 + xb;
         const int phys = btg[x];
         const float zs = A.sm_scale * skg[x];
@@ -377,7 +341,6 @@ int launch_decode(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, int
     A.P = pool.P; A.n = tab.n; A.t = pool.t; A.kv_heads = kv_heads; A.layer_begin = layer_begin; A.B = B; A.Hq = Hq;
     A.rep = Hq / kv_heads;
     A.sm_scale = sm_scale;
-    A.walk_by_id = B > 1 ? 1 : 0;      // a single request shares nothing with another
     const int64_t tuples = (int64_t)n_layers * B * kv_heads;
     A.nsplit = pick_nsplit(tuples, max_blocks);
     A.blocks_per_split = (max_blocks + A.nsplit - 1) / A.nsplit;

@@ -21,24 +21,25 @@
 // are data dependent and rarely multiples of 256) all wavefronts drop the same MFMA tiles and finish together.
 //
 // K is walked in 64-byte slices per row.  A ring of four LDS stages (each BM left + BN right rows x 64 bytes) is
-// filled by global_load_lds_dwordx4: the data never passes through registers, so two slices can be in flight
-// while one is being multiplied and one is ready, with no staging registers at all.  Every wavefront issues four
-// such loads per slice (1 KB each: 16 rows x 64 bytes).  A load writes LDS at (wave-uniform base + lane * 16), so
-// the XOR swizzle that keeps the fragment reads conflict-free (the LDS has 64 four-byte banks) is applied on the
-// global side: lane L covers row L / 4 and fetches logical 16-byte chunk (L & 3) ^ ((row >> 2) & 3) of that row's
-// slice.
+// filled by global_load_lds_dwordx4: the data never passes through registers, so three slices can be on their way
+// while one is being multiplied, with no staging registers at all.  Every wavefront issues four such loads per
+// slice (1 KB each: 16 rows x 64 bytes).  A load writes LDS at (wave-uniform base + lane * 16), so the XOR swizzle
+// that keeps the fragment reads conflict-free (the LDS has 64 four-byte banks) is applied on the global side: lane L
+// covers row L / 4 and fetches logical 16-byte chunk (L & 3) ^ ((row >> 2) & 3) of that row's slice.
 //
 // Fragment reads are ds_read_b128 in inline assembly.  The compiler cannot tell that they never touch a stage
 // that is still being filled and would otherwise wait for every outstanding global -> LDS load before each LDS
 // read.  Each read's destination registers are handed to the following wait statement as in/out operands, which
-// is what orders the MFMAs behind the wait.  Fragments are double buffered (one set per 32-byte half slice), and
-// the first half of slice j + 1 is read before the barrier that ends iteration j; that is legal because the loads
-// of slice j + 1 were completed before the previous barrier.
+// is what orders the MFMAs behind the wait.  Fragments are double buffered (one set per 32-byte half slice).
 //
-// Iteration j (slice j in stage j & 3):   read set1 <- slice j, second half;  MFMAs on set0 + 2 loads of slice
-// j + 3;  wait set1;  read set0 <- slice j + 1, first half;  MFMAs on set1 + 2 loads;  wait until only this
-// iteration's 4 loads are outstanding;  barrier.  The stage written in iteration j held slice j - 1, which every
-// wavefront finished reading before the previous barrier.
+// Iteration j (slice j in stage j & 3):   read set1 <- slice j, second half;  MFMAs on set0 + the 2 right-panel loads
+// of slice j + 3;  wait set1;  wait until only this wavefront's last 8 loads are outstanding;  BARRIER;  read set0 <-
+// slice j + 1, first half;  MFMAs on set1 + the 2 left-tile loads of slice j + 4 into stage j & 3.
+// The one barrier of an iteration sits where two things become true at once: every wavefront holds slice j in
+// registers, so stage j & 3 may be overwritten, and every wavefront's loads of slice j + 1 have landed, so it may be
+// read.  A load therefore has two to three iterations to arrive (its data is first touched right after the barrier
+// of the iteration before its slice), which covers an L2 miss that goes out to memory; with the barrier at the end of
+// the iteration the same ring gave it one to two.
 #include "common.h"
 
 namespace kvfuse {
@@ -255,17 +256,27 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
                 acc[mt][nt][e] = 0.0f;
 
     // ---- prologue: slices 0, 1, 2 on their way; 0 and 1 landed and visible before the first iteration
-    int pf_kt = 0, pf_rt = 0;
-#define KVF_DMA_ADVANCE()                                                                                          \
+    // The A (left) part of a slice is issued half an iteration before its B (right) part, so each part walks the
+    // slices with its own counters.  Past the last slice of the last row tile both keep loading rows that exist (the
+    // ids of the last row tile, the panel from its start), and those loads are only waited for, never read.
+    int pf_kt_a = 0, pf_rt_a = 0, pf_kt_b = 0;
+#define KVF_DMA_ADVANCE_A()                                                                                        \
     do {                                                                                                           \
-        pa0 += 64; pa1 += 64; pb0 += 64; pb1 += 64;                                                                \
-        if (++pf_kt == nk) {                                                                                       \
-            pf_kt = 0;                                                                                             \
-            ++pf_rt;                                                                                               \
-            const int na0 = pf_rt == 1 ? ia10 : (pf_rt == 2 ? ia20 : ia30);                                        \
-            const int na1 = pf_rt == 1 ? ia11 : (pf_rt == 2 ? ia21 : ia31);                                        \
+        pa0 += 64; pa1 += 64;                                                                                      \
+        if (++pf_kt_a == nk) {                                                                                     \
+            pf_kt_a = 0;                                                                                           \
+            ++pf_rt_a;                                                                                             \
+            const int na0 = pf_rt_a == 1 ? ia10 : (pf_rt_a == 2 ? ia20 : ia30);                                    \
+            const int na1 = pf_rt_a == 1 ? ia11 : (pf_rt_a == 2 ? ia21 : ia31);                                    \
             pa0 = kg + (int64_t)na0 * row_bytes + ld_chunk;                                                        \
             pa1 = kg + (int64_t)na1 * row_bytes + ld_chunk;                                                        \
+        }                                                                                                          \
+    } while (0)
+#define KVF_DMA_ADVANCE_B()                                                                                        \
+    do {                                                                                                           \
+        pb0 += 64; pb1 += 64;                                                                                      \
+        if (++pf_kt_b == nk) {                                                                                     \
+            pf_kt_b = 0;                                                                                           \
             pb0 -= row_bytes;                                                                                      \
             pb1 -= row_bytes;                                                                                      \
         }                                                                                                          \
@@ -277,9 +288,13 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
         KVF_DMA(pa1, so + dma_a1);
         KVF_DMA(pb0, so + dma_b0);
         KVF_DMA(pb1, so + dma_b1);
-        KVF_DMA_ADVANCE();
+        KVF_DMA_ADVANCE_A();
+        KVF_DMA_ADVANCE_B();
     }
-    asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    KVF_DMA(pa0, 3 * STAGE + dma_a0);       // the A part of slice 3; its B part follows in the first iteration
+    KVF_DMA(pa1, 3 * STAGE + dma_a1);
+    KVF_DMA_ADVANCE_A();
+    asm volatile("s_waitcnt vmcnt(10)" ::: "memory");     // slice 0 has landed
     __syncthreads();
     KVF_READ_SET(0, fa_lo, fb_lo)
     KVF_WAIT_SET(0);     // nothing but the loop body below runs while fragment reads are on their way
@@ -290,37 +305,40 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
     do {                                                                                                           \
         const uint32_t cur = (uint32_t)(it & 3) * STAGE;                                                           \
         const uint32_t nxt = (uint32_t)((it + 1) & 3) * STAGE;                                                     \
-        const int dst = ((it + 3) & 3) * STAGE;                                                                    \
+        const int dst_b = ((it + 3) & 3) * STAGE;                                                                  \
+        const int dst_a = (it & 3) * STAGE;                                                                        \
         const uint32_t ra1 = fa_hi + cur, rb1 = fb_hi + cur, ra0 = fa_lo + nxt, rb0 = fb_lo + nxt;                 \
         KVF_WAIT_SET(0);                                                                                           \
         KVF_READ_SET(1, ra1, rb1)                                                                                  \
         __builtin_amdgcn_sched_barrier(0);                                                                         \
         M(0, 0, 0) M(0, 1, 0)                                                                                      \
         __builtin_amdgcn_sched_barrier(0);                                                                         \
-        KVF_DMA(pa0, dst + dma_a0);                                                                                \
+        KVF_DMA(pb0, dst_b + dma_b0);                                                                              \
         __builtin_amdgcn_sched_barrier(0);                                                                         \
         M(0, 0, 1) M(0, 1, 1) MH(0, 0, 2) MH(0, 1, 2)                                                              \
         __builtin_amdgcn_sched_barrier(0);                                                                         \
-        KVF_DMA(pa1, dst + dma_a1);                                                                                \
+        KVF_DMA(pb1, dst_b + dma_b1);                                                                              \
         __builtin_amdgcn_sched_barrier(0);                                                                         \
         MH(0, 0, 3) MH(0, 1, 3)                                                                                    \
         __builtin_amdgcn_sched_barrier(0);                                                                         \
+        KVF_DMA_ADVANCE_B();                                                                                       \
         KVF_WAIT_SET(1);                                                                                           \
+        /* Slice it is now in registers in every wavefront that passes the barrier, so its stage is free; and all   \
+           but the last 8 loads of this wavefront (slices it + 2 and it + 3) have landed, so slice it + 1 is there. */ \
+        asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");                                             \
         KVF_READ_SET(0, ra0, rb0)                                                                                  \
         __builtin_amdgcn_sched_barrier(0);                                                                         \
         M(1, 0, 0) M(1, 1, 0)                                                                                      \
         __builtin_amdgcn_sched_barrier(0);                                                                         \
-        KVF_DMA(pb0, dst + dma_b0);                                                                                \
+        KVF_DMA(pa0, dst_a + dma_a0);                                                                              \
         __builtin_amdgcn_sched_barrier(0);                                                                         \
         M(1, 0, 1) M(1, 1, 1) MH(1, 0, 2) MH(1, 1, 2)                                                              \
         __builtin_amdgcn_sched_barrier(0);                                                                         \
-        KVF_DMA(pb1, dst + dma_b1);                                                                                \
+        KVF_DMA(pa1, dst_a + dma_a1);                                                                              \
         __builtin_amdgcn_sched_barrier(0);                                                                         \
         MH(1, 0, 3) MH(1, 1, 3)                                                                                    \
         __builtin_amdgcn_sched_barrier(0);                                                                         \
-        KVF_DMA_ADVANCE();                                                                                         \
-        /* all but this iteration's four loads have landed (slice it + 2), then everyone may read it */            \
-        asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");                                             \
+        KVF_DMA_ADVANCE_A();                                                                                       \
     } while (0)
     // MFMA tiles that lie wholly outside the valid part are dropped (their accumulators stay zero, which the epilogue
     // treats like any entry below the candidate floor).  Fragment reads and loads stay as they are: every wavefront
@@ -459,7 +477,8 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
 #undef KVF_WAIT_SET
 #undef KVF_MMA
 #undef KVF_MMA_HI
-#undef KVF_DMA_ADVANCE
+#undef KVF_DMA_ADVANCE_A
+#undef KVF_DMA_ADVANCE_B
 #undef KVF_SLICE
 #undef KVF_MMA_IF
 #undef KVF_MMA_HI_IF
