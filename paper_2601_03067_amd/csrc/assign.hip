@@ -16,6 +16,8 @@
 //   finalize one workgroup per (group, node): members grouped by target in ascending right index (CSR), evicted
 //            blocks entered in the remap table, targets to rebuild appended to the merge work list, and the node's
 //            surviving set cat(left, non-fused right in order) compacted in place for the parent node.
+#include <algorithm>
+
 #include "common.h"
 
 namespace kvfuse {
@@ -248,14 +250,66 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
             for (int off = 32; off >= 1; off >>= 1)
                 smax = fmaxf(smax, __shfl_xor(smax, off, 64));
             unsigned long long mask = __ballot(lane < cnt && (double)cv >= (double)smax - 2.0 * band);
-            while (mask) {
-                const int src = __ffsll((long long)mask) - 1;
-                mask &= mask - 1;
-                const int i = __shfl(ci, src, 64);
-                const double cs = cosine(l_ids[i]);
-                if (cs > bv || (cs == bv && i < bi)) {
-                    bv = cs;
-                    bi = i;
+            if constexpr (CPL > 0) {
+                // Every contender costs one block read that nothing else shares, so the chain "row -> physical id ->
+                // block -> dot product" is what a column waits for.  The ids and norms of all contenders are fetched
+                // at once (one per lane), and the block of the next contender is on its way while the current one
+                // is multiplied.  Same operations in the same order as cosine_f64_reg.
+                const int pid = lane < cnt ? l_ids[ci] : 0;
+                const double pna = norm_g[pid];
+                const int chunks = pool.r / Elem<T>::PER16;
+                uint4 nraw[CPL];
+                int src = mask ? __ffsll((long long)mask) - 1 : 0;      // a listed column has at least its maximum in mask
+                if (mask) {
+                    const uint4 *pa = reinterpret_cast<const uint4 *>(pool_g + (int64_t)__shfl(pid, src, 64) * pool.r);
+#pragma unroll
+                    for (int q = 0; q < CPL; ++q)
+                        nraw[q] = pa[min(lane + 64 * q, chunks - 1)];
+                }
+                while (mask) {
+                    mask &= mask - 1;
+                    const int i = __shfl(ci, src, 64);
+                    const double na = __shfl(pna, src, 64);
+                    uint4 araw[CPL];
+#pragma unroll
+                    for (int q = 0; q < CPL; ++q)
+                        araw[q] = nraw[q];
+                    if (mask) {
+                        src = __ffsll((long long)mask) - 1;
+                        const uint4 *pa = reinterpret_cast<const uint4 *>(pool_g + (int64_t)__shfl(pid, src, 64) * pool.r);
+#pragma unroll
+                        for (int q = 0; q < CPL; ++q)
+                            nraw[q] = pa[min(lane + 64 * q, chunks - 1)];
+                    }
+                    double dot = 0.0;
+#pragma unroll
+                    for (int q = 0; q < CPL; ++q) {
+                        if (lane + 64 * q < chunks) {
+                            double x[Elem<T>::PER16], y[Elem<T>::PER16];
+                            Elem<T>::widen(araw[q], x);
+                            Elem<T>::widen(braw[q], y);
+#pragma unroll
+                            for (int e = 0; e < Elem<T>::PER16; ++e)
+                                dot = fma(x[e], y[e], dot);
+                        }
+                    }
+                    dot = wave_sum(dot);
+                    const double cs = (na == 0.0 || nb == 0.0) ? 0.0 : dot / (na * nb);
+                    if (cs > bv || (cs == bv && i < bi)) {
+                        bv = cs;
+                        bi = i;
+                    }
+                }
+            } else {
+                while (mask) {
+                    const int src = __ffsll((long long)mask) - 1;
+                    mask &= mask - 1;
+                    const int i = __shfl(ci, src, 64);
+                    const double cs = cosine(l_ids[i]);
+                    if (cs > bv || (cs == bv && i < bi)) {
+                        bv = cs;
+                        bi = i;
+                    }
                 }
             }
         } else {
@@ -425,6 +479,22 @@ __global__ __launch_bounds__(256) void assign_finalize_kernel(int P, TableDesc t
     }
 }
 
+// Workgroups of 256 threads of `kernel` that the current device holds at once (asked once per kernel).
+template <typename K> static int resident_workgroups(K kernel)
+{
+    static int cached = 0;
+    if (cached <= 0) {
+        int per_cu = 0, dev = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 256, 0) != hipSuccess || per_cu <= 0)
+            per_cu = 2;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            cus <= 0)
+            cus = 256;
+        cached = per_cu * cus;
+    }
+    return cached;
+}
+
 void launch_assign(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, const WorkDesc &w, const HeightDesc &h,
                    int height, double thr, double band, int rule)
 {
@@ -432,9 +502,15 @@ void launch_assign(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, co
     assign_reset_kernel<<<1, 1, 0, s>>>(w, height);
     if (cols > 0) {
         assign_screen_kernel<<<(unsigned)((cols + 255) / 256), 256, 0, s>>>(w, h, height, thr, band, rule);
-        const unsigned rgrid = (unsigned)(cols < 4096 ? (cols + 3) / 4 : 1024);
+        unsigned rgrid = 0;
         const int cpl = (pool.r / (pool.dtype == KVFUSE_BF16 ? 8 : 4) + 63) / 64;     // 16-byte chunks per lane
-#define KVF_REFINE(T, C) assign_refine_kernel<T, C><<<rgrid, 256, 0, s>>>(pool, w, h, height, thr, band, rule)
+        // a persistent grid: exactly as many workgroups as the GPU holds at once (a workgroup that had to wait for a
+        // free slot would start its share of the list when the others are nearly done)
+#define KVF_REFINE(T, C)                                                                                         \
+    do {                                                                                                         \
+        rgrid = (unsigned)std::min<int64_t>((cols + 3) / 4, resident_workgroups(assign_refine_kernel<T, C>));    \
+        assign_refine_kernel<T, C><<<rgrid, 256, 0, s>>>(pool, w, h, height, thr, band, rule);                   \
+    } while (0)
         if (pool.dtype == KVFUSE_BF16) {
             if (cpl <= 1) KVF_REFINE(bf16_t, 1);
             else if (cpl <= 2) KVF_REFINE(bf16_t, 2);
