@@ -42,6 +42,128 @@ def make_recipe(wl, name):
     raise SystemExit(f"unknown workload {name}")
 
 
+# The two configurations whose un-fused cache exceeds one GPU's HBM: name -> (full recipe, layers per slab, thresholds).
+# Layers are independent in every step of the path (method section: one table per layer), so such a configuration is
+# processed in slabs of layers that are generated, fused and decoded one after the other in the same buffers, and its
+# totals are sums over the slabs.
+WHOLE_CONFIGS = {
+    "zipf_bff": (lambda wl: wl.zipf_bff(), 4, (0.85, 0.9, 0.95)),        # config 4: 80 layers, 344 GB un-fused
+    "mixed": (lambda wl: wl.mixed(), 4, (0.9,)),                          # config 5: 32 layers, 292 GB un-fused
+}
+
+
+def run_whole_config(args, torch, kb, wl):
+    """Config 4 or 5 as a whole: every layer slab, every threshold of the configuration, decode attention for every
+    request on every layer.  One JSON line; `value` = all logical blocks of all layers over the summed step times."""
+    make, slab_layers, thresholds = WHOLE_CONFIGS[args.workload]
+    rec = make(wl)
+    if args.thr is not None:
+        thresholds = (args.thr,)
+    if args.slab_layers:
+        slab_layers = args.slab_layers
+    dev = "cuda:0"
+    H = rec.kv_heads
+    if rec.layers % slab_layers:
+        raise SystemExit(f"--slab-layers must divide the {rec.layers} layers of {rec.name}")
+    n_slabs = rec.layers // slab_layers
+    if args.max_slabs:
+        n_slabs = min(n_slabs, args.max_slabs)
+    Gs = slab_layers * H
+    elem = 2 if rec.dtype == torch.bfloat16 else 4
+    K = torch.empty(Gs, rec.n, rec.r, device=dev, dtype=rec.dtype)
+    V = torch.empty_like(K)
+    bt = torch.empty(Gs, rec.n, device=dev, dtype=torch.int32)
+    K0, V0, bt0 = torch.empty_like(K), torch.empty_like(V), torch.empty_like(bt)
+    ctx = kb.Context(dev)
+    cache = kb.Cache(K, V, bt, rec.t, rec.d)
+    spec = kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr, rec.group_size)
+    plan = kb.Plan(ctx, cache, spec, args.cand_cap)
+    rs = torch.tensor(rec.req_start, dtype=torch.int32, device=dev)
+    cl = torch.tensor(rec.ctx_len, dtype=torch.int32, device=dev)
+    max_blocks = int(((rec.ctx_len + rec.t - 1) // rec.t).max())
+    ws = torch.empty(kb.decode_workspace_bytes(slab_layers, rec.B, rec.q_heads, H, rec.d, max_blocks), device=dev, dtype=torch.uint8)
+    out = torch.empty(slab_layers, rec.B, rec.q_heads, rec.d, device=dev, dtype=torch.float32)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    per_thr = {}
+    t_gen = 0.0
+    for si in range(n_slabs):
+        layers = list(range(si * slab_layers, min(rec.layers, (si + 1) * slab_layers)))
+        t0 = time.perf_counter()
+        for li, layer in enumerate(layers):
+            m = wl.materialise(rec, dev, groups=range(layer * H, (layer + 1) * H))
+            K0[li * H:(li + 1) * H].copy_(m["K"]); V0[li * H:(li + 1) * H].copy_(m["V"]); bt0[li * H:(li + 1) * H].copy_(m["bt"])
+            del m
+        q = wl.queries(rec, dev, layers=layers)
+        torch.cuda.synchronize()
+        t_gen += time.perf_counter() - t0
+        for thr in thresholds:
+            acc = per_thr.setdefault(thr, {"ms": [], "stage": {}, "fused": 0, "physical": 0, "logical": 0, "flops": 0.0,
+                                           "refined": 0, "overflow": 0, "near": 0, "targets": 0})
+            reps = args.steps + (args.warmup if si == 0 else 0)
+            for rep in range(reps):
+                K.copy_(K0); V.copy_(V0); bt.copy_(bt0)
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                ev[0].record()
+                st = kb.fuse_tree(ctx, plan, thr, want_stats=True, want_timing=True)
+                ev[1].record()
+                kb.paged_decode_attn(ctx, cache, H, q, rs, cl, max_blocks, workspace=ws, out=out)
+                ev[2].record()
+                torch.cuda.synchronize()
+                wall = (time.perf_counter() - t1) * 1e3
+                if si == 0 and rep < args.warmup:
+                    continue
+                acc["ms"].append(wall / 1.0)
+                for k2, v2 in (("norms", st.ms_norms), ("similarity", st.ms_similarity), ("assign", st.ms_assign),
+                               ("merge", st.ms_merge), ("rewrite", st.ms_rewrite), ("decode", ev[1].elapsed_time(ev[2]))):
+                    acc["stage"][k2] = acc["stage"].get(k2, 0.0) + v2 / args.steps
+                if rep == reps - 1:
+                    acc["fused"] += st.fused; acc["physical"] += st.physical_blocks; acc["logical"] += st.logical_blocks
+                    acc["flops"] += st.sim_flops; acc["refined"] += st.refined; acc["overflow"] += st.cand_overflow
+                    acc["near"] += st.near_threshold; acc["targets"] += st.merge_targets
+        print(f"bench.py: slab {si + 1}/{n_slabs} (layers {layers[0]}..{layers[-1]}) done, "
+              + ", ".join(f"thr {t}: {per_thr[t]['ms'][-1]:.1f} ms" for t in thresholds), file=sys.stderr, flush=True)
+    main_thr = rec.thr if rec.thr in per_thr else thresholds[0]
+    a = per_thr[main_thr]
+    slab_ms = [sum(a["ms"][i * args.steps:(i + 1) * args.steps]) / args.steps for i in range(n_slabs)]
+    total_ms = sum(slab_ms)
+    blocks = a["logical"]
+    peak = 2500.0 if rec.dtype == torch.bfloat16 else 157.3
+    sim_tflops = a["flops"] / (a["stage"]["similarity"] * 1e-3) / 1e12
+    phys_bytes = a["physical"] * rec.r * elem * 2
+    line = {
+        "metric": "KV blocks fused/sec (+ % MFMA peak); fused-table decode attn HBM GB/s",
+        "value": blocks / (total_ms * 1e-3), "unit": "blocks/s",
+        "value_is": "logical KV blocks of ALL layers through norms, the whole fusion tree and one decode-attention step, over the "
+                    "summed step times of the layer slabs (the un-fused cache exceeds one GPU's HBM; layers are independent, "
+                    "so the configuration runs slab after slab in the same buffers and totals are sums over slabs)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": total_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if rec.dtype == torch.bfloat16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{rec.name} (whole configuration): {rec.layers} layers x {H} KV heads in {n_slabs} slabs of "
+                               f"{slab_layers} layers, d {rec.d}, block {rec.t}, {rec.B} requests, {rec.n} logical blocks per group, "
+                               f"thr {main_thr}; decode attention for every request on every layer",
+                   "groups": n_slabs * Gs, "logical_blocks": blocks, "physical_blocks_after": a["physical"],
+                   "compression_ratio": blocks / a["physical"] if a["physical"] else 0.0, "fused": a["fused"],
+                   "near_threshold": a["near"], "refined_fp64": a["refined"], "cand_overflow": a["overflow"],
+                   "slabs": n_slabs, "slab_layers": slab_layers,
+                   "unfused_cache_GB": rec.layers * H * rec.n * rec.r * elem * 2 / 1e9},
+        "stages_ms": a["stage"],
+        "per_slab_ms": {"min": min(slab_ms), "median": sorted(slab_ms)[len(slab_ms) // 2], "max": max(slab_ms), "all": slab_ms},
+        "thresholds": {str(t): {"ms_total": sum(per_thr[t]["ms"]) / args.steps, "compression_ratio": per_thr[t]["logical"] / max(per_thr[t]["physical"], 1),
+                                "fused": per_thr[t]["fused"], "refined_fp64": per_thr[t]["refined"], "stages_ms": per_thr[t]["stage"]}
+                       for t in thresholds},
+        "decode": {"ms": a["stage"]["decode"], "physical_GBps": phys_bytes / (a["stage"]["decode"] * 1e-3) / 1e9,
+                   "frac_of_hbm_peak_physical": phys_bytes / (a["stage"]["decode"] * 1e-3) / 1e9 / 8000.0},
+        "merge": {"ms": a["stage"]["merge"],
+                  "GBps": (2 * a["targets"] + a["fused"]) * rec.r * elem * 2 / (a["stage"]["merge"] * 1e-3) / 1e9},
+        "roofline": {"kernel": "similarity_ring_kernel", "bound": "mfma", "achieved": sim_tflops, "peak": peak, "unit": "TFLOP/s",
+                     "frac": sim_tflops / peak, "traffic": None, "flops_total": a["flops"], "ms_total": a["stage"]["similarity"]},
+        "generation_s": t_gen,
+    }
+    print(json.dumps(line))
+
+
 def cpu_baseline(wl, reduced=False):
     """Time the oracle (as it stands) on the host cores over a bounded sample of the workload the GPU is timed on:
     one group per core (at least 8 groups) of the llama8b_bff recipe at its full per-group shape, 64 requests x 128
@@ -181,6 +303,8 @@ def main():
                     help="reading of Algorithm 1's threshold line: most similar row, or first row above the threshold")
     ap.add_argument("--shortest-first", action="store_true",
                     help="build the tree over the requests in ascending number of blocks (remark on the order of requests)")
+    ap.add_argument("--slab-layers", type=int, default=0, help="layers per slab of a whole-configuration run (zipf_bff, mixed)")
+    ap.add_argument("--max-slabs", type=int, default=0, help="stop a whole-configuration run after this many slabs (quick checks)")
     ap.add_argument("--per-height", action="store_true",
                     help="after the timed steps, run one more fusion height by height and add a per-height table of the "
                          "similarity stage (set sizes, valid and issued MFMA work, bytes loaded, time) to the output")
@@ -198,6 +322,9 @@ def main():
     from paper_2601_03067_amd import workloads as wl
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.workload in WHOLE_CONFIGS:
+        run_whole_config(args, torch, kb, wl)
+        return
     dev = "cuda:0"
     rec = make_recipe(wl, args.workload)
     if args.thr is not None:

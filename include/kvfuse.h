@@ -24,7 +24,8 @@
  *     r * sizeof(element) must be a multiple of 128 bytes and at most 32 KiB (KVFUSE_ESHAPE otherwise).
  *     The fusion steps never look inside a block, so the paper's own vector -- one per block over all KV heads
  *     of a layer (method section: r = t*h*d, one table per layer) -- is the same call with G = layers,
- *     d := h*d and the pool laid out [layers][P][t][h][d]; the attention entry points need the per-head layout.
+ *     d := h*d and the pool laid out [layers][P][t][h][d]; kvfuse_paged_decode_attn_all_heads decodes through such a
+ *     cache, the other attention entry points need the per-head layout.
  *   - Representation (method section: one unit vector and one scalar norm per block): logical block
  *     x of group g stands for  scale[g][x] * stored(bt[g][x]).  Blocks that were never fused stay as they
  *     were written (scale exactly 1); a fused representative is stored as a unit vector rounded to the
@@ -231,6 +232,17 @@ int kvfuse_paged_decode_attn(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvf
                              int32_t layer_begin, int32_t n_layers, const void *q, const int32_t *req_start,
                              const int32_t *ctx_len, int32_t B, int32_t Hq, int32_t max_blocks, float sm_scale,
                              void *workspace, size_t workspace_bytes, float *out);
+
+/* The same decode step over the paper's own block vector (method section: r = t * h * d, one vector per block over
+ * all KV heads of a layer, one block table per layer).  The pool is laid out [layers][P][t][kv_heads][head size]
+ * (pool.G = layers, pool.d = kv_heads * head size), the table and the scales are [layers][n]: every KV head of a layer
+ * reads its head-size slice of the token rows of the same blocks, through the same table entry and the same pair of
+ * scales.  q, out, req_start, ctx_len, the workspace (kvfuse_decode_workspace_bytes with d = head size) and the limits
+ * are those of kvfuse_paged_decode_attn; head size in {64, 128}. */
+int kvfuse_paged_decode_attn_all_heads(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table, int32_t kv_heads,
+                                       int32_t layer_begin, int32_t n_layers, const void *q, const int32_t *req_start,
+                                       const int32_t *ctx_len, int32_t B, int32_t Hq, int32_t max_blocks, float sm_scale,
+                                       void *workspace, size_t workspace_bytes, float *out);
 
 /* The same decode step for callers that cannot allocate device memory or provide a workspace (code under HIP graph
  * capture, tight serving loops, harnesses that forbid allocation).  The split-KV partial states live in a static

@@ -26,6 +26,7 @@ EXPORTS = [
     "kvfuse_plan_destroy", "kvfuse_plan_heights", "kvfuse_plan_view", "kvfuse_block_norms", "kvfuse_leaf_sets",
     "kvfuse_similarity", "kvfuse_assign", "kvfuse_merge", "kvfuse_rewrite_block_table", "kvfuse_fuse_tree",
     "kvfuse_decode_workspace_bytes", "kvfuse_paged_decode_attn", "kvfuse_paged_decode_attn_static",
+    "kvfuse_paged_decode_attn_all_heads",
 ]
 
 _vp, _i32, _i64, _f32, _f64 = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_double
@@ -84,6 +85,7 @@ lib.kvfuse_fuse_tree.argtypes = [_vp, _vp, _f64, _f64, _vp, _vp, _vp, C.POINTER(
 lib.kvfuse_decode_workspace_bytes.argtypes = [_i32, _i32, _i32, _i32, _i32, _i32, C.POINTER(C.c_size_t)]
 lib.kvfuse_paged_decode_attn.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _i32, _i32, _i32, _vp, _vp, _vp, _i32,
                                          _i32, _i32, _f32, _vp, C.c_size_t, _vp]
+lib.kvfuse_paged_decode_attn_all_heads.argtypes = lib.kvfuse_paged_decode_attn.argtypes
 lib.kvfuse_paged_decode_attn_static.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _i32, _i32, _i32, _vp, _vp, _vp, _i32,
                                                 _i32, _i32, _f32, _vp]
 DECODE_STATIC_SCRATCH_BYTES = 8 << 20
@@ -319,6 +321,25 @@ def paged_decode_attn(ctx, cache, kv_heads, q, req_start, ctx_len, max_blocks, l
     ctx.check(lib.kvfuse_paged_decode_attn(ctx.h, C.byref(cache.pool), C.byref(cache.table), kv_heads, layer_begin, n_layers,
                                            _ptr(q), _ptr(req_start), _ptr(ctx_len), B, Hq, max_blocks, sm_scale,
                                            _ptr(workspace), workspace.numel(), _ptr(out)))
+    return out
+
+
+def paged_decode_attn_all_heads(ctx, cache, kv_heads, q, req_start, ctx_len, max_blocks, layer_begin=0, sm_scale=None,
+                                workspace=None, out=None):
+    """Decode through a cache of all-head blocks: cache.K/V are [layers][P][t * kv_heads * head size], cache.d =
+    kv_heads * head size, one table per layer.  q [n_layers][B][Hq][head size] -> out float32, same shape."""
+    n_layers, B, Hq, hd = q.shape
+    assert q.is_contiguous() and q.dtype == cache.K.dtype and hd * kv_heads == cache.d
+    if sm_scale is None:
+        sm_scale = 1.0 / float(hd) ** 0.5
+    if out is None:
+        out = torch.empty(n_layers, B, Hq, hd, device=q.device, dtype=torch.float32)
+    nbytes = decode_workspace_bytes(n_layers, B, Hq, kv_heads, hd, max_blocks)
+    if workspace is None or workspace.numel() < nbytes:
+        workspace = torch.empty(nbytes, device=q.device, dtype=torch.uint8)
+    ctx.check(lib.kvfuse_paged_decode_attn_all_heads(ctx.h, C.byref(cache.pool), C.byref(cache.table), kv_heads, layer_begin,
+                                                     n_layers, _ptr(q), _ptr(req_start), _ptr(ctx_len), B, Hq, max_blocks,
+                                                     sm_scale, _ptr(workspace), workspace.numel(), _ptr(out)))
     return out
 
 

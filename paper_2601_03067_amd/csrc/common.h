@@ -125,7 +125,7 @@ void launch_rewrite(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, i
 size_t decode_workspace_bytes(int n_layers, int B, int Hq, int kv_heads, int d, int max_blocks);
 int launch_decode(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, int kv_heads, int layer_begin, int n_layers,
                   const void *q, const int32_t *req_start, const int32_t *ctx_len, int B, int Hq, int max_blocks,
-                  float sm_scale, void *workspace, size_t workspace_bytes, float *out);
+                  float sm_scale, void *workspace, size_t workspace_bytes, float *out, bool all_heads = false);
 
 // threshold statistics (threshold.hip)
 void launch_pair_cosines(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, const int32_t *pairs, int n_pairs,

@@ -64,10 +64,14 @@ struct DecodeArgs {
     float *part;   // [tuples][nsplit][REP][D + 2] : o, then m, l
     float *out;    // [n_layers][B][Hq][D]
     int32_t P, n, t, kv_heads, layer_begin, B, Hq, rep, nsplit, blocks_per_split;
+    int32_t gstride;   // groups between consecutive layers of the pool and the table: kv_heads, or 1 with all-head blocks
     float sm_scale;
 };
 
-template <typename T, int D, int REP>
+// AH = all-head blocks (method section: one vector per block over all KV heads, one table per layer): the pool is
+// [layers][P][t][kv_heads][D], so the tokens of a block lie kv_heads * D elements apart, the KV head selects a
+// D-element slice of each token row, and all KV heads of a layer share one block table and one scale per entry.
+template <typename T, int D, int REP, bool AH>
 __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs A)
 {
     constexpr int PER = Elem<T>::PER16;
@@ -86,15 +90,16 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs A)
     const int b = blockIdx.y / A.kv_heads;
     const int kvh = blockIdx.y - b * A.kv_heads;
     const int li = blockIdx.z;
-    const int g = (A.layer_begin + li) * A.kv_heads + kvh;
+    const int g = AH ? A.layer_begin + li : (A.layer_begin + li) * A.kv_heads + kvh;
+    const int64_t row = AH ? (int64_t)A.kv_heads * D : (int64_t)D;      // elements from one token of a block to the next
     const int ctx = A.ctx_len[b];
     const int nb = (ctx + A.t - 1) / A.t;
     const int blk_lo = split * A.blocks_per_split;
     const int blk_hi = min(nb, blk_lo + A.blocks_per_split);
     const int x0 = A.req_start[b];
-    const int64_t r = (int64_t)A.t * D;
-    const T *kg = (const T *)A.kpool + (int64_t)g * A.P * r;
-    const T *vg = (const T *)A.vpool + (int64_t)g * A.P * r;
+    const int64_t r = (int64_t)A.t * row;
+    const T *kg = (const T *)A.kpool + (int64_t)g * A.P * r + (AH ? kvh * D : 0);
+    const T *vg = (const T *)A.vpool + (int64_t)g * A.P * r + (AH ? kvh * D : 0);
     const int32_t *btg = A.bt + (int64_t)g * A.n;
     const float *skg = A.scale_k + (int64_t)g * A.n;
     const float *svg = A.scale_v + (int64_t)g * A.n;
@@ -131,7 +136,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs A)
         for (int sub = 0; sub < A.t; sub += 16) {
             // ---- logits: 16 tokens x 16 heads
             floatx4 z = {0.0f, 0.0f, 0.0f, 0.0f};
-            const uint4 *krow = reinterpret_cast<const uint4 *>(kblk + (int64_t)(sub + ktok) * D + kq * (D / 4));
+            const uint4 *krow = reinterpret_cast<const uint4 *>(kblk + (int64_t)(sub + ktok) * row + kq * (D / 4));
             uint4 kf[NF];
 #pragma unroll
             for (int f = 0; f < NF; ++f)
@@ -140,7 +145,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs A)
             uint4 vf[NPASS];
 #pragma unroll
             for (int ps = 0; ps < NPASS; ++ps)
-                vf[ps] = reinterpret_cast<const uint4 *>(vblk + (int64_t)(sub + ps * RPP + tr) * D)[dl];
+                vf[ps] = reinterpret_cast<const uint4 *>(vblk + (int64_t)(sub + ps * RPP + tr) * row)[dl];
 #pragma unroll
             for (int f = 0; f < NF; ++f)
                 QkMma<T>::run(kf[f], qf[f], z);
@@ -317,7 +322,10 @@ static void launch_decode_t(hipStream_t s, const DecodeArgs &A, int n_layers, in
     const dim3 cgrid(1, (unsigned)(A.B * A.kv_heads), (unsigned)n_layers);
 #define KVF_DEC(R)                                                    \
     do {                                                              \
-        decode_kernel<T, D, R><<<grid, 256, 0, s>>>(A);               \
+        if (A.gstride == 1 && A.kv_heads > 1)                         \
+            decode_kernel<T, D, R, true><<<grid, 256, 0, s>>>(A);     \
+        else                                                          \
+            decode_kernel<T, D, R, false><<<grid, 256, 0, s>>>(A);    \
         if (A.nsplit > 1)                                             \
             decode_combine_kernel<D, R><<<cgrid, 256, 0, s>>>(A);     \
     } while (0)
@@ -333,13 +341,15 @@ static void launch_decode_t(hipStream_t s, const DecodeArgs &A, int n_layers, in
 
 int launch_decode(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, int kv_heads, int layer_begin, int n_layers,
                   const void *q, const int32_t *req_start, const int32_t *ctx_len, int B, int Hq, int max_blocks,
-                  float sm_scale, void *workspace, size_t workspace_bytes, float *out)
+                  float sm_scale, void *workspace, size_t workspace_bytes, float *out, bool all_heads)
 {
+    const int head_dim = all_heads ? pool.d / kv_heads : pool.d;
     DecodeArgs A;
     A.kpool = pool.k; A.vpool = pool.v; A.bt = tab.bt; A.scale_k = tab.scale_k; A.scale_v = tab.scale_v;
     A.q = q; A.req_start = req_start; A.ctx_len = ctx_len; A.out = out;
     A.P = pool.P; A.n = tab.n; A.t = pool.t; A.kv_heads = kv_heads; A.layer_begin = layer_begin; A.B = B; A.Hq = Hq;
     A.rep = Hq / kv_heads;
+    A.gstride = all_heads ? 1 : kv_heads;
     A.sm_scale = sm_scale;
     const int64_t tuples = (int64_t)n_layers * B * kv_heads;
     A.nsplit = pick_nsplit(tuples, max_blocks);
@@ -347,16 +357,16 @@ int launch_decode(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, int
     if (A.blocks_per_split < 1)
         A.blocks_per_split = 1;
     A.part = (float *)workspace;
-    if (A.nsplit > 1 && workspace_bytes < decode_workspace_bytes(n_layers, B, Hq, kv_heads, pool.d, max_blocks))
+    if (A.nsplit > 1 && workspace_bytes < decode_workspace_bytes(n_layers, B, Hq, kv_heads, head_dim, max_blocks))
         return KVFUSE_ENOMEM;
     if (tuples == 0)
         return KVFUSE_OK;
     const int rep_pad = pick_rep(A.rep);
     if (pool.dtype == KVFUSE_BF16) {
-        if (pool.d == 128) launch_decode_t<bf16_t, 128>(s, A, n_layers, rep_pad);
+        if (head_dim == 128) launch_decode_t<bf16_t, 128>(s, A, n_layers, rep_pad);
         else launch_decode_t<bf16_t, 64>(s, A, n_layers, rep_pad);
     } else {
-        if (pool.d == 128) launch_decode_t<float, 128>(s, A, n_layers, rep_pad);
+        if (head_dim == 128) launch_decode_t<float, 128>(s, A, n_layers, rep_pad);
         else launch_decode_t<float, 64>(s, A, n_layers, rep_pad);
     }
     return KVFUSE_OK;

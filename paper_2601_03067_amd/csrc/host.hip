@@ -737,10 +737,10 @@ int kvfuse_decode_workspace_bytes(int32_t n_layers, int32_t B, int32_t Hq, int32
     return KVFUSE_OK;
 }
 
-int kvfuse_paged_decode_attn(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table, int32_t kv_heads,
-                             int32_t layer_begin, int32_t n_layers, const void *q, const int32_t *req_start,
-                             const int32_t *ctx_len, int32_t B, int32_t Hq, int32_t max_blocks, float sm_scale,
-                             void *workspace, size_t workspace_bytes, float *out)
+static int decode_entry(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table, int32_t kv_heads,
+                        int32_t layer_begin, int32_t n_layers, const void *q, const int32_t *req_start, const int32_t *ctx_len,
+                        int32_t B, int32_t Hq, int32_t max_blocks, float sm_scale, void *workspace, size_t workspace_bytes,
+                        float *out, bool all_heads)
 {
     if (!ctx)
         return KVFUSE_EINVAL;
@@ -750,21 +750,43 @@ int kvfuse_paged_decode_attn(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvf
     if (!pool || !pool->k || !pool->v || !table || !table->bt || !table->scale_k || !table->scale_v || !q || !req_start ||
         !ctx_len || !out)
         return fail(c, KVFUSE_EINVAL, "decode: null pointer");
+    const int64_t groups_per_layer = all_heads ? 1 : kv_heads;
     if (kv_heads <= 0 || Hq <= 0 || Hq % kv_heads != 0 || Hq / kv_heads > 16 || B < 0 || n_layers < 0 || layer_begin < 0 ||
-        max_blocks < 0 || (int64_t)(layer_begin + n_layers) * kv_heads > pool->G)
+        max_blocks < 0 || (int64_t)(layer_begin + n_layers) * groups_per_layer > pool->G)
         return fail(c, KVFUSE_EINVAL, "decode: head counts or layer range do not fit the pool");
     if (pool->dtype != KVFUSE_BF16 && pool->dtype != KVFUSE_F32)
         return fail(c, KVFUSE_ESHAPE, "decode: dtype must be KVFUSE_BF16 or KVFUSE_F32");
-    if ((pool->d != 64 && pool->d != 128) || pool->t % 16 != 0 || pool->t <= 0)
-        return fail(c, KVFUSE_ESHAPE, "decode: needs d in {64, 128} and t a multiple of 16");
+    if (all_heads && pool->d % kv_heads != 0)
+        return fail(c, KVFUSE_ESHAPE, "decode (all-head blocks): pool.d must be kv_heads times the head size");
+    const int head_dim = all_heads ? pool->d / kv_heads : pool->d;
+    if ((head_dim != 64 && head_dim != 128) || pool->t % 16 != 0 || pool->t <= 0)
+        return fail(c, KVFUSE_ESHAPE, "decode: needs a head size of 64 or 128 and t a multiple of 16");
     if (B * (int64_t)kv_heads > 65535 || n_layers > 65535)
         return fail(c, KVFUSE_ESHAPE, "decode: B * kv_heads and n_layers must be <= 65535 per call");
     const int rc = launch_decode(c->stream, to_desc(*pool), to_desc(*table), kv_heads, layer_begin, n_layers, q, req_start,
-                                 ctx_len, B, Hq, max_blocks, sm_scale, workspace, workspace_bytes, out);
+                                 ctx_len, B, Hq, max_blocks, sm_scale, workspace, workspace_bytes, out, all_heads);
     if (rc)
         return fail(c, rc, "decode: workspace too small");
     KVF_HIP(c, hipGetLastError());
     return KVFUSE_OK;
+}
+
+int kvfuse_paged_decode_attn(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table, int32_t kv_heads,
+                             int32_t layer_begin, int32_t n_layers, const void *q, const int32_t *req_start,
+                             const int32_t *ctx_len, int32_t B, int32_t Hq, int32_t max_blocks, float sm_scale,
+                             void *workspace, size_t workspace_bytes, float *out)
+{
+    return decode_entry(ctx, pool, table, kv_heads, layer_begin, n_layers, q, req_start, ctx_len, B, Hq, max_blocks, sm_scale,
+                        workspace, workspace_bytes, out, false);
+}
+
+int kvfuse_paged_decode_attn_all_heads(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_table *table, int32_t kv_heads,
+                                       int32_t layer_begin, int32_t n_layers, const void *q, const int32_t *req_start,
+                                       const int32_t *ctx_len, int32_t B, int32_t Hq, int32_t max_blocks, float sm_scale,
+                                       void *workspace, size_t workspace_bytes, float *out)
+{
+    return decode_entry(ctx, pool, table, kv_heads, layer_begin, n_layers, q, req_start, ctx_len, B, Hq, max_blocks, sm_scale,
+                        workspace, workspace_bytes, out, true);
 }
 
 }  // extern "C"

@@ -675,6 +675,51 @@ def test_decode_matches_oracle(kb, oracle, case):
     assert worst <= (1e-4 if rec.dtype == torch.float32 else 5e-3)
 
 
+@pytest.mark.parametrize("case", ["bf16_h4_d128_gqa2", "bf16_h2_d64_gqa8_t32", "f32_h2_d64_split"])
+def test_decode_through_all_head_blocks_matches_oracle(kb, oracle, case):
+    """The paper's own vector (method section: r = t * h * d, one table per layer): fusion over all-head blocks, then
+    decode attention through the per-layer table with kvfuse_paged_decode_attn_all_heads.  The oracle sees the same
+    cache as H per-head pools that are strided views of the all-head pool and share the layer's table and scales."""
+    _say("all-head decode case", case)
+    if case == "bf16_h4_d128_gqa2":
+        H, hd, rep, kw = 4, 128, 2, dict(n_req=5, tokens=16 * 40, layers=2, pool=80, t=16)
+    elif case == "bf16_h2_d64_gqa8_t32":
+        H, hd, rep, kw = 2, 64, 8, dict(n_req=4, tokens=32 * 25, layers=1, pool=40, t=32)
+    else:
+        H, hd, rep, kw = 2, 64, 2, dict(n_req=2, tokens=16 * 300, layers=1, pool=60, t=16, dtype=torch.float32)
+    rec = wl.zipf_bff(kv_heads=1, d=H * hd, thr=0.9, **kw)        # for the fusion steps: G = layers, d := h * d
+    mat = wl.materialise(rec, DEV, phys_perm=True)
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, band=max(1e-3, 1.25 * rec.r * 2.0 ** -22))
+    assert stats.fused > 0
+    Hq = H * rep
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(wl.MASTER_SEED + 11)
+    q = torch.randn(rec.layers, rec.B, Hq, hd, generator=gen).to(rec.dtype).to(DEV)
+    rs = torch.tensor(rec.req_start, dtype=torch.int32, device=DEV)
+    cl = torch.tensor(rec.ctx_len - 5, dtype=torch.int32, device=DEV)          # a partial last block
+    mb = int(rec.req_blocks.max())
+    out = kb.paged_decode_attn_all_heads(ctx, cache, H, q, rs, cl, mb)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for layer in range(rec.layers):
+        Kl = wl.to_numpy_pool(cache.K[layer]).reshape(rec.n, rec.t, H, hd)
+        Vl = wl.to_numpy_pool(cache.V[layer]).reshape(rec.n, rec.t, H, hd)
+        Kp = [np.ascontiguousarray(Kl[:, :, h, :]).reshape(rec.n, rec.t * hd) for h in range(H)]
+        Vp = [np.ascontiguousarray(Vl[:, :, h, :]).reshape(rec.n, rec.t * hd) for h in range(H)]
+        bt = [cache.bt[layer].cpu().numpy()] * H
+        sk = [cache.scale_k[layer].cpu().numpy().astype(np.float64)] * H
+        sv = [cache.scale_v[layer].cpu().numpy().astype(np.float64)] * H
+        ref = oracle.paged_decode_attention(q[layer].float().cpu().numpy().astype(np.float64), Kp, Vp, bt, sk, sv, rec.req_start,
+                                            rec.ctx_len - 5, rec.t, hd)
+        worst = max(worst, float(np.abs(out[layer].cpu().numpy() - ref).max()))
+    _say("  max abs err", worst)
+    assert worst <= 2e-2
+    assert worst <= (1e-4 if rec.dtype == torch.float32 else 5e-3)
+    with pytest.raises(kb.KvfuseError) as e:                                     # query heads that the KV heads do not divide
+        kb.paged_decode_attn_all_heads(ctx, cache, H, q[:, :, :Hq - 1].contiguous(), rs, cl, mb)
+    assert e.value.code == kb.EINVAL
+
+
 # ------------------------------------------------------------------------------------------ shared-block decode attention
 
 def _decode_shared(kb, ctx, rec, cache, q, min_cluster_blocks):
