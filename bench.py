@@ -220,6 +220,85 @@ def cpu_baseline(wl, reduced=False):
                       f"`value`: logical blocks through norms, fusion and decode per second"}
 
 
+class PowerSampler:
+    """Socket power from the amdgpu hwmon node (power1_input / power1_average, microwatts), read every few
+    milliseconds by a host thread while a GPU loop runs.  Readings only; nothing on the GPU is touched."""
+
+    def __init__(self):
+        import glob
+        self.files = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input") +
+                            glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average"))[:1]
+        caps = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_cap"))
+        self.cap_W = None
+        try:
+            self.cap_W = float(open(caps[0]).read()) / 1e6 if caps else None
+        except (OSError, ValueError):
+            pass
+
+    def measure(self, fn, seconds, sync):
+        """Run fn() back to back for about `seconds`; return (ms per call, mean W, max W) over the later two thirds."""
+        import threading
+        samples, stop = [], [False]
+
+        def loop():
+            while not stop[0]:
+                try:
+                    samples.append(float(open(self.files[0]).read()) / 1e6)
+                except (OSError, ValueError, IndexError):
+                    pass
+                time.sleep(0.004)
+        th = threading.Thread(target=loop)
+        th.start()
+        sync()
+        t0 = time.perf_counter()
+        n = 0
+        while time.perf_counter() - t0 < seconds:
+            fn()
+            sync()
+            n += 1
+        dt = time.perf_counter() - t0
+        stop[0] = True
+        th.join()
+        tail = samples[len(samples) // 3:]
+        return dt / n * 1e3, (sum(tail) / len(tail) if tail else None), (max(tail) if tail else None)
+
+
+def power_report(kb, kp, ctx, cache, plan, rec, restore, torch):
+    """Socket power while the similarity stage runs on full sets, next to the machine probes and an HBM-bound kernel:
+    shows which limit the dominant kernel runs at (the board's power cap is read from the same hwmon node)."""
+    ps = PowerSampler()
+    if not ps.files:
+        return {"error": "no hwmon power node readable"}
+    dev = cache.K.device
+    sync = lambda: torch.cuda.synchronize(dev)
+    restore()
+    kb.block_norms(ctx, cache)
+    kb.leaf_sets(ctx, plan)
+
+    def sim_tree():        # nothing fuses above 1: every similarity launch of the tree on full sets
+        kb.leaf_sets(ctx, plan)
+        for h in range(plan.n_heights):
+            kb.similarity(ctx, plan, h, 1.5, 1e-3, None)
+            kb.assign(ctx, plan, h, 1.5, 1e-3)
+    out = {"cap_W": ps.cap_W, "sensor": ps.files[0]}
+    ms, mean, mx = ps.measure(lambda: time.sleep(0.05), 1.0, sync)
+    out["idle"] = {"mean_W": mean, "max_W": mx}
+    ms, mean, mx = ps.measure(sim_tree, 2.5, sync)
+    out["similarity_all_heights_full_sets"] = {"ms": ms, "mean_W": mean, "max_W": mx}
+    ms, mean, mx = ps.measure(lambda: kp.mfma_bf16(True, dev), 2.0, sync)
+    out["mfma_probe_random_operands"] = {"mean_W": mean, "max_W": mx}
+    ms, mean, mx = ps.measure(lambda: kp.mfma_bf16(False, dev), 2.0, sync)
+    out["mfma_probe_constant_operands"] = {"mean_W": mean, "max_W": mx}
+    ms, mean, mx = ps.measure(lambda: kb.block_norms(ctx, cache), 1.5, sync)
+    out["block_norms_hbm_stream"] = {"ms": ms, "mean_W": mean, "max_W": mx}
+    cache.K.zero_()
+    kb.block_norms(ctx, cache)
+    ms, mean, mx = ps.measure(sim_tree, 2.5, sync)
+    out["similarity_all_heights_full_sets_zero_pool"] = {"ms": ms, "mean_W": mean, "max_W": mx}
+    restore()
+    return out
+
+
 def similarity_tile_model(ml, mr, big):
     """What the similarity kernel's tiling issues for nodes with ``ml`` left and ``mr`` right blocks (integer arrays
     of one shape): rows and columns of MFMA work per node after the skipped bands (sum over its tiles; work =
@@ -308,6 +387,9 @@ def main():
     ap.add_argument("--per-height", action="store_true",
                     help="after the timed steps, run one more fusion height by height and add a per-height table of the "
                          "similarity stage (set sizes, valid and issued MFMA work, bytes loaded, time) to the output")
+    ap.add_argument("--power", action="store_true",
+                    help="after the timed steps, sample the socket power (hwmon) while the similarity stage, the MFMA probes and "
+                         "the norm pass run, and add the readings and the board's power cap to the output")
     ap.add_argument("--calib-copy-gib", type=float, default=0.0,
                     help="also run a plain device copy of this many GiB (3 times) so that rocprofv3 --pmc FETCH_SIZE / "
                          "WRITE_SIZE readings can be scaled by a kernel of known traffic")
@@ -589,6 +671,8 @@ def main():
     }
     if args.per_height:
         line["per_height"] = per_height_table(kb, ctx, cache, plan, rec, restore, rec.thr)
+    if args.power:
+        line["power"] = power_report(kb, kp, ctx, cache, plan, rec, restore, torch)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, reduced=args.cpu_baseline_reduced)
     print(json.dumps(line))

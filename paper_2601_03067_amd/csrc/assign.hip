@@ -479,22 +479,6 @@ __global__ __launch_bounds__(256) void assign_finalize_kernel(int P, TableDesc t
     }
 }
 
-// Workgroups of 256 threads of `kernel` that the current device holds at once (asked once per kernel).
-template <typename K> static int resident_workgroups(K kernel)
-{
-    static int cached = 0;
-    if (cached <= 0) {
-        int per_cu = 0, dev = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 256, 0) != hipSuccess || per_cu <= 0)
-            per_cu = 2;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            cus <= 0)
-            cus = 256;
-        cached = per_cu * cus;
-    }
-    return cached;
-}
-
 void launch_assign(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, const WorkDesc &w, const HeightDesc &h,
                    int height, double thr, double band, int rule)
 {

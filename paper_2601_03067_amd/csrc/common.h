@@ -112,6 +112,24 @@ static inline TableDesc to_desc(const kvfuse_table &t)
     return TableDesc{t.n, t.bt, t.scale_k, t.scale_v, t.orig_norm_k, t.orig_norm_v, t.refcount, t.remap};
 }
 
+// Workgroups of `threads` threads of `kernel` that the current device holds at once: the size of a persistent grid
+// (a workgroup that had to wait for a free slot would start its share of the work when the others are nearly done).
+// Asked once per kernel.
+template <typename K> static int resident_workgroups(K kernel, int threads = 256)
+{
+    static int cached = 0;
+    if (cached <= 0) {
+        int per_cu = 0, dev = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess || per_cu <= 0)
+            per_cu = 2;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            cus <= 0)
+            cus = 256;
+        cached = per_cu * cus;
+    }
+    return cached;
+}
+
 // launchers, one per source file
 void launch_block_norms(hipStream_t s, const PoolDesc &pool, const TableDesc &tab);
 void launch_leaf_sets(hipStream_t s, const WorkDesc &w, const TableDesc &tab, int P, const int32_t *slot_init);
