@@ -384,6 +384,9 @@ def main():
                     help="build the tree over the requests in ascending number of blocks (remark on the order of requests)")
     ap.add_argument("--slab-layers", type=int, default=0, help="layers per slab of a whole-configuration run (zipf_bff, mixed)")
     ap.add_argument("--max-slabs", type=int, default=0, help="stop a whole-configuration run after this many slabs (quick checks)")
+    ap.add_argument("--screen-prefix", type=int, default=0,
+                    help="elements of every key block the similarity screen multiplies in the TIMED steps (0 = whole blocks, the "
+                         "default; the opt-in prefix screen is measured outside the timed steps either way)")
     ap.add_argument("--per-height", action="store_true",
                     help="after the timed steps, run one more fusion height by height and add a per-height table of the "
                          "similarity stage (set sizes, valid and issued MFMA work, bytes loaded, time) to the output")
@@ -426,6 +429,8 @@ def main():
     plan = kb.Plan(ctx, cache, spec, args.cand_cap)
     rule = {"argmax": kb.RULE_ARGMAX, "first_row": kb.RULE_FIRST_ROW}[args.assign_rule]
     kb.set_assign_rule(ctx, plan, rule)
+    if args.screen_prefix:
+        kb.set_screen_prefix(ctx, plan, args.screen_prefix)
     rs = torch.tensor(rec.req_start, dtype=torch.int32, device=dev)
     cl = torch.tensor(rec.ctx_len, dtype=torch.int32, device=dev)
     max_blocks = int(((rec.ctx_len + rec.t - 1) // rec.t).max())
@@ -573,6 +578,35 @@ def main():
     variants["replicate_rescaled"] = {"ms": sev[0].elapsed_time(sev[1]), "blocks_rewritten_at_least": stats.fused,
                                       "includes": "scatter of scale * representative for K and V, table restore, norm pass"}
 
+    # The opt-in prefix screen (an exact shortcut: similarity over the first quarter of every key block + a bound on the
+    # tails, every candidate evaluated in full in fp64).  Measured outside the timed steps; the tables must be the same.
+    prefix_screen = None
+    if not args.screen_prefix and rec.r >= 512:
+        restore()
+        ref_st = kb.fuse_tree(ctx, plan, rec.thr, want_stats=True)          # the full-length screen on the same input
+        bt_ref, k_ref = cache.bt.clone(), cache.K.clone()
+        fused_ref = ref_st.fused
+        pfx = rec.r // 4
+        kb.set_screen_prefix(ctx, plan, pfx)
+        best = None
+        for _ in range(3):
+            restore()
+            torch.cuda.synchronize()
+            pst = kb.fuse_tree(ctx, plan, rec.thr, want_stats=True, want_timing=True)
+            if best is None or pst.ms_total < best.ms_total:
+                best = pst
+        same = bool(torch.equal(cache.bt, bt_ref)) and bool(torch.equal(cache.K, k_ref)) and best.fused == fused_ref
+        del bt_ref, k_ref
+        ms_equiv = best.ms_total + stage["decode"] / max(args.steps, 1)
+        prefix_screen = {"prefix_elements": pfx, "block_elements": rec.r, "fuse_ms": best.ms_total, "similarity_ms": best.ms_similarity,
+                         "assign_ms": best.ms_assign, "merge_ms": best.ms_merge, "norms_ms": best.ms_norms,
+                         "refined_fp64": best.refined, "cand_overflow": best.cand_overflow,
+                         "tables_and_fused_keys_equal_to_full_screen": same,
+                         "executed_similarity_TFLOPs": best.sim_flops * pfx / rec.r / (best.ms_similarity * 1e-3) / 1e12,
+                         "step_ms_with_decode": ms_equiv, "blocks_per_s_with_decode": rec.G * rec.n / (ms_equiv * 1e-3),
+                         "note": "opt-in (kvfuse_plan_set_screen_prefix); not used in the timed steps, `value` and `roofline`"}
+        kb.set_screen_prefix(ctx, plan, 0)
+
     # decode attention over the un-fused cache (logical = physical bytes): the clean HBM figure of the decode kernel
     restore()
     cache.identity_scales()
@@ -656,6 +690,7 @@ def main():
                   "frac_of_read2_write1_probe": (2 * stats.merge_targets + stats.fused) * blk_bytes * 2 / (stage["merge"] * 1e-3) / 1e9
                                                 / probes["read2_write1_GBps"]},
         "variants": variants,
+        "prefix_screen": prefix_screen,
         "norms": {"ms": stage["norms"], "GBps": logi_bytes / (stage["norms"] * 1e-3) / 1e9},
         "roofline": {"kernel": "similarity_ring_kernel (256 x 256 tile instance on the upper heights, 128 x 128 on the lowest)",
                      "bound": "mfma", "achieved": sim_tflops, "peak": peak,

@@ -380,6 +380,26 @@ double kvfuse_threshold_feedback(double thr, double observed_cr, double target_c
  * waits for the stream). */
 int kvfuse_plan_set_group_mask(kvfuse_ctx *ctx, kvfuse_plan *plan, const uint8_t *enable);
 
+/* ---- prefix screen ------------------------------------------------------------------------------------------ */
+
+/* An exact shortcut for Algorithm 1's product sim <- k_l k_r^T when only the entries above a threshold matter.  With a
+ * prefix of p elements, cos(a, b) <= <a[0:p], b[0:p]> / (|a| |b|) + tail(a) * tail(b), where tail(x) = |x[p:]| / |x|
+ * (Cauchy-Schwarz on the two tails).  The similarity step then multiplies only the first prefix_elements of every key
+ * block and lists a pair as a candidate when this upper bound clears thr - 2 * band; the assignment step evaluates every
+ * candidate in full, in fp64, exactly as it does for the undecided candidates of the full-length screen, so targets,
+ * tables and fused blocks are the same as without the shortcut.  What changes is the work: on caches whose unrelated
+ * blocks spread their energy over the whole block a quarter of the block rejects practically every unrelated pair
+ * (tail product about 0.75 against a threshold of 0.9) and the matrix product shrinks fourfold; a prefix that is too
+ * short for the data (tail product near or above the threshold) only produces more candidates, up to a full fp64 rescan
+ * of the overflowing columns -- slower, never wrong.
+ *   prefix_elements  0 switches the shortcut off (the default); otherwise a multiple of 64 bytes worth of elements, at
+ *                    least 128 bytes and shorter than a block
+ *   tail_share       device [G][P] float, owned by the caller, alive while the plan is used: tail(x) of every key block,
+ *                    rounded up; written by kvfuse_leaf_sets / kvfuse_fuse_tree and after every merge
+ * Applies to the following kvfuse_leaf_sets, kvfuse_similarity (without a dense matrix), kvfuse_assign, kvfuse_merge
+ * and kvfuse_fuse_tree calls on this plan. */
+int kvfuse_plan_set_screen_prefix(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t prefix_elements, float *tail_share);
+
 /* ---- variants of the method ---------------------------------------------------------------------------- */
 
 /* Algorithm 1 loops over the rows of sim, collects for each row the right blocks above the threshold and evicts

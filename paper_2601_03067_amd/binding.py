@@ -126,6 +126,7 @@ lib.kvfuse_threshold_feedback.argtypes = [_f64] * 6
 lib.kvfuse_threshold_feedback.restype = _f64
 lib.kvfuse_plan_set_group_mask.argtypes = [_vp, _vp, _vp]
 lib.kvfuse_plan_set_assign_rule.argtypes = [_vp, _vp, _i32]
+lib.kvfuse_plan_set_screen_prefix.argtypes = [_vp, _vp, _i32, _vp]
 lib.kvfuse_tree_spec_shortest_first.argtypes = [C.POINTER(TreeSpec), _vp, _vp, _vp, _vp]
 lib.kvfuse_replicate_rescaled.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _vp]
 lib.kvfuse_drop_rescale.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table)]
@@ -445,6 +446,16 @@ def set_group_mask(ctx, plan, enable):
         assert enable.dtype == torch.uint8 and enable.is_contiguous() and enable.numel() == plan.cache.pool.G
     plan.group_mask = enable
     ctx.check(lib.kvfuse_plan_set_group_mask(ctx.h, plan.h, _ptr(enable) if enable is not None else None))
+
+
+def set_screen_prefix(ctx, plan, prefix_elements):
+    """kvfuse_plan_set_screen_prefix; allocates the [G][P] tail-share array the call needs and keeps it with the plan."""
+    if prefix_elements:
+        plan.tail_share = torch.empty(plan.cache.G, plan.cache.P, device=plan.cache.K.device, dtype=torch.float32)
+        ctx.check(lib.kvfuse_plan_set_screen_prefix(ctx.h, plan.h, int(prefix_elements), _ptr(plan.tail_share)))
+    else:
+        ctx.check(lib.kvfuse_plan_set_screen_prefix(ctx.h, plan.h, 0, None))
+        plan.tail_share = None
 
 
 def set_assign_rule(ctx, plan, rule):

@@ -95,8 +95,10 @@ __global__ void assign_reset_kernel(WorkDesc w, int height)
 
 // One THREAD per right block: everything the screen settles on its own (no candidate; or one candidate clear of the
 // threshold and of all others by more than 2 * band).  Columns it cannot settle go to the re-check list.
+// bound != 0: the listed values are not cosines but heads of upper bounds (prefix screen): they settle nothing except
+// "no candidate, no fusion", so every listed column goes to the re-check, which then evaluates all its candidates.
 __global__ __launch_bounds__(256) void assign_screen_kernel(WorkDesc w, HeightDesc h, int height, double thr, double band,
-                                                            int rule)
+                                                            int rule, int bound)
 {
     const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (id >= (int64_t)w.G * h.total_r_cap)
@@ -112,7 +114,7 @@ __global__ __launch_bounds__(256) void assign_screen_kernel(WorkDesc w, HeightDe
     const int64_t cidx = (int64_t)g * w.r_stride + c;
     const int cnt = ml > 0 ? w.cand_cnt[cidx] : 0;
     int result = -1;
-    bool recheck = cnt > w.cand_cap;
+    bool recheck = cnt > w.cand_cap || (bound && cnt > 0);
     if (cnt > 0 && !recheck && rule == KVFUSE_RULE_FIRST_ROW) {
         // lowest row that certainly clears the threshold; open = some undecided row comes before it
         int i_def = 0x7FFFFFFF;
@@ -157,7 +159,7 @@ __global__ __launch_bounds__(256) void assign_screen_kernel(WorkDesc w, HeightDe
 // too long for that: both operands are streamed.
 template <typename T, int CPL>
 __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkDesc w, HeightDesc h, int height, double thr,
-                                                            double band, int rule)
+                                                            double band, int rule, int bound)
 {
     const int lane = threadIdx.x & 63;
     const int n_items = w.n_refine[height];
@@ -202,7 +204,7 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
                     ci = w.cand_idx[cidx * w.cand_cap + lane];
                     cv = w.cand_val[cidx * w.cand_cap + lane];
                 }
-                const bool certain = lane < cnt && (double)cv > thr + 2.0 * band;
+                const bool certain = !bound && lane < cnt && (double)cv > thr + 2.0 * band;
                 int i_def = certain ? ci : 0x7FFFFFFF;
 #pragma unroll
                 for (int off = 32; off >= 1; off >>= 1)
@@ -249,7 +251,7 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1)
                 smax = fmaxf(smax, __shfl_xor(smax, off, 64));
-            unsigned long long mask = __ballot(lane < cnt && (double)cv >= (double)smax - 2.0 * band);
+            unsigned long long mask = __ballot(lane < cnt && (bound || (double)cv >= (double)smax - 2.0 * band));
             if constexpr (CPL > 0) {
                 // Every contender costs one block read that nothing else shares, so the chain "row -> physical id ->
                 // block -> dot product" is what a column waits for.  The ids and norms of all contenders are fetched
@@ -485,7 +487,8 @@ void launch_assign(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, co
     const int64_t cols = (int64_t)w.G * h.total_r_cap;
     assign_reset_kernel<<<1, 1, 0, s>>>(w, height);
     if (cols > 0) {
-        assign_screen_kernel<<<(unsigned)((cols + 255) / 256), 256, 0, s>>>(w, h, height, thr, band, rule);
+        const int bound = (w.screen_prefix > 0 && w.screen_prefix < pool.r) ? 1 : 0;
+        assign_screen_kernel<<<(unsigned)((cols + 255) / 256), 256, 0, s>>>(w, h, height, thr, band, rule, bound);
         unsigned rgrid = 0;
         const int cpl = (pool.r / (pool.dtype == KVFUSE_BF16 ? 8 : 4) + 63) / 64;     // 16-byte chunks per lane
         // a persistent grid: exactly as many workgroups as the GPU holds at once (a workgroup that had to wait for a
@@ -493,7 +496,7 @@ void launch_assign(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, co
 #define KVF_REFINE(T, C)                                                                                         \
     do {                                                                                                         \
         rgrid = (unsigned)std::min<int64_t>((cols + 3) / 4, resident_workgroups(assign_refine_kernel<T, C>));    \
-        assign_refine_kernel<T, C><<<rgrid, 256, 0, s>>>(pool, w, h, height, thr, band, rule);                   \
+        assign_refine_kernel<T, C><<<rgrid, 256, 0, s>>>(pool, w, h, height, thr, band, rule, bound);                   \
     } while (0)
         if (pool.dtype == KVFUSE_BF16) {
             if (cpl <= 1) KVF_REFINE(bf16_t, 1);

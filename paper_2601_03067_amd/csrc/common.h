@@ -86,6 +86,8 @@ struct WorkDesc {
     int32_t *counters;   // [G][8]: 0 fused, 1 near-threshold, 2 refined, 3 candidate overflow, 4 invalid ids, 5 entries of shared blocks
     const uint8_t *group_enable;   // [G] or null: groups with 0 are skipped by the similarity step (nothing fuses)
     int32_t *leaf_src;   // [n] position in a set_ids row -> logical entry the leaf step fills it from, -1 = none
+    float *rem_k;        // [G][P] prefix screen: share of each key block's norm that lies beyond the prefix, rounded up
+    int32_t screen_prefix;   // elements of every block the similarity screen multiplies; 0 = the whole block
 };
 
 struct PoolDesc {
@@ -138,6 +140,8 @@ void launch_similarity(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, c
 void launch_assign(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, const WorkDesc &w, const HeightDesc &h,
                    int height, double thr, double band, int rule);
 void launch_merge(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const HeightDesc &h, int height);
+// prefix screen: tail shares of all key blocks (targets_of_height < 0) or of the targets merged at one height
+void launch_prefix_tails(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, int targets_of_height);
 void launch_rewrite(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, int32_t *free_list, int32_t *n_free,
                     int32_t *n_phys);
 size_t decode_workspace_bytes(int n_layers, int B, int Hq, int kv_heads, int d, int max_blocks);

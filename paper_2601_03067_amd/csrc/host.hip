@@ -259,6 +259,8 @@ static void carve(Carver &cv, int G, int n, int n_slots, int max_r, int max_l, i
     w.counters = cv.take<int32_t>((size_t)G * 8);
     w.group_enable = nullptr;
     w.leaf_src = cv.take<int32_t>((size_t)std::max(n, 1));
+    w.rem_k = nullptr;
+    w.screen_prefix = 0;
     slot_init = cv.take<int32_t>(n_slots);
     for (HostHeight &h : hs) {
         const size_t nn = h.l_off.size();
@@ -519,6 +521,7 @@ int kvfuse_leaf_sets(kvfuse_ctx *ctx, kvfuse_plan *plan)
     if (!ctx || !plan)
         return KVFUSE_EINVAL;
     launch_leaf_sets(ctx->c.stream, plan->p.work, plan->p.tab, plan->p.pool.P, plan->p.slot_init);
+    launch_prefix_tails(ctx->c.stream, plan->p.pool, plan->p.work, -1);      // no-op unless the prefix screen is on
     KVF_HIP(&ctx->c, hipGetLastError());
     return KVFUSE_OK;
 }
@@ -565,6 +568,7 @@ int kvfuse_merge(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t height)
     if (rc)
         return rc;
     launch_merge(ctx->c.stream, plan->p.pool, plan->p.work, plan->p.heights[height].dev, height);
+    launch_prefix_tails(ctx->c.stream, plan->p.pool, plan->p.work, height);
     KVF_HIP(&ctx->c, hipGetLastError());
     return KVFUSE_OK;
 }
@@ -622,6 +626,7 @@ int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band
     KVF_TRY(mark());
     launch_block_norms(c->stream, p.pool, p.tab);
     launch_leaf_sets(c->stream, p.work, p.tab, p.pool.P, p.slot_init);
+    launch_prefix_tails(c->stream, p.pool, p.work, -1);
     KVF_TRY(mark());
     for (int hgt = 0; hgt < nh; ++hgt) {
         const HeightDesc &d = p.heights[hgt].dev;
@@ -630,6 +635,7 @@ int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band
         launch_assign(c->stream, p.pool, p.tab, p.work, d, hgt, thr, band, p.assign_rule);
         KVF_TRY(mark());
         launch_merge(c->stream, p.pool, p.work, d, hgt);
+        launch_prefix_tails(c->stream, p.pool, p.work, hgt);
         KVF_TRY(mark());
     }
     launch_rewrite(c->stream, p.pool, p.tab, free_list, n_free, n_phys);
@@ -713,6 +719,29 @@ int kvfuse_plan_set_group_mask(kvfuse_ctx *ctx, kvfuse_plan *plan, const uint8_t
         KVF_HIP(c, hipStreamSynchronize(c->stream));
         KVF_HIP(c, hipMemcpy(p.group_enable_host.data(), enable, (size_t)p.work.G, hipMemcpyDeviceToHost));
     }
+    return KVFUSE_OK;
+}
+
+int kvfuse_plan_set_screen_prefix(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t prefix_elements, float *tail_share)
+{
+    if (!ctx)
+        return KVFUSE_EINVAL;
+    if (!plan)
+        return fail(&ctx->c, KVFUSE_EINVAL, "screen prefix: null plan");
+    Plan &p = plan->p;
+    if (prefix_elements == 0) {
+        p.work.screen_prefix = 0;
+        p.work.rem_k = nullptr;
+        return KVFUSE_OK;
+    }
+    const int per_slice = p.pool.dtype == KVFUSE_BF16 ? 32 : 16;     // elements of one 64-byte K slice
+    if (prefix_elements < 0 || prefix_elements >= p.pool.r || prefix_elements % per_slice != 0 || prefix_elements / per_slice < 2)
+        return fail(&ctx->c, KVFUSE_EINVAL, "screen prefix: must be 0, or at least 128 bytes, a multiple of 64 bytes and shorter "
+                                            "than a block");
+    if (!tail_share)
+        return fail(&ctx->c, KVFUSE_EINVAL, "screen prefix: needs a device array of G * P floats");
+    p.work.screen_prefix = prefix_elements;
+    p.work.rem_k = tail_share;
     return KVFUSE_OK;
 }
 

@@ -1,6 +1,8 @@
 // a1: block norms and table initialisation (method section: every block vector keeps its norm; leaf step of
 // Algorithm 1).  Pure HBM stream: every K and V byte is read once; one wavefront per block, 16-byte loads,
 // fp64 accumulation in a fixed order so that identical blocks get bit-identical norms.
+#include <algorithm>
+
 #include "common.h"
 
 namespace kvfuse {
@@ -139,6 +141,64 @@ void launch_leaf_sets(hipStream_t s, const WorkDesc &w, const TableDesc &tab, in
         leaf_sets_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(w, P, tab.bt, slot_init);
     if ((int64_t)w.G * w.n > 0)
         check_ids_kernel<<<(unsigned)(((int64_t)w.G * w.n + 255) / 256), 256, 0, s>>>(w, P, tab.bt, tab.refcount);
+}
+
+// Prefix screen (similarity.hip): rem[b] = |tail of block b| / |block b| for the key blocks, where the tail is everything
+// beyond the first `prefix` elements; fp64 sum of the prefix squares against the stored fp64 norm, rounded up to float
+// with an absolute margin of 1e-6 (the two sums differ in order, which matters when the tail is nearly empty).  One
+// wavefront per block.  With `active` the blocks are the targets that the merge step of one height has just rewritten.
+template <typename T>
+__global__ __launch_bounds__(256) void prefix_tails_kernel(const T *__restrict__ k, const double *__restrict__ norm_k, int64_t n_blocks,
+                                                           int P, int r, int prefix, float *__restrict__ rem,
+                                                           const int4 *__restrict__ active, const int32_t *__restrict__ n_active)
+{
+    const int lane = threadIdx.x & 63;
+    int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t stride = (int64_t)gridDim.x * 4;
+    const int64_t total = active ? (int64_t)*n_active : n_blocks;
+    for (; item < total; item += stride) {
+        int64_t b = item;
+        if (active) {
+            const int4 rec = active[2 * item];
+            b = (int64_t)rec.x * P + rec.y;
+        }
+        const uint4 *p = reinterpret_cast<const uint4 *>(k + b * r);
+        const int chunks = prefix / Elem<T>::PER16;
+        double ss = 0.0;
+        for (int c = lane; c < chunks; c += 64) {
+            double x[Elem<T>::PER16];
+            Elem<T>::widen(p[c], x);
+#pragma unroll
+            for (int e = 0; e < Elem<T>::PER16; ++e)
+                ss = fma(x[e], x[e], ss);
+        }
+        ss = wave_sum(ss);
+        if (lane == 0) {
+            const double nrm = norm_k[b];
+            const double tail2 = fmax(nrm * nrm - ss, 0.0);
+            rem[b] = nrm > 0.0 ? __double2float_ru(fmin(sqrt(tail2) / nrm, 1.0) + 1e-6) : 0.0f;
+        }
+    }
+}
+
+void launch_prefix_tails(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, int targets_of_height)
+{
+    if (w.screen_prefix <= 0 || !w.rem_k)
+        return;
+    const int64_t nb = (int64_t)pool.G * pool.P;
+    const bool act = targets_of_height >= 0;
+    const int64_t want = act ? (int64_t)w.G * w.l_stride : nb;
+    if (want <= 0)
+        return;
+    const unsigned grid = (unsigned)std::min<int64_t>((want + 3) / 4, 256 * 16);
+    const int4 *active = act ? w.active : nullptr;
+    const int32_t *n_active = act ? w.n_active + targets_of_height : nullptr;
+    if (pool.dtype == KVFUSE_BF16)
+        prefix_tails_kernel<bf16_t><<<grid, 256, 0, s>>>((const bf16_t *)pool.k, pool.norm_k, nb, pool.P, pool.r, w.screen_prefix,
+                                                         w.rem_k, active, n_active);
+    else
+        prefix_tails_kernel<float><<<grid, 256, 0, s>>>((const float *)pool.k, pool.norm_k, nb, pool.P, pool.r, w.screen_prefix,
+                                                        w.rem_k, active, n_active);
 }
 
 }  // namespace kvfuse

@@ -71,6 +71,7 @@ __device__ __forceinline__ void emit_candidate(int32_t *__restrict__ cand_cnt, i
 struct SimArgs {
     int32_t G, n, n_slots, r_stride, cand_cap, P, n_items;
     int32_t row_bytes;             // bytes of one block row
+    int32_t nk_screen;             // 64-byte slices of a row that are multiplied: all of them, or a prefix (see PREFIX)
     float thr_floor;
     int64_t total_s;
 };
@@ -99,7 +100,12 @@ constexpr int kRingRowTiles = 4;   // most row tiles of one work item (the host'
 
 // BIG: 256 x 256 tile, 8 wavefronts of 64 x 128, one workgroup per compute unit.  Otherwise 128 x 128, 4 wavefronts
 // of 64 x 64 and a 64 KB ring, two workgroups per compute unit: for nodes whose sets are smaller than a big tile.
-template <typename T, bool BIG, bool DENSE>
+// PREFIX: only the first nk_screen slices of every row are multiplied, and a pair becomes a candidate when an upper
+// bound of its cosine clears the floor: cos(a, b) <= <a_head, b_head> / (|a| |b|) + rem_a * rem_b, where rem_x is the
+// share of |x| that lies beyond the prefix (Cauchy-Schwarz on the tails; `rem` holds it per block, rounded up).  On
+// caches whose unrelated blocks are spread over the whole block length a quarter of the row settles almost every pair;
+// every candidate is then evaluated in full in fp64 by the assignment step, so the decisions are the same.
+template <typename T, bool BIG, bool DENSE, bool PREFIX>
 __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_kernel(
     SimArgs A, const char *__restrict__ kpool, const float *__restrict__ inv_norm, const int32_t *__restrict__ set_ids,
     const int32_t *__restrict__ set_cnt, const int32_t *__restrict__ item_node, const int32_t *__restrict__ item_col0,
@@ -107,8 +113,10 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
     const int32_t *__restrict__ r_off, const int32_t *__restrict__ l_slot, const int32_t *__restrict__ r_slot,
     const int32_t *__restrict__ r_base, const int32_t *__restrict__ r_cap, const int64_t *__restrict__ s_base,
     unsigned long long *__restrict__ best_packed, int32_t *__restrict__ cand_cnt, int32_t *__restrict__ cand_idx,
-    float *__restrict__ cand_val, float *__restrict__ dense_s, const uint8_t *__restrict__ group_enable)
+    float *__restrict__ cand_val, float *__restrict__ dense_s, const uint8_t *__restrict__ group_enable,
+    const float *__restrict__ rem)
 {
+    static_assert(!(DENSE && PREFIX), "the dense matrix is the full-length product");
     constexpr int WN = 2, TM = 2, TN = BIG ? 4 : 2, NT = BIG ? 512 : 256, BM = BIG ? 256 : 128, BN = BM;
     constexpr int WM = NT / 64 / WN;          // wavefronts along the rows
     // MFMA tile (mt, nt) of wavefront (wm, wn) covers rows mt * WM * 32 + wm * 32 .. + 31 and columns
@@ -125,6 +133,8 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
     __shared__ float lds_invl[RT * BM];      // inverse norms of all left rows of the item; NaN past the end
     __shared__ float lds_invr[BN];
     __shared__ float lds_tcol[BN];
+    __shared__ __attribute__((aligned(16))) float lds_reml[PREFIX ? RT * BM : 1];     // PREFIX: tail share of the left rows
+    __shared__ float lds_tcolb[PREFIX ? BN : 1];         // PREFIX: tail share of the right blocks / their inverse norm
     // The column maximum (best_packed) is a diagnostic: the assignment step works from the candidate lists alone.  It
     // is kept only in the instantiation that also writes the dense matrix; in the production one it cost four of
     // the six vector instructions per accumulator in the epilogue, during which the MFMA units of the CU idle.
@@ -163,7 +173,7 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
     const int wm = wave / WN, wn = wave % WN;
     const int half = lane >> 5;
     const int64_t row_bytes = A.row_bytes;
-    const int nk = A.row_bytes >> 6;                          // 64-byte slices per row
+    const int nk = A.nk_screen;                               // 64-byte slices walked per row
     const int n_rt = (row_end - row0 + BM - 1) / BM;
     const char *__restrict__ kg = kpool + (int64_t)g * A.P * row_bytes;
     const float *__restrict__ inv_g = inv_norm + (int64_t)g * A.P;
@@ -231,10 +241,14 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
         const float ir = col < mr ? inv_g[r_ids[col]] : 0.0f;
         lds_invr[x] = ir;
         lds_tcol[x] = col >= mr ? INFINITY : (ir > 0.0f ? A.thr_floor / ir : (A.thr_floor < 0.0f ? -INFINITY : INFINITY));
+        if constexpr (PREFIX)
+            lds_tcolb[x] = (col < mr && ir > 0.0f) ? rem[(int64_t)g * A.P + r_ids[col]] / ir : 0.0f;
     }
     for (int x = tid; x < RT * BM; x += NT) {
         const int row = row0 + x;
         lds_invl[x] = row < row_end ? inv_g[l_ids[row]] : __uint_as_float(0x7FC00000u);
+        if constexpr (PREFIX)
+            lds_reml[x] = row < row_end ? rem[(int64_t)g * A.P + l_ids[row]] : 0.0f;
     }
     if constexpr (BEST) {
 #pragma unroll
@@ -277,8 +291,8 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
         pb0 += 64; pb1 += 64;                                                                                      \
         if (++pf_kt_b == nk) {                                                                                     \
             pf_kt_b = 0;                                                                                           \
-            pb0 -= row_bytes;                                                                                      \
-            pb1 -= row_bytes;                                                                                      \
+            pb0 -= (int64_t)nk * 64;                                                                               \
+            pb1 -= (int64_t)nk * 64;                                                                               \
         }                                                                                                          \
     } while (0)
 #pragma unroll 1
@@ -369,11 +383,12 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
         // ---- epilogue of row tile rt
         {
             uint32_t kmax[TN];
-            float tcol[TN];
+            float tcol[TN], tcolb[TN];
 #pragma unroll
             for (int nt = 0; nt < TN; ++nt) {
                 kmax[nt] = 0u;
                 tcol[nt] = lds_tcol[nt * NT_STRIDE + wn * 32 + (lane & 31)];
+                tcolb[nt] = PREFIX ? lds_tcolb[nt * NT_STRIDE + wn * 32 + (lane & 31)] : 0.0f;
             }
 #pragma unroll
             for (int mt = 0; mt < TM; ++mt)
@@ -382,14 +397,22 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
                     const int rl0 = mt * MT_STRIDE + wm * 32 + eg * 8 + half * 4;
                     const float4 il4 = *reinterpret_cast<const float4 *>(&lds_invl[rt * BM + rl0]);
                     const float il[4] = {il4.x, il4.y, il4.z, il4.w};
+                    float rl[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                    if constexpr (PREFIX) {
+                        const float4 rl4 = *reinterpret_cast<const float4 *>(&lds_reml[rt * BM + rl0]);
+                        rl[0] = rl4.x; rl[1] = rl4.y; rl[2] = rl4.z; rl[3] = rl4.w;
+                    }
 #pragma unroll
                     for (int nt = 0; nt < TN; ++nt) {
-                        float t[4];
+                        float t[4], lim[4];
                         bool hit = false;
 #pragma unroll
                         for (int q = 0; q < 4; ++q) {
                             t[q] = acc[mt][nt][eg * 4 + q] * il[q];
-                            hit |= t[q] > tcol[nt];
+                            // the floor of this pair, lowered by what the unseen tails could add at most (rem is rounded up with a
+                            // margin far above the rounding of this line)
+                            lim[q] = PREFIX ? fmaf(-rl[q], tcolb[nt], tcol[nt]) : tcol[nt];
+                            hit |= t[q] > lim[q];
                             if constexpr (BEST) {
                                 const uint32_t key = (__float_as_uint(fmaxf(t[q], 0.0f)) & ~CODE_MASK) |
                                                      (CODE_MASK - (uint32_t)(mt * 16 + eg * 4 + q));
@@ -400,7 +423,7 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
                             const int cl = nt * NT_STRIDE + wn * 32 + (lane & 31);
 #pragma unroll
                             for (int q = 0; q < 4; ++q)
-                                if (t[q] > tcol[nt]) {
+                                if (t[q] > lim[q]) {
                                     const int row = row0 + rt * BM + rl0 + q;
                                     const float sv = t[q] * lds_invr[cl];
                                     const int k = atomicAdd(&lds_ncand, 1);
@@ -505,18 +528,22 @@ static void launch_ring(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, 
     A.G = w.G; A.n = w.n; A.n_slots = w.n_slots; A.r_stride = w.r_stride; A.cand_cap = w.cand_cap; A.P = pool.P;
     A.n_items = tt.n_items;
     A.row_bytes = pool.r * (int)sizeof(T);
+    const bool prefix = !dense_s && w.screen_prefix > 0 && w.screen_prefix < pool.r;
+    A.nk_screen = (prefix ? w.screen_prefix * (int)sizeof(T) : A.row_bytes) >> 6;
     A.thr_floor = thr_floor;
     A.total_s = h.total_s;
     const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
-#define KVF_SIM_LAUNCH(D)                                                                                              \
-    similarity_ring_kernel<T, BIG, D><<<grid, BIG ? 512 : 256, 0, s>>>(                                                                 \
+#define KVF_SIM_LAUNCH(D, PF)                                                                                          \
+    similarity_ring_kernel<T, BIG, D, PF><<<grid, BIG ? 512 : 256, 0, s>>>(                                                             \
         A, (const char *)pool.k, pool.inv_norm_k, w.set_ids, w.set_cnt, tt.node, tt.col0, tt.row0, tt.rows, h.l_off, h.r_off, \
         h.l_slot, h.r_slot, h.r_base, h.r_cap, h.s_base, w.best_packed, w.cand_cnt, w.cand_idx, w.cand_val, dense_s,           \
-        w.group_enable)
+        w.group_enable, w.rem_k)
     if (dense_s)
-        KVF_SIM_LAUNCH(true);
+        KVF_SIM_LAUNCH(true, false);
+    else if (prefix)
+        KVF_SIM_LAUNCH(false, true);
     else
-        KVF_SIM_LAUNCH(false);
+        KVF_SIM_LAUNCH(false, false);
 #undef KVF_SIM_LAUNCH
 }
 

@@ -167,13 +167,13 @@ def test_single_node_steps_match_oracle(kb, oracle, kind, cand_cap):
 # ------------------------------------------------------------------------------------------ whole tree
 
 def _run_tree_case(kb, oracle, rec, name, cand_cap=16, thr=None, phys_perm=True, group_size=None, groups=None, band=1e-3,
-                   rule="argmax", shortest_first=False):
+                   rule="argmax", shortest_first=False, screen_prefix=0):
     _say("tree case", name, "G", rec.G, "n", rec.n, "r", rec.r, "leaves", len(rec.leaf_start), "cand_cap", cand_cap,
          "rule", rule, "shortest_first", shortest_first)
     mat = wl.materialise(rec, DEV, groups=groups, phys_perm=phys_perm)
     host = gu.host_copy(mat)
     cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, thr=thr, cand_cap=cand_cap, group_size=group_size, band=band, rule=rule,
-                                          shortest_first=shortest_first)
+                                          shortest_first=shortest_first, screen_prefix=screen_prefix)
     res = gu.oracle_fuse(oracle, rec, host, thr=thr, group_size=group_size, rule=rule, shortest_first=shortest_first)
     safe = gu.check_ambiguity(res, name)
     assert len(safe) == len(res)
@@ -257,6 +257,58 @@ def test_tree_zipf_threshold_in_the_thick_of_the_cosines(kb, oracle):
                       thr=1.0 / (1.0 + sigma * sigma))
     cache, plan, stats, res, mat = _run_tree_case(kb, oracle, rec, "zipf_at_threshold", cand_cap=16)
     assert stats.refined > 100 and stats.near_threshold > 100
+
+
+@pytest.mark.parametrize("rule", ["argmax", "first_row"])
+@pytest.mark.parametrize("which", ["small_bf16_quarter", "small_bf16_half_cap2", "zipf_small_quarter", "zipf_at_threshold_half",
+                                   "mixed_small_f32_quarter", "r4096_bf16_eighth", "tiny_too_short_a_prefix"])
+def test_tree_prefix_screen_gives_the_same_tables(kb, oracle, which, rule):
+    """The prefix screen (similarity over the first p elements of every key block + a Cauchy-Schwarz bound on the tails,
+    every candidate evaluated in full in fp64) must give exactly the oracle's tables, pools and counters: with a prefix
+    that rejects nearly everything (a quarter of random blocks), with few candidate slots (overflow -> column rescans),
+    on near-tied Zipf copies, with the threshold in the thick of the cosines, on binary32 pools, on long blocks, under
+    both readings of the threshold line, and with a prefix far too short for the data (every pair a candidate)."""
+    kw = dict(rule=rule)
+    if which == "small_bf16_quarter":
+        rec, kw = _small_bf16(), dict(kw, screen_prefix=64)
+    elif which == "small_bf16_half_cap2":
+        rec, kw = _small_bf16(n_req=5, tokens=900), dict(kw, screen_prefix=128, cand_cap=2)
+    elif which == "zipf_small_quarter":
+        rec = wl.zipf_bff(n_req=8, tokens=32 * 40, layers=1, kv_heads=2, pool=60, t=32, d=64, thr=0.9)
+        kw = dict(kw, screen_prefix=512, cand_cap=8)
+    elif which == "zipf_at_threshold_half":
+        sigma = 0.05
+        rec = wl.zipf_bff(n_req=8, tokens=32 * 40, layers=1, kv_heads=2, pool=60, t=32, d=64, sigma=sigma,
+                          thr=1.0 / (1.0 + sigma * sigma))
+        kw = dict(kw, screen_prefix=1024)
+    elif which == "mixed_small_f32_quarter":
+        rec = wl.mixed(n_req=9, min_tokens=40, max_tokens=900, chunk_tokens=256, layers=1, kv_heads=2, pool=48, t=8, d=32,
+                       dtype=torch.float32)
+        kw = dict(kw, screen_prefix=64)
+    elif which == "r4096_bf16_eighth":
+        rec = wl.zipf_bff(n_req=6, tokens=32 * 150, layers=1, kv_heads=2, pool=400, t=32, d=128, thr=0.95)
+        kw = dict(kw, screen_prefix=512, cand_cap=8)
+    else:
+        rec, kw = wl.tiny_bff(), dict(kw, screen_prefix=64, cand_cap=4)       # 64 of 1024 elements at thr 0.95: the bound rejects nothing
+    cache, plan, stats, res, mat = _run_tree_case(kb, oracle, rec, "prefix_screen_" + which, **kw)
+    assert stats.fused > 0
+    if which == "tiny_too_short_a_prefix":
+        assert stats.cand_overflow > 0
+
+
+def test_prefix_screen_rejects_bad_arguments(kb):
+    rec = _small_bf16()
+    mat = wl.materialise(rec, DEV)
+    ctx = kb.Context(DEV)
+    cache = kb.Cache(mat["K"], mat["V"], mat["bt"], rec.t, rec.d)
+    plan = kb.Plan(ctx, cache, kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr))
+    for bad in (rec.r, rec.r + 32, 32, 48, -64):      # whole block or more, one slice, not whole slices, negative
+        with pytest.raises(kb.KvfuseError) as e:
+            kb.set_screen_prefix(ctx, plan, bad)
+        assert e.value.code == kb.EINVAL
+    assert kb.lib.kvfuse_plan_set_screen_prefix(ctx.h, plan.h, 64, None) == kb.EINVAL      # no tail-share array
+    kb.set_screen_prefix(ctx, plan, 64)
+    kb.set_screen_prefix(ctx, plan, 0)
 
 
 @pytest.mark.parametrize("cand_cap", [16, 2])
