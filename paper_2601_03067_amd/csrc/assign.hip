@@ -147,9 +147,10 @@ __global__ __launch_bounds__(256) void assign_screen_kernel(WorkDesc w, HeightDe
         else
             recheck = true;
     }
-    if (recheck)
-        w.refine[atomicAdd(&w.n_refine[height], 1)] = (int32_t)cidx;
-    else
+    if (recheck) {      // (column, node): the re-check need not search for the node again
+        const int slot = atomicAdd(&w.n_refine[height], 1);
+        reinterpret_cast<int2 *>(w.refine)[slot] = make_int2((int32_t)cidx, node);
+    } else
         w.assign[cidx] = result;
 }
 
@@ -165,10 +166,11 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
     const int n_items = w.n_refine[height];
     const int n_waves = gridDim.x * 4;
     for (int it = blockIdx.x * 4 + (threadIdx.x >> 6); it < n_items; it += n_waves) {
-        const int64_t cidx = w.refine[it];
+        const int2 item = reinterpret_cast<const int2 *>(w.refine)[it];
+        const int64_t cidx = item.x;
+        const int node = item.y;
         const int g = (int)(cidx / w.r_stride);
         const int c = (int)(cidx - (int64_t)g * w.r_stride);
-        const int node = find_node(h.r_base, h.n_nodes, c);
         const int j = c - h.r_base[node];
         const int ml = w.set_cnt[(int64_t)g * w.n_slots + h.l_slot[node]];
         const int32_t *l_ids = w.set_ids + (int64_t)g * w.n + h.l_off[node];

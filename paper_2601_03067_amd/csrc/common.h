@@ -81,7 +81,7 @@ struct WorkDesc {
                          // two members, unused, unused) -- the merge kernel starts its block loads straight from it
     int32_t *seg_slot;   // [G][l_stride] position of a target in the work list
     int32_t *n_active;   // [max_heights]
-    int32_t *refine;     // [G * r_stride] columns (g * r_stride + c) that need the fp64 re-check
+    int32_t *refine;     // [G * r_stride][2] columns that need the fp64 re-check: (g * r_stride + c, node)
     int32_t *n_refine;   // [max_heights]
     int32_t *counters;   // [G][8]: 0 fused, 1 near-threshold, 2 refined, 3 candidate overflow, 4 invalid ids, 5 entries of shared blocks
     const uint8_t *group_enable;   // [G] or null: groups with 0 are skipped by the similarity step (nothing fuses)
@@ -133,15 +133,15 @@ template <typename K> static int resident_workgroups(K kernel, int threads = 256
 }
 
 // launchers, one per source file
-void launch_block_norms(hipStream_t s, const PoolDesc &pool, const TableDesc &tab);
+void launch_block_norms(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, float *rem = nullptr, int prefix = 0);
 void launch_leaf_sets(hipStream_t s, const WorkDesc &w, const TableDesc &tab, int P, const int32_t *slot_init);
 void launch_similarity(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const HeightDesc &h, float thr_floor,
                        float *dense_s);
 void launch_assign(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, const WorkDesc &w, const HeightDesc &h,
                    int height, double thr, double band, int rule);
 void launch_merge(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const HeightDesc &h, int height);
-// prefix screen: tail shares of all key blocks (targets_of_height < 0) or of the targets merged at one height
-void launch_prefix_tails(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, int targets_of_height);
+// prefix screen: tail shares of all key blocks (for callers that run the steps one by one)
+void launch_prefix_tails(hipStream_t s, const PoolDesc &pool, const WorkDesc &w);
 void launch_rewrite(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, int32_t *free_list, int32_t *n_free,
                     int32_t *n_phys);
 size_t decode_workspace_bytes(int n_layers, int B, int Hq, int kv_heads, int d, int max_blocks);
@@ -206,6 +206,13 @@ __device__ __forceinline__ double block_sum_256(double x, double *lds4)
         lds4[threadIdx.x >> 6] = x;
     __syncthreads();
     return ((lds4[0] + lds4[1]) + lds4[2]) + lds4[3];
+}
+
+// Prefix screen: share of a block's norm that lies beyond the prefix, from the sum of the tail squares and the norm,
+// rounded up to float with an absolute margin (the similarity kernel multiplies two of these into an upper bound).
+__device__ __forceinline__ float tail_share(double tail_squares, double norm)
+{
+    return norm > 0.0 ? __double2float_ru(fmin(sqrt(fmax(tail_squares, 0.0)) / norm, 1.0) + 1e-6) : 0.0f;
 }
 
 // Nearest-even rounding of a finite double straight to bfloat16 bits (no intermediate binary32 rounding).

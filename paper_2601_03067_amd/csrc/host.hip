@@ -254,7 +254,7 @@ static void carve(Carver &cv, int G, int n, int n_slots, int max_r, int max_l, i
     w.active = cv.take<int4>(2 * L);
     w.seg_slot = cv.take<int32_t>(L);
     w.n_active = cv.take<int32_t>(kMaxHeights);
-    w.refine = cv.take<int32_t>(R);
+    w.refine = cv.take<int32_t>(2 * R);
     w.n_refine = cv.take<int32_t>(kMaxHeights);
     w.counters = cv.take<int32_t>((size_t)G * 8);
     w.group_enable = nullptr;
@@ -521,7 +521,7 @@ int kvfuse_leaf_sets(kvfuse_ctx *ctx, kvfuse_plan *plan)
     if (!ctx || !plan)
         return KVFUSE_EINVAL;
     launch_leaf_sets(ctx->c.stream, plan->p.work, plan->p.tab, plan->p.pool.P, plan->p.slot_init);
-    launch_prefix_tails(ctx->c.stream, plan->p.pool, plan->p.work, -1);      // no-op unless the prefix screen is on
+    launch_prefix_tails(ctx->c.stream, plan->p.pool, plan->p.work);          // no-op unless the prefix screen is on
     KVF_HIP(&ctx->c, hipGetLastError());
     return KVFUSE_OK;
 }
@@ -568,7 +568,6 @@ int kvfuse_merge(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t height)
     if (rc)
         return rc;
     launch_merge(ctx->c.stream, plan->p.pool, plan->p.work, plan->p.heights[height].dev, height);
-    launch_prefix_tails(ctx->c.stream, plan->p.pool, plan->p.work, height);
     KVF_HIP(&ctx->c, hipGetLastError());
     return KVFUSE_OK;
 }
@@ -624,9 +623,8 @@ int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band
 
     const float floor_f = std::nextafterf((float)(thr - 2.0 * band), -INFINITY);
     KVF_TRY(mark());
-    launch_block_norms(c->stream, p.pool, p.tab);
+    launch_block_norms(c->stream, p.pool, p.tab, p.work.screen_prefix > 0 ? p.work.rem_k : nullptr, p.work.screen_prefix);
     launch_leaf_sets(c->stream, p.work, p.tab, p.pool.P, p.slot_init);
-    launch_prefix_tails(c->stream, p.pool, p.work, -1);
     KVF_TRY(mark());
     for (int hgt = 0; hgt < nh; ++hgt) {
         const HeightDesc &d = p.heights[hgt].dev;
@@ -635,7 +633,6 @@ int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band
         launch_assign(c->stream, p.pool, p.tab, p.work, d, hgt, thr, band, p.assign_rule);
         KVF_TRY(mark());
         launch_merge(c->stream, p.pool, p.work, d, hgt);
-        launch_prefix_tails(c->stream, p.pool, p.work, hgt);
         KVF_TRY(mark());
     }
     launch_rewrite(c->stream, p.pool, p.tab, free_list, n_free, n_phys);

@@ -180,7 +180,10 @@ __global__ __launch_bounds__(256) void merge_group_kernel(PoolDesc pool, WorkDes
         const double len = sqrt(ss);
         const double il = len == 0.0 ? 0.0 : 1.0 / len;
         uint4 *dst = reinterpret_cast<uint4 *>(pool_g + (int64_t)a * pool.r);
-        double ss2 = 0.0;
+        // ss2t: the squares of the new key block beyond the prefix of the prefix screen, for its tail share
+        const bool want_tail = w.rem_k != nullptr && w.screen_prefix > 0;     // uniform over the launch
+        const int prefix_chunks = w.screen_prefix / PER;
+        double ss2 = 0.0, ss2t = 0.0;
 #pragma unroll
         for (int c = 0; c < CPT; ++c) {
             const int ch = tg + GT * c;
@@ -194,9 +197,16 @@ __global__ __launch_bounds__(256) void merge_group_kernel(PoolDesc pool, WorkDes
 #pragma unroll
                 for (int e = 0; e < PER; ++e)
                     ss2 = fma(back[e], back[e], ss2);
+                if (want_tail && ch >= prefix_chunks) {
+#pragma unroll
+                    for (int e = 0; e < PER; ++e)
+                        ss2t = fma(back[e], back[e], ss2t);
+                }
             }
         }
         ss2 = wave_sum(ss2);
+        if (want_tail)
+            ss2t = wave_sum(ss2t);
         if constexpr (GW > 1) {
             if ((tg & 63) == 0)
                 red[grp][wv] = ss2;
@@ -206,12 +216,25 @@ __global__ __launch_bounds__(256) void merge_group_kernel(PoolDesc pool, WorkDes
             for (int q = 0; q < GW; ++q)
                 ss2 += red[grp][q];
             __syncthreads();
+            if (want_tail) {
+                if ((tg & 63) == 0)
+                    red[grp][wv] = ss2t;
+                __syncthreads();
+                ss2t = 0.0;
+#pragma unroll
+                for (int q = 0; q < GW; ++q)
+                    ss2t += red[grp][q];
+                __syncthreads();
+            }
         }
         const double nrm = sqrt(ss2);
         if (live && tg == 0) {
             norm_g[a] = nrm;
-            if (kv == 0)
+            if (kv == 0) {
                 pool.inv_norm_k[(int64_t)g * pool.P + a] = nrm > 0.0 ? (float)(1.0 / nrm) : 0.0f;
+                if (want_tail)
+                    w.rem_k[(int64_t)g * pool.P + a] = tail_share(ss2t, nrm);
+            }
         }
     }
 }
@@ -267,7 +290,9 @@ __global__ __launch_bounds__(256) void merge_kernel(PoolDesc pool, WorkDesc w, H
                     ss = fma(acc[c][e], acc[c][e], ss);
             const double len = sqrt(block_sum_256(ss, red));
             uint4 *dst = reinterpret_cast<uint4 *>(pool_g + (int64_t)a * pool.r);
-            double ss2 = 0.0;
+            const bool want_tail = w.rem_k != nullptr && w.screen_prefix > 0 && kv == 0;     // uniform over the workgroup
+            const int prefix_chunks = w.screen_prefix / PER;
+            double ss2 = 0.0, ss2t = 0.0;
 #pragma unroll
             for (int c = 0; c < MAXC; ++c) {
                 const int ch = tid + 256 * c;
@@ -280,13 +305,24 @@ __global__ __launch_bounds__(256) void merge_kernel(PoolDesc pool, WorkDesc w, H
 #pragma unroll
                     for (int e = 0; e < PER; ++e)
                         ss2 = fma(back[e], back[e], ss2);
+                    if (want_tail && ch >= prefix_chunks) {
+#pragma unroll
+                        for (int e = 0; e < PER; ++e)
+                            ss2t = fma(back[e], back[e], ss2t);
+                    }
                 }
             }
             const double nrm = sqrt(block_sum_256(ss2, red));
+            double tail2 = 0.0;
+            if (want_tail)
+                tail2 = block_sum_256(ss2t, red);
             if (tid == 0) {
                 norm_g[a] = nrm;
-                if (kv == 0)
+                if (kv == 0) {
                     pool.inv_norm_k[(int64_t)g * pool.P + a] = nrm > 0.0 ? (float)(1.0 / nrm) : 0.0f;
+                    if (want_tail)
+                        w.rem_k[(int64_t)g * pool.P + a] = tail_share(tail2, nrm);
+                }
             }
         }
     }

@@ -10,7 +10,8 @@ namespace kvfuse {
 template <typename T>
 __global__ __launch_bounds__(256) void block_norms_kernel(const T *__restrict__ kpool, const T *__restrict__ vpool,
                                                           int64_t n_blocks, int r, double *__restrict__ norm_k,
-                                                          double *__restrict__ norm_v, float *__restrict__ inv_norm_k)
+                                                          double *__restrict__ norm_v, float *__restrict__ inv_norm_k,
+                                                          float *__restrict__ rem, int prefix_chunks)
 {
     const int lane = threadIdx.x & 63;
     const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);   // wave index over 2 * n_blocks
@@ -20,7 +21,10 @@ __global__ __launch_bounds__(256) void block_norms_kernel(const T *__restrict__ 
     const int64_t b = is_v ? w - n_blocks : w;
     const uint4 *src = reinterpret_cast<const uint4 *>((is_v ? vpool : kpool) + b * (int64_t)r);
     const int chunks = r / Elem<T>::PER16;
-    double ss = 0.0;
+    // st: the squares beyond the prefix of the prefix screen, summed on their own (rem = |tail| / |block|, see
+    // prefix_tails_kernel); the norm's own sum keeps its order
+    const bool want_tail = rem != nullptr && !is_v;
+    double ss = 0.0, st = 0.0;
     for (int c = lane; c < chunks; c += 64) {
         const uint4 raw = src[c];
         double x[Elem<T>::PER16];
@@ -28,8 +32,15 @@ __global__ __launch_bounds__(256) void block_norms_kernel(const T *__restrict__ 
 #pragma unroll
         for (int i = 0; i < Elem<T>::PER16; ++i)
             ss = fma(x[i], x[i], ss);
+        if (want_tail && c >= prefix_chunks) {
+#pragma unroll
+            for (int i = 0; i < Elem<T>::PER16; ++i)
+                st = fma(x[i], x[i], st);
+        }
     }
     ss = wave_sum(ss);
+    if (want_tail)
+        st = wave_sum(st);
     if (lane == 0) {
         const double nrm = sqrt(ss);
         if (is_v) {
@@ -37,6 +48,8 @@ __global__ __launch_bounds__(256) void block_norms_kernel(const T *__restrict__ 
         } else {
             norm_k[b] = nrm;
             inv_norm_k[b] = nrm > 0.0 ? (float)(1.0 / nrm) : 0.0f;
+            if (want_tail)
+                rem[b] = tail_share(st, nrm);
         }
     }
 }
@@ -72,17 +85,18 @@ __global__ void table_init_kernel(TableDesc tab, int G, int P, const double *__r
     atomicAdd(&tab.refcount[(int64_t)g * P + p], 1);
 }
 
-void launch_block_norms(hipStream_t s, const PoolDesc &pool, const TableDesc &tab)
+void launch_block_norms(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, float *rem, int prefix)
 {
+    const int pchunks = prefix / (pool.dtype == KVFUSE_BF16 ? 8 : 4);
     const int64_t nb = (int64_t)pool.G * pool.P;
     const unsigned grid = (unsigned)((2 * nb + 3) / 4);
     if (nb > 0) {
         if (pool.dtype == KVFUSE_BF16)
             block_norms_kernel<bf16_t><<<grid, 256, 0, s>>>((const bf16_t *)pool.k, (const bf16_t *)pool.v, nb, pool.r,
-                                                            pool.norm_k, pool.norm_v, pool.inv_norm_k);
+                                                            pool.norm_k, pool.norm_v, pool.inv_norm_k, rem, pchunks);
         else
             block_norms_kernel<float><<<grid, 256, 0, s>>>((const float *)pool.k, (const float *)pool.v, nb, pool.r,
-                                                           pool.norm_k, pool.norm_v, pool.inv_norm_k);
+                                                           pool.norm_k, pool.norm_v, pool.inv_norm_k, rem, pchunks);
         table_clear_kernel<<<(unsigned)((nb + 255) / 256), 256, 0, s>>>(tab.refcount, tab.remap, nb);
     }
     const int64_t ne = (int64_t)pool.G * tab.n;
@@ -144,61 +158,44 @@ void launch_leaf_sets(hipStream_t s, const WorkDesc &w, const TableDesc &tab, in
 }
 
 // Prefix screen (similarity.hip): rem[b] = |tail of block b| / |block b| for the key blocks, where the tail is everything
-// beyond the first `prefix` elements; fp64 sum of the prefix squares against the stored fp64 norm, rounded up to float
-// with an absolute margin of 1e-6 (the two sums differ in order, which matters when the tail is nearly empty).  One
-// wavefront per block.  With `active` the blocks are the targets that the merge step of one height has just rewritten.
+// beyond the first `prefix` elements.  The norm pass and the merge step write it along with the norms (tail_share in
+// common.h); this kernel does the same for a caller who runs the steps one by one (kvfuse_leaf_sets): fp64 sum of the
+// tail squares against the stored norm, one wavefront per block.
 template <typename T>
 __global__ __launch_bounds__(256) void prefix_tails_kernel(const T *__restrict__ k, const double *__restrict__ norm_k, int64_t n_blocks,
-                                                           int P, int r, int prefix, float *__restrict__ rem,
-                                                           const int4 *__restrict__ active, const int32_t *__restrict__ n_active)
+                                                           int r, int prefix, float *__restrict__ rem)
 {
     const int lane = threadIdx.x & 63;
-    int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t stride = (int64_t)gridDim.x * 4;
-    const int64_t total = active ? (int64_t)*n_active : n_blocks;
-    for (; item < total; item += stride) {
-        int64_t b = item;
-        if (active) {
-            const int4 rec = active[2 * item];
-            b = (int64_t)rec.x * P + rec.y;
-        }
+    for (int64_t b = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); b < n_blocks; b += stride) {
         const uint4 *p = reinterpret_cast<const uint4 *>(k + b * r);
-        const int chunks = prefix / Elem<T>::PER16;
-        double ss = 0.0;
-        for (int c = lane; c < chunks; c += 64) {
+        const int chunks = r / Elem<T>::PER16;
+        double st = 0.0;
+        for (int c = prefix / Elem<T>::PER16 + lane; c < chunks; c += 64) {
             double x[Elem<T>::PER16];
             Elem<T>::widen(p[c], x);
 #pragma unroll
             for (int e = 0; e < Elem<T>::PER16; ++e)
-                ss = fma(x[e], x[e], ss);
+                st = fma(x[e], x[e], st);
         }
-        ss = wave_sum(ss);
-        if (lane == 0) {
-            const double nrm = norm_k[b];
-            const double tail2 = fmax(nrm * nrm - ss, 0.0);
-            rem[b] = nrm > 0.0 ? __double2float_ru(fmin(sqrt(tail2) / nrm, 1.0) + 1e-6) : 0.0f;
-        }
+        st = wave_sum(st);
+        if (lane == 0)
+            rem[b] = tail_share(st, norm_k[b]);
     }
 }
 
-void launch_prefix_tails(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, int targets_of_height)
+void launch_prefix_tails(hipStream_t s, const PoolDesc &pool, const WorkDesc &w)
 {
     if (w.screen_prefix <= 0 || !w.rem_k)
         return;
     const int64_t nb = (int64_t)pool.G * pool.P;
-    const bool act = targets_of_height >= 0;
-    const int64_t want = act ? (int64_t)w.G * w.l_stride : nb;
-    if (want <= 0)
+    if (nb <= 0)
         return;
-    const unsigned grid = (unsigned)std::min<int64_t>((want + 3) / 4, 256 * 16);
-    const int4 *active = act ? w.active : nullptr;
-    const int32_t *n_active = act ? w.n_active + targets_of_height : nullptr;
+    const unsigned grid = (unsigned)std::min<int64_t>((nb + 3) / 4, 256 * 16);
     if (pool.dtype == KVFUSE_BF16)
-        prefix_tails_kernel<bf16_t><<<grid, 256, 0, s>>>((const bf16_t *)pool.k, pool.norm_k, nb, pool.P, pool.r, w.screen_prefix,
-                                                         w.rem_k, active, n_active);
+        prefix_tails_kernel<bf16_t><<<grid, 256, 0, s>>>((const bf16_t *)pool.k, pool.norm_k, nb, pool.r, w.screen_prefix, w.rem_k);
     else
-        prefix_tails_kernel<float><<<grid, 256, 0, s>>>((const float *)pool.k, pool.norm_k, nb, pool.P, pool.r, w.screen_prefix,
-                                                        w.rem_k, active, n_active);
+        prefix_tails_kernel<float><<<grid, 256, 0, s>>>((const float *)pool.k, pool.norm_k, nb, pool.r, w.screen_prefix, w.rem_k);
 }
 
 }  // namespace kvfuse

@@ -18,16 +18,19 @@ DEV = "cuda:0"
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("rule", ["argmax", "first_row"])
+@pytest.mark.parametrize("rule", ["argmax", "first_row", "argmax_with_prefix_screen"])
 def test_llama8b_bff_full_size_sampled_groups_and_invariants(oracle, rule):
     kb = gu.load_binding()
+    screen_prefix = 0
+    if rule == "argmax_with_prefix_screen":      # the opt-in shortcut of the similarity step: same tables, by construction
+        rule, screen_prefix = "argmax", 512
     rec = wl.llama8b_bff()
     print("materialise", rec.name, "G", rec.G, "n", rec.n, flush=True)
     mat = wl.materialise(rec, DEV)
     rng = np.random.default_rng(20260103)
     sample = sorted({0, rec.G - 1, *rng.choice(rec.G, size=7, replace=False).tolist()})[:9]
     host = {g: (wl.to_numpy_pool(mat["K"][g]), wl.to_numpy_pool(mat["V"][g]), mat["bt"][g].cpu().numpy().copy()) for g in sample}
-    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, cand_cap=64, rule=rule)       # bench.py's candidate slots
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, cand_cap=64, rule=rule, screen_prefix=screen_prefix)   # bench.py's candidate slots
     print("rule", rule, "gpu fused", stats.fused, "CR", stats.compression_ratio, "refined", stats.refined, flush=True)
 
     # ---- invariants on every group
@@ -202,17 +205,17 @@ def test_one_layer_of_the_large_configs_invariants_and_decode(oracle, config):
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("config", ["config4_zipf_group_of_32768_blocks", "config5_mixed_128_requests"])
+@pytest.mark.parametrize("config", ["config4_zipf_group_of_32768_blocks", "config5_mixed_192_requests"])
 def test_large_config_groups_match_the_oracle_exactly(oracle, config, capsys):
     """Oracle parity at the group sizes of the two large configurations.
 
     Config 4: one whole group at its real size (256 requests x 128 blocks of 32 x 128 = 32768 blocks, 8 heights,
     every block a noisy copy of a Zipf-drawn base: hundreds of near-tied contenders per column, half of all decisions
     through the fp64 re-check).  Config 5: its recipe (ragged requests of 1 - 4 chunks, partial tail blocks, chunk
-    sub-trees below the request tree) at 128 of its 512 requests, about 33 k blocks per group: the largest request
-    count whose oracle run stays near two minutes on the host cores (the run time grows with the square of the
-    request count; the full 141 k-block group would take over half an hour and is checked through invariants and
-    determinism only, in the test above).  Tables, pools, reference counts, free lists, scales and norms are
+    sub-trees below the request tree) at 192 of its 512 requests, about 50 k blocks per group: a request count
+    whose oracle run stays between one and two minutes on 16 host threads (the run time grows with the square of the
+    request count; the full 141 k-block group would take about ten minutes without a sign of life and is checked
+    through invariants and determinism only, in the test above).  Tables, pools, reference counts, free lists, scales and norms are
     compared element by element.  The oracle shares the independent columns of a node out over the host threads."""
     import os
     import time
@@ -220,7 +223,7 @@ def test_large_config_groups_match_the_oracle_exactly(oracle, config, capsys):
     if config.startswith("config4"):
         rec = wl.zipf_bff(layers=1, kv_heads=1)
     else:
-        rec = wl.mixed(layers=1, kv_heads=1, n_req=128)
+        rec = wl.mixed(layers=1, kv_heads=1, n_req=192)
     with capsys.disabled():
         print(f"\n  {config}: materialise G {rec.G} n {rec.n} r {rec.r} requests {rec.B}", flush=True)
     mat = wl.materialise(rec, DEV)
