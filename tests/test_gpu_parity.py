@@ -296,6 +296,32 @@ def test_tree_prefix_screen_gives_the_same_tables(kb, oracle, which, rule):
         assert stats.cand_overflow > 0
 
 
+def test_prefix_screen_step_by_step_equals_the_tree_driver(kb, oracle):
+    """The same tree walked through the single-step entry points (norms, leaf sets, then similarity / assignment / merge
+    per height, rewrite) with the prefix screen on: the tail shares then come from kvfuse_leaf_sets and from the merge
+    step, not from the driver's norm pass.  Must equal the oracle like the driver's result."""
+    rec = _small_bf16(n_req=5, tokens=1000, kv_heads=2)
+    mat = wl.materialise(rec, DEV, phys_perm=True)
+    host = gu.host_copy(mat)
+    ctx = kb.Context(DEV)
+    cache = kb.Cache(mat["K"], mat["V"], mat["bt"], rec.t, rec.d)
+    plan = kb.Plan(ctx, cache, kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr), 16)
+    kb.set_screen_prefix(ctx, plan, 64)
+    kb.block_norms(ctx, cache)
+    kb.leaf_sets(ctx, plan)
+    for h in range(plan.n_heights):
+        kb.similarity(ctx, plan, h, rec.thr)
+        kb.assign(ctx, plan, h, rec.thr)
+        kb.merge(ctx, plan, h)
+    kb.rewrite_block_table(ctx, cache)
+    torch.cuda.synchronize()
+    res = gu.oracle_fuse(oracle, rec, host)
+    assert gu.check_ambiguity(res, "prefix_step_by_step") == list(range(rec.G))
+    for g in range(rec.G):
+        gu.compare_group(res[g], cache, g, False, "prefix_step_by_step")
+    assert sum(int(r.stats[1]) for r in res) > 50
+
+
 def test_prefix_screen_rejects_bad_arguments(kb):
     rec = _small_bf16()
     mat = wl.materialise(rec, DEV)
