@@ -387,6 +387,7 @@ def main():
     ap.add_argument("--screen-prefix", type=int, default=0,
                     help="elements of every key block the similarity screen multiplies in the TIMED steps (0 = whole blocks, the "
                          "default; the opt-in prefix screen is measured outside the timed steps either way)")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
     ap.add_argument("--per-height", action="store_true",
                     help="after the timed steps, run one more fusion height by height and add a per-height table of the "
                          "similarity stage (set sizes, valid and issued MFMA work, bytes loaded, time) to the output")
@@ -607,6 +608,51 @@ def main():
                          "note": "opt-in (kvfuse_plan_set_screen_prefix); not used in the timed steps, `value` and `roofline`"}
         kb.set_screen_prefix(ctx, plan, 0)
 
+    # The same step (fusion without the statistics read-back + decode) recorded once in a HIP graph on a stream of
+    # its own and replayed: what a serving loop pays per step when the ~45 launches are issued by the graph instead
+    # of by the host.  Outside the timed steps; tables must equal those of the eager call.
+    graph_replay = None
+    if not args.no_graph:
+        side = torch.cuda.Stream(dev)
+        restore()
+        ref_st = kb.fuse_tree(ctx, plan, rec.thr, want_stats=True)
+        bt_ref = cache.bt.clone()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            gctx = kb.Context(dev, stream=side)
+            gplan = kb.Plan(gctx, cache, spec, args.cand_cap)
+            kb.set_assign_rule(gctx, gplan, rule)
+
+            def gstep():
+                kb.fuse_tree(gctx, gplan, rec.thr, want_stats=False)
+                kb.paged_decode_attn(gctx, cache, rec.kv_heads, q, rs, cl, max_blocks, workspace=ws, out=out)
+
+            restore()
+            gstep()
+            side.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            restore()
+            with torch.cuda.graph(graph, stream=side):
+                gstep()
+            gev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            g_ms = []
+            for _ in range(max(args.steps, 1)):
+                restore()
+                side.synchronize()
+                gev[0].record(side)
+                graph.replay()
+                gev[1].record(side)
+                side.synchronize()
+                g_ms.append(gev[0].elapsed_time(gev[1]))
+            g_same = bool(torch.equal(cache.bt, bt_ref))
+            graph_replay = {"ms_per_step": sum(g_ms) / len(g_ms), "replays": len(g_ms),
+                            "blocks_per_s": rec.G * rec.n / (sum(g_ms) / len(g_ms) * 1e-3),
+                            "tables_equal_to_eager": g_same, "fused_eager": ref_st.fused,
+                            "note": "fusion (no statistics read-back) + decode as one HIP graph; not used in `value`"}
+            del graph, gplan, gctx
+        del bt_ref
+        torch.cuda.synchronize()
+
     # decode attention over the un-fused cache (logical = physical bytes): the clean HBM figure of the decode kernel
     restore()
     cache.identity_scales()
@@ -691,6 +737,7 @@ def main():
                                                 / probes["read2_write1_GBps"]},
         "variants": variants,
         "prefix_screen": prefix_screen,
+        "graph_replay": graph_replay,
         "norms": {"ms": stage["norms"], "GBps": logi_bytes / (stage["norms"] * 1e-3) / 1e9},
         "roofline": {"kernel": "similarity_ring_kernel (256 x 256 tile instance on the upper heights, 128 x 128 on the lowest)",
                      "bound": "mfma", "achieved": sim_tflops, "peak": peak,
