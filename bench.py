@@ -387,6 +387,8 @@ def main():
     ap.add_argument("--screen-prefix", type=int, default=0,
                     help="elements of every key block the similarity screen multiplies in the TIMED steps (0 = whole blocks, the "
                          "default; the opt-in prefix screen is measured outside the timed steps either way)")
+    ap.add_argument("--screen-fp8", action="store_true",
+                    help="run the timed steps with the fp8 screen (similarity over one-byte copies of the key blocks + error bound)")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
     ap.add_argument("--per-height", action="store_true",
                     help="after the timed steps, run one more fusion height by height and add a per-height table of the "
@@ -430,6 +432,8 @@ def main():
     plan = kb.Plan(ctx, cache, spec, args.cand_cap)
     rule = {"argmax": kb.RULE_ARGMAX, "first_row": kb.RULE_FIRST_ROW}[args.assign_rule]
     kb.set_assign_rule(ctx, plan, rule)
+    if args.screen_fp8:
+        kb.set_screen_fp8(ctx, plan)
     if args.screen_prefix:
         kb.set_screen_prefix(ctx, plan, args.screen_prefix)
     rs = torch.tensor(rec.req_start, dtype=torch.int32, device=dev)
@@ -608,6 +612,38 @@ def main():
                          "note": "opt-in (kvfuse_plan_set_screen_prefix); not used in the timed steps, `value` and `roofline`"}
         kb.set_screen_prefix(ctx, plan, 0)
 
+    # The opt-in fp8 screen (the other exact shortcut: similarity over one-byte e4m3 copies of the unit key blocks on the fp8
+    # matrix cores + each copy's measured error as a bound; candidates the bound cannot settle are evaluated in fp64).
+    # Measured outside the timed steps; the tables must be the same.
+    fp8_screen = None
+    if not args.screen_fp8 and not args.screen_prefix and rec.r % 64 == 0 and rec.r >= 128:
+        restore()
+        ref_st = kb.fuse_tree(ctx, plan, rec.thr, want_stats=True)
+        bt_ref, k_ref = cache.bt.clone(), cache.K.clone()
+        kb.set_screen_fp8(ctx, plan)
+        best = None
+        for _ in range(3):
+            restore()
+            torch.cuda.synchronize()
+            qst = kb.fuse_tree(ctx, plan, rec.thr, want_stats=True, want_timing=True)
+            if best is None or qst.ms_total < best.ms_total:
+                best = qst
+        same = bool(torch.equal(cache.bt, bt_ref)) and bool(torch.equal(cache.K, k_ref)) and best.fused == ref_st.fused
+        err = plan.k8_err[plan.k8_err > 0]
+        del bt_ref, k_ref
+        ms_equiv = best.ms_total + stage["decode"] / max(args.steps, 1)
+        eff = best.sim_flops / (best.ms_similarity * 1e-3) / 1e12
+        fp8_screen = {"fuse_ms": best.ms_total, "similarity_ms": best.ms_similarity, "assign_ms": best.ms_assign,
+                      "merge_ms": best.ms_merge, "norms_ms": best.ms_norms, "refined_fp64": best.refined,
+                      "cand_overflow": best.cand_overflow, "tables_and_fused_keys_equal_to_full_screen": same,
+                      "similarity_TFLOPs": eff, "frac_of_fp8_peak_5000": eff / 5000.0, "frac_of_bf16_peak_2500": eff / 2500.0,
+                      "copy_error_mean": float(err.mean()) if err.numel() else 0.0,
+                      "copy_error_max": float(err.max()) if err.numel() else 0.0,
+                      "extra_device_bytes": int(plan.k8.numel() + plan.k8_err.numel() * 4),
+                      "step_ms_with_decode": ms_equiv, "blocks_per_s_with_decode": rec.G * rec.n / (ms_equiv * 1e-3),
+                      "note": "opt-in (kvfuse_plan_set_screen_fp8); not used in the timed steps, `value` and `roofline`"}
+        kb.set_screen_fp8(ctx, plan, False)
+
     # The same step (fusion without the statistics read-back + decode) recorded once in a HIP graph on a stream of
     # its own and replayed: what a serving loop pays per step when the ~45 launches are issued by the graph instead
     # of by the host.  Outside the timed steps; tables must equal those of the eager call.
@@ -737,6 +773,7 @@ def main():
                                                 / probes["read2_write1_GBps"]},
         "variants": variants,
         "prefix_screen": prefix_screen,
+        "fp8_screen": fp8_screen,
         "graph_replay": graph_replay,
         "norms": {"ms": stage["norms"], "GBps": logi_bytes / (stage["norms"] * 1e-3) / 1e9},
         "roofline": {"kernel": "similarity_ring_kernel (256 x 256 tile instance on the upper heights, 128 x 128 on the lowest)",

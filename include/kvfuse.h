@@ -400,6 +400,29 @@ int kvfuse_plan_set_group_mask(kvfuse_ctx *ctx, kvfuse_plan *plan, const uint8_t
  * and kvfuse_fuse_tree calls on this plan. */
 int kvfuse_plan_set_screen_prefix(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t prefix_elements, float *tail_share);
 
+/* ---- fp8 screen --------------------------------------------------------------------------------------------- */
+
+/* A second exact shortcut for the same product (Algorithm 1, sim <- k_l k_r^T), for the same reason: only entries above
+ * the threshold matter, and every one of those is evaluated again in fp64.  Every key block is kept a second time as
+ * bytes: q(x) = e4m3(x / |x| * 256) (OCP 8-bit float, 4 exponent and 3 mantissa bits), together with its own measured
+ * error err(x) = | x / |x| - q(x) / 256 | (Euclidean norm, fp64, rounded up).  For two blocks
+ *     | cos(a, b) - <q(a), q(b)> / 256^2 |  <=  err(a) + err(b) + err(a) * err(b)
+ * (Cauchy-Schwarz twice), so the similarity step multiplies the byte copies on the fp8 matrix cores (twice the rate of
+ * bfloat16 and half the bytes through LDS and L2) and lists a pair when the product plus this bound clears
+ * thr - 2 * band.  The assignment step evaluates every listed candidate in full in fp64 on the pool itself: targets,
+ * tables and fused blocks are the same as without the shortcut, whatever the data; blocks that quantise badly (err is
+ * measured, not assumed: typically 0.02 - 0.03) only produce more candidates.  Combines with the prefix screen: the product
+ * then runs over the first prefix_elements bytes, which must be a multiple of 64 and at least 128 (set the prefix after
+ * this call, or switch it off first).
+ *   k8      device, G * P * t * d bytes, block b of group g at (g * P + b) * t * d; owned by the caller, alive while the
+ *           plan is used; written by kvfuse_leaf_sets / kvfuse_fuse_tree (all key blocks) and after every merge (the
+ *           rebuilt targets)
+ *   k8_err  device [G][P] float, err(x) of every key block, written along with k8
+ * Two NULLs switch the shortcut off (the default).  Blocks must have a multiple of 64 and at least 128 elements.
+ * Applies to the following kvfuse_leaf_sets, kvfuse_similarity, kvfuse_assign, kvfuse_merge and kvfuse_fuse_tree calls
+ * on this plan; with a dense matrix kvfuse_similarity then writes <q(a), q(b)> / 256^2 instead of the cosine. */
+int kvfuse_plan_set_screen_fp8(kvfuse_ctx *ctx, kvfuse_plan *plan, void *k8, float *k8_err);
+
 /* ---- variants of the method ---------------------------------------------------------------------------- */
 
 /* Algorithm 1 loops over the rows of sim, collects for each row the right blocks above the threshold and evicts

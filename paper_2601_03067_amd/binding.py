@@ -127,6 +127,7 @@ lib.kvfuse_threshold_feedback.restype = _f64
 lib.kvfuse_plan_set_group_mask.argtypes = [_vp, _vp, _vp]
 lib.kvfuse_plan_set_assign_rule.argtypes = [_vp, _vp, _i32]
 lib.kvfuse_plan_set_screen_prefix.argtypes = [_vp, _vp, _i32, _vp]
+lib.kvfuse_plan_set_screen_fp8.argtypes = [_vp, _vp, _vp, _vp]
 lib.kvfuse_tree_spec_shortest_first.argtypes = [C.POINTER(TreeSpec), _vp, _vp, _vp, _vp]
 lib.kvfuse_replicate_rescaled.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _vp]
 lib.kvfuse_drop_rescale.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table)]
@@ -456,6 +457,20 @@ def set_screen_prefix(ctx, plan, prefix_elements):
     else:
         ctx.check(lib.kvfuse_plan_set_screen_prefix(ctx.h, plan.h, 0, None))
         plan.tail_share = None
+
+
+def set_screen_fp8(ctx, plan, on=True):
+    """kvfuse_plan_set_screen_fp8; allocates the one-byte copy of the key pool and its [G][P] error array and keeps them
+    with the plan."""
+    if on:
+        c = plan.cache
+        k8 = torch.empty(c.G, c.P, c.t * c.d, device=c.K.device, dtype=torch.uint8)
+        err = torch.empty(c.G, c.P, device=c.K.device, dtype=torch.float32)
+        ctx.check(lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, _ptr(k8), _ptr(err)))
+        plan.k8, plan.k8_err = k8, err
+    else:
+        ctx.check(lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, None, None))
+        plan.k8 = plan.k8_err = None
 
 
 def set_assign_rule(ctx, plan, rule):

@@ -95,10 +95,14 @@ __global__ void assign_reset_kernel(WorkDesc w, int height)
 
 // One THREAD per right block: everything the screen settles on its own (no candidate; or one candidate clear of the
 // threshold and of all others by more than 2 * band).  Columns it cannot settle go to the re-check list.
-// bound != 0: the listed values are not cosines but heads of upper bounds (prefix screen): they settle nothing except
+// bound != 0: the listed values are not cosines but heads of upper bounds (prefix screen, fp8 screen): they settle nothing except
 // "no candidate, no fusion", so every listed column goes to the re-check, which then evaluates all its candidates.
+// bound == 2: the listed values are products of the fp8 copies: cosines to within band + err_a + err_b + err_a err_b, a
+// radius that differs from candidate to candidate (q8_err holds err per block).  The same two-sided reasoning then works
+// with an interval per candidate: a row is certain when its lower end clears thr + band, and it is the arg-max when its
+// lower end lies above the upper end of every other listed row.
 __global__ __launch_bounds__(256) void assign_screen_kernel(WorkDesc w, HeightDesc h, int height, double thr, double band,
-                                                            int rule, int bound)
+                                                            int rule, int bound, int P)
 {
     const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (id >= (int64_t)w.G * h.total_r_cap)
@@ -114,8 +118,51 @@ __global__ __launch_bounds__(256) void assign_screen_kernel(WorkDesc w, HeightDe
     const int64_t cidx = (int64_t)g * w.r_stride + c;
     const int cnt = ml > 0 ? w.cand_cnt[cidx] : 0;
     int result = -1;
-    bool recheck = cnt > w.cand_cap || (bound && cnt > 0);
-    if (cnt > 0 && !recheck && rule == KVFUSE_RULE_FIRST_ROW) {
+    bool recheck = cnt > w.cand_cap || (bound == 1 && cnt > 0);
+    if (cnt > 0 && !recheck && bound == 2) {
+        const float *qe = w.q8_err + (int64_t)g * P;
+        const int32_t *l_ids = w.set_ids + (int64_t)g * w.n + h.l_off[node];
+        const double eb = (double)qe[w.set_ids[(int64_t)g * w.n + h.r_off[node] + j]];
+        auto radius = [&](int row) {
+            const double ea = (double)qe[l_ids[row]];
+            return band + ea + eb + ea * eb;
+        };
+        if (rule == KVFUSE_RULE_FIRST_ROW) {
+            int i_def = 0x7FFFFFFF;
+            for (int k = 0; k < cnt; ++k) {
+                const int row = w.cand_idx[cidx * w.cand_cap + k];
+                if ((double)w.cand_val[cidx * w.cand_cap + k] - radius(row) > thr + band)
+                    i_def = min(i_def, row);
+            }
+            bool open = false;
+            for (int k = 0; k < cnt; ++k) {
+                const int row = w.cand_idx[cidx * w.cand_cap + k];
+                open |= row < i_def && !((double)w.cand_val[cidx * w.cand_cap + k] - radius(row) > thr + band);
+            }
+            if (open || i_def == 0x7FFFFFFF)
+                recheck = true;
+            else
+                result = i_def;
+        } else {
+            double lo_max = -INFINITY;
+            int kmax = -1;
+            for (int k = 0; k < cnt; ++k) {
+                const double lo = (double)w.cand_val[cidx * w.cand_cap + k] - radius(w.cand_idx[cidx * w.cand_cap + k]);
+                if (lo > lo_max) {
+                    lo_max = lo;
+                    kmax = k;
+                }
+            }
+            bool alone = lo_max > thr + band;
+            for (int k = 0; k < cnt; ++k)
+                if (k != kmax)
+                    alone &= (double)w.cand_val[cidx * w.cand_cap + k] + radius(w.cand_idx[cidx * w.cand_cap + k]) < lo_max;
+            if (alone)
+                result = w.cand_idx[cidx * w.cand_cap + kmax];
+            else
+                recheck = true;
+        }
+    } else if (cnt > 0 && !recheck && rule == KVFUSE_RULE_FIRST_ROW) {
         // lowest row that certainly clears the threshold; open = some undecided row comes before it
         int i_def = 0x7FFFFFFF;
         for (int k = 0; k < cnt; ++k)
@@ -194,6 +241,15 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
             else
                 return cosine_f64<T>(pool_g, pool.r, norm_g, a, b, lane);
         };
+        // radius of a listed value around the cosine: band, or (fp8 screen) band + the two copies' errors; per lane, for
+        // the candidate that lane holds
+        auto radius = [&](int row) __attribute__((always_inline)) {
+            if (bound != 2)
+                return band;
+            const float *qe = w.q8_err + (int64_t)g * pool.P;
+            const double ea = (double)qe[l_ids[row]], eb = (double)qe[b];
+            return band + ea + eb + ea * eb;
+        };
         double bv = -INFINITY;
         int bi = 0x7FFFFFFF;
         if (rule == KVFUSE_RULE_FIRST_ROW) {
@@ -206,7 +262,8 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
                     ci = w.cand_idx[cidx * w.cand_cap + lane];
                     cv = w.cand_val[cidx * w.cand_cap + lane];
                 }
-                const bool certain = !bound && lane < cnt && (double)cv > thr + 2.0 * band;
+                const bool certain = bound == 2 ? (lane < cnt && (double)cv - radius(ci) > thr + band)
+                                                : (!bound && lane < cnt && (double)cv > thr + 2.0 * band);
                 int i_def = certain ? ci : 0x7FFFFFFF;
 #pragma unroll
                 for (int off = 32; off >= 1; off >>= 1)
@@ -253,7 +310,17 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1)
                 smax = fmaxf(smax, __shfl_xor(smax, off, 64));
-            unsigned long long mask = __ballot(lane < cnt && (bound || (double)cv >= (double)smax - 2.0 * band));
+            unsigned long long mask;
+            if (bound == 2) {       // contenders: upper end not below the largest lower end
+                const double rad = lane < cnt ? radius(ci) : 0.0;
+                double lo = lane < cnt ? (double)cv - rad : -INFINITY;
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1)
+                    lo = fmax(lo, __shfl_xor(lo, off, 64));
+                mask = __ballot(lane < cnt && (double)cv + rad >= lo);
+            } else {
+                mask = __ballot(lane < cnt && (bound || (double)cv >= (double)smax - 2.0 * band));
+            }
             if constexpr (CPL > 0) {
                 // Every contender costs one block read that nothing else shares, so the chain "row -> physical id ->
                 // block -> dot product" is what a column waits for.  The ids and norms of all contenders are fetched
@@ -489,8 +556,9 @@ void launch_assign(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, co
     const int64_t cols = (int64_t)w.G * h.total_r_cap;
     assign_reset_kernel<<<1, 1, 0, s>>>(w, height);
     if (cols > 0) {
-        const int bound = (w.screen_prefix > 0 && w.screen_prefix < pool.r) ? 1 : 0;
-        assign_screen_kernel<<<(unsigned)((cols + 255) / 256), 256, 0, s>>>(w, h, height, thr, band, rule, bound);
+        // 1: the listed values are upper bounds only (prefix screen); 2: cosines within a per-pair radius (fp8 screen)
+        const int bound = (w.screen_prefix > 0 && w.screen_prefix < pool.r) ? 1 : (w.q8_k ? 2 : 0);
+        assign_screen_kernel<<<(unsigned)((cols + 255) / 256), 256, 0, s>>>(w, h, height, thr, band, rule, bound, pool.P);
         unsigned rgrid = 0;
         const int cpl = (pool.r / (pool.dtype == KVFUSE_BF16 ? 8 : 4) + 63) / 64;     // 16-byte chunks per lane
         // a persistent grid: exactly as many workgroups as the GPU holds at once (a workgroup that had to wait for a

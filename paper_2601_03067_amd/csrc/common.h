@@ -88,7 +88,13 @@ struct WorkDesc {
     int32_t *leaf_src;   // [n] position in a set_ids row -> logical entry the leaf step fills it from, -1 = none
     float *rem_k;        // [G][P] prefix screen: share of each key block's norm that lies beyond the prefix, rounded up
     int32_t screen_prefix;   // elements of every block the similarity screen multiplies; 0 = the whole block
+    uint8_t *q8_k;       // [G][P][r] fp8 screen: every key block / its norm * kQ8Scale as OCP e4m3 bytes; null = off
+    float *q8_err;       // [G][P] fp8 screen: |block / norm - decoded bytes / kQ8Scale| (Euclidean), rounded up
 };
+
+// fp8 screen: unit key vectors are multiplied by this before conversion to e4m3 (largest finite value 448), which puts
+// the elements of a typical block (around r^-1/2) in the middle of the format's normal range.
+constexpr float kQ8Scale = 256.0f;
 
 struct PoolDesc {
     void *k, *v;
@@ -133,7 +139,8 @@ template <typename K> static int resident_workgroups(K kernel, int threads = 256
 }
 
 // launchers, one per source file
-void launch_block_norms(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, float *rem = nullptr, int prefix = 0);
+void launch_block_norms(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, float *rem = nullptr, int prefix = 0,
+                        uint8_t *q8 = nullptr, float *q8_err = nullptr);
 void launch_leaf_sets(hipStream_t s, const WorkDesc &w, const TableDesc &tab, int P, const int32_t *slot_init);
 void launch_similarity(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const HeightDesc &h, float thr_floor,
                        float *dense_s);
@@ -142,6 +149,9 @@ void launch_assign(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, co
 void launch_merge(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const HeightDesc &h, int height);
 // prefix screen: tail shares of all key blocks (for callers that run the steps one by one)
 void launch_prefix_tails(hipStream_t s, const PoolDesc &pool, const WorkDesc &w);
+// fp8 screen: the e4m3 copy and its error for all key blocks, and for the targets the merge step of a height rebuilt
+void launch_quantise_all(hipStream_t s, const PoolDesc &pool, const WorkDesc &w);
+void launch_quantise_targets(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, int height);
 void launch_rewrite(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, int32_t *free_list, int32_t *n_free,
                     int32_t *n_phys);
 size_t decode_workspace_bytes(int n_layers, int B, int Hq, int kv_heads, int d, int max_blocks);
@@ -160,6 +170,7 @@ void launch_cosine_moments(hipStream_t s, const double *cos_in, int G, int n_pai
 #if defined(__HIPCC__)
 
 typedef uint16_t bf16_t;   // raw bfloat16 bits
+struct fp8_t { uint8_t bits; };   // element type of the fp8 screen copy (OCP e4m3)
 
 __device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 
@@ -213,6 +224,42 @@ __device__ __forceinline__ double block_sum_256(double x, double *lds4)
 __device__ __forceinline__ float tail_share(double tail_squares, double norm)
 {
     return norm > 0.0 ? __double2float_ru(fmin(sqrt(fmax(tail_squares, 0.0)) / norm, 1.0) + 1e-6) : 0.0f;
+}
+
+// fp8 screen: one 16-byte piece of a key block to e4m3 (x * mf with mf = kQ8Scale / norm, the hardware's nearest-even
+// conversion) and the squared error of that piece against the unit vector, decoded with the hardware's own conversion.
+// 16 bytes of a block (PER16 elements) -> PER16 bytes at dst, squares of the copy's errors added to se.
+template <typename T>
+__device__ __forceinline__ void quantise_chunk(const uint4 &raw, double inv, float mf, uint8_t *__restrict__ dst, double &se)
+{
+    constexpr int PER = Elem<T>::PER16;
+    const double inv_scale = 1.0 / (double)kQ8Scale;
+    double x[PER];
+    Elem<T>::widen(raw, x);
+    uint32_t w[PER / 4];
+#pragma unroll
+    for (int i = 0; i < PER / 4; ++i) {
+        int packed = __builtin_amdgcn_cvt_pk_fp8_f32((float)x[4 * i] * mf, (float)x[4 * i + 1] * mf, 0, false);
+        packed = __builtin_amdgcn_cvt_pk_fp8_f32((float)x[4 * i + 2] * mf, (float)x[4 * i + 3] * mf, packed, true);
+        w[i] = (uint32_t)packed;
+        const float d0 = __builtin_amdgcn_cvt_f32_fp8(packed, 0), d1 = __builtin_amdgcn_cvt_f32_fp8(packed, 1);
+        const float d2 = __builtin_amdgcn_cvt_f32_fp8(packed, 2), d3 = __builtin_amdgcn_cvt_f32_fp8(packed, 3);
+        const double dec[4] = {(double)d0, (double)d1, (double)d2, (double)d3};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const double diff = fma(x[4 * i + e], inv, -dec[e] * inv_scale);
+            se = fma(diff, diff, se);
+        }
+    }
+    if constexpr (PER == 8)
+        *reinterpret_cast<uint2 *>(dst) = make_uint2(w[0], w[1]);
+    else
+        *reinterpret_cast<uint32_t *>(dst) = w[0];
+}
+
+__device__ __forceinline__ float quantise_error(double se, double nrm)
+{
+    return nrm > 0.0 ? __double2float_ru(sqrt(se) + 1e-6) : 0.0f;
 }
 
 // Nearest-even rounding of a finite double straight to bfloat16 bits (no intermediate binary32 rounding).

@@ -70,7 +70,9 @@ __device__ __forceinline__ int find_base(const int32_t *__restrict__ base, int n
 
 // GW wavefronts per (target, tensor) item, 4 / GW items per workgroup; CPT = 16-byte chunks per thread.  With GW = 1
 // there are no barriers at all; with GW = 2 each thread holds half as much and more items are in flight per CU.
-template <typename T, int CPT, int GW>
+// Q8 (fp8 screen on): the rebuilt key block's one-byte copy and its error are written here as well, from the rounded
+// values this kernel has just stored.
+template <typename T, int CPT, int GW, bool Q8>
 __global__ __launch_bounds__(256) void merge_group_kernel(PoolDesc pool, WorkDesc w, HeightDesc h, int height)
 {
     constexpr int PER = Elem<T>::PER16;
@@ -184,6 +186,7 @@ __global__ __launch_bounds__(256) void merge_group_kernel(PoolDesc pool, WorkDes
         const bool want_tail = w.rem_k != nullptr && w.screen_prefix > 0;     // uniform over the launch
         const int prefix_chunks = w.screen_prefix / PER;
         double ss2 = 0.0, ss2t = 0.0;
+        uint4 outp[Q8 ? CPT : 1];
 #pragma unroll
         for (int c = 0; c < CPT; ++c) {
             const int ch = tg + GT * c;
@@ -192,6 +195,8 @@ __global__ __launch_bounds__(256) void merge_group_kernel(PoolDesc pool, WorkDes
             for (int e = 0; e < PER; ++e)
                 u[e] = acc[c][e] * il;
             const uint4 packed_out = Store16<T>::pack(u, back);
+            if constexpr (Q8)
+                outp[c] = packed_out;
             if (live && ch < chunks) {
                 dst[ch] = packed_out;
 #pragma unroll
@@ -235,6 +240,33 @@ __global__ __launch_bounds__(256) void merge_group_kernel(PoolDesc pool, WorkDes
                 if (want_tail)
                     w.rem_k[(int64_t)g * pool.P + a] = tail_share(ss2t, nrm);
             }
+        }
+        if constexpr (Q8) {
+            double se = 0.0;
+            if (live && kv == 0) {      // uniform over the item's wavefronts
+                const double inv = nrm > 0.0 ? 1.0 / nrm : 0.0;
+                const float mf = (float)((double)kQ8Scale * inv);
+                uint8_t *q = w.q8_k + ((int64_t)g * pool.P + a) * pool.r;
+#pragma unroll
+                for (int c = 0; c < CPT; ++c) {
+                    const int ch = tg + GT * c;
+                    if (ch < chunks)
+                        quantise_chunk<T>(outp[c], inv, mf, q + (size_t)ch * PER, se);
+                }
+            }
+            se = wave_sum(se);
+            if constexpr (GW > 1) {
+                if ((tg & 63) == 0)
+                    red[grp][wv] = se;
+                __syncthreads();
+                se = 0.0;
+#pragma unroll
+                for (int q = 0; q < GW; ++q)
+                    se += red[grp][q];
+                __syncthreads();
+            }
+            if (live && kv == 0 && tg == 0)
+                w.q8_err[(int64_t)g * pool.P + a] = quantise_error(se, nrm);
         }
     }
 }
@@ -342,7 +374,13 @@ void launch_merge(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const 
         const unsigned wgrid = (unsigned)(want < 256 * 16 ? (want + 1) / 2 + 1 : 256 * 16);
         // up to 4 chunks per lane (bfloat16) one wavefront holds the block and no barrier is needed; longer blocks
         // and binary32 blocks of 4 chunks per lane are split over two wavefronts
-#define KVF_MERGE_G(T, C, W) merge_group_kernel<T, C, W><<<wgrid, 256, 0, s>>>(pool, w, h, height)
+#define KVF_MERGE_G(T, C, W)                                                          \
+    do {                                                                              \
+        if (w.q8_k)                                                                   \
+            merge_group_kernel<T, C, W, true><<<wgrid, 256, 0, s>>>(pool, w, h, height);  \
+        else                                                                          \
+            merge_group_kernel<T, C, W, false><<<wgrid, 256, 0, s>>>(pool, w, h, height); \
+    } while (0)
         if (pool.dtype == KVFUSE_BF16) {
             if (cpl <= 1) KVF_MERGE_G(bf16_t, 1, 1);
             else if (cpl <= 2) KVF_MERGE_G(bf16_t, 2, 1);
@@ -370,6 +408,7 @@ void launch_merge(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const 
         else KVF_MERGE(float, 8);
     }
 #undef KVF_MERGE
+    launch_quantise_targets(s, pool, w, height);        // no-op unless the fp8 screen is on
 }
 
 }  // namespace kvfuse

@@ -40,6 +40,8 @@
 // read.  A load therefore has two to three iterations to arrive (its data is first touched right after the barrier
 // of the iteration before its slice), which covers an L2 miss that goes out to memory; with the barrier at the end of
 // the iteration the same ring gave it one to two.
+#include <type_traits>
+
 #include "common.h"
 
 namespace kvfuse {
@@ -96,6 +98,29 @@ template <> struct MmaV<float> {
     }
 };
 
+template <> struct MmaV<fp8_t> {
+    // 16 bytes per lane = two K steps of 16 e4m3 values (8 bytes per lane each)
+    __device__ static __forceinline__ floatx16 run(const u32x4 a, const u32x4 b, floatx16 c)
+    {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8((long)(((unsigned long long)a.y << 32) | a.x),
+                                                       (long)(((unsigned long long)b.y << 32) | b.x), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8((long)(((unsigned long long)a.w << 32) | a.z),
+                                                       (long)(((unsigned long long)b.w << 32) | b.z), c, 0, 0, 0);
+        return c;
+    }
+};
+
+// One 64-byte K slice of the fp8 copies in a single instruction: v_mfma_f32_32x32x64_f8f6f4 with both operands e4m3
+// (twice the rate of the 16-wide instructions).  A lane supplies 32 bytes per operand, here as two 16-byte fragments;
+// any assignment of a row's 64 bytes to (lane half, byte) works as long as both operands use the same one.
+typedef int intx8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ floatx16 mma_q8(const u32x4 al, const u32x4 ah, const u32x4 bl, const u32x4 bh, floatx16 c)
+{
+    const intx8 a = {(int)al.x, (int)al.y, (int)al.z, (int)al.w, (int)ah.x, (int)ah.y, (int)ah.z, (int)ah.w};
+    const intx8 b = {(int)bl.x, (int)bl.y, (int)bl.z, (int)bl.w, (int)bh.x, (int)bh.y, (int)bh.z, (int)bh.w};
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
+}
+
 constexpr int kRingRowTiles = 4;   // most row tiles of one work item (the host's tile table keeps to it)
 
 // BIG: 256 x 256 tile, 8 wavefronts of 64 x 128, one workgroup per compute unit.  Otherwise 128 x 128, 4 wavefronts
@@ -105,6 +130,11 @@ constexpr int kRingRowTiles = 4;   // most row tiles of one work item (the host'
 // share of |x| that lies beyond the prefix (Cauchy-Schwarz on the tails; `rem` holds it per block, rounded up).  On
 // caches whose unrelated blocks are spread over the whole block length a quarter of the row settles almost every pair;
 // every candidate is then evaluated in full in fp64 by the assignment step, so the decisions are the same.
+// T = fp8_t (fp8 screen): kpool is the e4m3 copy of the key blocks (unit vectors times kQ8Scale, one byte per element),
+// qerr the measured error of every block's copy.  With u = a / |a|, v = b / |b| and U, V their decoded copies / kQ8Scale,
+// |<u, v> - <U, V>| <= |u - U| + |U| |v - V| <= err_a + (1 + err_a) err_b, so <U, V> plus that is an upper bound of the
+// cosine, listed when it clears the floor and evaluated in full by the assignment step like a prefix-screen candidate.
+// The two bounds add up when both shortcuts are on.
 template <typename T, bool BIG, bool DENSE, bool PREFIX>
 __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_kernel(
     SimArgs A, const char *__restrict__ kpool, const float *__restrict__ inv_norm, const int32_t *__restrict__ set_ids,
@@ -114,9 +144,11 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
     const int32_t *__restrict__ r_base, const int32_t *__restrict__ r_cap, const int64_t *__restrict__ s_base,
     unsigned long long *__restrict__ best_packed, int32_t *__restrict__ cand_cnt, int32_t *__restrict__ cand_idx,
     float *__restrict__ cand_val, float *__restrict__ dense_s, const uint8_t *__restrict__ group_enable,
-    const float *__restrict__ rem)
+    const float *__restrict__ rem, const float *__restrict__ qerr)
 {
     static_assert(!(DENSE && PREFIX), "the dense matrix is the full-length product");
+    constexpr bool Q8 = std::is_same<T, fp8_t>::value;
+    constexpr float Q8_INV = 1.0f / kQ8Scale;
     constexpr int WN = 2, TM = 2, TN = BIG ? 4 : 2, NT = BIG ? 512 : 256, BM = BIG ? 256 : 128, BN = BM;
     constexpr int WM = NT / 64 / WN;          // wavefronts along the rows
     // MFMA tile (mt, nt) of wavefront (wm, wn) covers rows mt * WM * 32 + wm * 32 .. + 31 and columns
@@ -135,10 +167,12 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
     __shared__ float lds_tcol[BN];
     __shared__ __attribute__((aligned(16))) float lds_reml[PREFIX ? RT * BM : 1];     // PREFIX: tail share of the left rows
     __shared__ float lds_tcolb[PREFIX ? BN : 1];         // PREFIX: tail share of the right blocks / their inverse norm
+    __shared__ __attribute__((aligned(16))) float lds_errl[Q8 ? RT * BM : 1];        // Q8: copy error of the left rows
+    __shared__ float lds_c1[Q8 ? BN : 1];                // Q8: (1 + copy error of the right block) / its inverse norm
     // The column maximum (best_packed) is a diagnostic: the assignment step works from the candidate lists alone.  It
     // is kept only in the instantiation that also writes the dense matrix; in the production one it cost four of
     // the six vector instructions per accumulator in the epilogue, during which the MFMA units of the CU idle.
-    constexpr bool BEST = DENSE;
+    constexpr bool BEST = DENSE && !Q8;      // (no room in LDS for it next to the fp8 screen's arrays)
     __shared__ uint32_t lds_bkey[BEST ? TN : 1][BEST ? NT : 1];
     __shared__ int lds_brt[BEST ? TN : 1][BEST ? NT : 1];
     constexpr int MAXC = 512;
@@ -233,20 +267,81 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
 #define KVF_MMA_HI(S, MT, NTI) if constexpr (TN > 2) { acc[MT][TN > 2 ? NTI : 0] = MmaV<T>::run(fa##MT##_##S, fb##NTI##_##S, acc[MT][TN > 2 ? NTI : 0]); }
     u32x4 fa0_0, fa1_0, fb0_0, fb1_0, fb2_0, fb3_0;
     u32x4 fa0_1, fa1_1, fb0_1, fb1_1, fb2_1, fb3_1;
+    // fp8 screen: one MFMA takes a whole 64-byte slice of a row, so the two fragment sets are split by tile instead of
+    // by K.  Set 0 = left tile 0 and the first half of the right tiles (p0, p1), set 1 = left tile 1 and the second half
+    // (q0, q1), each as a low and a high 16-byte fragment.  MFMA groups of a slice: G1 = tile 0 x p (set 0 only),
+    // G2 = tile 0 x q and tile 1 x p (both sets), G3 = tile 1 x q (set 1 only); set 1 is read under G1, the next slice's
+    // set 0 under G3, and the barrier sits between G2 and G3 where the other loop has it.
+    u32x4 za0l, za0h, zp0l, zp0h, zp1l, zp1h;
+    u32x4 za1l, za1h, zq0l, zq0h, zq1l, zq1h;
+#define KVF_Q8_WAIT_SET0()                                                                                         \
+    do {                                                                                                           \
+        if constexpr (TN > 2)                                                                                      \
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(za0l), "+v"(za0h), "+v"(zp0l), "+v"(zp0h), "+v"(zp1l), "+v"(zp1h)); \
+        else                                                                                                       \
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(za0l), "+v"(za0h), "+v"(zp0l), "+v"(zp0h));                 \
+    } while (0)
+#define KVF_Q8_WAIT_SET1()                                                                                         \
+    do {                                                                                                           \
+        if constexpr (TN > 2)                                                                                      \
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(za1l), "+v"(za1h), "+v"(zq0l), "+v"(zq0h), "+v"(zq1l), "+v"(zq1h)); \
+        else                                                                                                       \
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(za1l), "+v"(za1h), "+v"(zq0l), "+v"(zq0h));                 \
+    } while (0)
+#define KVF_Q8_READ_SET0(OFF)                                      \
+    KVF_DS_READ(za0l, fa_lo + (OFF), 0);                           \
+    KVF_DS_READ(zp0l, fb_lo + (OFF), 0);                           \
+    KVF_DS_READ(za0h, fa_hi + (OFF), 0);                           \
+    KVF_DS_READ(zp0h, fb_hi + (OFF), 0);                           \
+    if constexpr (TN > 2) {                                        \
+        KVF_DS_READ(zp1l, fb_lo + (OFF), NT_STRIDE * 64);          \
+        KVF_DS_READ(zp1h, fb_hi + (OFF), NT_STRIDE * 64);          \
+    }                                                              \
+    if constexpr (DENSE) { KVF_Q8_WAIT_SET0(); }
+#define KVF_Q8_READ_SET1(OFF)                                      \
+    KVF_DS_READ(za1l, fa_lo + (OFF), MT_STRIDE * 64);              \
+    KVF_DS_READ(zq0l, fb_lo + (OFF), (TN / 2) * NT_STRIDE * 64);   \
+    KVF_DS_READ(za1h, fa_hi + (OFF), MT_STRIDE * 64);              \
+    KVF_DS_READ(zq0h, fb_hi + (OFF), (TN / 2) * NT_STRIDE * 64);   \
+    if constexpr (TN > 2) {                                        \
+        KVF_DS_READ(zq1l, fb_lo + (OFF), (TN / 2 + 1) * NT_STRIDE * 64); \
+        KVF_DS_READ(zq1h, fb_hi + (OFF), (TN / 2 + 1) * NT_STRIDE * 64); \
+    }                                                              \
+    if constexpr (DENSE) { KVF_Q8_WAIT_SET1(); }
+    // tile (MT, NTI) from the fragments A (za0 / za1) and B (zp0, zp1, zq0, zq1); tiles of index 1 within a set exist only
+    // in the big configuration
+#define KVF_Q8_MMA(MT, NTI, A, B) acc[MT][NTI] = mma_q8(A##l, A##h, B##l, B##h, acc[MT][NTI]);
+#define KVF_Q8_MMA_HI(MT, NTI, A, B) if constexpr (TN > 2) { acc[MT][TN > 2 ? NTI : 0] = mma_q8(A##l, A##h, B##l, B##h, acc[MT][TN > 2 ? NTI : 0]); }
 
     // ---- epilogue state
     constexpr uint32_t CODE_MASK = TM * 16 - 1;
     for (int x = tid; x < BN; x += NT) {
         const int col = col0 + x;
-        const float ir = col < mr ? inv_g[r_ids[col]] : 0.0f;
-        lds_invr[x] = ir;
-        lds_tcol[x] = col >= mr ? INFINITY : (ir > 0.0f ? A.thr_floor / ir : (A.thr_floor < 0.0f ? -INFINITY : INFINITY));
-        if constexpr (PREFIX)
-            lds_tcolb[x] = (col < mr && ir > 0.0f) ? rem[(int64_t)g * A.P + r_ids[col]] / ir : 0.0f;
+        if constexpr (Q8) {
+            // the copies are unit vectors times kQ8Scale: "inverse norm" 1 / kQ8Scale for every block
+            const int64_t id = (int64_t)g * A.P + r_ids[min(col, mr - 1)];
+            const float eb = col < mr ? qerr[id] : 0.0f;
+            lds_invr[x] = col < mr ? Q8_INV : 0.0f;
+            lds_tcol[x] = col < mr ? (A.thr_floor - eb) * kQ8Scale : INFINITY;
+            lds_c1[x] = (1.0f + eb) * kQ8Scale;
+            if constexpr (PREFIX)
+                lds_tcolb[x] = col < mr ? rem[id] * kQ8Scale : 0.0f;
+        } else {
+            const float ir = col < mr ? inv_g[r_ids[col]] : 0.0f;
+            lds_invr[x] = ir;
+            lds_tcol[x] = col >= mr ? INFINITY : (ir > 0.0f ? A.thr_floor / ir : (A.thr_floor < 0.0f ? -INFINITY : INFINITY));
+            if constexpr (PREFIX)
+                lds_tcolb[x] = (col < mr && ir > 0.0f) ? rem[(int64_t)g * A.P + r_ids[col]] / ir : 0.0f;
+        }
     }
     for (int x = tid; x < RT * BM; x += NT) {
         const int row = row0 + x;
-        lds_invl[x] = row < row_end ? inv_g[l_ids[row]] : __uint_as_float(0x7FC00000u);
+        if constexpr (Q8) {
+            lds_invl[x] = row < row_end ? Q8_INV : __uint_as_float(0x7FC00000u);
+            lds_errl[x] = row < row_end ? qerr[(int64_t)g * A.P + l_ids[row]] : 0.0f;
+        } else {
+            lds_invl[x] = row < row_end ? inv_g[l_ids[row]] : __uint_as_float(0x7FC00000u);
+        }
         if constexpr (PREFIX)
             lds_reml[x] = row < row_end ? rem[(int64_t)g * A.P + l_ids[row]] : 0.0f;
     }
@@ -310,8 +405,13 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
     KVF_DMA_ADVANCE_A();
     asm volatile("s_waitcnt vmcnt(10)" ::: "memory");     // slice 0 has landed
     __syncthreads();
-    KVF_READ_SET(0, fa_lo, fb_lo)
-    KVF_WAIT_SET(0);     // nothing but the loop body below runs while fragment reads are on their way
+    if constexpr (Q8) {
+        KVF_Q8_READ_SET0(0u)
+        KVF_Q8_WAIT_SET0();
+    } else {
+        KVF_READ_SET(0, fa_lo, fb_lo)
+        KVF_WAIT_SET(0);     // nothing but the loop body below runs while fragment reads are on their way
+    }
 
     // One K slice.  M and MH stand for the MFMA statements: the plain ones, or the ones that test whether their
     // tile lies inside the valid part of a ragged workgroup tile.
@@ -364,31 +464,85 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
 #define KVF_MMA_IF(S, MT, NTI) if ((MT == 0 || act_m1) && act_n[NTI]) { KVF_MMA(S, MT, NTI) }
 #define KVF_MMA_HI_IF(S, MT, NTI) if ((MT == 0 || act_m1) && act_n[NTI]) { KVF_MMA_HI(S, MT, NTI) }
 
+#define KVF_Q8_MMA_IF(MT, NTI, A, B) if ((MT == 0 || act_m1) && act_n[NTI]) { KVF_Q8_MMA(MT, NTI, A, B) }
+#define KVF_Q8_MMA_HI_IF(MT, NTI, A, B) if ((MT == 0 || act_m1) && act_n[TN > 2 ? NTI : 0]) { KVF_Q8_MMA_HI(MT, NTI, A, B) }
+    // One K slice of the fp8 screen (same ring, same loads, same barrier as KVF_SLICE).
+#define KVF_Q8_SLICE(M, MH)                                                                                        \
+    do {                                                                                                           \
+        const uint32_t cur = (uint32_t)(it & 3) * STAGE;                                                           \
+        const uint32_t nxt = (uint32_t)((it + 1) & 3) * STAGE;                                                     \
+        const int dst_b = ((it + 3) & 3) * STAGE;                                                                  \
+        const int dst_a = (it & 3) * STAGE;                                                                        \
+        KVF_Q8_WAIT_SET0();                                                                                        \
+        KVF_Q8_READ_SET1(cur)                                                                                      \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        M(0, 0, za0, zp0)                                                                                          \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        KVF_DMA(pb0, dst_b + dma_b0);                                                                              \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        MH(0, 1, za0, zp1)                                                                                         \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        KVF_DMA(pb1, dst_b + dma_b1);                                                                              \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        KVF_DMA_ADVANCE_B();                                                                                       \
+        KVF_Q8_WAIT_SET1();                                                                                        \
+        M(0, TN / 2, za0, zq0) MH(0, TN / 2 + 1, za0, zq1) M(1, 0, za1, zp0) MH(1, 1, za1, zp1)                    \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        /* every wavefront that passes the barrier holds slice it in registers, and its loads of slice it + 1 have  \
+           landed (all but the last 8 loads of this wavefront, slices it + 2 and it + 3) */                          \
+        asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");                                             \
+        KVF_Q8_READ_SET0(nxt)                                                                                      \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        M(1, TN / 2, za1, zq0)                                                                                     \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        KVF_DMA(pa0, dst_a + dma_a0);                                                                              \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        MH(1, TN / 2 + 1, za1, zq1)                                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        KVF_DMA(pa1, dst_a + dma_a1);                                                                              \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        KVF_DMA_ADVANCE_A();                                                                                       \
+    } while (0)
+
     int it = 0;
     for (int rt = 0; rt < n_rt; ++rt) {
         const bool act_m1 = row_end - (row0 + rt * BM) > MT_STRIDE;
-        if (act_m1 && act_n[TN - 1]) {
+        if constexpr (Q8) {
+            if (act_m1 && act_n[TN - 1]) {
 #pragma unroll 1
-            for (int kt = 0; kt < nk; ++kt, ++it)
-                KVF_SLICE(KVF_MMA, KVF_MMA_HI);
+                for (int kt = 0; kt < nk; ++kt, ++it)
+                    KVF_Q8_SLICE(KVF_Q8_MMA, KVF_Q8_MMA_HI);
+            } else {
+#pragma unroll 1
+                for (int kt = 0; kt < nk; ++kt, ++it)
+                    KVF_Q8_SLICE(KVF_Q8_MMA_IF, KVF_Q8_MMA_HI_IF);
+            }
+            KVF_Q8_WAIT_SET0();
         } else {
+            if (act_m1 && act_n[TN - 1]) {
 #pragma unroll 1
-            for (int kt = 0; kt < nk; ++kt, ++it)
-                KVF_SLICE(KVF_MMA_IF, KVF_MMA_HI_IF);
+                for (int kt = 0; kt < nk; ++kt, ++it)
+                    KVF_SLICE(KVF_MMA, KVF_MMA_HI);
+            } else {
+#pragma unroll 1
+                for (int kt = 0; kt < nk; ++kt, ++it)
+                    KVF_SLICE(KVF_MMA_IF, KVF_MMA_HI_IF);
+            }
+            // the prefetched fragments of the next row tile's first slice must be in their registers before anything
+            // else may touch them
+            KVF_WAIT_SET(0);
         }
-        // the prefetched fragments of the next row tile's first slice must be in their registers before anything
-        // else may touch them
-        KVF_WAIT_SET(0);
 
         // ---- epilogue of row tile rt
         {
             uint32_t kmax[TN];
-            float tcol[TN], tcolb[TN];
+            float tcol[TN], tcolb[TN], c1[TN];
 #pragma unroll
             for (int nt = 0; nt < TN; ++nt) {
                 kmax[nt] = 0u;
                 tcol[nt] = lds_tcol[nt * NT_STRIDE + wn * 32 + (lane & 31)];
                 tcolb[nt] = PREFIX ? lds_tcolb[nt * NT_STRIDE + wn * 32 + (lane & 31)] : 0.0f;
+                c1[nt] = Q8 ? lds_c1[nt * NT_STRIDE + wn * 32 + (lane & 31)] : 0.0f;
             }
 #pragma unroll
             for (int mt = 0; mt < TM; ++mt)
@@ -402,6 +556,11 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
                         const float4 rl4 = *reinterpret_cast<const float4 *>(&lds_reml[rt * BM + rl0]);
                         rl[0] = rl4.x; rl[1] = rl4.y; rl[2] = rl4.z; rl[3] = rl4.w;
                     }
+                    float el[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                    if constexpr (Q8) {
+                        const float4 el4 = *reinterpret_cast<const float4 *>(&lds_errl[rt * BM + rl0]);
+                        el[0] = el4.x; el[1] = el4.y; el[2] = el4.z; el[3] = el4.w;
+                    }
 #pragma unroll
                     for (int nt = 0; nt < TN; ++nt) {
                         float t[4], lim[4];
@@ -411,7 +570,11 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
                             t[q] = acc[mt][nt][eg * 4 + q] * il[q];
                             // the floor of this pair, lowered by what the unseen tails could add at most (rem is rounded up with a
                             // margin far above the rounding of this line)
-                            lim[q] = PREFIX ? fmaf(-rl[q], tcolb[nt], tcol[nt]) : tcol[nt];
+                            lim[q] = tcol[nt];
+                            if constexpr (Q8)           // the copies' errors: - err_a (1 + err_b); - err_b is in tcol
+                                lim[q] = fmaf(-el[q], c1[nt], lim[q]);
+                            if constexpr (PREFIX)
+                                lim[q] = fmaf(-rl[q], tcolb[nt], lim[q]);
                             hit |= t[q] > lim[q];
                             if constexpr (BEST) {
                                 const uint32_t key = (__float_as_uint(fmaxf(t[q], 0.0f)) & ~CODE_MASK) |
@@ -505,6 +668,15 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
 #undef KVF_SLICE
 #undef KVF_MMA_IF
 #undef KVF_MMA_HI_IF
+#undef KVF_Q8_WAIT_SET0
+#undef KVF_Q8_WAIT_SET1
+#undef KVF_Q8_READ_SET0
+#undef KVF_Q8_READ_SET1
+#undef KVF_Q8_MMA
+#undef KVF_Q8_MMA_HI
+#undef KVF_Q8_MMA_IF
+#undef KVF_Q8_MMA_HI_IF
+#undef KVF_Q8_SLICE
 }
 
 __global__ void similarity_clear_kernel(unsigned long long *__restrict__ best_packed, int32_t *__restrict__ cand_cnt,
@@ -529,15 +701,16 @@ static void launch_ring(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, 
     A.n_items = tt.n_items;
     A.row_bytes = pool.r * (int)sizeof(T);
     const bool prefix = !dense_s && w.screen_prefix > 0 && w.screen_prefix < pool.r;
+    const char *kpool = std::is_same<T, fp8_t>::value ? (const char *)w.q8_k : (const char *)pool.k;
     A.nk_screen = (prefix ? w.screen_prefix * (int)sizeof(T) : A.row_bytes) >> 6;
     A.thr_floor = thr_floor;
     A.total_s = h.total_s;
     const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
 #define KVF_SIM_LAUNCH(D, PF)                                                                                          \
     similarity_ring_kernel<T, BIG, D, PF><<<grid, BIG ? 512 : 256, 0, s>>>(                                                             \
-        A, (const char *)pool.k, pool.inv_norm_k, w.set_ids, w.set_cnt, tt.node, tt.col0, tt.row0, tt.rows, h.l_off, h.r_off, \
+        A, kpool, pool.inv_norm_k, w.set_ids, w.set_cnt, tt.node, tt.col0, tt.row0, tt.rows, h.l_off, h.r_off, \
         h.l_slot, h.r_slot, h.r_base, h.r_cap, h.s_base, w.best_packed, w.cand_cnt, w.cand_idx, w.cand_val, dense_s,           \
-        w.group_enable, w.rem_k)
+        w.group_enable, w.rem_k, w.q8_err)
     if (dense_s)
         KVF_SIM_LAUNCH(true, false);
     else if (prefix)
@@ -555,7 +728,12 @@ void launch_similarity(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, c
     if (cols > 0)
         similarity_clear_kernel<<<(unsigned)((cols + 255) / 256), 256, 0, s>>>(w.best_packed, w.cand_cnt, cols);
     const bool big = h.use_big_tiles;
-    if (pool.dtype == KVFUSE_BF16) {
+    if (w.q8_k) {
+        if (big)
+            launch_ring<fp8_t, true>(s, pool, w, h, h.big, thr_floor, dense_s);
+        else
+            launch_ring<fp8_t, false>(s, pool, w, h, h.small, thr_floor, dense_s);
+    } else if (pool.dtype == KVFUSE_BF16) {
         if (big)
             launch_ring<bf16_t, true>(s, pool, w, h, h.big, thr_floor, dense_s);
         else

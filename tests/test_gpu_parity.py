@@ -167,13 +167,13 @@ def test_single_node_steps_match_oracle(kb, oracle, kind, cand_cap):
 # ------------------------------------------------------------------------------------------ whole tree
 
 def _run_tree_case(kb, oracle, rec, name, cand_cap=16, thr=None, phys_perm=True, group_size=None, groups=None, band=1e-3,
-                   rule="argmax", shortest_first=False, screen_prefix=0):
+                   rule="argmax", shortest_first=False, screen_prefix=0, screen_fp8=False):
     _say("tree case", name, "G", rec.G, "n", rec.n, "r", rec.r, "leaves", len(rec.leaf_start), "cand_cap", cand_cap,
          "rule", rule, "shortest_first", shortest_first)
     mat = wl.materialise(rec, DEV, groups=groups, phys_perm=phys_perm)
     host = gu.host_copy(mat)
     cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, thr=thr, cand_cap=cand_cap, group_size=group_size, band=band, rule=rule,
-                                          shortest_first=shortest_first, screen_prefix=screen_prefix)
+                                          shortest_first=shortest_first, screen_prefix=screen_prefix, screen_fp8=screen_fp8)
     res = gu.oracle_fuse(oracle, rec, host, thr=thr, group_size=group_size, rule=rule, shortest_first=shortest_first)
     safe = gu.check_ambiguity(res, name)
     assert len(safe) == len(res)
@@ -320,6 +320,152 @@ def test_prefix_screen_step_by_step_equals_the_tree_driver(kb, oracle):
     for g in range(rec.G):
         gu.compare_group(res[g], cache, g, False, "prefix_step_by_step")
     assert sum(int(r.stats[1]) for r in res) > 50
+
+
+# OCP e4m3 (4 exponent bits, bias 7, 3 mantissa bits, no infinities, 0x7F / 0xFF = NaN), written out from the format's
+# definition: what the bytes of the fp8 screen's copy mean.
+def _e4m3_table():
+    out = np.zeros(256, np.float64)
+    for b in range(256):
+        e, m = (b >> 3) & 15, b & 7
+        if e == 15 and m == 7:
+            v = np.nan
+        elif e == 0:
+            v = m / 8.0 * 2.0 ** -6
+        else:
+            v = (1.0 + m / 8.0) * 2.0 ** (e - 7)
+        out[b] = -v if b & 0x80 else v
+    return out
+
+
+@pytest.mark.parametrize("kind", ["bf16", "bf16_big"])
+def test_fp8_screen_copy_and_bound(kb, oracle, kind):
+    """The fp8 screen's ingredients on one node: the one-byte copy is the e4m3 rounding of the unit blocks times 256 (checked
+    against the format written out above: every byte decodes to within half a spacing of its element), the stored error is
+    the copy's true Euclidean error (recomputed here in fp64 from the bytes), and the dense product of the copies stays
+    within err_a + err_b + err_a err_b of the oracle's cosine for every pair -- the inequality the screen's candidate rule
+    rests on."""
+    K, V, bt, ml, mr, t, d = _two_leaf_case(kind)
+    Kh, bth = wl.to_numpy_pool(K[0]), bt[0].numpy().copy()
+    K, V, bt = K.to(DEV), V.to(DEV), bt.to(DEV)
+    ctx = kb.Context(DEV)
+    cache = kb.Cache(K, V, bt, t, d)
+    plan = kb.Plan(ctx, cache, kb.tree_spec([0, ml], [ml, mr], [0, 1, 2]), 16)
+    kb.set_screen_fp8(ctx, plan)
+    kb.block_norms(ctx, cache)
+    kb.leaf_sets(ctx, plan)
+    view = plan.view(0)
+    dense = torch.full((1, view.total_s), float("nan"), device=DEV)
+    kb.similarity(ctx, plan, 0, 0.9, 1e-3, dense)
+    torch.cuda.synchronize()
+    nk = oracle.block_norms(Kh)
+    dec = _e4m3_table()[plan.k8[0].cpu().numpy()]                 # [P][r]
+    assert np.isfinite(dec).all()
+    live = nk > 0
+    Kf = oracle.pool_to_f64(Kh)
+    unit = np.zeros_like(Kf)
+    unit[live] = Kf[live] / nk[live, None]
+    # every byte is a nearest e4m3 value of unit * 256: spacing 2^(e - 3) at binade e, 2^-9 below 2^-6; the kernel rounds
+    # the product with a binary32 factor first, hence the small allowance
+    target = unit * 256.0
+    spacing = np.maximum(2.0 ** (np.floor(np.log2(np.maximum(np.abs(target), 2.0 ** -6))) - 3), 2.0 ** -9)
+    assert (np.abs(dec - target) <= 0.5 * spacing * (1 + 1e-5)).all()
+    err_true = np.sqrt(((unit - dec / 256.0) ** 2).sum(1))
+    err_gpu = plan.k8_err[0].cpu().numpy().astype(np.float64)
+    assert (err_gpu >= err_true).all() and (err_gpu <= err_true + 3e-6).all()
+    assert (err_gpu[~live] == 0).all() and 0.01 < err_gpu[live].mean() < 0.04
+    _say("fp8 copy", kind, "mean err", err_gpu[live].mean(), "max err", err_gpu.max())
+    L, R = bth[:ml], bth[ml:]
+    S = oracle.similarity(Kh, nk, L, R)
+    S_q = dense[0].cpu().numpy().reshape(ml, mr).astype(np.float64)
+    ea, eb = err_gpu[L][:, None], err_gpu[R][None, :]
+    slack = ea + eb + ea * eb + Kh.shape[1] * 2.0 ** -22
+    worst = (np.abs(S_q - S) / slack).max()
+    _say("  max |<q(a), q(b)> / 256^2 - cos| / bound =", worst)
+    assert worst <= 1.0
+    # and the product is what the decoded bytes give (format and operand layout of the matrix instruction)
+    exact_q = (dec[L] @ dec[R].T) / 65536.0
+    assert np.abs(S_q - exact_q).max() <= Kh.shape[1] * 2.0 ** -22
+
+
+@pytest.mark.parametrize("rule", ["argmax", "first_row"])
+@pytest.mark.parametrize("which", ["small_bf16", "small_bf16_cap2", "zipf_small", "zipf_at_threshold", "mixed_small_f32",
+                                   "r4096_bf16_with_quarter_prefix", "tiny_f32_with_half_prefix", "r8192_bf16_long_blocks"])
+def test_tree_fp8_screen_gives_the_same_tables(kb, oracle, which, rule):
+    """The fp8 screen (similarity over one-byte copies of the key blocks + their measured error as a bound, every candidate
+    evaluated in full in fp64) must give exactly the oracle's tables, pools and counters, alone and together with the prefix
+    screen, for both pool types and both readings of the threshold line."""
+    kw = dict(rule=rule, screen_fp8=True)
+    if which == "small_bf16":
+        rec = _small_bf16()
+    elif which == "small_bf16_cap2":
+        rec, kw = _small_bf16(n_req=5, tokens=900), dict(kw, cand_cap=2)
+    elif which == "zipf_small":
+        rec = wl.zipf_bff(n_req=8, tokens=32 * 40, layers=1, kv_heads=2, pool=60, t=32, d=64, thr=0.9)
+        kw = dict(kw, cand_cap=8)
+    elif which == "zipf_at_threshold":
+        sigma = 0.05
+        rec = wl.zipf_bff(n_req=8, tokens=32 * 40, layers=1, kv_heads=2, pool=60, t=32, d=64, sigma=sigma,
+                          thr=1.0 / (1.0 + sigma * sigma))
+    elif which == "mixed_small_f32":
+        rec = wl.mixed(n_req=9, min_tokens=40, max_tokens=900, chunk_tokens=256, layers=1, kv_heads=2, pool=48, t=8, d=32,
+                       dtype=torch.float32)
+    elif which == "r4096_bf16_with_quarter_prefix":
+        rec = wl.zipf_bff(n_req=6, tokens=32 * 150, layers=1, kv_heads=2, pool=400, t=32, d=128, thr=0.95)
+        kw = dict(kw, screen_prefix=1024, cand_cap=8)
+    elif which == "r8192_bf16_long_blocks":
+        # blocks too long for a wavefront's registers: the norm pass, the merge step and the re-check take their streaming
+        # forms, and the copies of rebuilt targets come from the kernel that follows the merge
+        rec = wl.zipf_bff(n_req=5, tokens=64 * 30, layers=1, kv_heads=1, pool=40, t=64, d=128, thr=0.9)
+        kw = dict(kw, band=2.5e-3)          # at least r * 2^-22
+    else:
+        rec, kw = wl.tiny_bff(), dict(kw, screen_prefix=512, cand_cap=4)
+    cache, plan, stats, res, mat = _run_tree_case(kb, oracle, rec, "fp8_screen_" + which, **kw)
+    assert stats.fused > 0
+
+
+def test_fp8_screen_step_by_step_and_arguments(kb, oracle):
+    """The single-step entry points with the fp8 screen on (the copy then comes from kvfuse_leaf_sets and is refreshed after
+    every kvfuse_merge), and the argument checks of the switch."""
+    rec = _small_bf16(n_req=5, tokens=1000, kv_heads=2)
+    mat = wl.materialise(rec, DEV, phys_perm=True)
+    host = gu.host_copy(mat)
+    ctx = kb.Context(DEV)
+    cache = kb.Cache(mat["K"], mat["V"], mat["bt"], rec.t, rec.d)
+    plan = kb.Plan(ctx, cache, kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr), 16)
+    k8 = torch.empty(cache.G, cache.P, rec.r, device=DEV, dtype=torch.uint8)
+    err = torch.empty(cache.G, cache.P, device=DEV, dtype=torch.float32)
+    # one of the two arrays missing
+    assert kb.lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, k8.data_ptr(), None) == kb.EINVAL
+    assert kb.lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, None, err.data_ptr()) == kb.EINVAL
+    # a prefix that is fine for the bfloat16 product (96 elements = 192 bytes of the pool) is no multiple of 64 bytes of the copy
+    kb.set_screen_prefix(ctx, plan, 96)
+    assert kb.lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, k8.data_ptr(), err.data_ptr()) == kb.EINVAL
+    kb.set_screen_prefix(ctx, plan, 0)
+    kb.set_screen_fp8(ctx, plan)
+    with pytest.raises(kb.KvfuseError):
+        kb.set_screen_prefix(ctx, plan, 96)
+    kb.set_screen_prefix(ctx, plan, 128)
+    kb.block_norms(ctx, cache)
+    kb.leaf_sets(ctx, plan)
+    for h in range(plan.n_heights):
+        kb.similarity(ctx, plan, h, rec.thr)
+        kb.assign(ctx, plan, h, rec.thr)
+        kb.merge(ctx, plan, h)
+    kb.rewrite_block_table(ctx, cache)
+    torch.cuda.synchronize()
+    res = gu.oracle_fuse(oracle, rec, host)
+    assert gu.check_ambiguity(res, "fp8_step_by_step") == list(range(rec.G))
+    for g in range(rec.G):
+        gu.compare_group(res[g], cache, g, False, "fp8_step_by_step")
+    assert sum(int(r.stats[1]) for r in res) > 50
+    # blocks too short or of an odd length for the byte copy
+    small = wl.tiny_bff()
+    m2 = wl.materialise(small, DEV)
+    c2 = kb.Cache(m2["K"][:, :, :96].contiguous(), m2["V"][:, :, :96].contiguous(), m2["bt"], 4, 24)
+    p2 = kb.Plan(ctx, c2, kb.tree_spec(small.leaf_start, small.leaf_count, small.unit_leaf_ptr), 4)
+    with pytest.raises(kb.KvfuseError):
+        kb.set_screen_fp8(ctx, p2)
 
 
 def test_prefix_screen_rejects_bad_arguments(kb):
