@@ -18,19 +18,22 @@ DEV = "cuda:0"
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("rule", ["argmax", "first_row", "argmax_with_prefix_screen"])
+@pytest.mark.parametrize("rule", ["argmax", "first_row", "argmax_with_prefix_screen", "argmax_with_fp8_screen"])
 def test_llama8b_bff_full_size_sampled_groups_and_invariants(oracle, rule):
     kb = gu.load_binding()
-    screen_prefix = 0
-    if rule == "argmax_with_prefix_screen":      # the opt-in shortcut of the similarity step: same tables, by construction
+    screen_prefix, screen_fp8 = 0, False
+    if rule == "argmax_with_prefix_screen":      # the opt-in shortcuts of the similarity step: same tables, by construction
         rule, screen_prefix = "argmax", 512
+    elif rule == "argmax_with_fp8_screen":
+        rule, screen_fp8 = "argmax", True
     rec = wl.llama8b_bff()
     print("materialise", rec.name, "G", rec.G, "n", rec.n, flush=True)
     mat = wl.materialise(rec, DEV)
     rng = np.random.default_rng(20260103)
     sample = sorted({0, rec.G - 1, *rng.choice(rec.G, size=7, replace=False).tolist()})[:9]
     host = {g: (wl.to_numpy_pool(mat["K"][g]), wl.to_numpy_pool(mat["V"][g]), mat["bt"][g].cpu().numpy().copy()) for g in sample}
-    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, cand_cap=64, rule=rule, screen_prefix=screen_prefix)   # bench.py's candidate slots
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, cand_cap=64, rule=rule, screen_prefix=screen_prefix,
+                                          screen_fp8=screen_fp8)          # bench.py's candidate slots
     print("rule", rule, "gpu fused", stats.fused, "CR", stats.compression_ratio, "refined", stats.refined, flush=True)
 
     # ---- invariants on every group
@@ -246,6 +249,17 @@ def test_large_config_groups_match_the_oracle_exactly(oracle, config, capsys):
     gu.compare_group(res[0], cache, 0, False, config)
     assert stats.fused == int(res[0].stats[1]) and stats.physical_blocks == res[0].n_physical
     assert stats.near_threshold == int(res[0].stats[2])
+
+    # the fp8 screen on the same input: the same tables, pools and counters as the full product (hence as the oracle)
+    want = {k: getattr(cache, k).clone() for k in ("bt", "K", "V", "scale_k", "scale_v", "refcount", "n_phys", "norm_k")}
+    del cache, plan
+    mat2 = wl.materialise(rec, DEV)
+    cache2, plan2, stats2, ctx2 = gu.gpu_fuse(rec, mat2, cand_cap=64, screen_fp8=True)
+    with capsys.disabled():
+        print(f"  fp8 screen: fused {stats2.fused} refined {stats2.refined} overflow {stats2.cand_overflow}", flush=True)
+    for k, v in want.items():
+        assert torch.equal(getattr(cache2, k), v), k
+    assert (stats2.fused, stats2.near_threshold, stats2.physical_blocks) == (stats.fused, stats.near_threshold, stats.physical_blocks)
 
 
 class _GroupView:
