@@ -78,6 +78,10 @@ def run_whole_config(args, torch, kb, wl):
     cache = kb.Cache(K, V, bt, rec.t, rec.d)
     spec = kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr, rec.group_size)
     plan = kb.Plan(ctx, cache, spec, args.cand_cap)
+    if args.screen_fp8:
+        kb.set_screen_fp8(ctx, plan)
+    if args.screen_prefix:
+        kb.set_screen_prefix(ctx, plan, args.screen_prefix)
     rs = torch.tensor(rec.req_start, dtype=torch.int32, device=dev)
     cl = torch.tensor(rec.ctx_len, dtype=torch.int32, device=dev)
     max_blocks = int(((rec.ctx_len + rec.t - 1) // rec.t).max())
@@ -147,6 +151,7 @@ def run_whole_config(args, torch, kb, wl):
                    "compression_ratio": blocks / a["physical"] if a["physical"] else 0.0, "fused": a["fused"],
                    "near_threshold": a["near"], "refined_fp64": a["refined"], "cand_overflow": a["overflow"],
                    "slabs": n_slabs, "slab_layers": slab_layers,
+                   "screen": ("fp8 copies" if args.screen_fp8 else "full product") + (f", prefix of {args.screen_prefix}" if args.screen_prefix else ""),
                    "unfused_cache_GB": rec.layers * H * rec.n * rec.r * elem * 2 / 1e9},
         "stages_ms": a["stage"],
         "per_slab_ms": {"min": min(slab_ms), "median": sorted(slab_ms)[len(slab_ms) // 2], "max": max(slab_ms), "all": slab_ms},
