@@ -23,8 +23,8 @@ def _state(cache, out):
     return [t.clone() for t in (cache.K, cache.V, cache.bt, cache.scale_k, cache.scale_v, cache.refcount, cache.n_phys, out)]
 
 
-@pytest.mark.parametrize("screen_prefix", [0, 256])
-def test_fusion_and_decode_replayed_from_a_graph(oracle, screen_prefix):
+@pytest.mark.parametrize("screen", ["full_product", "prefix_256", "fp8_copies"])
+def test_fusion_and_decode_replayed_from_a_graph(oracle, screen):
     kb = gu.load_binding()
     rec = wl.llama8b_bff(n_req=6, tokens=16 * 150, layers=1, kv_heads=3, prefix_tokens=192, near_pool=24, t=16, d=64)
     mat = wl.materialise(rec, DEV, phys_perm=True)
@@ -44,8 +44,10 @@ def test_fusion_and_decode_replayed_from_a_graph(oracle, screen_prefix):
         ctx = kb.Context(DEV, stream=side)
         cache = kb.Cache(mat["K"], mat["V"], mat["bt"], rec.t, rec.d)
         plan = kb.Plan(ctx, cache, kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr), 16)
-        if screen_prefix:
-            kb.set_screen_prefix(ctx, plan, screen_prefix)
+        if screen == "prefix_256":
+            kb.set_screen_prefix(ctx, plan, 256)
+        elif screen == "fp8_copies":
+            kb.set_screen_fp8(ctx, plan)
 
         def step():
             cache.K.copy_(K0)
