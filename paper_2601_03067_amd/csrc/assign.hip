@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void assign_screen_kernel(WorkDesc w, HeightDe
     const int64_t cidx = (int64_t)g * w.r_stride + c;
     const int cnt = ml > 0 ? w.cand_cnt[cidx] : 0;
     int result = -1;
-    bool recheck = cnt > w.cand_cap || (bound == 1 && cnt > 0);
+    bool recheck = cnt > w.cand_cap || ((bound == 1 || bound == 3) && cnt > 0);
     if (cnt > 0 && !recheck && bound == 2) {
         const float *qe = w.q8_err + (int64_t)g * P;
         const int32_t *l_ids = w.set_ids + (int64_t)g * w.n + h.l_off[node];
@@ -214,6 +214,8 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
     const int n_waves = gridDim.x * 4;
     for (int it = blockIdx.x * 4 + (threadIdx.x >> 6); it < n_items; it += n_waves) {
         const int2 item = reinterpret_cast<const int2 *>(w.refine)[it];
+        if (item.x < 0)         // settled by assign_q8_fill_kernel
+            continue;
         const int64_t cidx = item.x;
         const int node = item.y;
         const int g = (int)(cidx / w.r_stride);
@@ -244,7 +246,7 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
         // radius of a listed value around the cosine: band, or (fp8 screen) band + the two copies' errors; per lane, for
         // the candidate that lane holds
         auto radius = [&](int row) __attribute__((always_inline)) {
-            if (bound != 2)
+            if (bound < 2)
                 return band;
             const float *qe = w.q8_err + (int64_t)g * pool.P;
             const double ea = (double)qe[l_ids[row]], eb = (double)qe[b];
@@ -262,7 +264,7 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
                     ci = w.cand_idx[cidx * w.cand_cap + lane];
                     cv = w.cand_val[cidx * w.cand_cap + lane];
                 }
-                const bool certain = bound == 2 ? (lane < cnt && (double)cv - radius(ci) > thr + band)
+                const bool certain = bound >= 2 ? (lane < cnt && (double)cv - radius(ci) > thr + band)
                                                 : (!bound && lane < cnt && (double)cv > thr + 2.0 * band);
                 int i_def = certain ? ci : 0x7FFFFFFF;
 #pragma unroll
@@ -311,7 +313,7 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
             for (int off = 32; off >= 1; off >>= 1)
                 smax = fmaxf(smax, __shfl_xor(smax, off, 64));
             unsigned long long mask;
-            if (bound == 2) {       // contenders: upper end not below the largest lower end
+            if (bound >= 2) {       // contenders: upper end not below the largest lower end
                 const double rad = lane < cnt ? radius(ci) : 0.0;
                 double lo = lane < cnt ? (double)cv - rad : -INFINITY;
 #pragma unroll
@@ -401,6 +403,111 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
             atomicAdd(&cn[2], 1);
             if (cnt > w.cand_cap)
                 atomicAdd(&cn[3], 1);
+        }
+    }
+}
+
+// 16 e4m3 bytes times 16 e4m3 bytes, accumulated in binary32 (every product is exact).
+__device__ __forceinline__ float dot16_e4m3(const uint4 &a, const uint4 &b, float acc)
+{
+    typedef float floatx2 __attribute__((ext_vector_type(2)));
+    const uint32_t wa[4] = {a.x, a.y, a.z, a.w}, wb[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const floatx2 a0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)wa[i], false), a1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)wa[i], true);
+        const floatx2 b0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)wb[i], false), b1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)wb[i], true);
+        acc = fmaf(a0.x, b0.x, acc);
+        acc = fmaf(a0.y, b0.y, acc);
+        acc = fmaf(a1.x, b1.x, acc);
+        acc = fmaf(a1.y, b1.y, acc);
+    }
+    return acc;
+}
+
+// Both screens on (bound == 3): the similarity step has listed heads of upper bounds over a prefix of the fp8 copies, which
+// settle nothing.  One WAVEFRONT per listed column multiplies the whole copies of its candidates (r bytes each instead of
+// the pool's r elements, binary32 arithmetic) and writes the results back into the list: from here on a listed value is a
+// cosine to within band + err_a + err_b + err_a err_b, as with the fp8 screen alone.  Columns that these intervals settle
+// (one row whose lower end clears thr + band and every other row's upper end; or no row whose upper end reaches
+// thr - band; the row-order rule accordingly) are assigned here and struck from the list; the rest goes on to the fp64
+// re-check with the new values.
+__global__ __launch_bounds__(256) void assign_q8_fill_kernel(PoolDesc pool, WorkDesc w, HeightDesc h, int height, double thr,
+                                                             double band, int rule)
+{
+    const int lane = threadIdx.x & 63;
+    const int n_items = w.n_refine[height];
+    const int n_waves = gridDim.x * 4;
+    const int ch = pool.r / 16;
+    const float inv_s2 = 1.0f / (kQ8Scale * kQ8Scale);
+    for (int it = blockIdx.x * 4 + (threadIdx.x >> 6); it < n_items; it += n_waves) {
+        const int2 item = reinterpret_cast<const int2 *>(w.refine)[it];
+        const int64_t cidx = item.x;
+        const int node = item.y;
+        const int cnt = w.cand_cnt[cidx];
+        if (cnt > w.cand_cap)           // overflowed list: the re-check rescans the whole column
+            continue;
+        const int g = (int)(cidx / w.r_stride);
+        const int c = (int)(cidx - (int64_t)g * w.r_stride);
+        const int j = c - h.r_base[node];
+        const int32_t *l_ids = w.set_ids + (int64_t)g * w.n + h.l_off[node];
+        const int b = w.set_ids[(int64_t)g * w.n + h.r_off[node] + j];
+        const uint8_t *q8_g = w.q8_k + (int64_t)g * pool.P * pool.r;
+        const float *qe = w.q8_err + (int64_t)g * pool.P;
+        const uint4 *pb = reinterpret_cast<const uint4 *>(q8_g + (int64_t)b * pool.r);
+        int ci = 0x7FFFFFFF, pid = 0;
+        if (lane < cnt) {
+            ci = w.cand_idx[cidx * w.cand_cap + lane];
+            pid = l_ids[ci];
+        }
+        float cv = -INFINITY;
+        for (int k = 0; k < cnt; ++k) {
+            const uint4 *pa = reinterpret_cast<const uint4 *>(q8_g + (int64_t)__shfl(pid, k, 64) * pool.r);
+            float dot = 0.0f;
+            for (int q = lane; q < ch; q += 64)
+                dot = dot16_e4m3(pa[q], pb[q], dot);
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1)
+                dot += __shfl_xor(dot, off, 64);
+            if (lane == k)
+                cv = dot * inv_s2;
+        }
+        double lo = -INFINITY, hi = -INFINITY;
+        if (lane < cnt) {
+            w.cand_val[cidx * w.cand_cap + lane] = cv;
+            const double ea = (double)qe[pid], eb = (double)qe[b];
+            const double rad = band + ea + eb + ea * eb;
+            lo = (double)cv - rad;
+            hi = (double)cv + rad;
+        }
+        bool settled = false;
+        int result = -1;
+        if (rule == KVFUSE_RULE_FIRST_ROW) {
+            const bool certain = lane < cnt && lo > thr + band;
+            int i_def = certain ? ci : 0x7FFFFFFF;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1)
+                i_def = min(i_def, __shfl_xor(i_def, off, 64));
+            const unsigned long long open = __ballot(lane < cnt && !certain && ci < i_def && !(hi < thr - band));
+            settled = open == 0ull;
+            result = i_def == 0x7FFFFFFF ? -1 : i_def;
+        } else {
+            double lo_max = lo, hi_max = hi;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                lo_max = fmax(lo_max, __shfl_xor(lo_max, off, 64));
+                hi_max = fmax(hi_max, __shfl_xor(hi_max, off, 64));
+            }
+            const unsigned long long cont = __ballot(lane < cnt && hi >= lo_max);
+            if (hi_max < thr - band) {
+                settled = true;
+            } else if (__popcll(cont) == 1 && lo_max > thr + band) {
+                settled = true;
+                result = __shfl(ci, __ffsll((long long)cont) - 1, 64);
+            }
+        }
+        if (settled && lane == 0) {
+            w.assign[cidx] = result;
+            reinterpret_cast<int2 *>(w.refine)[it] = make_int2(-1, node);
         }
     }
 }
@@ -556,9 +663,15 @@ void launch_assign(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, co
     const int64_t cols = (int64_t)w.G * h.total_r_cap;
     assign_reset_kernel<<<1, 1, 0, s>>>(w, height);
     if (cols > 0) {
-        // 1: the listed values are upper bounds only (prefix screen); 2: cosines within a per-pair radius (fp8 screen)
-        const int bound = (w.screen_prefix > 0 && w.screen_prefix < pool.r) ? 1 : (w.q8_k ? 2 : 0);
+        // 1: the listed values are upper bounds only (prefix screen); 2: cosines within a per-pair radius (fp8 screen);
+        // 3: both screens: upper bounds that assign_q8_fill_kernel turns into the values of 2
+        const bool prefix = w.screen_prefix > 0 && w.screen_prefix < pool.r;
+        const int bound = prefix ? (w.q8_k ? 3 : 1) : (w.q8_k ? 2 : 0);
         assign_screen_kernel<<<(unsigned)((cols + 255) / 256), 256, 0, s>>>(w, h, height, thr, band, rule, bound, pool.P);
+        if (bound == 3) {
+            const unsigned fgrid = (unsigned)std::min<int64_t>((cols + 3) / 4, resident_workgroups(assign_q8_fill_kernel));
+            assign_q8_fill_kernel<<<fgrid, 256, 0, s>>>(pool, w, h, height, thr, band, rule);
+        }
         unsigned rgrid = 0;
         const int cpl = (pool.r / (pool.dtype == KVFUSE_BF16 ? 8 : 4) + 63) / 64;     // 16-byte chunks per lane
         // a persistent grid: exactly as many workgroups as the GPU holds at once (a workgroup that had to wait for a

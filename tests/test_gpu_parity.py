@@ -390,7 +390,8 @@ def test_fp8_screen_copy_and_bound(kb, oracle, kind):
 
 @pytest.mark.parametrize("rule", ["argmax", "first_row"])
 @pytest.mark.parametrize("which", ["small_bf16", "small_bf16_cap2", "zipf_small", "zipf_at_threshold", "mixed_small_f32",
-                                   "r4096_bf16_with_quarter_prefix", "tiny_f32_with_half_prefix", "r8192_bf16_long_blocks"])
+                                   "r4096_bf16_with_quarter_prefix", "tiny_f32_with_half_prefix", "r8192_bf16_long_blocks",
+                                   "zipf_at_threshold_with_half_prefix", "small_bf16_cap2_with_half_prefix"])
 def test_tree_fp8_screen_gives_the_same_tables(kb, oracle, which, rule):
     """The fp8 screen (similarity over one-byte copies of the key blocks + their measured error as a bound, every candidate
     evaluated in full in fp64) must give exactly the oracle's tables, pools and counters, alone and together with the prefix
@@ -413,6 +414,13 @@ def test_tree_fp8_screen_gives_the_same_tables(kb, oracle, which, rule):
     elif which == "r4096_bf16_with_quarter_prefix":
         rec = wl.zipf_bff(n_req=6, tokens=32 * 150, layers=1, kv_heads=2, pool=400, t=32, d=128, thr=0.95)
         kw = dict(kw, screen_prefix=1024, cand_cap=8)
+    elif which == "zipf_at_threshold_with_half_prefix":
+        sigma = 0.05
+        rec = wl.zipf_bff(n_req=8, tokens=32 * 40, layers=1, kv_heads=2, pool=60, t=32, d=64, sigma=sigma,
+                          thr=1.0 / (1.0 + sigma * sigma))
+        kw = dict(kw, screen_prefix=1024)
+    elif which == "small_bf16_cap2_with_half_prefix":
+        rec, kw = _small_bf16(n_req=5, tokens=900), dict(kw, cand_cap=2, screen_prefix=128)
     elif which == "r8192_bf16_long_blocks":
         # blocks too long for a wavefront's registers: the norm pass, the merge step and the re-check take their streaming
         # forms, and the copies of rebuilt targets come from the kernel that follows the merge
