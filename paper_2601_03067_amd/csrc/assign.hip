@@ -101,12 +101,11 @@ __global__ void assign_reset_kernel(WorkDesc w, int height)
 // radius that differs from candidate to candidate (q8_err holds err per block).  The same two-sided reasoning then works
 // with an interval per candidate: a row is certain when its lower end clears thr + band, and it is the arg-max when its
 // lower end lies above the upper end of every other listed row.
-__global__ __launch_bounds__(256) void assign_screen_kernel(WorkDesc w, HeightDesc h, int height, double thr, double band,
-                                                            int rule, int bound, int P)
+// The decision for column `id`; valid = the column exists, recheck = it goes to the list, else result is its assignment.
+__device__ __forceinline__ void screen_column(const WorkDesc &w, const HeightDesc &h, double thr, double band, int rule, int bound,
+                                              int P, int64_t id, bool &valid, bool &recheck_out, int &result_out, int64_t &cidx_out,
+                                              int &node_out)
 {
-    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (id >= (int64_t)w.G * h.total_r_cap)
-        return;
     const int g = (int)(id / h.total_r_cap);
     const int c = (int)(id - (int64_t)g * h.total_r_cap);
     const int node = find_node(h.r_base, h.n_nodes, c);
@@ -115,6 +114,7 @@ __global__ __launch_bounds__(256) void assign_screen_kernel(WorkDesc w, HeightDe
     const int mr = w.set_cnt[(int64_t)g * w.n_slots + h.r_slot[node]];
     if (j >= mr)
         return;
+    valid = true;
     const int64_t cidx = (int64_t)g * w.r_stride + c;
     const int cnt = ml > 0 ? w.cand_cnt[cidx] : 0;
     int result = -1;
@@ -194,11 +194,46 @@ __global__ __launch_bounds__(256) void assign_screen_kernel(WorkDesc w, HeightDe
         else
             recheck = true;
     }
-    if (recheck) {      // (column, node): the re-check need not search for the node again
-        const int slot = atomicAdd(&w.n_refine[height], 1);
-        reinterpret_cast<int2 *>(w.refine)[slot] = make_int2((int32_t)cidx, node);
-    } else
-        w.assign[cidx] = result;
+    recheck_out = recheck;
+    result_out = result;
+    cidx_out = cidx;
+    node_out = node;
+}
+
+__global__ __launch_bounds__(256) void assign_screen_kernel(WorkDesc w, HeightDesc h, int height, double thr, double band,
+                                                            int rule, int bound, int P)
+{
+    __shared__ int wave_cnt[4];
+    __shared__ int wg_base;
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    bool valid = false, recheck = false;
+    int result = -1, node = 0;
+    int64_t cidx = 0;
+    if (id < (int64_t)w.G * h.total_r_cap)
+        screen_column(w, h, thr, band, rule, bound, P, id, valid, recheck, result, cidx, node);
+    // List entries are (column, node): the re-check need not search for the node again.  One atomic per workgroup, not
+    // per column: with a screen whose listed values settle nothing every fusing column of a height lands in the list, and
+    // that many atomics on one counter would take longer than everything else in this kernel.
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const unsigned long long listed = __ballot(valid && recheck);
+    if (lane == 0)
+        wave_cnt[wave] = __popcll(listed);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int total = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+        wg_base = total > 0 ? atomicAdd(&w.n_refine[height], total) : 0;
+    }
+    __syncthreads();
+    if (valid) {
+        if (recheck) {
+            int slot = wg_base + __popcll(listed & ((1ull << lane) - 1ull));
+            for (int q = 0; q < wave; ++q)
+                slot += wave_cnt[q];
+            reinterpret_cast<int2 *>(w.refine)[slot] = make_int2((int32_t)cidx, node);
+        } else {
+            w.assign[cidx] = result;
+        }
+    }
 }
 
 // One WAVEFRONT per listed column: fp64 cosines of the contenders (or of the whole column when the candidate list
@@ -434,80 +469,110 @@ __device__ __forceinline__ float dot16_e4m3(const uint4 &a, const uint4 &b, floa
 __global__ __launch_bounds__(256) void assign_q8_fill_kernel(PoolDesc pool, WorkDesc w, HeightDesc h, int height, double thr,
                                                              double band, int rule)
 {
+    // A column's data hangs on a chain of dependent loads (list entry -> candidate count and column -> candidate row ->
+    // physical id -> the copies).  A wavefront therefore takes kBatch list entries at a time and walks the chains of all of
+    // them side by side, one entry per lane, before it multiplies their copies one entry after the other.
+    constexpr int kBatch = 16;
     const int lane = threadIdx.x & 63;
     const int n_items = w.n_refine[height];
     const int n_waves = gridDim.x * 4;
     const int ch = pool.r / 16;
     const float inv_s2 = 1.0f / (kQ8Scale * kQ8Scale);
-    for (int it = blockIdx.x * 4 + (threadIdx.x >> 6); it < n_items; it += n_waves) {
-        const int2 item = reinterpret_cast<const int2 *>(w.refine)[it];
-        const int64_t cidx = item.x;
-        const int node = item.y;
-        const int cnt = w.cand_cnt[cidx];
-        if (cnt > w.cand_cap)           // overflowed list: the re-check rescans the whole column
-            continue;
-        const int g = (int)(cidx / w.r_stride);
-        const int c = (int)(cidx - (int64_t)g * w.r_stride);
-        const int j = c - h.r_base[node];
-        const int32_t *l_ids = w.set_ids + (int64_t)g * w.n + h.l_off[node];
-        const int b = w.set_ids[(int64_t)g * w.n + h.r_off[node] + j];
-        const uint8_t *q8_g = w.q8_k + (int64_t)g * pool.P * pool.r;
-        const float *qe = w.q8_err + (int64_t)g * pool.P;
-        const uint4 *pb = reinterpret_cast<const uint4 *>(q8_g + (int64_t)b * pool.r);
-        int ci = 0x7FFFFFFF, pid = 0;
-        if (lane < cnt) {
-            ci = w.cand_idx[cidx * w.cand_cap + lane];
-            pid = l_ids[ci];
+    for (int base = (blockIdx.x * 4 + (threadIdx.x >> 6)) * kBatch; base < n_items; base += n_waves * kBatch) {
+        // ---- one list entry per lane: everything up to the first candidate's physical id
+        int64_t m_cidx = -1;
+        int m_node = 0, m_cnt = 0, m_g = 0, m_b = 0, m_ci0 = 0x7FFFFFFF, m_pid0 = 0;
+        float m_eb = 0.0f, m_ea0 = 0.0f;
+        if (lane < kBatch && base + lane < n_items) {
+            const int2 item = reinterpret_cast<const int2 *>(w.refine)[base + lane];
+            m_cidx = item.x;
+            m_node = item.y;
+            m_cnt = w.cand_cnt[m_cidx];
+            m_g = (int)(m_cidx / w.r_stride);
+            const int c = (int)(m_cidx - (int64_t)m_g * w.r_stride);
+            m_b = w.set_ids[(int64_t)m_g * w.n + h.r_off[m_node] + (c - h.r_base[m_node])];
+            m_ci0 = w.cand_idx[m_cidx * w.cand_cap];
+            m_pid0 = w.set_ids[(int64_t)m_g * w.n + h.l_off[m_node] + m_ci0];
+            m_eb = w.q8_err[(int64_t)m_g * pool.P + m_b];
+            m_ea0 = w.q8_err[(int64_t)m_g * pool.P + m_pid0];
         }
-        float cv = -INFINITY;
-        for (int k = 0; k < cnt; ++k) {
-            const uint4 *pa = reinterpret_cast<const uint4 *>(q8_g + (int64_t)__shfl(pid, k, 64) * pool.r);
-            float dot = 0.0f;
-            for (int q = lane; q < ch; q += 64)
-                dot = dot16_e4m3(pa[q], pb[q], dot);
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1)
-                dot += __shfl_xor(dot, off, 64);
-            if (lane == k)
-                cv = dot * inv_s2;
-        }
-        double lo = -INFINITY, hi = -INFINITY;
-        if (lane < cnt) {
-            w.cand_val[cidx * w.cand_cap + lane] = cv;
-            const double ea = (double)qe[pid], eb = (double)qe[b];
-            const double rad = band + ea + eb + ea * eb;
-            lo = (double)cv - rad;
-            hi = (double)cv + rad;
-        }
-        bool settled = false;
-        int result = -1;
-        if (rule == KVFUSE_RULE_FIRST_ROW) {
-            const bool certain = lane < cnt && lo > thr + band;
-            int i_def = certain ? ci : 0x7FFFFFFF;
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1)
-                i_def = min(i_def, __shfl_xor(i_def, off, 64));
-            const unsigned long long open = __ballot(lane < cnt && !certain && ci < i_def && !(hi < thr - band));
-            settled = open == 0ull;
-            result = i_def == 0x7FFFFFFF ? -1 : i_def;
-        } else {
-            double lo_max = lo, hi_max = hi;
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                lo_max = fmax(lo_max, __shfl_xor(lo_max, off, 64));
-                hi_max = fmax(hi_max, __shfl_xor(hi_max, off, 64));
+        const int n_here = min(kBatch, n_items - base);
+        for (int t = 0; t < n_here; ++t) {
+            const int64_t cidx = __shfl(m_cidx, t, 64);
+            const int node = __shfl(m_node, t, 64);
+            const int cnt = __shfl(m_cnt, t, 64);
+            if (cnt > w.cand_cap)           // overflowed list: the re-check rescans the whole column
+                continue;
+            const int g = __shfl(m_g, t, 64);
+            const int b = __shfl(m_b, t, 64);
+            const double eb = (double)__shfl(m_eb, t, 64);
+            const int32_t *l_ids = w.set_ids + (int64_t)g * w.n + h.l_off[node];
+            const uint8_t *q8_g = w.q8_k + (int64_t)g * pool.P * pool.r;
+            const float *qe = w.q8_err + (int64_t)g * pool.P;
+            const uint4 *pb = reinterpret_cast<const uint4 *>(q8_g + (int64_t)b * pool.r);
+            // candidates one per lane; the first one is already known
+            const int ci0 = __shfl(m_ci0, t, 64), pid0 = __shfl(m_pid0, t, 64);
+            const float ea0 = __shfl(m_ea0, t, 64);
+            int ci = 0x7FFFFFFF, pid = 0;
+            double ea = 0.0;
+            if (lane == 0) {
+                ci = ci0;
+                pid = pid0;
+                ea = (double)ea0;
+            } else if (lane < cnt) {
+                ci = w.cand_idx[cidx * w.cand_cap + lane];
+                pid = l_ids[ci];
+                ea = (double)qe[pid];
             }
-            const unsigned long long cont = __ballot(lane < cnt && hi >= lo_max);
-            if (hi_max < thr - band) {
-                settled = true;
-            } else if (__popcll(cont) == 1 && lo_max > thr + band) {
-                settled = true;
-                result = __shfl(ci, __ffsll((long long)cont) - 1, 64);
+            float cv = -INFINITY;
+            for (int k = 0; k < cnt; ++k) {
+                const uint4 *pa = reinterpret_cast<const uint4 *>(q8_g + (int64_t)__shfl(pid, k, 64) * pool.r);
+                float dot = 0.0f;
+                for (int q = lane; q < ch; q += 64)
+                    dot = dot16_e4m3(pa[q], pb[q], dot);
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1)
+                    dot += __shfl_xor(dot, off, 64);
+                if (lane == k)
+                    cv = dot * inv_s2;
             }
-        }
-        if (settled && lane == 0) {
-            w.assign[cidx] = result;
-            reinterpret_cast<int2 *>(w.refine)[it] = make_int2(-1, node);
+            double lo = -INFINITY, hi = -INFINITY;
+            if (lane < cnt) {
+                w.cand_val[cidx * w.cand_cap + lane] = cv;
+                const double rad = band + ea + eb + ea * eb;
+                lo = (double)cv - rad;
+                hi = (double)cv + rad;
+            }
+            bool settled = false;
+            int result = -1;
+            if (rule == KVFUSE_RULE_FIRST_ROW) {
+                const bool certain = lane < cnt && lo > thr + band;
+                int i_def = certain ? ci : 0x7FFFFFFF;
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1)
+                    i_def = min(i_def, __shfl_xor(i_def, off, 64));
+                const unsigned long long open = __ballot(lane < cnt && !certain && ci < i_def && !(hi < thr - band));
+                settled = open == 0ull;
+                result = i_def == 0x7FFFFFFF ? -1 : i_def;
+            } else {
+                double lo_max = lo, hi_max = hi;
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) {
+                    lo_max = fmax(lo_max, __shfl_xor(lo_max, off, 64));
+                    hi_max = fmax(hi_max, __shfl_xor(hi_max, off, 64));
+                }
+                const unsigned long long cont = __ballot(lane < cnt && hi >= lo_max);
+                if (hi_max < thr - band) {
+                    settled = true;
+                } else if (__popcll(cont) == 1 && lo_max > thr + band) {
+                    settled = true;
+                    result = __shfl(ci, __ffsll((long long)cont) - 1, 64);
+                }
+            }
+            if (settled && lane == 0) {
+                w.assign[cidx] = result;
+                reinterpret_cast<int2 *>(w.refine)[base + t] = make_int2(-1, node);
+            }
         }
     }
 }
@@ -669,7 +734,7 @@ void launch_assign(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, co
         const int bound = prefix ? (w.q8_k ? 3 : 1) : (w.q8_k ? 2 : 0);
         assign_screen_kernel<<<(unsigned)((cols + 255) / 256), 256, 0, s>>>(w, h, height, thr, band, rule, bound, pool.P);
         if (bound == 3) {
-            const unsigned fgrid = (unsigned)std::min<int64_t>((cols + 3) / 4, resident_workgroups(assign_q8_fill_kernel));
+            const unsigned fgrid = (unsigned)std::min<int64_t>((cols + 63) / 64, resident_workgroups(assign_q8_fill_kernel));
             assign_q8_fill_kernel<<<fgrid, 256, 0, s>>>(pool, w, h, height, thr, band, rule);
         }
         unsigned rgrid = 0;
