@@ -98,18 +98,6 @@ template <> struct MmaV<float> {
     }
 };
 
-template <> struct MmaV<fp8_t> {
-    // 16 bytes per lane = two K steps of 16 e4m3 values (8 bytes per lane each)
-    __device__ static __forceinline__ floatx16 run(const u32x4 a, const u32x4 b, floatx16 c)
-    {
-        c = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8((long)(((unsigned long long)a.y << 32) | a.x),
-                                                       (long)(((unsigned long long)b.y << 32) | b.x), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8((long)(((unsigned long long)a.w << 32) | a.z),
-                                                       (long)(((unsigned long long)b.w << 32) | b.z), c, 0, 0, 0);
-        return c;
-    }
-};
-
 // One 64-byte K slice of the fp8 copies in a single instruction: v_mfma_f32_32x32x64_f8f6f4 with both operands e4m3
 // (twice the rate of the 16-wide instructions).  A lane supplies 32 bytes per operand, here as two 16-byte fragments;
 // any assignment of a row's 64 bytes to (lane half, byte) works as long as both operands use the same one.

@@ -391,7 +391,7 @@ def test_fp8_screen_copy_and_bound(kb, oracle, kind):
 @pytest.mark.parametrize("rule", ["argmax", "first_row"])
 @pytest.mark.parametrize("which", ["small_bf16", "small_bf16_cap2", "zipf_small", "zipf_at_threshold", "mixed_small_f32",
                                    "r4096_bf16_with_quarter_prefix", "tiny_f32_with_half_prefix", "r8192_bf16_long_blocks",
-                                   "zipf_at_threshold_with_half_prefix", "small_bf16_cap2_with_half_prefix"])
+                                   "zipf_at_threshold_with_half_prefix", "small_bf16_cap2_with_half_prefix", "r128_bf16_two_slices"])
 def test_tree_fp8_screen_gives_the_same_tables(kb, oracle, which, rule):
     """The fp8 screen (similarity over one-byte copies of the key blocks + their measured error as a bound, every candidate
     evaluated in full in fp64) must give exactly the oracle's tables, pools and counters, alone and together with the prefix
@@ -419,6 +419,8 @@ def test_tree_fp8_screen_gives_the_same_tables(kb, oracle, which, rule):
         rec = wl.zipf_bff(n_req=8, tokens=32 * 40, layers=1, kv_heads=2, pool=60, t=32, d=64, sigma=sigma,
                           thr=1.0 / (1.0 + sigma * sigma))
         kw = dict(kw, screen_prefix=1024)
+    elif which == "r128_bf16_two_slices":
+        rec = _small_bf16(n_req=4, tokens=4 * 140, t=4, d=32, prefix_tokens=32)        # the shortest blocks the byte copies allow
     elif which == "small_bf16_cap2_with_half_prefix":
         rec, kw = _small_bf16(n_req=5, tokens=900), dict(kw, cand_cap=2, screen_prefix=128)
     elif which == "r8192_bf16_long_blocks":
