@@ -339,7 +339,8 @@ def per_height_table(kb, ctx, cache, plan, rec, restore, thr):
     restore()
     kb.block_norms(ctx, cache)
     kb.leaf_sets(ctx, plan)
-    elem = 2 if rec.dtype == torch.bfloat16 else 4
+    # bytes per element of what the similarity kernel reads: the pool, or its one-byte copy under the fp8 screen
+    elem = 1 if getattr(plan, "k8", None) is not None else (2 if rec.dtype == torch.bfloat16 else 4)
     rows = []
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     for h in range(plan.n_heights):
