@@ -268,7 +268,7 @@ class PowerSampler:
         return dt / n * 1e3, (sum(tail) / len(tail) if tail else None), (max(tail) if tail else None)
 
 
-def power_report(kb, kp, ctx, cache, plan, rec, restore, torch):
+def power_report(kb, kp, ctx, cache, plan, rec, restore, torch, decode_step=None):
     """Socket power while the similarity stage runs on full sets, next to the machine probes and an HBM-bound kernel:
     shows which limit the dominant kernel runs at (the board's power cap is read from the same hwmon node)."""
     ps = PowerSampler()
@@ -294,8 +294,16 @@ def power_report(kb, kp, ctx, cache, plan, rec, restore, torch):
     out["mfma_probe_random_operands"] = {"mean_W": mean, "max_W": mx}
     ms, mean, mx = ps.measure(lambda: kp.mfma_bf16(False, dev), 2.0, sync)
     out["mfma_probe_constant_operands"] = {"mean_W": mean, "max_W": mx}
+    ms, mean, mx = ps.measure(lambda: kp.mfma_fp8(True, dev), 2.0, sync)
+    out["mfma_fp8_probe_random_operands"] = {"mean_W": mean, "max_W": mx}
+    ms, mean, mx = ps.measure(lambda: kp.mfma_fp8(False, dev), 2.0, sync)
+    out["mfma_fp8_probe_constant_operands"] = {"mean_W": mean, "max_W": mx}
     ms, mean, mx = ps.measure(lambda: kb.block_norms(ctx, cache), 1.5, sync)
     out["block_norms_hbm_stream"] = {"ms": ms, "mean_W": mean, "max_W": mx}
+    if decode_step is not None:         # decode attention over the un-fused cache: the other HBM stream of a step
+        cache.identity_scales()
+        ms, mean, mx = ps.measure(decode_step, 1.5, sync)
+        out["decode_unfused_hbm_stream"] = {"ms": ms, "mean_W": mean, "max_W": mx}
     cache.K.zero_()
     kb.block_norms(ctx, cache)
     ms, mean, mx = ps.measure(sim_tree, 2.5, sync)
@@ -713,6 +721,8 @@ def main():
     blk_bytes_probe = rec.r * (2 if rec.dtype == torch.bfloat16 else 4)
     probes = {"mfma_bf16_random_operands_TFLOPs": kp.mfma_bf16(True, dev),
               "mfma_bf16_constant_operands_TFLOPs": kp.mfma_bf16(False, dev),
+              "mfma_fp8_random_operands_TFLOPs": kp.mfma_fp8(True, dev),
+              "mfma_fp8_constant_operands_TFLOPs": kp.mfma_fp8(False, dev),
               "tile_loop_bf16_TFLOPs": kp.tile_loop_bf16(K0, True) if rec.dtype == torch.bfloat16 else None,
               "tile_loop_bf16_no_loads_TFLOPs": kp.tile_loop_bf16(K0, False) if rec.dtype == torch.bfloat16 else None,
               "copy_kernel_GBps": kp.copy(K0, cache.K, repeats=3),
@@ -797,7 +807,9 @@ def main():
     if args.per_height:
         line["per_height"] = per_height_table(kb, ctx, cache, plan, rec, restore, rec.thr)
     if args.power:
-        line["power"] = power_report(kb, kp, ctx, cache, plan, rec, restore, torch)
+        line["power"] = power_report(kb, kp, ctx, cache, plan, rec, restore, torch,
+                                     decode_step=lambda: kb.paged_decode_attn(ctx, cache, rec.kv_heads, q, rs, cl, max_blocks,
+                                                                              workspace=ws, out=out))
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, reduced=args.cpu_baseline_reduced)
     print(json.dumps(line))

@@ -35,6 +35,10 @@ const char *kvfuse_probe_last_error(void);
  * tflops: host.  About 50 - 100 ms. */
 int kvfuse_probe_mfma_bf16(void *hip_stream, int32_t random_operands, void *scratch, size_t scratch_bytes, double *tflops);
 
+/* The same for the fp8 instruction of the opt-in fp8 screen (v_mfma_f32_32x32x64_f8f6f4 on two e4m3 operands), whose
+ * nominal dense peak is twice the bfloat16 one.  Same arguments. */
+int kvfuse_probe_mfma_fp8(void *hip_stream, int32_t random_operands, void *scratch, size_t scratch_bytes, double *tflops);
+
 /* Rate of a plain device copy kernel (one 16-byte chunk per lane, one workgroup per 4 KB, workgroups handed out in
  * address order), read + write bytes per second: the HBM ceiling for one read per write.  src, dst: device, bytes each
  * (below 8 TiB), not overlapping; gbps: host. */

@@ -48,6 +48,70 @@ __global__ __launch_bounds__(512, 1) void probe_mfma_kernel(const uint4 *__restr
         sink[0] = s;
 }
 
+// The same with the fp8 instruction of the fp8 screen, v_mfma_f32_32x32x64_f8f6f4 on two e4m3 operands (32 bytes per lane
+// and operand): eight accumulators, operands in registers.
+typedef int intx8 __attribute__((ext_vector_type(8)));
+__global__ __launch_bounds__(512, 1) void probe_mfma_fp8_kernel(const uint4 *__restrict__ operands, int iters, float *__restrict__ sink)
+{
+    const int tid = threadIdx.x;
+    uint4 a[8], b[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        a[q] = operands[(tid * 8 + q) & 4095];
+        b[q] = operands[(tid * 8 + q + 2048) & 4095];
+    }
+    floatx16 acc[8];
+#pragma unroll
+    for (int x = 0; x < 8; ++x)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            acc[x][e] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                const uint4 a0 = a[(x + s) & 3], a1 = a[4 + ((x + s) & 3)];
+                const uint4 b0 = b[(x * 3 + s) & 3], b1 = b[4 + ((x * 3 + s) & 3)];
+                const intx8 av = {(int)a0.x, (int)a0.y, (int)a0.z, (int)a0.w, (int)a1.x, (int)a1.y, (int)a1.z, (int)a1.w};
+                const intx8 bv = {(int)b0.x, (int)b0.y, (int)b0.z, (int)b0.w, (int)b1.x, (int)b1.y, (int)b1.z, (int)b1.w};
+                acc[x] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, bv, acc[x], 0, 0, 0, 0, 0, 0);
+            }
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int x = 0; x < 8; ++x)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            s += acc[x][e];
+    if (s == 12345.678f)
+        sink[0] = s;
+}
+
+// fp8 operands: e4m3 ones (0x38), or pseudo-random values with exponents within two binades of 1, random mantissa and sign
+__global__ void probe_fill_fp8_kernel(uint4 *__restrict__ operands, int random_operands)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= 4096)
+        return;
+    uint32_t w[4];
+    uint32_t st = 0x9E3779B9u * (uint32_t)(i + 1);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        uint32_t v = 0x38383838u;
+        if (random_operands) {
+            v = 0u;
+            for (int by = 0; by < 4; ++by) {
+                st = st * 1664525u + 1013904223u;
+                const uint32_t e = 5u + ((st >> 12) & 3u), m = (st >> 8) & 7u, sg = (st >> 20) & 1u;
+                v |= ((sg << 7) | (e << 3) | m) << (8 * by);
+            }
+        }
+        w[k] = v;
+    }
+    operands[i] = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
 __global__ void probe_fill_kernel(uint4 *__restrict__ operands, int random_operands)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -194,6 +258,14 @@ void launch_probe_mfma(hipStream_t s, const void *operands, int workgroups, int 
 {
     probe_mfma_kernel<<<workgroups, 512, 0, s>>>(reinterpret_cast<const uint4 *>(operands), iters, sink);
 }
+void launch_probe_fill_fp8(hipStream_t s, void *operands, int random_operands)
+{
+    probe_fill_fp8_kernel<<<16, 256, 0, s>>>(reinterpret_cast<uint4 *>(operands), random_operands);
+}
+void launch_probe_mfma_fp8(hipStream_t s, const void *operands, int workgroups, int iters, float *sink)
+{
+    probe_mfma_fp8_kernel<<<workgroups, 512, 0, s>>>(reinterpret_cast<const uint4 *>(operands), iters, sink);
+}
 void launch_probe_copy(hipStream_t s, const void *src, void *dst, size_t bytes)
 {
     const size_t n16 = bytes / 16;
@@ -227,7 +299,7 @@ extern "C" {
 
 const char *kvfuse_probe_last_error(void) { return last_error.c_str(); }
 
-int kvfuse_probe_mfma_bf16(void *hip_stream, int32_t random_operands, void *scratch, size_t scratch_bytes, double *tflops)
+static int probe_mfma(void *hip_stream, int32_t random_operands, void *scratch, size_t scratch_bytes, double *tflops, bool fp8)
 {
     hipStream_t stream = (hipStream_t)hip_stream;
     if (!scratch || !tflops || scratch_bytes < (size_t)KVFUSE_PROBE_SCRATCH_BYTES)
@@ -242,10 +314,19 @@ int kvfuse_probe_mfma_bf16(void *hip_stream, int32_t random_operands, void *scra
     hipEvent_t e0, e1;
     PROBE_HIP(hipEventCreate(&e0));
     PROBE_HIP(hipEventCreate(&e1));
-    launch_probe_fill(stream, scratch, random_operands);
-    launch_probe_mfma(stream, scratch, wgs, iters / 10, sink);     // warm-up
+    auto run = [&](int n) {
+        if (fp8)
+            launch_probe_mfma_fp8(stream, scratch, wgs, n, sink);
+        else
+            launch_probe_mfma(stream, scratch, wgs, n, sink);
+    };
+    if (fp8)
+        launch_probe_fill_fp8(stream, scratch, random_operands);
+    else
+        launch_probe_fill(stream, scratch, random_operands);
+    run(iters / 10);     // warm-up
     hipError_t err = hipEventRecord(e0, stream);
-    launch_probe_mfma(stream, scratch, wgs, iters, sink);
+    run(iters);
     if (err == hipSuccess)
         err = hipEventRecord(e1, stream);
     if (err == hipSuccess)
@@ -257,9 +338,19 @@ int kvfuse_probe_mfma_bf16(void *hip_stream, int32_t random_operands, void *scra
     (void)hipEventDestroy(e1);
     PROBE_HIP(err);
     PROBE_HIP(hipGetLastError());
-    // per wavefront and iteration: 32 MFMAs of 2 * 32 * 32 * 16 flops
-    *tflops = ms > 0.0f ? (double)wgs * 8.0 * iters * 32.0 * 32768.0 / (ms * 1e-3) / 1e12 : 0.0;
+    // per wavefront and iteration: 32 MFMAs of 2 * 32 * 32 * 16 flops (bfloat16) or 2 * 32 * 32 * 64 (fp8)
+    *tflops = ms > 0.0f ? (double)wgs * 8.0 * iters * 32.0 * (fp8 ? 131072.0 : 32768.0) / (ms * 1e-3) / 1e12 : 0.0;
     return KVFUSE_PROBE_OK;
+}
+
+int kvfuse_probe_mfma_bf16(void *hip_stream, int32_t random_operands, void *scratch, size_t scratch_bytes, double *tflops)
+{
+    return probe_mfma(hip_stream, random_operands, scratch, scratch_bytes, tflops, false);
+}
+
+int kvfuse_probe_mfma_fp8(void *hip_stream, int32_t random_operands, void *scratch, size_t scratch_bytes, double *tflops)
+{
+    return probe_mfma(hip_stream, random_operands, scratch, scratch_bytes, tflops, true);
 }
 
 int kvfuse_probe_copy(void *hip_stream, const void *src, void *dst, size_t bytes, int32_t repeats, double *gbps)

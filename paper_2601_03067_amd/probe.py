@@ -19,6 +19,7 @@ SCRATCH_BYTES = 65792
 _vp, _i32 = C.c_void_p, C.c_int32
 lib.kvfuse_probe_last_error.restype = C.c_char_p
 lib.kvfuse_probe_mfma_bf16.argtypes = [_vp, _i32, _vp, C.c_size_t, C.POINTER(C.c_double)]
+lib.kvfuse_probe_mfma_fp8.argtypes = [_vp, _i32, _vp, C.c_size_t, C.POINTER(C.c_double)]
 lib.kvfuse_probe_copy.argtypes = [_vp, _vp, _vp, C.c_size_t, _i32, C.POINTER(C.c_double)]
 lib.kvfuse_probe_tile_loop_bf16.argtypes = [_vp, _vp, C.c_size_t, _i32, _vp, C.POINTER(C.c_double)]
 lib.kvfuse_probe_read2_write1.argtypes = [_vp, _vp, C.c_size_t, _i32, _i32, C.POINTER(C.c_double)]
@@ -48,6 +49,14 @@ def mfma_bf16(random_operands=True, device="cuda:0"):
     scratch = torch.empty(SCRATCH_BYTES, device=device, dtype=torch.uint8)
     out = C.c_double(0.0)
     _check(lib.kvfuse_probe_mfma_bf16(_stream(device), 1 if random_operands else 0, _ptr(scratch), scratch.numel(), C.byref(out)))
+    return out.value
+
+
+def mfma_fp8(random_operands=True, device="cuda:0"):
+    """Sustained rate of the fp8 (e4m3) 32 x 32 x 64 MFMA of the whole GPU in TFLOP/s (operands in registers)."""
+    scratch = torch.empty(SCRATCH_BYTES, device=device, dtype=torch.uint8)
+    out = C.c_double(0.0)
+    _check(lib.kvfuse_probe_mfma_fp8(_stream(device), 1 if random_operands else 0, _ptr(scratch), scratch.numel(), C.byref(out)))
     return out.value
 
 

@@ -41,7 +41,7 @@ def test_every_declared_function_is_exported(lib):
 def test_probe_library_is_separate_and_exports_its_header(lib):
     """The machine probes are bench tooling: their own header and shared library, nothing of them in the product."""
     names = _declared(PROBE_HEADER)
-    assert len(names) == 5 and all(n.startswith("kvfuse_probe_") for n in names)
+    assert len(names) == 6 and all(n.startswith("kvfuse_probe_") for n in names)
     plib = ctypes.CDLL(PROBE_LIB)
     assert not [n for n in names if not hasattr(plib, n)]
     assert not [n for n in names if hasattr(lib, n)]

@@ -1161,6 +1161,9 @@ def test_machine_probes_run_and_copy_is_exact():
     const = kp.mfma_bf16(False, DEV)
     _say("  mfma bf16 TFLOP/s: random operands", round(rnd), "constant operands", round(const), "copy GB/s (small)", round(gbps))
     assert 50 < rnd < 2600 and 50 < const < 2600      # below the nominal dense peak of 2500 plus timing slack
+    rnd8, const8 = kp.mfma_fp8(True, DEV), kp.mfma_fp8(False, DEV)
+    _say("  mfma fp8 TFLOP/s: random operands", round(rnd8), "constant operands", round(const8))
+    assert 50 < rnd8 < 5200 and 50 < const8 < 5200    # nominal dense fp8 peak 5000
     data = torch.randn(4 << 20, device=DEV).to(torch.bfloat16)          # 8 MiB of cache-like values
     loop = kp.tile_loop_bf16(data, True)
     loop0 = kp.tile_loop_bf16(data, False)
