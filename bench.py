@@ -644,7 +644,6 @@ def main():
                 best = qst
         same = bool(torch.equal(cache.bt, bt_ref)) and bool(torch.equal(cache.K, k_ref)) and best.fused == ref_st.fused
         err = plan.k8_err[plan.k8_err > 0]
-        del bt_ref, k_ref
         ms_equiv = best.ms_total + stage["decode"] / max(args.steps, 1)
         eff = best.sim_flops / (best.ms_similarity * 1e-3) / 1e12
         fp8_screen = {"fuse_ms": best.ms_total, "similarity_ms": best.ms_similarity, "assign_ms": best.ms_assign,
@@ -656,6 +655,25 @@ def main():
                       "extra_device_bytes": int(plan.k8.numel() + plan.k8_err.numel() * 4),
                       "step_ms_with_decode": ms_equiv, "blocks_per_s_with_decode": rec.G * rec.n / (ms_equiv * 1e-3),
                       "note": "opt-in (kvfuse_plan_set_screen_fp8); not used in the timed steps, `value` and `roofline`"}
+        if rec.r // 4 >= 128 and (rec.r // 4) % 64 == 0:
+            # both shortcuts together: the product over the first quarter of the copies
+            kb.set_screen_prefix(ctx, plan, rec.r // 4)
+            best2 = None
+            for _ in range(3):
+                restore()
+                torch.cuda.synchronize()
+                bst = kb.fuse_tree(ctx, plan, rec.thr, want_stats=True, want_timing=True)
+                if best2 is None or bst.ms_total < best2.ms_total:
+                    best2 = bst
+            same2 = bool(torch.equal(cache.bt, bt_ref)) and bool(torch.equal(cache.K, k_ref)) and best2.fused == ref_st.fused
+            ms2 = best2.ms_total + stage["decode"] / max(args.steps, 1)
+            fp8_screen["with_quarter_prefix"] = {
+                "fuse_ms": best2.ms_total, "similarity_ms": best2.ms_similarity, "assign_ms": best2.ms_assign,
+                "merge_ms": best2.ms_merge, "norms_ms": best2.ms_norms, "refined_fp64": best2.refined,
+                "tables_and_fused_keys_equal_to_full_screen": same2,
+                "step_ms_with_decode": ms2, "blocks_per_s_with_decode": rec.G * rec.n / (ms2 * 1e-3)}
+            kb.set_screen_prefix(ctx, plan, 0)
+        del bt_ref, k_ref
         kb.set_screen_fp8(ctx, plan, False)
 
     # The same step (fusion without the statistics read-back + decode) recorded once in a HIP graph on a stream of
