@@ -409,11 +409,15 @@ int kvfuse_plan_set_screen_prefix(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t pr
  *     | cos(a, b) - <q(a), q(b)> / 256^2 |  <=  err(a) + err(b) + err(a) * err(b)
  * (Cauchy-Schwarz twice), so the similarity step multiplies the byte copies on the fp8 matrix cores (twice the rate of
  * bfloat16 and half the bytes through LDS and L2) and lists a pair when the product plus this bound clears
- * thr - 2 * band.  The assignment step evaluates every listed candidate in full in fp64 on the pool itself: targets,
- * tables and fused blocks are the same as without the shortcut, whatever the data; blocks that quantise badly (err is
- * measured, not assumed: typically 0.02 - 0.03) only produce more candidates.  Combines with the prefix screen: the product
+ * thr - 2 * band.  The assignment step takes a listed product as the centre of an interval of radius band + bound: a
+ * column is settled from the intervals when one row's lower end clears thr + band and every other listed row's upper
+ * end (or, under the row-order rule, when no undecided row comes before the first certain one); every other column is
+ * evaluated in fp64 on the pool itself, exactly as the undecided columns of the full-length screen are.  Targets, tables
+ * and fused blocks are therefore the same as without the shortcut, whatever the data; blocks that quantise badly (err is
+ * measured, not assumed: typically 0.02 - 0.03) only get wider intervals.  Combines with the prefix screen: the product
  * then runs over the first prefix_elements bytes, which must be a multiple of 64 and at least 128 (set the prefix after
- * this call, or switch it off first).
+ * this call, or switch it off first); the assignment step then first multiplies the whole copies of the listed pairs to
+ * get such intervals back.
  *   k8      device, G * P * t * d bytes, block b of group g at (g * P + b) * t * d; owned by the caller, alive while the
  *           plan is used; written by kvfuse_leaf_sets / kvfuse_fuse_tree (all key blocks) and after every merge (the
  *           rebuilt targets)
