@@ -546,10 +546,11 @@ def test_tree_shortest_first_order(kb, oracle, which):
     assert stats.fused > 20
 
 
-@pytest.mark.parametrize("seed", [1, 2, 3, 4, 5, 6, 10, 14, 20, 21])
+@pytest.mark.parametrize("seed", [1, 2, 3, 4, 5, 6, 10, 14, 20, 21, 22, 23, 24, 25, 27, 30, 33, 35])
 def test_tree_seeded_sweep(kb, oracle, seed):
     """Seeded small workloads of all four structures with the variants mixed at random: assignment rule, request order,
-    request groups, candidate slots (1 slot = every multi-candidate column is rescanned), dtype."""
+    request groups, candidate slots (1 slot = every multi-candidate column is rescanned), dtype, and which screen the
+    similarity step uses (full product, prefix, fp8 copies, both)."""
     rng = np.random.default_rng(seed)
     kind = seed % 4
     dtype = torch.bfloat16 if seed % 3 else torch.float32
@@ -572,8 +573,10 @@ def test_tree_seeded_sweep(kb, oracle, seed):
     shortest_first = bool(seed % 5 == 0 or seed % 7 == 0)
     group_size = int(rng.choice([0, 0, 2, 3]))
     cand_cap = int(rng.choice([1, 3, 16, 64]))
-    _run_tree_case(kb, oracle, rec, f"sweep_{seed}", cand_cap=cand_cap, rule=rule, shortest_first=shortest_first,
-                   group_size=group_size)
+    screen = ("full", "prefix", "fp8", "both")[(seed // 2) % 4]      # blocks have 256 or 512 elements here
+    _run_tree_case(kb, oracle, rec, f"sweep_{seed}_{screen}", cand_cap=cand_cap, rule=rule, shortest_first=shortest_first,
+                   group_size=group_size, screen_prefix=128 if screen in ("prefix", "both") else 0,
+                   screen_fp8=screen in ("fp8", "both"))
 
 
 def test_tree_variants_combined(kb, oracle):
