@@ -251,10 +251,12 @@ __device__ __forceinline__ void quantise_chunk(const uint4 &raw, double inv, flo
             se = fma(diff, diff, se);
         }
     }
-    if constexpr (PER == 8)
-        *reinterpret_cast<uint2 *>(dst) = make_uint2(w[0], w[1]);
-    else
-        *reinterpret_cast<uint32_t *>(dst) = w[0];
+    if constexpr (PER == 8) {
+        __builtin_nontemporal_store(w[0], reinterpret_cast<uint32_t *>(dst));
+        __builtin_nontemporal_store(w[1], reinterpret_cast<uint32_t *>(dst) + 1);
+    } else {
+        __builtin_nontemporal_store(w[0], reinterpret_cast<uint32_t *>(dst));
+    }
 }
 
 __device__ __forceinline__ float quantise_error(double se, double nrm)
