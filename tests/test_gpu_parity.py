@@ -1120,9 +1120,11 @@ def test_pair_cosines_and_moments_match_oracle(kb, kind):
     assert kb.exceedance_rate(1e6, mu, math.sqrt(var), rec.thr) == pytest.approx(th.exceedance_rate(1e6, mu, math.sqrt(var), rec.thr), rel=1e-12, abs=1e-300)
 
 
-def test_group_mask_skips_groups_and_leaves_the_rest_unchanged(kb, oracle):
-    """A switched-off group comes out of the tree untouched; the other groups are bit-identical to an unmasked run."""
-    _say("group mask")
+@pytest.mark.parametrize("screen", ["full_product", "both_screens"])
+def test_group_mask_skips_groups_and_leaves_the_rest_unchanged(kb, oracle, screen):
+    """A switched-off group comes out of the tree untouched; the other groups are bit-identical to an unmasked run (which
+    uses the full product, also when the masked run goes through the two screens)."""
+    _say("group mask", screen)
     rec = _small_bf16(n_req=6, tokens=800, kv_heads=4)
     mat_a = wl.materialise(rec, DEV, phys_perm=True)
     cache_a, plan_a, stats_a, ctx = gu.gpu_fuse(rec, mat_a)
@@ -1130,6 +1132,9 @@ def test_group_mask_skips_groups_and_leaves_the_rest_unchanged(kb, oracle):
     K0, V0, bt0 = mat_b["K"].clone(), mat_b["V"].clone(), mat_b["bt"].clone()
     cache_b = kb.Cache(mat_b["K"], mat_b["V"], mat_b["bt"], rec.t, rec.d)
     plan_b = kb.Plan(ctx, cache_b, kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr, rec.group_size), 16)
+    if screen == "both_screens":
+        kb.set_screen_fp8(ctx, plan_b)
+        kb.set_screen_prefix(ctx, plan_b, 128)
     mask = torch.tensor([1, 0, 1, 0], dtype=torch.uint8, device=DEV)
     kb.set_group_mask(ctx, plan_b, mask)
     stats_b = kb.fuse_tree(ctx, plan_b, rec.thr, want_stats=True)
