@@ -92,6 +92,16 @@ def test_llama8b_bff_full_size_sampled_groups_and_invariants(oracle, rule):
     print("decode max abs err on sampled outputs", worst, flush=True)
     assert worst <= 2e-2
 
+    # ---- shared-block decode attention at full size: same outputs as the per-request kernel, hence as the oracle
+    if rule == "argmax" and not screen_prefix and not screen_fp8:
+        splan = kb.SharedDecodePlan(ctx, cache, rec.kv_heads, rec.req_start, rec.ctx_len, rec.q_heads, min_cluster_blocks=4)
+        out_sh = kb.paged_decode_attn_shared(ctx, cache, splan, q)
+        torch.cuda.synchronize()
+        assert splan.info.clusters >= rec.G                      # the common prefix of every group, at least
+        d_sh = float((out_sh - out).abs().max())
+        print("shared-block decode: clusters", splan.info.clusters, "max abs diff vs per-request decode", d_sh, flush=True)
+        assert d_sh <= 1e-5
+
 
 @pytest.mark.timeout(600)
 def test_cff_long_full_size_sampled_groups_and_invariants(oracle):
@@ -150,6 +160,33 @@ def test_cff_long_full_size_sampled_groups_and_invariants(oracle):
         worst = max(worst, float(np.abs(out[layer].cpu().numpy() - ref).max()))
     print("decode max abs err on sampled outputs", worst, flush=True)
     assert worst <= 2e-2
+
+    # ---- chunked-prefill attention of the last chunk over the fused 32768-token context, two layers, with and without
+    # reuse of fused blocks; sampled query rows of every head against the oracle
+    chunk_tokens = int(rec.leaf_count[-1]) * rec.t
+    total = int(rec.ctx_len[0])
+    cb_tok = (total - 1) // chunk_tokens * chunk_tokens
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(20260103 + 33)
+    qp = torch.randn(2, total - cb_tok, rec.q_heads, rec.d, generator=gen).to(rec.dtype).to(DEV)
+    rows = np.unique(np.concatenate([[0, 1, total - cb_tok - 1], rng.choice(total - cb_tok, size=29, replace=False)]))
+    outs = []
+    for reuse in (True, False):
+        pp = kb.PrefillPlan(ctx, cache, rec.kv_heads, rec.q_heads, int(rec.req_start[0]), cb_tok, cb_tok, total, n_layers=2,
+                            reuse=reuse)
+        outs.append(kb.prefill_attn(ctx, cache, pp, qp))
+    torch.cuda.synchronize()
+    assert float((outs[0] - outs[1]).abs().max()) <= 1e-4
+    worst = 0.0
+    for layer in range(2):
+        gs = [layer * rec.kv_heads + h for h in range(rec.kv_heads)]
+        ref = oracle.causal_prefill_attention(
+            qp[layer][rows].float().cpu().numpy(), cb_tok + rows, [wl.to_numpy_pool(cache.K[g]) for g in gs],
+            [wl.to_numpy_pool(cache.V[g]) for g in gs], [bt[g] for g in gs], [sk[g].astype(np.float64) for g in gs],
+            [cache.scale_v[g].cpu().numpy().astype(np.float64) for g in gs], int(rec.req_start[0]), rec.t, rec.d)
+        worst = max(worst, float(np.abs(outs[0][layer][rows].cpu().numpy() - ref).max()))
+    print("prefill (last chunk, 2 layers) max abs err on", len(rows), "sampled query rows", worst, flush=True)
+    assert worst <= 5e-3
 
 
 @pytest.mark.timeout(600)
