@@ -213,6 +213,12 @@ int kvfuse_rewrite_block_table(kvfuse_ctx *ctx, const kvfuse_pool *pool, const k
 int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band, int32_t *free_list,
                      int32_t *n_free, int32_t *n_phys, kvfuse_stats *stats, int32_t want_timing);
 
+/* The counters of the last tree run on this plan, group by group (the results section reports that layers fuse very
+ * different numbers of blocks; kvfuse_stats holds the sums).  out: host [G][4] int32: right blocks fused, decisions within
+ * `band` of thr, decisions re-evaluated in fp64, columns whose candidate list overflowed.  Waits for the context's
+ * stream.  n_groups must be the plan's G. */
+int kvfuse_plan_group_counters(kvfuse_ctx *ctx, const kvfuse_plan *plan, int32_t *out, int32_t n_groups);
+
 /* ---- a7: paged decode attention through the (fused) table -------------------------------------------- */
 
 /* Workspace bytes for a decode call over n_layers layers, B requests, Hq query heads, kv_heads KV heads. */

@@ -126,6 +126,7 @@ lib.kvfuse_threshold_feedback.argtypes = [_f64] * 6
 lib.kvfuse_threshold_feedback.restype = _f64
 lib.kvfuse_plan_set_group_mask.argtypes = [_vp, _vp, _vp]
 lib.kvfuse_plan_set_assign_rule.argtypes = [_vp, _vp, _i32]
+lib.kvfuse_plan_group_counters.argtypes = [_vp, _vp, _vp, _i32]
 lib.kvfuse_plan_set_screen_prefix.argtypes = [_vp, _vp, _i32, _vp]
 lib.kvfuse_plan_set_screen_fp8.argtypes = [_vp, _vp, _vp, _vp]
 lib.kvfuse_tree_spec_shortest_first.argtypes = [C.POINTER(TreeSpec), _vp, _vp, _vp, _vp]
@@ -471,6 +472,13 @@ def set_screen_fp8(ctx, plan, on=True):
     else:
         ctx.check(lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, None, None))
         plan.k8 = plan.k8_err = None
+
+
+def group_counters(ctx, plan):
+    """kvfuse_plan_group_counters -> numpy [G][4]: fused, near-threshold, refined in fp64, candidate overflow, per group."""
+    out = np.zeros((plan.cache.G, 4), np.int32)
+    ctx.check(lib.kvfuse_plan_group_counters(ctx.h, plan.h, out.ctypes.data, plan.cache.G))
+    return out
 
 
 def set_assign_rule(ctx, plan, rule):

@@ -705,6 +705,25 @@ int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band
 #undef KVF_TRY
 }
 
+int kvfuse_plan_group_counters(kvfuse_ctx *ctx, const kvfuse_plan *plan, int32_t *out, int32_t n_groups)
+{
+    if (!ctx)
+        return KVFUSE_EINVAL;
+    Ctx *c = &ctx->c;
+    if (!plan || !out)
+        return fail(c, KVFUSE_EINVAL, "group counters: null plan or output");
+    const WorkDesc &w = plan->p.work;
+    if (n_groups != w.G)
+        return fail(c, KVFUSE_EINVAL, "group counters: n_groups must be the plan's number of groups");
+    std::vector<int32_t> raw((size_t)w.G * 8);
+    KVF_HIP(c, hipStreamSynchronize(c->stream));
+    KVF_HIP(c, hipMemcpy(raw.data(), w.counters, raw.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+    for (int g = 0; g < w.G; ++g)
+        for (int k = 0; k < 4; ++k)
+            out[(size_t)g * 4 + k] = raw[(size_t)g * 8 + k];
+    return KVFUSE_OK;
+}
+
 int kvfuse_plan_set_group_mask(kvfuse_ctx *ctx, kvfuse_plan *plan, const uint8_t *enable)
 {
     if (!ctx)

@@ -184,6 +184,10 @@ def _run_tree_case(kb, oracle, rec, name, cand_cap=16, thr=None, phys_perm=True,
         assert stats.near_threshold == sum(int(r.stats[2]) for r in res)
         assert stats.physical_blocks == sum(r.n_physical for r in res)
         assert math.isclose(stats.compression_ratio, sum(len(r.bt) for r in res) / sum(r.n_physical for r in res))
+    # the same counters group by group
+    per_group = kb.group_counters(ctx, plan)
+    assert per_group[:, 0].tolist() == [int(r.stats[1]) for r in res] and per_group[:, 1].tolist() == [int(r.stats[2]) for r in res]
+    assert int(per_group[:, 2].sum()) == stats.refined and int(per_group[:, 3].sum()) == stats.cand_overflow
     _say("  fused", stats.fused, "refined", stats.refined, "overflow", stats.cand_overflow, "CR", round(stats.compression_ratio, 4))
     return cache, plan, stats, res, mat
 
