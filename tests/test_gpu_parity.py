@@ -438,6 +438,32 @@ def test_tree_fp8_screen_gives_the_same_tables(kb, oracle, which, rule):
     assert stats.fused > 0
 
 
+@pytest.mark.parametrize("screen", ["full", "prefix", "fp8", "both"])
+def test_tree_screens_when_unrelated_blocks_share_a_direction(kb, oracle, screen):
+    """Keys with a strong common component (unrelated blocks at cosine 0.8, threshold 0.9): the case the two screens are
+    not made for.  Their bounds list many pairs that do not fuse, candidate lists overflow and columns are rescanned in
+    fp64 -- slower, and still exactly the oracle's tables, pools and counters."""
+    rec = _small_bf16(n_req=5, tokens=8 * 110, kv_heads=2)
+    mat = wl.materialise(rec, DEV, phys_perm=True)
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(4242)
+    for g in range(rec.G):
+        mu = (2.0 * torch.randn(rec.r, generator=gen)).to(DEV)
+        mat["K"][g] = (mat["K"][g].float() + mu).to(rec.dtype)
+    host = gu.host_copy(mat)
+    prefix = {"prefix": 64, "both": 128}.get(screen, 0)       # blocks of 256 elements; the byte copies need 128 at least
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, cand_cap=8, screen_prefix=prefix, screen_fp8=screen in ("fp8", "both"))
+    res = gu.oracle_fuse(oracle, rec, host)
+    assert gu.check_ambiguity(res, "common_direction_" + screen) == list(range(rec.G))
+    for g in range(rec.G):
+        gu.compare_group(res[g], cache, g, False, "common_direction_" + screen)
+    assert stats.fused == sum(int(r.stats[1]) for r in res) > 50
+    assert stats.near_threshold == sum(int(r.stats[2]) for r in res)
+    _say("  screen", screen, "fused", stats.fused, "refined", stats.refined, "overflow", stats.cand_overflow)
+    if screen != "full":
+        assert stats.cand_overflow > 0        # the bounds did list more pairs than the lists hold
+
+
 def test_fp8_screen_step_by_step_and_arguments(kb, oracle):
     """The single-step entry points with the fp8 screen on (the copy then comes from kvfuse_leaf_sets and is refreshed after
     every kvfuse_merge), and the argument checks of the switch."""
