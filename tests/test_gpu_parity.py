@@ -464,6 +464,38 @@ def test_tree_screens_when_unrelated_blocks_share_a_direction(kb, oracle, screen
         assert stats.cand_overflow > 0        # the bounds did list more pairs than the lists hold
 
 
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_tree_seeded_sweep_with_a_common_direction(kb, oracle, seed):
+    """Seeded variations of the case above: strength of the common component, threshold, pool type, candidate slots, both
+    readings of the threshold line, all four screens.  Many of them overflow most candidate lists."""
+    rng = np.random.default_rng(1000 + seed)
+    dtype = torch.bfloat16 if seed % 3 else torch.float32
+    rec = wl.llama8b_bff(n_req=int(rng.integers(3, 7)), tokens=8 * int(rng.integers(40, 120)), layers=1, kv_heads=2,
+                         prefix_tokens=8 * int(rng.integers(0, 8)), near_pool=int(rng.integers(4, 30)), t=8, d=32, dtype=dtype,
+                         seed=seed)
+    rec.thr = float(rng.choice([0.8, 0.85, 0.9, 0.95]))
+    mat = wl.materialise(rec, DEV, phys_perm=True)
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(seed)
+    amp = float(rng.choice([0.5, 1.0, 2.0, 3.0]))
+    for g in range(rec.G):
+        mu = (amp * torch.randn(rec.r, generator=gen)).to(DEV)
+        mat["K"][g] = (mat["K"][g].float() + mu).to(rec.dtype)
+    host = gu.host_copy(mat)
+    screen = ("full", "prefix", "fp8", "both")[seed % 4]
+    rule = "first_row" if (seed // 4) % 2 else "argmax"
+    prefix = {"prefix": 64, "both": 128}.get(screen, 0)
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, cand_cap=int(rng.choice([2, 8, 64])), rule=rule, screen_prefix=prefix,
+                                          screen_fp8=screen in ("fp8", "both"))
+    res = gu.oracle_fuse(oracle, rec, host, rule=rule)
+    assert gu.check_ambiguity(res, f"common_direction_sweep_{seed}") == list(range(rec.G))
+    for g in range(rec.G):
+        gu.compare_group(res[g], cache, g, rec.dtype == torch.float32, f"common_direction_sweep_{seed}")
+    assert stats.fused == sum(int(r.stats[1]) for r in res) and stats.near_threshold == sum(int(r.stats[2]) for r in res)
+    _say("  seed", seed, screen, rule, "amp", amp, "thr", rec.thr, "fused", stats.fused, "refined", stats.refined, "overflow",
+         stats.cand_overflow)
+
+
 def test_fp8_screen_step_by_step_and_arguments(kb, oracle):
     """The single-step entry points with the fp8 screen on (the copy then comes from kvfuse_leaf_sets and is refreshed after
     every kvfuse_merge), and the argument checks of the switch."""
