@@ -201,6 +201,34 @@ def test_tree_tiny_config_all_groups(kb, oracle):
     assert math.isclose(stats.compression_ratio, 32 / 22)
 
 
+@pytest.mark.parametrize("screen_fp8", [False, True])
+def test_tree_rescaling_blocks_by_powers_of_two_changes_only_the_scales(kb, screen_fp8):
+    """The direction-plus-norm representation on the GPU path: every block times its own power of two (exact) gives the
+    same table, the same fused representatives bit for bit, and scales that carry exactly that factor."""
+    rec = _small_bf16(n_req=5, tokens=8 * 90, kv_heads=2)
+    mat_a = wl.materialise(rec, DEV, phys_perm=True)
+    mat_b = wl.materialise(rec, DEV, phys_perm=True)
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(31)
+    fk = (2.0 ** torch.randint(-6, 7, (rec.G, rec.n, 1), generator=gen).float()).to(DEV)
+    fv = (2.0 ** torch.randint(-6, 7, (rec.G, rec.n, 1), generator=gen).float()).to(DEV)
+    mat_b["K"] = (mat_b["K"].float() * fk).to(rec.dtype)
+    mat_b["V"] = (mat_b["V"].float() * fv).to(rec.dtype)
+    assert torch.equal((mat_b["K"].float() / fk).to(rec.dtype), mat_a["K"])
+    bt0 = mat_a["bt"].clone().long()
+    ca, pa, sa, _ = gu.gpu_fuse(rec, mat_a, screen_fp8=screen_fp8)
+    cb, pb, sb, _ = gu.gpu_fuse(rec, mat_b, screen_fp8=screen_fp8)
+    assert sa.fused == sb.fused > 50 and torch.equal(ca.bt, cb.bt) and torch.equal(ca.refcount, cb.refcount)
+    for g in range(rec.G):
+        fused = ca.refcount[g] > 1
+        assert torch.equal(ca.K[g][fused], cb.K[g][fused]) and torch.equal(ca.V[g][fused], cb.V[g][fused])
+        moved = fused[ca.bt[g].long()]
+        fkx, fvx = fk[g, bt0[g], 0], fv[g, bt0[g], 0]            # factor of the block entry x had before fusion
+        assert torch.equal(cb.scale_k[g][moved], ca.scale_k[g][moved] * fkx[moved])
+        assert torch.equal(cb.scale_v[g][moved], ca.scale_v[g][moved] * fvx[moved])
+        assert bool((cb.scale_k[g][~moved] == 1).all())
+
+
 def test_tree_threshold_above_one_is_identity(kb, oracle):
     rec = wl.tiny_bff()
     mat = wl.materialise(rec, DEV)

@@ -203,6 +203,34 @@ def test_identical_blocks_in_different_leaves_collapse(oracle):
     assert res1.bt.tolist() == list(range(2 * m)) and res1.compression_ratio == 1.0
 
 
+@pytest.mark.parametrize("kind", ["f32", "bf16"])
+def test_rescaling_blocks_by_powers_of_two_changes_only_the_scales(oracle, kind):
+    """Method section: a block is a unit direction plus a norm.  Multiplying every block by its own power of two is
+    exact in binary floating point and leaves every direction, hence every cosine, decision and fused representative,
+    bit for bit as it was; only the norms, and with them the scales of the logical blocks, pick up the factor."""
+    rec = wl.llama8b_bff(n_req=4, tokens=8 * 40, layers=1, kv_heads=1, prefix_tokens=32, near_pool=8, t=8, d=16,
+                         dtype=torch.float32 if kind == "f32" else torch.bfloat16)
+    m = wl.materialise(rec, "cpu", phys_perm=True)
+    K, V, bt = m["K"][0], m["V"][0], m["bt"][0].numpy()
+    rng = np.random.default_rng(99)
+    fk = torch.from_numpy(2.0 ** rng.integers(-6, 7, size=rec.n)).to(K.dtype)[:, None]
+    fv = torch.from_numpy(2.0 ** rng.integers(-6, 7, size=rec.n)).to(K.dtype)[:, None]
+    K2, V2 = K * fk, V * fv
+    assert torch.equal(K2 / fk, K) and torch.equal(V2 / fv, V)            # the scaling is exact
+    a = oracle.fuse_group(wl.to_numpy_pool(K), wl.to_numpy_pool(V), bt, rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr, rec.thr)
+    b = oracle.fuse_group(wl.to_numpy_pool(K2), wl.to_numpy_pool(V2), bt, rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr, rec.thr)
+    assert int(a.stats[1]) > 20 and np.array_equal(a.bt, b.bt) and np.array_equal(a.refcount, b.refcount)
+    assert np.array_equal(a.stats[:4], b.stats[:4])
+    fused = a.refcount > 1                                                # representatives: unit vectors, identical
+    assert fused.any() and np.array_equal(a.kpool[fused], b.kpool[fused]) and np.array_equal(a.vpool[fused], b.vpool[fused])
+    # logical entry x had its original block at bt[x]: its scale carries that block's factor wherever it points now
+    fkx, fvx = fk.double().numpy()[bt, 0], fv.double().numpy()[bt, 0]
+    moved = fused[a.bt]
+    assert np.array_equal(b.scale_k[moved], a.scale_k[moved] * fkx[moved])
+    assert np.array_equal(b.scale_v[moved], a.scale_v[moved] * fvx[moved])
+    assert (a.scale_k[~moved] == 1.0).all() and (b.scale_k[~moved] == 1.0).all()      # untouched blocks stay raw
+
+
 def test_threshold_above_one_changes_nothing(oracle):
     rec = wl.tiny_bff()
     m = wl.materialise(rec, "cpu")
