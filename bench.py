@@ -79,7 +79,7 @@ def run_whole_config(args, torch, kb, wl):
     spec = kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr, rec.group_size)
     plan = kb.Plan(ctx, cache, spec, args.cand_cap)
     if args.screen_fp8:
-        kb.set_screen_fp8(ctx, plan)
+        kb.set_screen_fp8(ctx, plan, centre=args.centre)
     if args.screen_prefix:
         kb.set_screen_prefix(ctx, plan, args.screen_prefix)
     rs = torch.tensor(rec.req_start, dtype=torch.int32, device=dev)
@@ -151,7 +151,7 @@ def run_whole_config(args, torch, kb, wl):
                    "compression_ratio": blocks / a["physical"] if a["physical"] else 0.0, "fused": a["fused"],
                    "near_threshold": a["near"], "refined_fp64": a["refined"], "cand_overflow": a["overflow"],
                    "slabs": n_slabs, "slab_layers": slab_layers,
-                   "screen": ("fp8 copies" if args.screen_fp8 else "full product") + (f", prefix of {args.screen_prefix}" if args.screen_prefix else ""),
+                   "screen": (("centred fp8 copies" if args.centre else "fp8 copies") if args.screen_fp8 else "full product") + (f", prefix of {args.screen_prefix}" if args.screen_prefix else ""),
                    "unfused_cache_GB": rec.layers * H * rec.n * rec.r * elem * 2 / 1e9},
         "stages_ms": a["stage"],
         "per_slab_ms": {"min": min(slab_ms), "median": sorted(slab_ms)[len(slab_ms) // 2], "max": max(slab_ms), "all": slab_ms},
@@ -403,6 +403,8 @@ def main():
                          "default; the opt-in prefix screen is measured outside the timed steps either way)")
     ap.add_argument("--screen-fp8", action="store_true",
                     help="run the timed steps with the fp8 screen (similarity over one-byte copies of the key blocks + error bound)")
+    ap.add_argument("--centre", action="store_true",
+                    help="with --screen-fp8: take each group's common key direction out of the one-byte copies first")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
     ap.add_argument("--per-height", action="store_true",
                     help="after the timed steps, run one more fusion height by height and add a per-height table of the "
@@ -447,7 +449,7 @@ def main():
     rule = {"argmax": kb.RULE_ARGMAX, "first_row": kb.RULE_FIRST_ROW}[args.assign_rule]
     kb.set_assign_rule(ctx, plan, rule)
     if args.screen_fp8:
-        kb.set_screen_fp8(ctx, plan)
+        kb.set_screen_fp8(ctx, plan, centre=args.centre)
     if args.screen_prefix:
         kb.set_screen_prefix(ctx, plan, args.screen_prefix)
     rs = torch.tensor(rec.req_start, dtype=torch.int32, device=dev)
@@ -652,7 +654,7 @@ def main():
                       "similarity_TFLOPs": eff, "frac_of_fp8_peak_5000": eff / 5000.0, "frac_of_bf16_peak_2500": eff / 2500.0,
                       "copy_error_mean": float(err.mean()) if err.numel() else 0.0,
                       "copy_error_max": float(err.max()) if err.numel() else 0.0,
-                      "extra_device_bytes": int(plan.k8.numel() + plan.k8_err.numel() * 4),
+                      "extra_device_bytes": int(plan.k8.numel() + plan.k8_side.numel() * 4),
                       "step_ms_with_decode": ms_equiv, "blocks_per_s_with_decode": rec.G * rec.n / (ms_equiv * 1e-3),
                       "note": "opt-in (kvfuse_plan_set_screen_fp8); not used in the timed steps, `value` and `roofline`"}
         if rec.r // 4 >= 128 and (rec.r // 4) % 64 == 0:
@@ -673,7 +675,56 @@ def main():
                 "tables_and_fused_keys_equal_to_full_screen": same2,
                 "step_ms_with_decode": ms2, "blocks_per_s_with_decode": rec.G * rec.n / (ms2 * 1e-3)}
             kb.set_screen_prefix(ctx, plan, 0)
-        del bt_ref, k_ref
+        # the same with each group's common key direction taken out of the copies first (on this input the keys share
+        # none, so this shows what the extra arithmetic costs), ...
+        def timed_fuse(k_in=None, runs=3):
+            best_t = None
+            for _ in range(runs):
+                restore()
+                if k_in is not None:
+                    cache.K.copy_(k_in)
+                torch.cuda.synchronize()
+                t_st = kb.fuse_tree(ctx, plan, rec.thr, want_stats=True, want_timing=True)
+                if best_t is None or t_st.ms_total < best_t.ms_total:
+                    best_t = t_st
+            return best_t
+
+        def brief(st, **more):
+            return dict({"fuse_ms": st.ms_total, "similarity_ms": st.ms_similarity, "assign_ms": st.ms_assign,
+                         "merge_ms": st.ms_merge, "norms_ms": st.ms_norms, "fused": st.fused, "refined_fp64": st.refined,
+                         "cand_overflow": st.cand_overflow}, **more)
+
+        kb.set_screen_fp8(ctx, plan, centre=True)
+        cst = timed_fuse()
+        same_c = bool(torch.equal(cache.bt, bt_ref)) and bool(torch.equal(cache.K, k_ref)) and cst.fused == ref_st.fused
+        cerr = plan.k8_err[plan.k8_err > 0]
+        fp8_screen["centred"] = brief(cst, tables_and_fused_keys_equal_to_full_screen=same_c,
+                                      copy_error_mean=float(cerr.mean()) if cerr.numel() else 0.0)
+        # ... and all three screens on keys that do share one: every key block of a group gets the same random offset of
+        # 2.35 times the keys' own spread, which puts unrelated blocks at a cosine of about 0.85: within the plain copies'
+        # error bound (0.054 for a pair) of the threshold 0.9, outside that of the centred ones (0.02).  Still closer to
+        # the threshold (0.87 and up) the centred copies overflow their lists as well and only the full product is fast.
+        del k_ref
+        gen = torch.Generator(device="cpu")
+        gen.manual_seed(2601)
+        mu = (2.35 * torch.randn(rec.G, 1, rec.r, generator=gen)).to(dev)
+        k_common = torch.empty_like(K0)
+        for g0 in range(0, rec.G, 16):
+            k_common[g0:g0 + 16] = (K0[g0:g0 + 16].float() + mu[g0:g0 + 16]).to(K0.dtype)
+        common = {"recipe": "every key block of group g + 2.35 * N(0, 1)[t * d] drawn once per group"}
+        kb.set_screen_fp8(ctx, plan, False)
+        fst = timed_fuse(k_common)
+        bt_c, k_c = cache.bt.clone(), cache.K.clone()
+        common["full_product"] = brief(fst)
+        for name, centre in (("fp8_copies", False), ("fp8_copies_centred", True)):
+            kb.set_screen_fp8(ctx, plan, centre=centre)
+            xst = timed_fuse(k_common, runs=2)
+            xerr = plan.k8_err[plan.k8_err > 0]
+            common[name] = brief(xst, copy_error_mean=float(xerr.mean()) if xerr.numel() else 0.0,
+                                 tables_and_fused_keys_equal_to_full_screen=bool(torch.equal(cache.bt, bt_c)) and
+                                 bool(torch.equal(cache.K, k_c)) and xst.fused == fst.fused)
+        fp8_screen["keys_with_a_common_direction"] = common
+        del bt_ref, bt_c, k_c, k_common, mu
         kb.set_screen_fp8(ctx, plan, False)
 
     # The same step (fusion without the statistics read-back + decode) recorded once in a HIP graph on a stream of

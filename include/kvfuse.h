@@ -410,28 +410,40 @@ int kvfuse_plan_set_screen_prefix(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t pr
 
 /* A second exact shortcut for the same product (Algorithm 1, sim <- k_l k_r^T), for the same reason: only entries above
  * the threshold matter, and every one of those is evaluated again in fp64.  Every key block is kept a second time as
- * bytes: q(x) = e4m3(x / |x| * 256) (OCP 8-bit float, 4 exponent and 3 mantissa bits), together with its own measured
- * error err(x) = | x / |x| - q(x) / 256 | (Euclidean norm, fp64, rounded up).  For two blocks
- *     | cos(a, b) - <q(a), q(b)> / 256^2 |  <=  err(a) + err(b) + err(a) * err(b)
- * (Cauchy-Schwarz twice), so the similarity step multiplies the byte copies on the fp8 matrix cores (twice the rate of
- * bfloat16 and half the bytes through LDS and L2) and lists a pair when the product plus this bound clears
- * thr - 2 * band.  The assignment step takes a listed product as the centre of an interval of radius band + bound: a
- * column is settled from the intervals when one row's lower end clears thr + band and every other listed row's upper
- * end (or, under the row-order rule, when no undecided row comes before the first certain one); every other column is
- * evaluated in fp64 on the pool itself, exactly as the undecided columns of the full-length screen are.  Targets, tables
- * and fused blocks are therefore the same as without the shortcut, whatever the data; blocks that quantise badly (err is
- * measured, not assumed: typically 0.02 - 0.03) only get wider intervals.  Combines with the prefix screen: the product
- * then runs over the first prefix_elements bytes, which must be a multiple of 64 and at least 128 (set the prefix after
- * this call, or switch it off first); the assignment step then first multiplies the whole copies of the listed pairs to
- * get such intervals back.
- *   k8      device, G * P * t * d bytes, block b of group g at (g * P + b) * t * d; owned by the caller, alive while the
- *           plan is used; written by kvfuse_leaf_sets / kvfuse_fuse_tree (all key blocks) and after every merge (the
- *           rebuilt targets)
- *   k8_err  device [G][P] float, err(x) of every key block, written along with k8
+ * bytes.  With u = x / |x| the unit block, m a direction of the group (see `centre`; without one alpha = 0 below),
+ *     alpha(x) = <m, u> in binary32,  u_c = u - alpha(x) m,  q(x) = e4m3(u_c * 256 / |u_c|),  scale(x) = |u_c| / 256
+ * (OCP 8-bit float, 4 exponent and 3 mantissa bits), together with err(x) = | u_c - q(x) scale(x) | (Euclidean norm,
+ * fp64, measured on the bytes actually written) plus what the roundings of alpha and of |m| cost, rounded up.  For two
+ * blocks
+ *     | cos(a, b) - ( <q(a), q(b)> scale(a) scale(b) + alpha(a) alpha(b) ) |  <=  err(a) + err(b) + err(a) * err(b)
+ * (the identity <u, v> = <u_c, v_c> + alpha alpha' for a unit m, and Cauchy-Schwarz twice), so the similarity step
+ * multiplies the byte copies on the fp8 matrix cores (twice the rate of bfloat16 and half the bytes through LDS and L2)
+ * and lists a pair when that value plus this bound clears thr - 2 * band.  The assignment step takes a listed value as
+ * the centre of an interval of radius band + bound: a column is settled from the intervals when one row's lower end
+ * clears thr + band and every other listed row's upper end (or, under the row-order rule, when no undecided row comes
+ * before the first certain one); every other column is evaluated in fp64 on the pool itself, exactly as the undecided
+ * columns of the full-length screen are.  Targets, tables and fused blocks are therefore the same as without the
+ * shortcut, whatever the data and whatever m; blocks that quantise badly (err is measured, not assumed: typically
+ * 0.02 - 0.03) only get wider intervals.
+ *   centre  non-zero: before the copies are written, kvfuse_leaf_sets / kvfuse_fuse_tree take as m of each group the
+ *           normalised sum of up to 64 of its unit key blocks (even steps through the pool).  Keys of real caches share
+ *           a direction (a common offset, a few heavy channels), so that unrelated blocks have cosines of 0.5 and more;
+ *           uncentred, err is then too coarse to tell 0.8 from 0.9 and most columns go to the fp64 evaluation.  With the
+ *           shared part taken out and carried exactly by alpha, the bytes describe what tells the blocks apart and the
+ *           intervals shrink by |u_c| / |u|.  Costs one small kernel per pass and two more sweeps over registers per
+ *           block.  Ignored (copies uncentred) while the prefix screen is on and for blocks of more than 8192 elements.
+ * Combines with the prefix screen: the product then runs over the first prefix_elements bytes, which must be a multiple
+ * of 64 and at least 128 (set the prefix after this call, or switch it off first); the assignment step then first
+ * multiplies the whole copies of the listed pairs to get such intervals back.
+ *   k8       device, G * P * t * d bytes, block b of group g at (g * P + b) * t * d; owned by the caller, alive while the
+ *            plan is used; written by kvfuse_leaf_sets / kvfuse_fuse_tree (all key blocks) and after every merge (the
+ *            rebuilt targets)
+ *   k8_side  device, 3 * G * P + G * t * d floats, owned by the caller likewise: [G][P] err, then [G][P] scale, then
+ *            [G][P] alpha, written along with k8, then [G][t * d] the directions m (unused without `centre`)
  * Two NULLs switch the shortcut off (the default).  Blocks must have a multiple of 64 and at least 128 elements.
  * Applies to the following kvfuse_leaf_sets, kvfuse_similarity, kvfuse_assign, kvfuse_merge and kvfuse_fuse_tree calls
- * on this plan; with a dense matrix kvfuse_similarity then writes <q(a), q(b)> / 256^2 instead of the cosine. */
-int kvfuse_plan_set_screen_fp8(kvfuse_ctx *ctx, kvfuse_plan *plan, void *k8, float *k8_err);
+ * on this plan; with a dense matrix kvfuse_similarity then writes the value above instead of the cosine. */
+int kvfuse_plan_set_screen_fp8(kvfuse_ctx *ctx, kvfuse_plan *plan, void *k8, float *k8_side, int32_t centre);
 
 /* ---- variants of the method ---------------------------------------------------------------------------- */
 

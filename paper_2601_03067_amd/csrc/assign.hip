@@ -120,7 +120,7 @@ __device__ __forceinline__ void screen_column(const WorkDesc &w, const HeightDes
     int result = -1;
     bool recheck = cnt > w.cand_cap || ((bound == 1 || bound == 3) && cnt > 0);
     if (cnt > 0 && !recheck && bound == 2) {
-        const float *qe = w.q8_err + (int64_t)g * P;
+        const float *qe = w.q8.err + (int64_t)g * P;
         const int32_t *l_ids = w.set_ids + (int64_t)g * w.n + h.l_off[node];
         const double eb = (double)qe[w.set_ids[(int64_t)g * w.n + h.r_off[node] + j]];
         auto radius = [&](int row) {
@@ -283,7 +283,7 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
         auto radius = [&](int row) __attribute__((always_inline)) {
             if (bound < 2)
                 return band;
-            const float *qe = w.q8_err + (int64_t)g * pool.P;
+            const float *qe = w.q8.err + (int64_t)g * pool.P;
             const double ea = (double)qe[l_ids[row]], eb = (double)qe[b];
             return band + ea + eb + ea * eb;
         };
@@ -477,7 +477,6 @@ __global__ __launch_bounds__(256) void assign_q8_fill_kernel(PoolDesc pool, Work
     const int n_items = w.n_refine[height];
     const int n_waves = gridDim.x * 4;
     const int ch = pool.r / 16;
-    const float inv_s2 = 1.0f / (kQ8Scale * kQ8Scale);
     for (int base = (blockIdx.x * 4 + (threadIdx.x >> 6)) * kBatch; base < n_items; base += n_waves * kBatch) {
         // ---- one list entry per lane: everything up to the first candidate's physical id
         int64_t m_cidx = -1;
@@ -493,8 +492,8 @@ __global__ __launch_bounds__(256) void assign_q8_fill_kernel(PoolDesc pool, Work
             m_b = w.set_ids[(int64_t)m_g * w.n + h.r_off[m_node] + (c - h.r_base[m_node])];
             m_ci0 = w.cand_idx[m_cidx * w.cand_cap];
             m_pid0 = w.set_ids[(int64_t)m_g * w.n + h.l_off[m_node] + m_ci0];
-            m_eb = w.q8_err[(int64_t)m_g * pool.P + m_b];
-            m_ea0 = w.q8_err[(int64_t)m_g * pool.P + m_pid0];
+            m_eb = w.q8.err[(int64_t)m_g * pool.P + m_b];
+            m_ea0 = w.q8.err[(int64_t)m_g * pool.P + m_pid0];
         }
         const int n_here = min(kBatch, n_items - base);
         for (int t = 0; t < n_here; ++t) {
@@ -507,14 +506,18 @@ __global__ __launch_bounds__(256) void assign_q8_fill_kernel(PoolDesc pool, Work
             const int b = __shfl(m_b, t, 64);
             const double eb = (double)__shfl(m_eb, t, 64);
             const int32_t *l_ids = w.set_ids + (int64_t)g * w.n + h.l_off[node];
-            const uint8_t *q8_g = w.q8_k + (int64_t)g * pool.P * pool.r;
-            const float *qe = w.q8_err + (int64_t)g * pool.P;
+            const uint8_t *q8_g = w.q8.k + (int64_t)g * pool.P * pool.r;
+            const float *qe = w.q8.err + (int64_t)g * pool.P;
+            const float *qs = w.q8.scale + (int64_t)g * pool.P;
+            const float *qa = w.q8.alpha + (int64_t)g * pool.P;
+            const float sb = qs[b], ab = qa[b];
             const uint4 *pb = reinterpret_cast<const uint4 *>(q8_g + (int64_t)b * pool.r);
             // candidates one per lane; the first one is already known
             const int ci0 = __shfl(m_ci0, t, 64), pid0 = __shfl(m_pid0, t, 64);
             const float ea0 = __shfl(m_ea0, t, 64);
             int ci = 0x7FFFFFFF, pid = 0;
             double ea = 0.0;
+            float sa = 0.0f, aa = 0.0f;
             if (lane == 0) {
                 ci = ci0;
                 pid = pid0;
@@ -523,6 +526,10 @@ __global__ __launch_bounds__(256) void assign_q8_fill_kernel(PoolDesc pool, Work
                 ci = w.cand_idx[cidx * w.cand_cap + lane];
                 pid = l_ids[ci];
                 ea = (double)qe[pid];
+            }
+            if (lane < cnt) {
+                sa = qs[pid];
+                aa = qa[pid];
             }
             float cv = -INFINITY;
             for (int k = 0; k < cnt; ++k) {
@@ -534,7 +541,7 @@ __global__ __launch_bounds__(256) void assign_q8_fill_kernel(PoolDesc pool, Work
                 for (int off = 32; off >= 1; off >>= 1)
                     dot += __shfl_xor(dot, off, 64);
                 if (lane == k)
-                    cv = dot * inv_s2;
+                    cv = fmaf(dot * sa, sb, aa * ab);
             }
             double lo = -INFINITY, hi = -INFINITY;
             if (lane < cnt) {
@@ -731,7 +738,7 @@ void launch_assign(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, co
         // 1: the listed values are upper bounds only (prefix screen); 2: cosines within a per-pair radius (fp8 screen);
         // 3: both screens: upper bounds that assign_q8_fill_kernel turns into the values of 2
         const bool prefix = w.screen_prefix > 0 && w.screen_prefix < pool.r;
-        const int bound = prefix ? (w.q8_k ? 3 : 1) : (w.q8_k ? 2 : 0);
+        const int bound = prefix ? (w.q8.k ? 3 : 1) : (w.q8.k ? 2 : 0);
         assign_screen_kernel<<<(unsigned)((cols + 255) / 256), 256, 0, s>>>(w, h, height, thr, band, rule, bound, pool.P);
         if (bound == 3) {
             const unsigned fgrid = (unsigned)std::min<int64_t>((cols + 63) / 64, resident_workgroups(assign_q8_fill_kernel));

@@ -63,6 +63,20 @@ struct HeightDesc {
     int64_t total_s;
 };
 
+// fp8 screen.  With u = block / |block| and, when a direction m of the group is given, u_c = u - alpha m (alpha the
+// binary32 value stored here; without a direction alpha = 0 and u_c = u):
+//   k      [G][P][r]  e4m3(u_c * kQ8Scale / |u_c|), one byte per element
+//   scale  [G][P]     |u_c| / kQ8Scale: decoded bytes * scale reconstruct u_c
+//   alpha  [G][P]
+//   err    [G][P]     |u_c - decoded bytes * scale| + what the exact identity <u, v> = <u_c, v_c> + alpha_u alpha_v loses
+//                     because m is not exactly unit and alpha is rounded, rounded up: for two blocks
+//                     |<u, v> - (<copy_u, copy_v> scale_u scale_v + alpha_u alpha_v)| <= err_u + err_v + err_u err_v
+//   dir    [G][r]     m, or null
+struct Q8Desc {
+    uint8_t *k;
+    float *err, *scale, *alpha, *dir;
+};
+
 // Group-strided work arrays of a plan (device).
 struct WorkDesc {
     int32_t G, n, n_slots, r_stride, l_stride, cand_cap;
@@ -88,8 +102,7 @@ struct WorkDesc {
     int32_t *leaf_src;   // [n] position in a set_ids row -> logical entry the leaf step fills it from, -1 = none
     float *rem_k;        // [G][P] prefix screen: share of each key block's norm that lies beyond the prefix, rounded up
     int32_t screen_prefix;   // elements of every block the similarity screen multiplies; 0 = the whole block
-    uint8_t *q8_k;       // [G][P][r] fp8 screen: every key block / its norm * kQ8Scale as OCP e4m3 bytes; null = off
-    float *q8_err;       // [G][P] fp8 screen: |block / norm - decoded bytes / kQ8Scale| (Euclidean), rounded up
+    Q8Desc q8;           // fp8 screen: the one-byte copies of the key blocks and what goes with them; q8.k null = off
 };
 
 // fp8 screen: unit key vectors are multiplied by this before conversion to e4m3 (largest finite value 448), which puts
@@ -140,7 +153,9 @@ template <typename K> static int resident_workgroups(K kernel, int threads = 256
 
 // launchers, one per source file
 void launch_block_norms(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, float *rem = nullptr, int prefix = 0,
-                        uint8_t *q8 = nullptr, float *q8_err = nullptr);
+                        const Q8Desc *q8 = nullptr);
+// fp8 screen: the direction of every group that its key blocks are centred on (no-op unless one is asked for)
+void launch_centre_direction(hipStream_t s, const PoolDesc &pool, const WorkDesc &w);
 void launch_leaf_sets(hipStream_t s, const WorkDesc &w, const TableDesc &tab, int P, const int32_t *slot_init);
 void launch_similarity(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const HeightDesc &h, float thr_floor,
                        float *dense_s);
@@ -226,28 +241,68 @@ __device__ __forceinline__ float tail_share(double tail_squares, double norm)
     return norm > 0.0 ? __double2float_ru(fmin(sqrt(fmax(tail_squares, 0.0)) / norm, 1.0) + 1e-6) : 0.0f;
 }
 
-// fp8 screen: one 16-byte piece of a key block to e4m3 (x * mf with mf = kQ8Scale / norm, the hardware's nearest-even
-// conversion) and the squared error of that piece against the unit vector, decoded with the hardware's own conversion.
-// 16 bytes of a block (PER16 elements) -> PER16 bytes at dst, squares of the copy's errors added to se.
+// fp8 screen: the parameters of one block's copy.  u_c,i = x_i * inv - alpha * m_i;  byte_i = e4m3(u_c,i * gain);
+// decoded byte_i * shat reconstructs u_c,i (shat is the binary32 value stored as the block's scale).
+struct Q8Block {
+    double inv, alpha, gain, shat;
+};
+
+// The direction's values for one 16-byte piece of a block (PER16 elements from element offset e0), zeros without one.
+template <int PER>
+__device__ __forceinline__ void q8_dir_chunk(const float *__restrict__ dir_g, int e0, double *m)
+{
+    if (dir_g) {
+#pragma unroll
+        for (int i = 0; i < PER / 4; ++i) {
+            const float4 f = *reinterpret_cast<const float4 *>(dir_g + e0 + 4 * i);
+            m[4 * i] = (double)f.x; m[4 * i + 1] = (double)f.y; m[4 * i + 2] = (double)f.z; m[4 * i + 3] = (double)f.w;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            m[i] = 0.0;
+    }
+}
+
+// <m, x> over one piece.
 template <typename T>
-__device__ __forceinline__ void quantise_chunk(const uint4 &raw, double inv, float mf, uint8_t *__restrict__ dst, double &se)
+__device__ __forceinline__ void q8_dir_dot_chunk(const uint4 &raw, const float *__restrict__ dir_g, int e0, double &sm)
 {
     constexpr int PER = Elem<T>::PER16;
-    const double inv_scale = 1.0 / (double)kQ8Scale;
-    double x[PER];
+    double x[PER], m[PER];
     Elem<T>::widen(raw, x);
+    q8_dir_chunk<PER>(dir_g, e0, m);
+#pragma unroll
+    for (int i = 0; i < PER; ++i)
+        sm = fma(m[i], x[i], sm);
+}
+
+// One piece to e4m3 (the hardware's nearest-even conversion) and the squared error of that piece, decoded with the
+// hardware's own conversion.
+template <typename T>
+__device__ __forceinline__ void quantise_chunk(const uint4 &raw, const float *__restrict__ dir_g, int e0, const Q8Block &p,
+                                               uint8_t *__restrict__ dst, double &se)
+{
+    constexpr int PER = Elem<T>::PER16;
+    double x[PER], m[PER];
+    Elem<T>::widen(raw, x);
+    q8_dir_chunk<PER>(dir_g, e0, m);
     uint32_t w[PER / 4];
 #pragma unroll
     for (int i = 0; i < PER / 4; ++i) {
-        int packed = __builtin_amdgcn_cvt_pk_fp8_f32((float)x[4 * i] * mf, (float)x[4 * i + 1] * mf, 0, false);
-        packed = __builtin_amdgcn_cvt_pk_fp8_f32((float)x[4 * i + 2] * mf, (float)x[4 * i + 3] * mf, packed, true);
+        double uc[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            uc[e] = fma(x[4 * i + e], p.inv, -p.alpha * m[4 * i + e]);
+        int packed = __builtin_amdgcn_cvt_pk_fp8_f32((float)(uc[0] * p.gain), (float)(uc[1] * p.gain), 0, false);
+        packed = __builtin_amdgcn_cvt_pk_fp8_f32((float)(uc[2] * p.gain), (float)(uc[3] * p.gain), packed, true);
         w[i] = (uint32_t)packed;
         const float d0 = __builtin_amdgcn_cvt_f32_fp8(packed, 0), d1 = __builtin_amdgcn_cvt_f32_fp8(packed, 1);
         const float d2 = __builtin_amdgcn_cvt_f32_fp8(packed, 2), d3 = __builtin_amdgcn_cvt_f32_fp8(packed, 3);
         const double dec[4] = {(double)d0, (double)d1, (double)d2, (double)d3};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const double diff = fma(x[4 * i + e], inv, -dec[e] * inv_scale);
+            const double diff = fma(-dec[e], p.shat, uc[e]);
             se = fma(diff, diff, se);
         }
     }
@@ -259,9 +314,38 @@ __device__ __forceinline__ void quantise_chunk(const uint4 &raw, double inv, flo
     }
 }
 
+// The copy's parameters from the block's norm and, with a direction m, dot_m = <m, x> (all lanes pass the same values).
+// Without a direction the copy holds the unit vector itself.  With one, alpha is <m, u> rounded to binary32 and the
+// copy is scaled by an estimate of |u_c| from |u_c|^2 = 1 - 2 alpha <m, u> + alpha^2 |m|^2 with |m| taken as 1.  The
+// estimate only sets the gain: the copy's error is measured with the scale actually stored.  It must not be so low
+// that an element leaves e4m3's range (448 against the 256 aimed at): m is the binary32 rounding of an fp64 unit vector,
+// so | |m|^2 - 1 | < 2^-22 and the estimate of |u_c|^2 is off by less than 3e-7; with the floor of 1e-6 the true value
+// is below 1.3 times the estimate and the largest element below 256 * 1.15.
+__device__ __forceinline__ Q8Block q8_block(double nrm, bool centred, double dot_m)
+{
+    Q8Block p;
+    p.inv = nrm > 0.0 ? 1.0 / nrm : 0.0;
+    p.alpha = 0.0;
+    p.gain = (double)kQ8Scale;
+    p.shat = (double)(1.0f / kQ8Scale);
+    if (centred) {
+        const double a = dot_m * p.inv;
+        p.alpha = (double)(float)a;
+        const double c = sqrt(fmax(fma(p.alpha, p.alpha - 2.0 * a, 1.0), 1e-6));
+        p.shat = (double)(float)(c / (double)kQ8Scale);
+        p.gain = 1.0 / p.shat;
+    }
+    return p;
+}
+
+// What goes into err on top of the measured distance |u_c - decoded copy * scale|.  The identity behind the screen,
+// <u, v> = <u_c, v_c> + alpha_u alpha_v, holds exactly for a unit m and alpha = <m, u>; the stored m and alpha are
+// binary32 roundings of these, so <m, u_c> and |m|^2 - 1 are not zero but below 2^-21 each, and the identity is off by
+// less than (|alpha_u| + |alpha_v| + |alpha_u alpha_v|) 2^-21 < 1.5e-6 for a pair.  The margin (twice 2e-6 for a pair)
+// covers that and the binary32 arithmetic of the similarity kernel's test.
 __device__ __forceinline__ float quantise_error(double se, double nrm)
 {
-    return nrm > 0.0 ? __double2float_ru(sqrt(se) + 1e-6) : 0.0f;
+    return nrm > 0.0 ? __double2float_ru(sqrt(se) + 2e-6) : 0.0f;
 }
 
 // Nearest-even rounding of a finite double straight to bfloat16 bits (no intermediate binary32 rounding).

@@ -48,6 +48,12 @@ struct Plan {
     int max_r = 0, max_l = 0;
     std::vector<uint8_t> group_enable_host;   // copy of the group mask for the statistics; empty = all groups
     int assign_rule = KVFUSE_RULE_ARGMAX;
+    float *q8_dir_mem = nullptr;    // fp8 screen with centring asked for: the caller's [G][r] floats for the directions
+
+    // The copies are centred only where that pays and fits: not together with the prefix screen (a block's share of the
+    // common direction differs between prefix and tail) and not for blocks whose direction kernel would need more than
+    // 64 KiB of LDS.
+    void refresh_q8_dir() { work.q8.dir = (work.q8.k && q8_dir_mem && work.screen_prefix == 0 && pool.r <= 8192) ? q8_dir_mem : nullptr; }
 };
 
 // Similarity tile shapes (must match the two kernel instantiations): big 256 x 256, small 128 x 128.
@@ -261,8 +267,7 @@ static void carve(Carver &cv, int G, int n, int n_slots, int max_r, int max_l, i
     w.leaf_src = cv.take<int32_t>((size_t)std::max(n, 1));
     w.rem_k = nullptr;
     w.screen_prefix = 0;
-    w.q8_k = nullptr;
-    w.q8_err = nullptr;
+    w.q8 = Q8Desc{};
     slot_init = cv.take<int32_t>(n_slots);
     for (HostHeight &h : hs) {
         const size_t nn = h.l_off.size();
@@ -524,7 +529,8 @@ int kvfuse_leaf_sets(kvfuse_ctx *ctx, kvfuse_plan *plan)
         return KVFUSE_EINVAL;
     launch_leaf_sets(ctx->c.stream, plan->p.work, plan->p.tab, plan->p.pool.P, plan->p.slot_init);
     launch_prefix_tails(ctx->c.stream, plan->p.pool, plan->p.work);          // no-op unless the prefix screen is on
-    launch_quantise_all(ctx->c.stream, plan->p.pool, plan->p.work);          // no-op unless the fp8 screen is on
+    launch_centre_direction(ctx->c.stream, plan->p.pool, plan->p.work);      // no-ops unless the fp8 screen is on
+    launch_quantise_all(ctx->c.stream, plan->p.pool, plan->p.work);
     KVF_HIP(&ctx->c, hipGetLastError());
     return KVFUSE_OK;
 }
@@ -626,8 +632,9 @@ int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band
 
     const float floor_f = std::nextafterf((float)(thr - 2.0 * band), -INFINITY);
     KVF_TRY(mark());
+    launch_centre_direction(c->stream, p.pool, p.work);                      // no-op unless the fp8 copies are centred
     launch_block_norms(c->stream, p.pool, p.tab, p.work.screen_prefix > 0 ? p.work.rem_k : nullptr, p.work.screen_prefix,
-                       p.work.q8_k, p.work.q8_err);
+                       p.work.q8.k ? &p.work.q8 : nullptr);
     launch_leaf_sets(c->stream, p.work, p.tab, p.pool.P, p.slot_init);
     KVF_TRY(mark());
     for (int hgt = 0; hgt < nh; ++hgt) {
@@ -752,10 +759,11 @@ int kvfuse_plan_set_screen_prefix(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t pr
     if (prefix_elements == 0) {
         p.work.screen_prefix = 0;
         p.work.rem_k = nullptr;
+        p.refresh_q8_dir();
         return KVFUSE_OK;
     }
     // elements of one 64-byte K slice of what the screen multiplies: the pool, or its one-byte copy
-    const int per_slice = p.work.q8_k ? 64 : (p.pool.dtype == KVFUSE_BF16 ? 32 : 16);
+    const int per_slice = p.work.q8.k ? 64 : (p.pool.dtype == KVFUSE_BF16 ? 32 : 16);
     if (prefix_elements < 0 || prefix_elements >= p.pool.r || prefix_elements % per_slice != 0 || prefix_elements / per_slice < 2)
         return fail(&ctx->c, KVFUSE_EINVAL, "screen prefix: must be 0, or at least 128 bytes, a multiple of 64 bytes (of the pool, "
                                             "or of its one-byte copy when the fp8 screen is on) and shorter than a block");
@@ -763,30 +771,36 @@ int kvfuse_plan_set_screen_prefix(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t pr
         return fail(&ctx->c, KVFUSE_EINVAL, "screen prefix: needs a device array of G * P floats");
     p.work.screen_prefix = prefix_elements;
     p.work.rem_k = tail_share;
+    p.refresh_q8_dir();
     return KVFUSE_OK;
 }
 
-int kvfuse_plan_set_screen_fp8(kvfuse_ctx *ctx, kvfuse_plan *plan, void *k8, float *k8_err)
+int kvfuse_plan_set_screen_fp8(kvfuse_ctx *ctx, kvfuse_plan *plan, void *k8, float *k8_side, int32_t centre)
 {
     if (!ctx)
         return KVFUSE_EINVAL;
     if (!plan)
         return fail(&ctx->c, KVFUSE_EINVAL, "fp8 screen: null plan");
     Plan &p = plan->p;
-    if (!k8 && !k8_err) {
-        p.work.q8_k = nullptr;
-        p.work.q8_err = nullptr;
+    if (!k8 && !k8_side) {
+        p.work.q8 = Q8Desc{};
+        p.q8_dir_mem = nullptr;
         return KVFUSE_OK;
     }
-    if (!k8 || !k8_err)
-        return fail(&ctx->c, KVFUSE_EINVAL, "fp8 screen: needs G * P * t * d bytes and G * P floats of device memory (or two nulls "
-                                            "to switch it off)");
+    if (!k8 || !k8_side)
+        return fail(&ctx->c, KVFUSE_EINVAL, "fp8 screen: needs G * P * t * d bytes and 3 * G * P + G * t * d floats of device "
+                                            "memory (or two nulls to switch it off)");
     if (p.pool.r % 64 != 0 || p.pool.r < 128)
         return fail(&ctx->c, KVFUSE_EINVAL, "fp8 screen: blocks must have a multiple of 64 and at least 128 elements");
     if (p.work.screen_prefix > 0 && (p.work.screen_prefix % 64 != 0 || p.work.screen_prefix < 128))
         return fail(&ctx->c, KVFUSE_EINVAL, "fp8 screen: the screen prefix in force is not a multiple of 64 elements of at least 128");
-    p.work.q8_k = static_cast<uint8_t *>(k8);
-    p.work.q8_err = k8_err;
+    const size_t gp = (size_t)p.pool.G * p.pool.P;
+    p.work.q8.k = static_cast<uint8_t *>(k8);
+    p.work.q8.err = k8_side;
+    p.work.q8.scale = k8_side + gp;
+    p.work.q8.alpha = k8_side + 2 * gp;
+    p.q8_dir_mem = centre ? k8_side + 3 * gp : nullptr;
+    p.refresh_q8_dir();
     return KVFUSE_OK;
 }
 

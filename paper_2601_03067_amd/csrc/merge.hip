@@ -242,31 +242,53 @@ __global__ __launch_bounds__(256) void merge_group_kernel(PoolDesc pool, WorkDes
             }
         }
         if constexpr (Q8) {
+            auto group_sum = [&](double v) {
+                v = wave_sum(v);
+                if constexpr (GW > 1) {
+                    if ((tg & 63) == 0)
+                        red[grp][wv] = v;
+                    __syncthreads();
+                    v = 0.0;
+#pragma unroll
+                    for (int q = 0; q < GW; ++q)
+                        v += red[grp][q];
+                    __syncthreads();
+                }
+                return v;
+            };
+            const bool doq = live && kv == 0;               // uniform over the item's wavefronts
+            const bool centred = w.q8.dir != nullptr;       // uniform over the launch
+            const float *dir_g = (doq && centred) ? w.q8.dir + (int64_t)g * pool.r : nullptr;
+            double sm = 0.0;
+            if (centred) {
+                if (doq) {
+#pragma unroll
+                    for (int c = 0; c < CPT; ++c) {
+                        const int ch = tg + GT * c;
+                        if (ch < chunks)
+                            q8_dir_dot_chunk<T>(outp[c], dir_g, ch * PER, sm);
+                    }
+                }
+                sm = group_sum(sm);
+            }
+            const Q8Block blk = q8_block(nrm, centred, sm);
             double se = 0.0;
-            if (live && kv == 0) {      // uniform over the item's wavefronts
-                const double inv = nrm > 0.0 ? 1.0 / nrm : 0.0;
-                const float mf = (float)((double)kQ8Scale * inv);
-                uint8_t *q = w.q8_k + ((int64_t)g * pool.P + a) * pool.r;
+            if (doq) {
+                uint8_t *q = w.q8.k + ((int64_t)g * pool.P + a) * pool.r;
 #pragma unroll
                 for (int c = 0; c < CPT; ++c) {
                     const int ch = tg + GT * c;
                     if (ch < chunks)
-                        quantise_chunk<T>(outp[c], inv, mf, q + (size_t)ch * PER, se);
+                        quantise_chunk<T>(outp[c], dir_g, ch * PER, blk, q + (size_t)ch * PER, se);
                 }
             }
-            se = wave_sum(se);
-            if constexpr (GW > 1) {
-                if ((tg & 63) == 0)
-                    red[grp][wv] = se;
-                __syncthreads();
-                se = 0.0;
-#pragma unroll
-                for (int q = 0; q < GW; ++q)
-                    se += red[grp][q];
-                __syncthreads();
+            se = group_sum(se);
+            if (doq && tg == 0) {
+                const int64_t b = (int64_t)g * pool.P + a;
+                w.q8.err[b] = quantise_error(se, nrm);
+                w.q8.scale[b] = (float)blk.shat;
+                w.q8.alpha[b] = nrm > 0.0 ? (float)blk.alpha : 0.0f;
             }
-            if (live && kv == 0 && tg == 0)
-                w.q8_err[(int64_t)g * pool.P + a] = quantise_error(se, nrm);
         }
     }
 }
@@ -376,7 +398,7 @@ void launch_merge(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const 
         // and binary32 blocks of 4 chunks per lane are split over two wavefronts
 #define KVF_MERGE_G(T, C, W)                                                          \
     do {                                                                              \
-        if (w.q8_k)                                                                   \
+        if (w.q8.k)                                                                  \
             merge_group_kernel<T, C, W, true><<<wgrid, 256, 0, s>>>(pool, w, h, height);  \
         else                                                                          \
             merge_group_kernel<T, C, W, false><<<wgrid, 256, 0, s>>>(pool, w, h, height); \

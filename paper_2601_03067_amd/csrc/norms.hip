@@ -7,26 +7,39 @@
 
 namespace kvfuse {
 
-// fp8 screen (similarity.hip): the e4m3 copy of a key block, q = e4m3(x / |x| * kQ8Scale) element by element, and the
-// error it really has, err = | x / |x| - decode(q) / kQ8Scale | as a Euclidean norm in fp64, rounded up with a margin.
-// The similarity kernel adds err(a) + err(b) + err(a) err(b) to the product of two copies, which bounds their cosine from
-// above whatever the conversion did (the decode used here is the hardware's, the one the matrix cores apply).  One
-// wavefront per block.  A block of norm 0 becomes zeros with err 0 (its cosines are 0 by definition).
+// fp8 screen (similarity.hip): the one-byte copy of a key block and what goes with it (Q8Desc in common.h).  With
+// u = x / |x|: alpha = <m, u> rounded to binary32 (0 without a direction m), u_c = u - alpha m, the copy holds
+// e4m3(u_c * kQ8Scale / |u_c|) element by element, and err bounds what the similarity kernel's value
+// <copy_a, copy_b> scale_a scale_b + alpha_a alpha_b can miss of the cosine: the Euclidean distance between u_c and the
+// decoded copy (fp64, with the hardware's own decode, the one the matrix cores apply), plus what the rounding of alpha
+// and of m's norm take from the identity <u, v> = <u_c, v_c> + alpha_u alpha_v, rounded up with a margin.  Taking the
+// common direction out first matters when unrelated blocks share one: the copies then spend their eight bits on what
+// tells the blocks apart.  One wavefront per block.  A block of norm 0 becomes zeros with err 0 (its cosines are 0 by
+// definition).
 template <typename T>
-__device__ __forceinline__ void quantise_block(const T *__restrict__ src, double nrm, uint8_t *__restrict__ dst,
-                                               float *__restrict__ err_out, int r, int lane)
+__device__ __forceinline__ void quantise_block(const T *__restrict__ src, double nrm, const float *__restrict__ dir_g,
+                                               uint8_t *__restrict__ dst, float *__restrict__ err_out, float *__restrict__ scale_out,
+                                               float *__restrict__ alpha_out, int r, int lane)
 {
     constexpr int PER = Elem<T>::PER16;
     const int chunks = r / PER;
-    const double inv = nrm > 0.0 ? 1.0 / nrm : 0.0;
-    const float mf = (float)((double)kQ8Scale * inv);
     const uint4 *p = reinterpret_cast<const uint4 *>(src);
+    double sm = 0.0;
+    if (dir_g) {
+        for (int c = lane; c < chunks; c += 64)
+            q8_dir_dot_chunk<T>(p[c], dir_g, c * PER, sm);
+        sm = wave_sum(sm);
+    }
+    const Q8Block blk = q8_block(nrm, dir_g != nullptr, sm);
     double se = 0.0;
     for (int c = lane; c < chunks; c += 64)
-        quantise_chunk<T>(p[c], inv, mf, dst + (size_t)c * PER, se);
+        quantise_chunk<T>(p[c], dir_g, c * PER, blk, dst + (size_t)c * PER, se);
     se = wave_sum(se);
-    if (lane == 0)
+    if (lane == 0) {
         *err_out = quantise_error(se, nrm);
+        *scale_out = (float)blk.shat;
+        *alpha_out = nrm > 0.0 ? (float)blk.alpha : 0.0f;
+    }
 }
 
 // KEEP > 0 (fp8 screen on, blocks of at most 64 * KEEP chunks): the wavefront of a key block holds the block in registers,
@@ -35,8 +48,7 @@ template <typename T, int KEEP>
 __global__ __launch_bounds__(256) void block_norms_kernel(const T *__restrict__ kpool, const T *__restrict__ vpool,
                                                           int64_t n_blocks, int r, double *__restrict__ norm_k,
                                                           double *__restrict__ norm_v, float *__restrict__ inv_norm_k,
-                                                          float *__restrict__ rem, int prefix_chunks, uint8_t *__restrict__ q8,
-                                                          float *__restrict__ q8_err)
+                                                          float *__restrict__ rem, int prefix_chunks, Q8Desc q8, int P)
 {
     constexpr int PER = Elem<T>::PER16;
     const int lane = threadIdx.x & 63;
@@ -50,7 +62,8 @@ __global__ __launch_bounds__(256) void block_norms_kernel(const T *__restrict__ 
     // st: the squares beyond the prefix of the prefix screen, summed on their own (rem = |tail| / |block|, see
     // prefix_tails_kernel); the norm's own sum keeps its order
     const bool want_tail = rem != nullptr && !is_v;
-    double ss = 0.0, st = 0.0;
+    double ss = 0.0, st = 0.0, sm = 0.0;
+    const float *dir_g = (KEEP > 0 && !is_v && q8.dir) ? q8.dir + (b / P) * (int64_t)r : nullptr;
     uint4 keep[KEEP > 0 ? KEEP : 1];
     if (KEEP > 0 && !is_v) {
 #pragma unroll
@@ -69,6 +82,13 @@ __global__ __launch_bounds__(256) void block_norms_kernel(const T *__restrict__ 
 #pragma unroll
                     for (int i = 0; i < PER; ++i)
                         st = fma(x[i], x[i], st);
+                }
+                if (dir_g) {
+                    double m[PER];
+                    q8_dir_chunk<PER>(dir_g, c * PER, m);
+#pragma unroll
+                    for (int i = 0; i < PER; ++i)
+                        sm = fma(m[i], x[i], sm);
                 }
             }
         }
@@ -103,22 +123,27 @@ __global__ __launch_bounds__(256) void block_norms_kernel(const T *__restrict__ 
     }
     // fp8 screen: the one-byte copy of the key block (from the registers, or for long blocks in a second walk while the
     // block is still in the cache)
-    if (q8 != nullptr && !is_v) {
+    if (q8.k != nullptr && !is_v) {
         if constexpr (KEEP > 0) {
-            const double inv = nrm > 0.0 ? 1.0 / nrm : 0.0;
-            const float mf = (float)((double)kQ8Scale * inv);
+            if (dir_g)
+                sm = wave_sum(sm);
+            const Q8Block blk = q8_block(nrm, dir_g != nullptr, sm);
             double se = 0.0;
 #pragma unroll
             for (int q = 0; q < KEEP; ++q) {
                 const int c = lane + 64 * q;
                 if (c < chunks)
-                    quantise_chunk<T>(keep[q], inv, mf, q8 + b * (int64_t)r + (size_t)c * PER, se);
+                    quantise_chunk<T>(keep[q], dir_g, c * PER, blk, q8.k + b * (int64_t)r + (size_t)c * PER, se);
             }
             se = wave_sum(se);
-            if (lane == 0)
-                q8_err[b] = quantise_error(se, nrm);
+            if (lane == 0) {
+                q8.err[b] = quantise_error(se, nrm);
+                q8.scale[b] = (float)blk.shat;
+                q8.alpha[b] = nrm > 0.0 ? (float)blk.alpha : 0.0f;
+            }
         } else {
-            quantise_block<T>((const T *)kpool + b * (int64_t)r, nrm, q8 + b * (int64_t)r, q8_err + b, r, lane);
+            quantise_block<T>((const T *)kpool + b * (int64_t)r, nrm, q8.dir ? q8.dir + (b / P) * (int64_t)r : nullptr,
+                              q8.k + b * (int64_t)r, q8.err + b, q8.scale + b, q8.alpha + b, r, lane);
         }
     }
 }
@@ -154,17 +179,20 @@ __global__ void table_init_kernel(TableDesc tab, int G, int P, const double *__r
     atomicAdd(&tab.refcount[(int64_t)g * P + p], 1);
 }
 
-void launch_block_norms(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, float *rem, int prefix, uint8_t *q8, float *q8_err)
+void launch_block_norms(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, float *rem, int prefix, const Q8Desc *q8p)
 {
+    Q8Desc q8 = {};
+    if (q8p)
+        q8 = *q8p;
     const int pchunks = prefix / (pool.dtype == KVFUSE_BF16 ? 8 : 4);
     const int64_t nb = (int64_t)pool.G * pool.P;
     const unsigned grid = (unsigned)((2 * nb + 3) / 4);
     if (nb > 0) {
         const int chunks = pool.r / (pool.dtype == KVFUSE_BF16 ? 8 : 4);
-        const int keep = !q8 ? 0 : (chunks <= 256 ? 4 : (chunks <= 512 ? 8 : 0));
+        const int keep = !q8.k ? 0 : (chunks <= 256 ? 4 : (chunks <= 512 ? 8 : 0));
 #define KVF_NORMS(T, KEEP)                                                                                              \
     block_norms_kernel<T, KEEP><<<grid, 256, 0, s>>>((const T *)pool.k, (const T *)pool.v, nb, pool.r, pool.norm_k, pool.norm_v, \
-                                                     pool.inv_norm_k, rem, pchunks, q8, q8_err)
+                                                     pool.inv_norm_k, rem, pchunks, q8, pool.P)
         if (pool.dtype == KVFUSE_BF16) {
             if (keep == 4) KVF_NORMS(bf16_t, 4);
             else if (keep == 8) KVF_NORMS(bf16_t, 8);
@@ -278,11 +306,12 @@ void launch_prefix_tails(hipStream_t s, const PoolDesc &pool, const WorkDesc &w)
 
 template <typename T>
 __global__ __launch_bounds__(256) void quantise_all_kernel(const T *__restrict__ k, const double *__restrict__ norm_k, int64_t n_blocks,
-                                                           int r, uint8_t *__restrict__ q8, float *__restrict__ q8_err)
+                                                           int P, int r, Q8Desc q8)
 {
     const int64_t b = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (b < n_blocks)
-        quantise_block<T>(k + b * r, norm_k[b], q8 + b * r, q8_err + b, r, threadIdx.x & 63);
+        quantise_block<T>(k + b * r, norm_k[b], q8.dir ? q8.dir + (b / P) * (int64_t)r : nullptr, q8.k + b * r, q8.err + b,
+                          q8.scale + b, q8.alpha + b, r, threadIdx.x & 63);
 }
 
 // The targets that the merge step of this height has rebuilt (the work list of the assignment step).
@@ -294,25 +323,88 @@ __global__ __launch_bounds__(256) void quantise_targets_kernel(PoolDesc pool, Wo
     for (int t = blockIdx.x * 4 + (threadIdx.x >> 6); t < n_act; t += stride) {
         const int4 rec = w.active[2 * (int64_t)t];
         const int64_t b = (int64_t)rec.x * pool.P + rec.y;
-        quantise_block<T>((const T *)pool.k + b * pool.r, pool.norm_k[b], w.q8_k + b * pool.r, w.q8_err + b, pool.r, threadIdx.x & 63);
+        quantise_block<T>((const T *)pool.k + b * pool.r, pool.norm_k[b], w.q8.dir ? w.q8.dir + (int64_t)rec.x * pool.r : nullptr,
+                          w.q8.k + b * pool.r, w.q8.err + b, w.q8.scale + b, w.q8.alpha + b, pool.r, threadIdx.x & 63);
     }
+}
+
+// The direction that the key blocks of a group are centred on: the normalised sum of up to 64 unit key blocks taken at
+// even steps through the group's pool (fp64, one workgroup per group, every element of the sum owned by one thread).
+// Any vector serves, the bound of the screen holds for all of them; this one follows the mean of the keys, which is
+// the direction that unrelated blocks of real caches share.  A zero sum gives a zero direction (no centring).
+template <typename T>
+__global__ __launch_bounds__(256) void centre_direction_kernel(const T *__restrict__ k, int P, int r, float *__restrict__ dir)
+{
+    constexpr int PER = Elem<T>::PER16;
+    extern __shared__ double acc[];          // [r]
+    __shared__ double red[4];
+    const int g = blockIdx.x, tid = threadIdx.x;
+    const int chunks = r / PER;
+    const T *kg = k + (int64_t)g * P * r;
+    for (int e = tid; e < r; e += 256)
+        acc[e] = 0.0;
+    const int n_s = P < 64 ? P : 64;
+    for (int s = 0; s < n_s; ++s) {
+        const uint4 *x = reinterpret_cast<const uint4 *>(kg + ((int64_t)s * P / n_s) * r);
+        double ss = 0.0;
+        for (int c = tid; c < chunks; c += 256) {
+            double v[PER];
+            Elem<T>::widen(x[c], v);
+#pragma unroll
+            for (int i = 0; i < PER; ++i)
+                ss = fma(v[i], v[i], ss);
+        }
+        __syncthreads();
+        ss = block_sum_256(ss, red);
+        const double inv = ss > 0.0 ? 1.0 / sqrt(ss) : 0.0;
+        for (int c = tid; c < chunks; c += 256) {
+            double v[PER];
+            Elem<T>::widen(x[c], v);
+#pragma unroll
+            for (int i = 0; i < PER; ++i)
+                acc[c * PER + i] = fma(v[i], inv, acc[c * PER + i]);
+        }
+    }
+    double nn = 0.0;
+    for (int c = tid; c < chunks; c += 256)
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            nn = fma(acc[c * PER + i], acc[c * PER + i], nn);
+    __syncthreads();
+    nn = block_sum_256(nn, red);
+    const double invn = nn > 0.0 ? 1.0 / sqrt(nn) : 0.0;
+    for (int c = tid; c < chunks; c += 256)
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            dir[(int64_t)g * r + c * PER + i] = (float)(acc[c * PER + i] * invn);
+}
+
+void launch_centre_direction(hipStream_t s, const PoolDesc &pool, const WorkDesc &w)
+{
+    if (!w.q8.k || !w.q8.dir || pool.G <= 0 || pool.P <= 0)
+        return;
+    const size_t lds = (size_t)pool.r * sizeof(double);
+    if (pool.dtype == KVFUSE_BF16)
+        centre_direction_kernel<bf16_t><<<pool.G, 256, lds, s>>>((const bf16_t *)pool.k, pool.P, pool.r, w.q8.dir);
+    else
+        centre_direction_kernel<float><<<pool.G, 256, lds, s>>>((const float *)pool.k, pool.P, pool.r, w.q8.dir);
 }
 
 void launch_quantise_all(hipStream_t s, const PoolDesc &pool, const WorkDesc &w)
 {
     const int64_t nb = (int64_t)pool.G * pool.P;
-    if (!w.q8_k || nb <= 0)
+    if (!w.q8.k || nb <= 0)
         return;
     const unsigned grid = (unsigned)((nb + 3) / 4);
     if (pool.dtype == KVFUSE_BF16)
-        quantise_all_kernel<bf16_t><<<grid, 256, 0, s>>>((const bf16_t *)pool.k, pool.norm_k, nb, pool.r, w.q8_k, w.q8_err);
+        quantise_all_kernel<bf16_t><<<grid, 256, 0, s>>>((const bf16_t *)pool.k, pool.norm_k, nb, pool.P, pool.r, w.q8);
     else
-        quantise_all_kernel<float><<<grid, 256, 0, s>>>((const float *)pool.k, pool.norm_k, nb, pool.r, w.q8_k, w.q8_err);
+        quantise_all_kernel<float><<<grid, 256, 0, s>>>((const float *)pool.k, pool.norm_k, nb, pool.P, pool.r, w.q8);
 }
 
 void launch_quantise_targets(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, int height)
 {
-    if (!w.q8_k || (int64_t)w.G * w.l_stride <= 0)
+    if (!w.q8.k || (int64_t)w.G * w.l_stride <= 0)
         return;
     const unsigned grid = (unsigned)std::min<int64_t>(((int64_t)w.G * w.l_stride + 3) / 4, 256 * 8);
     if (pool.dtype == KVFUSE_BF16)

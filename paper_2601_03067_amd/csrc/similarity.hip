@@ -118,11 +118,11 @@ constexpr int kRingRowTiles = 4;   // most row tiles of one work item (the host'
 // share of |x| that lies beyond the prefix (Cauchy-Schwarz on the tails; `rem` holds it per block, rounded up).  On
 // caches whose unrelated blocks are spread over the whole block length a quarter of the row settles almost every pair;
 // every candidate is then evaluated in full in fp64 by the assignment step, so the decisions are the same.
-// T = fp8_t (fp8 screen): kpool is the e4m3 copy of the key blocks (unit vectors times kQ8Scale, one byte per element),
-// qerr the measured error of every block's copy.  With u = a / |a|, v = b / |b| and U, V their decoded copies / kQ8Scale,
-// |<u, v> - <U, V>| <= |u - U| + |U| |v - V| <= err_a + (1 + err_a) err_b, so <U, V> plus that is an upper bound of the
-// cosine, listed when it clears the floor and evaluated in full by the assignment step like a prefix-screen candidate.
-// The two bounds add up when both shortcuts are on.
+// T = fp8_t (fp8 screen): kpool holds the one-byte copies of the key blocks and q8 what goes with them (Q8Desc in
+// common.h): for two blocks the kernel's value <copy_a, copy_b> scale_a scale_b + alpha_a alpha_b is within
+// err_a + err_b + err_a err_b of their cosine, so the value plus that is an upper bound of the cosine, listed when it
+// clears the floor and evaluated in full by the assignment step like a prefix-screen candidate.  The two bounds add up
+// when both shortcuts are on.
 template <typename T, bool BIG, bool DENSE, bool PREFIX>
 __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_kernel(
     SimArgs A, const char *__restrict__ kpool, const float *__restrict__ inv_norm, const int32_t *__restrict__ set_ids,
@@ -132,11 +132,10 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
     const int32_t *__restrict__ r_base, const int32_t *__restrict__ r_cap, const int64_t *__restrict__ s_base,
     unsigned long long *__restrict__ best_packed, int32_t *__restrict__ cand_cnt, int32_t *__restrict__ cand_idx,
     float *__restrict__ cand_val, float *__restrict__ dense_s, const uint8_t *__restrict__ group_enable,
-    const float *__restrict__ rem, const float *__restrict__ qerr)
+    const float *__restrict__ rem, const Q8Desc q8)
 {
     static_assert(!(DENSE && PREFIX), "the dense matrix is the full-length product");
     constexpr bool Q8 = std::is_same<T, fp8_t>::value;
-    constexpr float Q8_INV = 1.0f / kQ8Scale;
     constexpr int WN = 2, TM = 2, TN = BIG ? 4 : 2, NT = BIG ? 512 : 256, BM = BIG ? 256 : 128, BN = BM;
     constexpr int WM = NT / 64 / WN;          // wavefronts along the rows
     // MFMA tile (mt, nt) of wavefront (wm, wn) covers rows mt * WM * 32 + wm * 32 .. + 31 and columns
@@ -156,14 +155,17 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
     __shared__ __attribute__((aligned(16))) float lds_reml[PREFIX ? RT * BM : 1];     // PREFIX: tail share of the left rows
     __shared__ float lds_tcolb[PREFIX ? BN : 1];         // PREFIX: tail share of the right blocks / their inverse norm
     __shared__ __attribute__((aligned(16))) float lds_errl[Q8 ? RT * BM : 1];        // Q8: copy error of the left rows
-    __shared__ float lds_c1[Q8 ? BN : 1];                // Q8: (1 + copy error of the right block) / its inverse norm
+    __shared__ float lds_c1[Q8 ? BN : 1];                // Q8: (1 + copy error of the right block) / its scale
+    __shared__ __attribute__((aligned(16))) float lds_all[Q8 ? RT * BM : 1];         // Q8: alpha of the left rows
+    __shared__ float lds_alr[Q8 ? BN : 1];               // Q8: alpha of the right blocks
+    __shared__ float lds_alrs[Q8 ? BN : 1];              // Q8: the same / the block's scale
     // The column maximum (best_packed) is a diagnostic: the assignment step works from the candidate lists alone.  It
     // is kept only in the instantiation that also writes the dense matrix; in the production one it cost four of
     // the six vector instructions per accumulator in the epilogue, during which the MFMA units of the CU idle.
     constexpr bool BEST = DENSE && !Q8;      // (no room in LDS for it next to the fp8 screen's arrays)
     __shared__ uint32_t lds_bkey[BEST ? TN : 1][BEST ? NT : 1];
     __shared__ int lds_brt[BEST ? TN : 1][BEST ? NT : 1];
-    constexpr int MAXC = 512;
+    constexpr int MAXC = (BIG || !Q8) ? 512 : 256;      // (two small fp8 workgroups must fit one compute unit's LDS)
     __shared__ int lds_ncand;
     __shared__ int lds_cand_row[MAXC];
     __shared__ int lds_cand_col[MAXC];
@@ -306,14 +308,21 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
     for (int x = tid; x < BN; x += NT) {
         const int col = col0 + x;
         if constexpr (Q8) {
-            // the copies are unit vectors times kQ8Scale: "inverse norm" 1 / kQ8Scale for every block
+            // The "inverse norm" of a copy is its scale (positive for every block).  The test of a pair,
+            //   acc scale_l scale_r + alpha_l alpha_r > floor - err_r - err_l (1 + err_r) [- rem_l rem_r],
+            // is taken with everything that belongs to the column divided by scale_r beforehand.
             const int64_t id = (int64_t)g * A.P + r_ids[min(col, mr - 1)];
-            const float eb = col < mr ? qerr[id] : 0.0f;
-            lds_invr[x] = col < mr ? Q8_INV : 0.0f;
-            lds_tcol[x] = col < mr ? (A.thr_floor - eb) * kQ8Scale : INFINITY;
-            lds_c1[x] = (1.0f + eb) * kQ8Scale;
+            const bool ok = col < mr;
+            const float eb = ok ? q8.err[id] : 0.0f;
+            const float ir = q8.scale[id];
+            const float ar = ok ? q8.alpha[id] : 0.0f;
+            lds_invr[x] = ok ? ir : 0.0f;
+            lds_tcol[x] = ok ? (A.thr_floor - eb) / ir : INFINITY;
+            lds_c1[x] = ok ? (1.0f + eb) / ir : 0.0f;
+            lds_alr[x] = ar;
+            lds_alrs[x] = ar / ir;
             if constexpr (PREFIX)
-                lds_tcolb[x] = col < mr ? rem[id] * kQ8Scale : 0.0f;
+                lds_tcolb[x] = ok ? rem[id] / ir : 0.0f;
         } else {
             const float ir = col < mr ? inv_g[r_ids[col]] : 0.0f;
             lds_invr[x] = ir;
@@ -325,8 +334,10 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
     for (int x = tid; x < RT * BM; x += NT) {
         const int row = row0 + x;
         if constexpr (Q8) {
-            lds_invl[x] = row < row_end ? Q8_INV : __uint_as_float(0x7FC00000u);
-            lds_errl[x] = row < row_end ? qerr[(int64_t)g * A.P + l_ids[row]] : 0.0f;
+            const int64_t id = (int64_t)g * A.P + l_ids[min(row, row_end - 1)];
+            lds_invl[x] = row < row_end ? q8.scale[id] : __uint_as_float(0x7FC00000u);
+            lds_errl[x] = row < row_end ? q8.err[id] : 0.0f;
+            lds_all[x] = row < row_end ? q8.alpha[id] : 0.0f;
         } else {
             lds_invl[x] = row < row_end ? inv_g[l_ids[row]] : __uint_as_float(0x7FC00000u);
         }
@@ -524,13 +535,14 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
         // ---- epilogue of row tile rt
         {
             uint32_t kmax[TN];
-            float tcol[TN], tcolb[TN], c1[TN];
+            float tcol[TN], tcolb[TN], c1[TN], alrs[TN];
 #pragma unroll
             for (int nt = 0; nt < TN; ++nt) {
                 kmax[nt] = 0u;
                 tcol[nt] = lds_tcol[nt * NT_STRIDE + wn * 32 + (lane & 31)];
                 tcolb[nt] = PREFIX ? lds_tcolb[nt * NT_STRIDE + wn * 32 + (lane & 31)] : 0.0f;
                 c1[nt] = Q8 ? lds_c1[nt * NT_STRIDE + wn * 32 + (lane & 31)] : 0.0f;
+                alrs[nt] = Q8 ? lds_alrs[nt * NT_STRIDE + wn * 32 + (lane & 31)] : 0.0f;
             }
 #pragma unroll
             for (int mt = 0; mt < TM; ++mt)
@@ -544,10 +556,12 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
                         const float4 rl4 = *reinterpret_cast<const float4 *>(&lds_reml[rt * BM + rl0]);
                         rl[0] = rl4.x; rl[1] = rl4.y; rl[2] = rl4.z; rl[3] = rl4.w;
                     }
-                    float el[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                    float el[4] = {0.0f, 0.0f, 0.0f, 0.0f}, al[4] = {0.0f, 0.0f, 0.0f, 0.0f};
                     if constexpr (Q8) {
                         const float4 el4 = *reinterpret_cast<const float4 *>(&lds_errl[rt * BM + rl0]);
                         el[0] = el4.x; el[1] = el4.y; el[2] = el4.z; el[3] = el4.w;
+                        const float4 al4 = *reinterpret_cast<const float4 *>(&lds_all[rt * BM + rl0]);
+                        al[0] = al4.x; al[1] = al4.y; al[2] = al4.z; al[3] = al4.w;
                     }
 #pragma unroll
                     for (int nt = 0; nt < TN; ++nt) {
@@ -559,8 +573,10 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
                             // the floor of this pair, lowered by what the unseen tails could add at most (rem is rounded up with a
                             // margin far above the rounding of this line)
                             lim[q] = tcol[nt];
-                            if constexpr (Q8)           // the copies' errors: - err_a (1 + err_b); - err_b is in tcol
-                                lim[q] = fmaf(-el[q], c1[nt], lim[q]);
+                            if constexpr (Q8) {         // the copies' errors: - err_a (1 + err_b); - err_b is in tcol;
+                                lim[q] = fmaf(-el[q], c1[nt], lim[q]);      // and the part of the cosine that lies along
+                                lim[q] = fmaf(-al[q], alrs[nt], lim[q]);    // the common direction moves over to this side
+                            }
                             if constexpr (PREFIX)
                                 lim[q] = fmaf(-rl[q], tcolb[nt], lim[q]);
                             hit |= t[q] > lim[q];
@@ -576,7 +592,9 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
                             for (int q = 0; q < 4; ++q)
                                 if (t[q] > lim[q]) {
                                     const int row = row0 + rt * BM + rl0 + q;
-                                    const float sv = t[q] * lds_invr[cl];
+                                    float sv = t[q] * lds_invr[cl];
+                                    if constexpr (Q8)
+                                        sv = fmaf(al[q], lds_alr[cl], sv);
                                     const int k = atomicAdd(&lds_ncand, 1);
                                     if (k < MAXC) {
                                         lds_cand_row[k] = row;
@@ -600,9 +618,12 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
                             const int rl = mt * MT_STRIDE + wm * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
                             const int row = row0 + rt * BM + rl;
                             const int col = col0 + nt * NT_STRIDE + wn * 32 + (lane & 31);
-                            if (row < row_end && col < mr)
-                                dense_s[(int64_t)g * A.total_s + s_base[node] + (int64_t)row * r_cap[node] + col] =
-                                    acc[mt][nt][e] * lds_invl[rt * BM + rl] * lds_invr[nt * NT_STRIDE + wn * 32 + (lane & 31)];
+                            if (row < row_end && col < mr) {
+                                float sv = acc[mt][nt][e] * lds_invl[rt * BM + rl] * lds_invr[nt * NT_STRIDE + wn * 32 + (lane & 31)];
+                                if constexpr (Q8)
+                                    sv = fmaf(lds_all[rt * BM + rl], lds_alr[nt * NT_STRIDE + wn * 32 + (lane & 31)], sv);
+                                dense_s[(int64_t)g * A.total_s + s_base[node] + (int64_t)row * r_cap[node] + col] = sv;
+                            }
                         }
             }
 #pragma unroll
@@ -689,7 +710,7 @@ static void launch_ring(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, 
     A.n_items = tt.n_items;
     A.row_bytes = pool.r * (int)sizeof(T);
     const bool prefix = !dense_s && w.screen_prefix > 0 && w.screen_prefix < pool.r;
-    const char *kpool = std::is_same<T, fp8_t>::value ? (const char *)w.q8_k : (const char *)pool.k;
+    const char *kpool = std::is_same<T, fp8_t>::value ? (const char *)w.q8.k : (const char *)pool.k;
     A.nk_screen = (prefix ? w.screen_prefix * (int)sizeof(T) : A.row_bytes) >> 6;
     A.thr_floor = thr_floor;
     A.total_s = h.total_s;
@@ -698,7 +719,7 @@ static void launch_ring(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, 
     similarity_ring_kernel<T, BIG, D, PF><<<grid, BIG ? 512 : 256, 0, s>>>(                                                             \
         A, kpool, pool.inv_norm_k, w.set_ids, w.set_cnt, tt.node, tt.col0, tt.row0, tt.rows, h.l_off, h.r_off, \
         h.l_slot, h.r_slot, h.r_base, h.r_cap, h.s_base, w.best_packed, w.cand_cnt, w.cand_idx, w.cand_val, dense_s,           \
-        w.group_enable, w.rem_k, w.q8_err)
+        w.group_enable, w.rem_k, w.q8)
     if (dense_s)
         KVF_SIM_LAUNCH(true, false);
     else if (prefix)
@@ -716,7 +737,7 @@ void launch_similarity(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, c
     if (cols > 0)
         similarity_clear_kernel<<<(unsigned)((cols + 255) / 256), 256, 0, s>>>(w.best_packed, w.cand_cnt, cols);
     const bool big = h.use_big_tiles;
-    if (w.q8_k) {
+    if (w.q8.k) {
         if (big)
             launch_ring<fp8_t, true>(s, pool, w, h, h.big, thr_floor, dense_s);
         else

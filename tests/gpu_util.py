@@ -22,8 +22,8 @@ def gpu_fuse(rec, mat, thr=None, cand_cap=16, band=1e-3, group_size=None, timing
     plan = kb.Plan(ctx, cache, spec, cand_cap)
     if rule is not None:
         kb.set_assign_rule(ctx, plan, {"argmax": kb.RULE_ARGMAX, "first_row": kb.RULE_FIRST_ROW}[rule])
-    if screen_fp8:
-        kb.set_screen_fp8(ctx, plan)
+    if screen_fp8:          # True, or "centred" for copies with the group's common direction taken out
+        kb.set_screen_fp8(ctx, plan, centre=(screen_fp8 == "centred"))
     if screen_prefix:
         kb.set_screen_prefix(ctx, plan, screen_prefix)
     stats = kb.fuse_tree(ctx, plan, rec.thr if thr is None else thr, band, want_stats=True, want_timing=timing)

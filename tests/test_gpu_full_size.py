@@ -19,7 +19,7 @@ DEV = "cuda:0"
 
 @pytest.mark.timeout(900)
 @pytest.mark.parametrize("rule", ["argmax", "first_row", "argmax_with_prefix_screen", "argmax_with_fp8_screen",
-                                  "argmax_with_both_screens"])
+                                  "argmax_with_both_screens", "argmax_with_centred_fp8_screen"])
 def test_llama8b_bff_full_size_sampled_groups_and_invariants(oracle, rule):
     kb = gu.load_binding()
     screen_prefix, screen_fp8 = 0, False
@@ -27,6 +27,8 @@ def test_llama8b_bff_full_size_sampled_groups_and_invariants(oracle, rule):
         rule, screen_prefix = "argmax", 512
     elif rule == "argmax_with_fp8_screen":
         rule, screen_fp8 = "argmax", True
+    elif rule == "argmax_with_centred_fp8_screen":
+        rule, screen_fp8 = "argmax", "centred"
     elif rule == "argmax_with_both_screens":
         rule, screen_prefix, screen_fp8 = "argmax", 512, True
     rec = wl.llama8b_bff()

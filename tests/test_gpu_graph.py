@@ -23,7 +23,7 @@ def _state(cache, out):
     return [t.clone() for t in (cache.K, cache.V, cache.bt, cache.scale_k, cache.scale_v, cache.refcount, cache.n_phys, out)]
 
 
-@pytest.mark.parametrize("screen", ["full_product", "prefix_256", "fp8_copies"])
+@pytest.mark.parametrize("screen", ["full_product", "prefix_256", "fp8_copies", "fp8_copies_centred"])
 def test_fusion_and_decode_replayed_from_a_graph(oracle, screen):
     kb = gu.load_binding()
     rec = wl.llama8b_bff(n_req=6, tokens=16 * 150, layers=1, kv_heads=3, prefix_tokens=192, near_pool=24, t=16, d=64)
@@ -46,8 +46,8 @@ def test_fusion_and_decode_replayed_from_a_graph(oracle, screen):
         plan = kb.Plan(ctx, cache, kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr), 16)
         if screen == "prefix_256":
             kb.set_screen_prefix(ctx, plan, 256)
-        elif screen == "fp8_copies":
-            kb.set_screen_fp8(ctx, plan)
+        elif screen.startswith("fp8_copies"):
+            kb.set_screen_fp8(ctx, plan, centre=screen.endswith("centred"))
 
         def step():
             cache.K.copy_(K0)

@@ -64,8 +64,8 @@ def test_block_norms_match_oracle(kb, oracle, which):
 def _two_leaf_case(kind):
     """One tree node: left leaf and right leaf with planted duplicates, ragged against the 128 x 128 tiles
     (or, for the *_big kinds, against the 256 x 256 tiles with several row tiles and column panels)."""
-    rng = np.random.default_rng({"f32": 5, "bf16": 6, "f32_big": 7, "bf16_big": 8}[kind])
-    ml, mr = {"bf16": (150, 201), "f32": (70, 45), "bf16_big": (700, 530), "f32_big": (300, 290)}[kind]
+    rng = np.random.default_rng({"f32": 5, "bf16": 6, "f32_big": 7, "bf16_big": 8, "bf16_common": 9}[kind])
+    ml, mr = {"bf16": (150, 201), "f32": (70, 45), "bf16_big": (700, 530), "f32_big": (300, 290), "bf16_common": (150, 201)}[kind]
     r = 256 if kind.startswith("bf16") else 96
     n = ml + mr
     protos = rng.standard_normal((40, r))
@@ -77,6 +77,8 @@ def _two_leaf_case(kind):
     x[ml + 4] = x[7]                      # two right blocks for one target
     x[9] = x[8]                           # identical left rows: lowest row must win
     x[ml + 5] = x[8] + 1e-4 * rng.standard_normal(r)
+    if kind == "bf16_common":             # every block shares a strong component: unrelated blocks at cosine 0.8
+        x += 2.0 * rng.standard_normal(r)[None]
     x[11] = 0.0                           # zero blocks on both sides
     x[ml + 6] = 0.0
     y = rng.standard_normal((n, r))
@@ -370,20 +372,23 @@ def _e4m3_table():
     return out
 
 
-@pytest.mark.parametrize("kind", ["bf16", "bf16_big"])
-def test_fp8_screen_copy_and_bound(kb, oracle, kind):
-    """The fp8 screen's ingredients on one node: the one-byte copy is the e4m3 rounding of the unit blocks times 256 (checked
-    against the format written out above: every byte decodes to within half a spacing of its element), the stored error is
-    the copy's true Euclidean error (recomputed here in fp64 from the bytes), and the dense product of the copies stays
-    within err_a + err_b + err_a err_b of the oracle's cosine for every pair -- the inequality the screen's candidate rule
-    rests on."""
+@pytest.mark.parametrize("centre", [False, True])
+@pytest.mark.parametrize("kind", ["bf16", "bf16_big", "bf16_common"])
+def test_fp8_screen_copy_and_bound(kb, oracle, kind, centre):
+    """The fp8 screen's ingredients on one node.  With u the unit block, m the group's direction (zero when the copies
+    are not centred), alpha = <m, u> and u_c = u - alpha m: the one-byte copy is the e4m3 rounding of u_c * 256 / |u_c|
+    (checked against the format written out above: every byte decodes to within half a spacing of its element), the
+    stored scale is |u_c| / 256, the stored error covers the copy's true Euclidean error plus what a non-unit m and the
+    rounding of alpha cost (all recomputed here in fp64 from the bytes and the stored direction), and the kernel's value
+    <q(a), q(b)> scale_a scale_b + alpha_a alpha_b stays within err_a + err_b + err_a err_b of the oracle's cosine for
+    every pair -- the inequality the screen's candidate rule rests on."""
     K, V, bt, ml, mr, t, d = _two_leaf_case(kind)
     Kh, bth = wl.to_numpy_pool(K[0]), bt[0].numpy().copy()
     K, V, bt = K.to(DEV), V.to(DEV), bt.to(DEV)
     ctx = kb.Context(DEV)
     cache = kb.Cache(K, V, bt, t, d)
     plan = kb.Plan(ctx, cache, kb.tree_spec([0, ml], [ml, mr], [0, 1, 2]), 16)
-    kb.set_screen_fp8(ctx, plan)
+    kb.set_screen_fp8(ctx, plan, centre=centre)
     kb.block_norms(ctx, cache)
     kb.leaf_sets(ctx, plan)
     view = plan.view(0)
@@ -395,40 +400,70 @@ def test_fp8_screen_copy_and_bound(kb, oracle, kind):
     assert np.isfinite(dec).all()
     live = nk > 0
     Kf = oracle.pool_to_f64(Kh)
+    P, r = Kf.shape
     unit = np.zeros_like(Kf)
     unit[live] = Kf[live] / nk[live, None]
-    # every byte is a nearest e4m3 value of unit * 256: spacing 2^(e - 3) at binade e, 2^-9 below 2^-6; the kernel rounds
-    # the product with a binary32 factor first, hence the small allowance
-    target = unit * 256.0
+    m = plan.k8_dir[0].cpu().numpy().astype(np.float64)
+    alpha = plan.k8_alpha[0].cpu().numpy().astype(np.float64)
+    scale = plan.k8_scale[0].cpu().numpy().astype(np.float64)
+    err_gpu = plan.k8_err[0].cpu().numpy().astype(np.float64)
+    if centre:
+        # the direction: the normalised sum of the unit blocks taken at even steps through the pool (up to 64 of them)
+        n_s = min(P, 64)
+        want_m = unit[[s * P // n_s for s in range(n_s)]].sum(0)
+        want_m /= np.linalg.norm(want_m)
+        assert np.abs(m - want_m).max() < 1e-6
+        assert np.abs(alpha[live] - unit[live] @ m).max() < 1e-6
+        if kind == "bf16_common":
+            assert alpha[live].min() > 0.7              # the shared component is most of every block
+    else:
+        assert (m == 0).all() and (alpha == 0).all()
+    assert (alpha[~live] == 0).all() and (scale > 0).all()
+    uc = unit - alpha[:, None] * m[None]
+    c = np.sqrt((uc ** 2).sum(1))
+    assert np.abs(scale[live] * 256.0 / c[live] - 1.0).max() < 1e-4           # the scale follows |u_c| (it need not be exact)
+    # every byte is a nearest e4m3 value of u_c / scale: spacing 2^(e - 3) at binade e, 2^-9 below 2^-6; the kernel
+    # rounds the product to binary32 first, hence the small allowance
+    target = np.where(live[:, None], uc / scale[:, None], 0.0)
+    assert np.abs(target).max() < 448.0
     spacing = np.maximum(2.0 ** (np.floor(np.log2(np.maximum(np.abs(target), 2.0 ** -6))) - 3), 2.0 ** -9)
     assert (np.abs(dec - target) <= 0.5 * spacing * (1 + 1e-5)).all()
-    err_true = np.sqrt(((unit - dec / 256.0) ** 2).sum(1))
-    err_gpu = plan.k8_err[0].cpu().numpy().astype(np.float64)
-    assert (err_gpu >= err_true).all() and (err_gpu <= err_true + 3e-6).all()
-    assert (err_gpu[~live] == 0).all() and 0.01 < err_gpu[live].mean() < 0.04
-    _say("fp8 copy", kind, "mean err", err_gpu[live].mean(), "max err", err_gpu.max())
+    # the stored error: the measured distance, plus a margin that covers what the identity <u, v> = <u_c, v_c> +
+    # alpha_u alpha_v loses because the stored m and alpha are binary32 values (recomputed here: far below the margin)
+    err_copy = np.sqrt(((uc - dec * scale[:, None]) ** 2).sum(1))
+    loss = np.abs((uc * m[None]).sum(1)) + np.abs(alpha) * abs((m ** 2).sum() - 1.0)
+    assert loss.max() < 5e-7
+    err_true = np.where(live, err_copy + loss, 0.0)
+    assert (err_gpu >= err_true + np.where(live, 1e-6, 0.0)).all() and (err_gpu <= err_copy + 3e-6).all()
+    assert (err_gpu[~live] == 0).all() and 0.002 < err_gpu[live].mean() < 0.04
+    _say("fp8 copy", kind, "centred" if centre else "plain", "mean err", err_gpu[live].mean(), "max err", err_gpu.max(),
+         "mean |u_c|", c[live].mean())
     L, R = bth[:ml], bth[ml:]
     S = oracle.similarity(Kh, nk, L, R)
     S_q = dense[0].cpu().numpy().reshape(ml, mr).astype(np.float64)
     ea, eb = err_gpu[L][:, None], err_gpu[R][None, :]
     slack = ea + eb + ea * eb + Kh.shape[1] * 2.0 ** -22
     worst = (np.abs(S_q - S) / slack).max()
-    _say("  max |<q(a), q(b)> / 256^2 - cos| / bound =", worst)
+    _say("  max |value - cos| / bound =", worst, "  mean bound", slack.mean())
     assert worst <= 1.0
-    # and the product is what the decoded bytes give (format and operand layout of the matrix instruction)
-    exact_q = (dec[L] @ dec[R].T) / 65536.0
+    # and the value is what the decoded bytes give (format and operand layout of the matrix instruction)
+    exact_q = (dec[L] * scale[L, None]) @ (dec[R] * scale[R, None]).T + alpha[L][:, None] * alpha[R][None, :]
     assert np.abs(S_q - exact_q).max() <= Kh.shape[1] * 2.0 ** -22
+    if centre and kind == "bf16_common":
+        assert slack.mean() < 0.03          # against about 0.05 uncentred: the intervals shrink with |u_c|
 
 
+@pytest.mark.parametrize("centre", [False, True])
 @pytest.mark.parametrize("rule", ["argmax", "first_row"])
 @pytest.mark.parametrize("which", ["small_bf16", "small_bf16_cap2", "zipf_small", "zipf_at_threshold", "mixed_small_f32",
                                    "r4096_bf16_with_quarter_prefix", "tiny_f32_with_half_prefix", "r8192_bf16_long_blocks",
                                    "zipf_at_threshold_with_half_prefix", "small_bf16_cap2_with_half_prefix", "r128_bf16_two_slices"])
-def test_tree_fp8_screen_gives_the_same_tables(kb, oracle, which, rule):
+def test_tree_fp8_screen_gives_the_same_tables(kb, oracle, which, rule, centre):
     """The fp8 screen (similarity over one-byte copies of the key blocks + their measured error as a bound, every candidate
     evaluated in full in fp64) must give exactly the oracle's tables, pools and counters, alone and together with the prefix
-    screen, for both pool types and both readings of the threshold line."""
-    kw = dict(rule=rule, screen_fp8=True)
+    screen, for both pool types and both readings of the threshold line, with and without the common direction taken out
+    of the copies (which the library only does where the prefix screen is off)."""
+    kw = dict(rule=rule, screen_fp8="centred" if centre else True)
     if which == "small_bf16":
         rec = _small_bf16()
     elif which == "small_bf16_cap2":
@@ -462,15 +497,21 @@ def test_tree_fp8_screen_gives_the_same_tables(kb, oracle, which, rule):
         kw = dict(kw, band=2.5e-3)          # at least r * 2^-22
     else:
         rec, kw = wl.tiny_bff(), dict(kw, screen_prefix=512, cand_cap=4)
-    cache, plan, stats, res, mat = _run_tree_case(kb, oracle, rec, "fp8_screen_" + which, **kw)
+    cache, plan, stats, res, mat = _run_tree_case(kb, oracle, rec, "fp8_screen_" + which + ("_centred" if centre else ""), **kw)
     assert stats.fused > 0
+    centred_here = bool(centre) and not kw.get("screen_prefix") and rec.r <= 8192
+    assert bool((plan.k8_alpha != 0).any()) == centred_here
 
 
-@pytest.mark.parametrize("screen", ["full", "prefix", "fp8", "both"])
+_OVERFLOW_SEEN = {}
+
+
+@pytest.mark.parametrize("screen", ["full", "prefix", "fp8", "both", "fp8_centred"])
 def test_tree_screens_when_unrelated_blocks_share_a_direction(kb, oracle, screen):
-    """Keys with a strong common component (unrelated blocks at cosine 0.8, threshold 0.9): the case the two screens are
-    not made for.  Their bounds list many pairs that do not fuse, candidate lists overflow and columns are rescanned in
-    fp64 -- slower, and still exactly the oracle's tables, pools and counters."""
+    """Keys with a strong common component (unrelated blocks at cosine 0.8, threshold 0.9): the case the prefix screen and
+    the plain byte copies are not made for.  Their bounds list many pairs that do not fuse, candidate lists overflow and
+    columns are rescanned in fp64 -- slower, and still exactly the oracle's tables, pools and counters.  Copies with the
+    common direction taken out keep their resolution here: far fewer columns overflow."""
     rec = _small_bf16(n_req=5, tokens=8 * 110, kv_heads=2)
     mat = wl.materialise(rec, DEV, phys_perm=True)
     gen = torch.Generator(device="cpu")
@@ -480,7 +521,8 @@ def test_tree_screens_when_unrelated_blocks_share_a_direction(kb, oracle, screen
         mat["K"][g] = (mat["K"][g].float() + mu).to(rec.dtype)
     host = gu.host_copy(mat)
     prefix = {"prefix": 64, "both": 128}.get(screen, 0)       # blocks of 256 elements; the byte copies need 128 at least
-    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, cand_cap=8, screen_prefix=prefix, screen_fp8=screen in ("fp8", "both"))
+    fp8 = "centred" if screen == "fp8_centred" else screen in ("fp8", "both")
+    cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, cand_cap=8, screen_prefix=prefix, screen_fp8=fp8)
     res = gu.oracle_fuse(oracle, rec, host)
     assert gu.check_ambiguity(res, "common_direction_" + screen) == list(range(rec.G))
     for g in range(rec.G):
@@ -488,14 +530,17 @@ def test_tree_screens_when_unrelated_blocks_share_a_direction(kb, oracle, screen
     assert stats.fused == sum(int(r.stats[1]) for r in res) > 50
     assert stats.near_threshold == sum(int(r.stats[2]) for r in res)
     _say("  screen", screen, "fused", stats.fused, "refined", stats.refined, "overflow", stats.cand_overflow)
-    if screen != "full":
+    _OVERFLOW_SEEN[screen] = stats.cand_overflow
+    if screen not in ("full", "fp8_centred"):
         assert stats.cand_overflow > 0        # the bounds did list more pairs than the lists hold
+    if screen == "fp8_centred" and "fp8" in _OVERFLOW_SEEN:
+        assert stats.cand_overflow * 4 < _OVERFLOW_SEEN["fp8"]
 
 
-@pytest.mark.parametrize("seed", list(range(12)))
+@pytest.mark.parametrize("seed", list(range(20)))
 def test_tree_seeded_sweep_with_a_common_direction(kb, oracle, seed):
     """Seeded variations of the case above: strength of the common component, threshold, pool type, candidate slots, both
-    readings of the threshold line, all four screens.  Many of them overflow most candidate lists."""
+    readings of the threshold line, all five screens.  Many of them overflow most candidate lists."""
     rng = np.random.default_rng(1000 + seed)
     dtype = torch.bfloat16 if seed % 3 else torch.float32
     rec = wl.llama8b_bff(n_req=int(rng.integers(3, 7)), tokens=8 * int(rng.integers(40, 120)), layers=1, kv_heads=2,
@@ -510,11 +555,11 @@ def test_tree_seeded_sweep_with_a_common_direction(kb, oracle, seed):
         mu = (amp * torch.randn(rec.r, generator=gen)).to(DEV)
         mat["K"][g] = (mat["K"][g].float() + mu).to(rec.dtype)
     host = gu.host_copy(mat)
-    screen = ("full", "prefix", "fp8", "both")[seed % 4]
-    rule = "first_row" if (seed // 4) % 2 else "argmax"
+    screen = ("full", "prefix", "fp8", "both", "fp8_centred")[seed % 5]
+    rule = "first_row" if (seed // 5) % 2 else "argmax"
     prefix = {"prefix": 64, "both": 128}.get(screen, 0)
     cache, plan, stats, ctx = gu.gpu_fuse(rec, mat, cand_cap=int(rng.choice([2, 8, 64])), rule=rule, screen_prefix=prefix,
-                                          screen_fp8=screen in ("fp8", "both"))
+                                          screen_fp8="centred" if screen == "fp8_centred" else screen in ("fp8", "both"))
     res = gu.oracle_fuse(oracle, rec, host, rule=rule)
     assert gu.check_ambiguity(res, f"common_direction_sweep_{seed}") == list(range(rec.G))
     for g in range(rec.G):
@@ -524,9 +569,11 @@ def test_tree_seeded_sweep_with_a_common_direction(kb, oracle, seed):
          stats.cand_overflow)
 
 
-def test_fp8_screen_step_by_step_and_arguments(kb, oracle):
+@pytest.mark.parametrize("centre", [False, True])
+def test_fp8_screen_step_by_step_and_arguments(kb, oracle, centre):
     """The single-step entry points with the fp8 screen on (the copy then comes from kvfuse_leaf_sets and is refreshed after
-    every kvfuse_merge), and the argument checks of the switch."""
+    every kvfuse_merge), once together with the prefix screen and once with centred copies, and the argument checks of the
+    switch."""
     rec = _small_bf16(n_req=5, tokens=1000, kv_heads=2)
     mat = wl.materialise(rec, DEV, phys_perm=True)
     host = gu.host_copy(mat)
@@ -534,18 +581,19 @@ def test_fp8_screen_step_by_step_and_arguments(kb, oracle):
     cache = kb.Cache(mat["K"], mat["V"], mat["bt"], rec.t, rec.d)
     plan = kb.Plan(ctx, cache, kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr), 16)
     k8 = torch.empty(cache.G, cache.P, rec.r, device=DEV, dtype=torch.uint8)
-    err = torch.empty(cache.G, cache.P, device=DEV, dtype=torch.float32)
+    err = torch.empty(3 * cache.G * cache.P + cache.G * rec.r, device=DEV, dtype=torch.float32)
     # one of the two arrays missing
-    assert kb.lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, k8.data_ptr(), None) == kb.EINVAL
-    assert kb.lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, None, err.data_ptr()) == kb.EINVAL
+    assert kb.lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, k8.data_ptr(), None, 0) == kb.EINVAL
+    assert kb.lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, None, err.data_ptr(), 0) == kb.EINVAL
     # a prefix that is fine for the bfloat16 product (96 elements = 192 bytes of the pool) is no multiple of 64 bytes of the copy
     kb.set_screen_prefix(ctx, plan, 96)
-    assert kb.lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, k8.data_ptr(), err.data_ptr()) == kb.EINVAL
+    assert kb.lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, k8.data_ptr(), err.data_ptr(), 0) == kb.EINVAL
     kb.set_screen_prefix(ctx, plan, 0)
-    kb.set_screen_fp8(ctx, plan)
+    kb.set_screen_fp8(ctx, plan, centre=centre)
     with pytest.raises(kb.KvfuseError):
         kb.set_screen_prefix(ctx, plan, 96)
-    kb.set_screen_prefix(ctx, plan, 128)
+    if not centre:
+        kb.set_screen_prefix(ctx, plan, 128)
     kb.block_norms(ctx, cache)
     kb.leaf_sets(ctx, plan)
     for h in range(plan.n_heights):
@@ -559,6 +607,7 @@ def test_fp8_screen_step_by_step_and_arguments(kb, oracle):
     for g in range(rec.G):
         gu.compare_group(res[g], cache, g, False, "fp8_step_by_step")
     assert sum(int(r.stats[1]) for r in res) > 50
+    assert bool((plan.k8_alpha != 0).any()) == centre
     # blocks too short or of an odd length for the byte copy
     small = wl.tiny_bff()
     m2 = wl.materialise(small, DEV)
