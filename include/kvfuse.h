@@ -440,10 +440,12 @@ int kvfuse_plan_set_screen_prefix(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t pr
  *            rebuilt targets)
  *   k8_side  device, 3 * G * P + G * t * d floats, owned by the caller likewise: [G][P] err, then [G][P] scale, then
  *            [G][P] alpha, written along with k8, then [G][t * d] the directions m (unused without `centre`)
+ *   k8_bytes, k8_side_floats   what the caller allocated; smaller than stated above -> KVFUSE_EINVAL, nothing changes
  * Two NULLs switch the shortcut off (the default).  Blocks must have a multiple of 64 and at least 128 elements.
  * Applies to the following kvfuse_leaf_sets, kvfuse_similarity, kvfuse_assign, kvfuse_merge and kvfuse_fuse_tree calls
  * on this plan; with a dense matrix kvfuse_similarity then writes the value above instead of the cosine. */
-int kvfuse_plan_set_screen_fp8(kvfuse_ctx *ctx, kvfuse_plan *plan, void *k8, float *k8_side, int32_t centre);
+int kvfuse_plan_set_screen_fp8(kvfuse_ctx *ctx, kvfuse_plan *plan, void *k8, size_t k8_bytes, float *k8_side, size_t k8_side_floats,
+                               int32_t centre);
 
 /* ---- variants of the method ---------------------------------------------------------------------------- */
 

@@ -128,7 +128,7 @@ lib.kvfuse_plan_set_group_mask.argtypes = [_vp, _vp, _vp]
 lib.kvfuse_plan_set_assign_rule.argtypes = [_vp, _vp, _i32]
 lib.kvfuse_plan_group_counters.argtypes = [_vp, _vp, _vp, _i32]
 lib.kvfuse_plan_set_screen_prefix.argtypes = [_vp, _vp, _i32, _vp]
-lib.kvfuse_plan_set_screen_fp8.argtypes = [_vp, _vp, _vp, _vp, C.c_int32]
+lib.kvfuse_plan_set_screen_fp8.argtypes = [_vp, _vp, _vp, C.c_size_t, _vp, C.c_size_t, C.c_int32]
 lib.kvfuse_tree_spec_shortest_first.argtypes = [C.POINTER(TreeSpec), _vp, _vp, _vp, _vp]
 lib.kvfuse_replicate_rescaled.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table), _vp]
 lib.kvfuse_drop_rescale.argtypes = [_vp, C.POINTER(Pool), C.POINTER(Table)]
@@ -469,7 +469,7 @@ def set_screen_fp8(ctx, plan, on=True, centre=False):
         r = c.t * c.d
         k8 = torch.empty(c.G, c.P, r, device=c.K.device, dtype=torch.uint8)
         side = torch.zeros(3 * c.G * c.P + c.G * r, device=c.K.device, dtype=torch.float32)
-        ctx.check(lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, _ptr(k8), _ptr(side), 1 if centre else 0))
+        ctx.check(lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, _ptr(k8), k8.numel(), _ptr(side), side.numel(), 1 if centre else 0))
         gp = c.G * c.P
         plan.k8, plan.k8_side = k8, side
         plan.k8_err = side[:gp].view(c.G, c.P)
@@ -477,7 +477,7 @@ def set_screen_fp8(ctx, plan, on=True, centre=False):
         plan.k8_alpha = side[2 * gp:3 * gp].view(c.G, c.P)
         plan.k8_dir = side[3 * gp:].view(c.G, r)
     else:
-        ctx.check(lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, None, None, 0))
+        ctx.check(lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, None, 0, None, 0, 0))
         plan.k8 = plan.k8_side = plan.k8_err = plan.k8_scale = plan.k8_alpha = plan.k8_dir = None
 
 

@@ -775,7 +775,8 @@ int kvfuse_plan_set_screen_prefix(kvfuse_ctx *ctx, kvfuse_plan *plan, int32_t pr
     return KVFUSE_OK;
 }
 
-int kvfuse_plan_set_screen_fp8(kvfuse_ctx *ctx, kvfuse_plan *plan, void *k8, float *k8_side, int32_t centre)
+int kvfuse_plan_set_screen_fp8(kvfuse_ctx *ctx, kvfuse_plan *plan, void *k8, size_t k8_bytes, float *k8_side, size_t k8_side_floats,
+                               int32_t centre)
 {
     if (!ctx)
         return KVFUSE_EINVAL;
@@ -795,6 +796,8 @@ int kvfuse_plan_set_screen_fp8(kvfuse_ctx *ctx, kvfuse_plan *plan, void *k8, flo
     if (p.work.screen_prefix > 0 && (p.work.screen_prefix % 64 != 0 || p.work.screen_prefix < 128))
         return fail(&ctx->c, KVFUSE_EINVAL, "fp8 screen: the screen prefix in force is not a multiple of 64 elements of at least 128");
     const size_t gp = (size_t)p.pool.G * p.pool.P;
+    if (k8_bytes < gp * (size_t)p.pool.r || k8_side_floats < 3 * gp + (size_t)p.pool.G * p.pool.r)
+        return fail(&ctx->c, KVFUSE_EINVAL, "fp8 screen: arrays too small: need G * P * t * d bytes and 3 * G * P + G * t * d floats");
     p.work.q8.k = static_cast<uint8_t *>(k8);
     p.work.q8.err = k8_side;
     p.work.q8.scale = k8_side + gp;

@@ -583,11 +583,14 @@ def test_fp8_screen_step_by_step_and_arguments(kb, oracle, centre):
     k8 = torch.empty(cache.G, cache.P, rec.r, device=DEV, dtype=torch.uint8)
     err = torch.empty(3 * cache.G * cache.P + cache.G * rec.r, device=DEV, dtype=torch.float32)
     # one of the two arrays missing
-    assert kb.lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, k8.data_ptr(), None, 0) == kb.EINVAL
-    assert kb.lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, None, err.data_ptr(), 0) == kb.EINVAL
+    assert kb.lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, k8.data_ptr(), k8.numel(), None, 0, 0) == kb.EINVAL
+    assert kb.lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, None, 0, err.data_ptr(), err.numel(), 0) == kb.EINVAL
+    # arrays smaller than the copies and their side values need
+    assert kb.lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, k8.data_ptr(), k8.numel() - 1, err.data_ptr(), err.numel(), 0) == kb.EINVAL
+    assert kb.lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, k8.data_ptr(), k8.numel(), err.data_ptr(), cache.G * cache.P, 1) == kb.EINVAL
     # a prefix that is fine for the bfloat16 product (96 elements = 192 bytes of the pool) is no multiple of 64 bytes of the copy
     kb.set_screen_prefix(ctx, plan, 96)
-    assert kb.lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, k8.data_ptr(), err.data_ptr(), 0) == kb.EINVAL
+    assert kb.lib.kvfuse_plan_set_screen_fp8(ctx.h, plan.h, k8.data_ptr(), k8.numel(), err.data_ptr(), err.numel(), 0) == kb.EINVAL
     kb.set_screen_prefix(ctx, plan, 0)
     kb.set_screen_fp8(ctx, plan, centre=centre)
     with pytest.raises(kb.KvfuseError):
