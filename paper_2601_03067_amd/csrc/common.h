@@ -241,70 +241,92 @@ __device__ __forceinline__ float tail_share(double tail_squares, double norm)
     return norm > 0.0 ? __double2float_ru(fmin(sqrt(fmax(tail_squares, 0.0)) / norm, 1.0) + 1e-6) : 0.0f;
 }
 
-// fp8 screen: the parameters of one block's copy.  u_c,i = x_i * inv - alpha * m_i;  byte_i = e4m3(u_c,i * gain);
-// decoded byte_i * shat reconstructs u_c,i (shat is the binary32 value stored as the block's scale).
+// fp8 screen: the parameters of one block's copy.  With u_c,i = x_i / |x| - alpha m_i and `scale` the binary32 value
+// stored as the block's scale, the byte of element i is e4m3(t_i), t_i = x_i * a - b * m_i in binary32 with
+// a = 1 / (|x| scale) and b = alpha / scale, so that decoded byte * scale reconstructs u_c,i.  `wide` marks a block
+// whose norm is so small that a leaves binary32's range: its copy is zeros with a vacuous error.
 struct Q8Block {
-    double inv, alpha, gain, shat;
+    float a, b;
+    double alpha, scale;
+    bool wide;
 };
 
-// The direction's values for one 16-byte piece of a block (PER16 elements from element offset e0), zeros without one.
-template <int PER>
-__device__ __forceinline__ void q8_dir_chunk(const float *__restrict__ dir_g, int e0, double *m)
+// 16 bytes of pool data as binary32 (exact for both pool types).
+template <typename T> __device__ __forceinline__ void widen_f32(const uint4 &raw, float *out);
+template <> __device__ __forceinline__ void widen_f32<bf16_t>(const uint4 &raw, float *out)
 {
-    if (dir_g) {
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
-        for (int i = 0; i < PER / 4; ++i) {
-            const float4 f = *reinterpret_cast<const float4 *>(dir_g + e0 + 4 * i);
-            m[4 * i] = (double)f.x; m[4 * i + 1] = (double)f.y; m[4 * i + 2] = (double)f.z; m[4 * i + 3] = (double)f.w;
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < PER; ++i)
-            m[i] = 0.0;
+    for (int i = 0; i < 4; ++i) {
+        out[2 * i] = __uint_as_float(w[i] << 16);
+        out[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
     }
 }
+template <> __device__ __forceinline__ void widen_f32<float>(const uint4 &raw, float *out)
+{
+    out[0] = __uint_as_float(raw.x);
+    out[1] = __uint_as_float(raw.y);
+    out[2] = __uint_as_float(raw.z);
+    out[3] = __uint_as_float(raw.w);
+}
 
-// <m, x> over one piece.
+// <m, x> over one 16-byte piece of a block (PER16 elements from element offset e0), in fp64: alpha must be <m, u> to
+// binary32 rounding for the identity behind the centred copies to hold as closely as quantise_error assumes.
 template <typename T>
 __device__ __forceinline__ void q8_dir_dot_chunk(const uint4 &raw, const float *__restrict__ dir_g, int e0, double &sm)
 {
     constexpr int PER = Elem<T>::PER16;
-    double x[PER], m[PER];
-    Elem<T>::widen(raw, x);
-    q8_dir_chunk<PER>(dir_g, e0, m);
+    float x[PER];
+    widen_f32<T>(raw, x);
 #pragma unroll
-    for (int i = 0; i < PER; ++i)
-        sm = fma(m[i], x[i], sm);
+    for (int i = 0; i < PER / 4; ++i) {
+        const float4 f = *reinterpret_cast<const float4 *>(dir_g + e0 + 4 * i);
+        sm = fma((double)f.x, (double)x[4 * i], sm);
+        sm = fma((double)f.y, (double)x[4 * i + 1], sm);
+        sm = fma((double)f.z, (double)x[4 * i + 2], sm);
+        sm = fma((double)f.w, (double)x[4 * i + 3], sm);
+    }
 }
 
-// One piece to e4m3 (the hardware's nearest-even conversion) and the squared error of that piece, decoded with the
-// hardware's own conversion.
+// One piece to e4m3 (the hardware's nearest-even conversion) and, in se, the squared distance between t and the bytes
+// decoded with the hardware's own conversion, in units of the scale.  All in binary32: t_i * scale differs from the
+// exact u_c,i by at most 2^-24 (|x_i| / |x| + 2 |alpha m_i| + |u_c,i|) (the roundings of a, b, b * m_i and the
+// multiply-add), 2.4e-7 over a block in the Euclidean norm; quantise_error's margin covers it.
 template <typename T>
 __device__ __forceinline__ void quantise_chunk(const uint4 &raw, const float *__restrict__ dir_g, int e0, const Q8Block &p,
-                                               uint8_t *__restrict__ dst, double &se)
+                                               uint8_t *__restrict__ dst, float &se)
 {
     constexpr int PER = Elem<T>::PER16;
-    double x[PER], m[PER];
-    Elem<T>::widen(raw, x);
-    q8_dir_chunk<PER>(dir_g, e0, m);
+    float x[PER], t[PER];
+    widen_f32<T>(raw, x);
+    if (dir_g) {
+#pragma unroll
+        for (int i = 0; i < PER / 4; ++i) {
+            const float4 f = *reinterpret_cast<const float4 *>(dir_g + e0 + 4 * i);
+            t[4 * i] = fmaf(x[4 * i], p.a, -(p.b * f.x));
+            t[4 * i + 1] = fmaf(x[4 * i + 1], p.a, -(p.b * f.y));
+            t[4 * i + 2] = fmaf(x[4 * i + 2], p.a, -(p.b * f.z));
+            t[4 * i + 3] = fmaf(x[4 * i + 3], p.a, -(p.b * f.w));
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            t[i] = x[i] * p.a;
+    }
     uint32_t w[PER / 4];
 #pragma unroll
     for (int i = 0; i < PER / 4; ++i) {
-        double uc[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            uc[e] = fma(x[4 * i + e], p.inv, -p.alpha * m[4 * i + e]);
-        int packed = __builtin_amdgcn_cvt_pk_fp8_f32((float)(uc[0] * p.gain), (float)(uc[1] * p.gain), 0, false);
-        packed = __builtin_amdgcn_cvt_pk_fp8_f32((float)(uc[2] * p.gain), (float)(uc[3] * p.gain), packed, true);
+        int packed = __builtin_amdgcn_cvt_pk_fp8_f32(t[4 * i], t[4 * i + 1], 0, false);
+        packed = __builtin_amdgcn_cvt_pk_fp8_f32(t[4 * i + 2], t[4 * i + 3], packed, true);
         w[i] = (uint32_t)packed;
-        const float d0 = __builtin_amdgcn_cvt_f32_fp8(packed, 0), d1 = __builtin_amdgcn_cvt_f32_fp8(packed, 1);
-        const float d2 = __builtin_amdgcn_cvt_f32_fp8(packed, 2), d3 = __builtin_amdgcn_cvt_f32_fp8(packed, 3);
-        const double dec[4] = {(double)d0, (double)d1, (double)d2, (double)d3};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const double diff = fma(-dec[e], p.shat, uc[e]);
-            se = fma(diff, diff, se);
-        }
+        const float d0 = t[4 * i] - __builtin_amdgcn_cvt_f32_fp8(packed, 0);
+        const float d1 = t[4 * i + 1] - __builtin_amdgcn_cvt_f32_fp8(packed, 1);
+        const float d2 = t[4 * i + 2] - __builtin_amdgcn_cvt_f32_fp8(packed, 2);
+        const float d3 = t[4 * i + 3] - __builtin_amdgcn_cvt_f32_fp8(packed, 3);
+        se = fmaf(d0, d0, se);
+        se = fmaf(d1, d1, se);
+        se = fmaf(d2, d2, se);
+        se = fmaf(d3, d3, se);
     }
     if constexpr (PER == 8) {
         __builtin_nontemporal_store(w[0], reinterpret_cast<uint32_t *>(dst));
@@ -324,28 +346,35 @@ __device__ __forceinline__ void quantise_chunk(const uint4 &raw, const float *__
 __device__ __forceinline__ Q8Block q8_block(double nrm, bool centred, double dot_m)
 {
     Q8Block p;
-    p.inv = nrm > 0.0 ? 1.0 / nrm : 0.0;
+    const double inv = nrm > 0.0 ? 1.0 / nrm : 0.0;
     p.alpha = 0.0;
-    p.gain = (double)kQ8Scale;
-    p.shat = (double)(1.0f / kQ8Scale);
+    p.scale = (double)(1.0f / kQ8Scale);
     if (centred) {
-        const double a = dot_m * p.inv;
+        const double a = dot_m * inv;
         p.alpha = (double)(float)a;
         const double c = sqrt(fmax(fma(p.alpha, p.alpha - 2.0 * a, 1.0), 1e-6));
-        p.shat = (double)(float)(c / (double)kQ8Scale);
-        p.gain = 1.0 / p.shat;
+        p.scale = (double)(float)(c / (double)kQ8Scale);
     }
+    const double a_wide = inv / p.scale;
+    p.wide = !(a_wide < 1e37);
+    p.a = p.wide ? 0.0f : (float)a_wide;
+    p.b = p.wide ? 0.0f : (float)(p.alpha / p.scale);
     return p;
 }
 
-// What goes into err on top of the measured distance |u_c - decoded copy * scale|.  The identity behind the screen,
-// <u, v> = <u_c, v_c> + alpha_u alpha_v, holds exactly for a unit m and alpha = <m, u>; the stored m and alpha are
-// binary32 roundings of these, so <m, u_c> and |m|^2 - 1 are not zero but below 2^-21 each, and the identity is off by
-// less than (|alpha_u| + |alpha_v| + |alpha_u alpha_v|) 2^-21 < 1.5e-6 for a pair.  The margin (twice 2e-6 for a pair)
-// covers that and the binary32 arithmetic of the similarity kernel's test.
-__device__ __forceinline__ float quantise_error(double se, double nrm)
+// The stored error of a copy from the sum over the block of quantise_chunk's se.  On top of the measured distance
+// sqrt(se) * scale (the factor 1 + 1e-5 covers the binary32 sums) the margin covers: what binary32 loses in
+// quantise_chunk (2.4e-7); the identity behind the centred copies, <u, v> = <u_c, v_c> + alpha_u alpha_v, which holds
+// exactly for a unit m and alpha = <m, u> while the stored m and alpha are binary32 roundings of these, so that
+// <m, u_c> and |m|^2 - 1 are below 2^-21 each and the identity is off by less than
+// (|alpha_u| + |alpha_v| + |alpha_u alpha_v|) 2^-21 < 1.5e-6 for a pair, 0.75e-6 for each of its blocks; and the binary32
+// arithmetic of the similarity kernel's test (a few 1e-7).  A block whose copy could not be written (Q8Block::wide)
+// gets an error that makes every bound vacuous: all its pairs are then evaluated in fp64.
+__device__ __forceinline__ float quantise_error(double se, const Q8Block &p, double nrm)
 {
-    return nrm > 0.0 ? __double2float_ru(sqrt(se) + 2e-6) : 0.0f;
+    if (p.wide)
+        return nrm > 0.0 ? 2.0f : 0.0f;
+    return nrm > 0.0 ? __double2float_ru(sqrt(se) * p.scale * (1.0 + 1e-5) + 3e-6) : 0.0f;
 }
 
 // Nearest-even rounding of a finite double straight to bfloat16 bits (no intermediate binary32 rounding).

@@ -272,21 +272,21 @@ __global__ __launch_bounds__(256) void merge_group_kernel(PoolDesc pool, WorkDes
                 sm = group_sum(sm);
             }
             const Q8Block blk = q8_block(nrm, centred, sm);
-            double se = 0.0;
+            float se32 = 0.0f;
             if (doq) {
                 uint8_t *q = w.q8.k + ((int64_t)g * pool.P + a) * pool.r;
 #pragma unroll
                 for (int c = 0; c < CPT; ++c) {
                     const int ch = tg + GT * c;
                     if (ch < chunks)
-                        quantise_chunk<T>(outp[c], dir_g, ch * PER, blk, q + (size_t)ch * PER, se);
+                        quantise_chunk<T>(outp[c], dir_g, ch * PER, blk, q + (size_t)ch * PER, se32);
                 }
             }
-            se = group_sum(se);
+            const double se = group_sum((double)se32);
             if (doq && tg == 0) {
                 const int64_t b = (int64_t)g * pool.P + a;
-                w.q8.err[b] = quantise_error(se, nrm);
-                w.q8.scale[b] = (float)blk.shat;
+                w.q8.err[b] = quantise_error(se, blk, nrm);
+                w.q8.scale[b] = (float)blk.scale;
                 w.q8.alpha[b] = nrm > 0.0 ? (float)blk.alpha : 0.0f;
             }
         }

@@ -31,13 +31,13 @@ __device__ __forceinline__ void quantise_block(const T *__restrict__ src, double
         sm = wave_sum(sm);
     }
     const Q8Block blk = q8_block(nrm, dir_g != nullptr, sm);
-    double se = 0.0;
+    float se32 = 0.0f;
     for (int c = lane; c < chunks; c += 64)
-        quantise_chunk<T>(p[c], dir_g, c * PER, blk, dst + (size_t)c * PER, se);
-    se = wave_sum(se);
+        quantise_chunk<T>(p[c], dir_g, c * PER, blk, dst + (size_t)c * PER, se32);
+    const double se = wave_sum((double)se32);
     if (lane == 0) {
-        *err_out = quantise_error(se, nrm);
-        *scale_out = (float)blk.shat;
+        *err_out = quantise_error(se, blk, nrm);
+        *scale_out = (float)blk.scale;
         *alpha_out = nrm > 0.0 ? (float)blk.alpha : 0.0f;
     }
 }
@@ -83,13 +83,8 @@ __global__ __launch_bounds__(256) void block_norms_kernel(const T *__restrict__ 
                     for (int i = 0; i < PER; ++i)
                         st = fma(x[i], x[i], st);
                 }
-                if (dir_g) {
-                    double m[PER];
-                    q8_dir_chunk<PER>(dir_g, c * PER, m);
-#pragma unroll
-                    for (int i = 0; i < PER; ++i)
-                        sm = fma(m[i], x[i], sm);
-                }
+                if (dir_g)
+                    q8_dir_dot_chunk<T>(keep[q], dir_g, c * PER, sm);
             }
         }
     } else {
@@ -128,17 +123,17 @@ __global__ __launch_bounds__(256) void block_norms_kernel(const T *__restrict__ 
             if (dir_g)
                 sm = wave_sum(sm);
             const Q8Block blk = q8_block(nrm, dir_g != nullptr, sm);
-            double se = 0.0;
+            float se32 = 0.0f;
 #pragma unroll
             for (int q = 0; q < KEEP; ++q) {
                 const int c = lane + 64 * q;
                 if (c < chunks)
-                    quantise_chunk<T>(keep[q], dir_g, c * PER, blk, q8.k + b * (int64_t)r + (size_t)c * PER, se);
+                    quantise_chunk<T>(keep[q], dir_g, c * PER, blk, q8.k + b * (int64_t)r + (size_t)c * PER, se32);
             }
-            se = wave_sum(se);
+            const double se = wave_sum((double)se32);
             if (lane == 0) {
-                q8.err[b] = quantise_error(se, nrm);
-                q8.scale[b] = (float)blk.shat;
+                q8.err[b] = quantise_error(se, blk, nrm);
+                q8.scale[b] = (float)blk.scale;
                 q8.alpha[b] = nrm > 0.0 ? (float)blk.alpha : 0.0f;
             }
         } else {

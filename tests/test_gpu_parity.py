@@ -434,7 +434,7 @@ def test_fp8_screen_copy_and_bound(kb, oracle, kind, centre):
     loss = np.abs((uc * m[None]).sum(1)) + np.abs(alpha) * abs((m ** 2).sum() - 1.0)
     assert loss.max() < 5e-7
     err_true = np.where(live, err_copy + loss, 0.0)
-    assert (err_gpu >= err_true + np.where(live, 1e-6, 0.0)).all() and (err_gpu <= err_copy + 3e-6).all()
+    assert (err_gpu >= err_true + np.where(live, 2e-6, 0.0)).all() and (err_gpu <= err_copy * (1 + 2e-5) + 4e-6).all()
     assert (err_gpu[~live] == 0).all() and 0.002 < err_gpu[live].mean() < 0.04
     _say("fp8 copy", kind, "centred" if centre else "plain", "mean err", err_gpu[live].mean(), "max err", err_gpu.max(),
          "mean |u_c|", c[live].mean())
