@@ -208,8 +208,10 @@ int kvfuse_rewrite_block_table(kvfuse_ctx *ctx, const kvfuse_pool *pool, const k
 
 /* a1 .. a5 over all heights of the plan.  If stats is not NULL the call synchronises the stream at the end
  * and fills it; want_timing additionally brackets the stages with HIP events on the stream.  With stats the call
- * also reports caller errors found on the device: ids outside [0, P), and a table that shares blocks on entry
- * (fused before, or a prefix cache) -- KVFUSE_EINVAL, the pool and table are then undefined. */
+ * also reports caller errors found on the device: ids outside [0, P), a table that shares blocks on entry
+ * (fused before, or a prefix cache), and key blocks whose norm is not finite or, unless zero, outside [2^-40, 2^40]
+ * (the similarity screen multiplies stored values in binary32; products of such blocks leave its range and a pair
+ * above the threshold could be missed) -- KVFUSE_EINVAL, the pool and table are then undefined. */
 int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band, int32_t *free_list,
                      int32_t *n_free, int32_t *n_phys, kvfuse_stats *stats, int32_t want_timing);
 

@@ -156,7 +156,7 @@ void launch_block_norms(hipStream_t s, const PoolDesc &pool, const TableDesc &ta
                         const Q8Desc *q8 = nullptr);
 // fp8 screen: the direction of every group that its key blocks are centred on (no-op unless one is asked for)
 void launch_centre_direction(hipStream_t s, const PoolDesc &pool, const WorkDesc &w);
-void launch_leaf_sets(hipStream_t s, const WorkDesc &w, const TableDesc &tab, int P, const int32_t *slot_init);
+void launch_leaf_sets(hipStream_t s, const WorkDesc &w, const TableDesc &tab, int P, const int32_t *slot_init, const double *norm_k);
 void launch_similarity(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const HeightDesc &h, float thr_floor,
                        float *dense_s);
 void launch_assign(hipStream_t s, const PoolDesc &pool, const TableDesc &tab, const WorkDesc &w, const HeightDesc &h,

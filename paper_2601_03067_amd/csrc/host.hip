@@ -527,7 +527,7 @@ int kvfuse_leaf_sets(kvfuse_ctx *ctx, kvfuse_plan *plan)
 {
     if (!ctx || !plan)
         return KVFUSE_EINVAL;
-    launch_leaf_sets(ctx->c.stream, plan->p.work, plan->p.tab, plan->p.pool.P, plan->p.slot_init);
+    launch_leaf_sets(ctx->c.stream, plan->p.work, plan->p.tab, plan->p.pool.P, plan->p.slot_init, plan->p.pool.norm_k);
     launch_prefix_tails(ctx->c.stream, plan->p.pool, plan->p.work);          // no-op unless the prefix screen is on
     launch_centre_direction(ctx->c.stream, plan->p.pool, plan->p.work);      // no-ops unless the fp8 screen is on
     launch_quantise_all(ctx->c.stream, plan->p.pool, plan->p.work);
@@ -635,7 +635,7 @@ int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band
     launch_centre_direction(c->stream, p.pool, p.work);                      // no-op unless the fp8 copies are centred
     launch_block_norms(c->stream, p.pool, p.tab, p.work.screen_prefix > 0 ? p.work.rem_k : nullptr, p.work.screen_prefix,
                        p.work.q8.k ? &p.work.q8 : nullptr);
-    launch_leaf_sets(c->stream, p.work, p.tab, p.pool.P, p.slot_init);
+    launch_leaf_sets(c->stream, p.work, p.tab, p.pool.P, p.slot_init, p.pool.norm_k);
     KVF_TRY(mark());
     for (int hgt = 0; hgt < nh; ++hgt) {
         const HeightDesc &d = p.heights[hgt].dev;
@@ -685,7 +685,7 @@ int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band
             targets += x;
         stats->merge_targets = (int32_t)std::min<int64_t>(targets, INT32_MAX);
     }
-    int64_t invalid = 0, shared = 0;
+    int64_t invalid = 0, shared = 0, out_of_range = 0;
     for (int g = 0; g < w.G; ++g) {
         const bool on = p.group_enable_host.empty() || p.group_enable_host[(size_t)g] != 0;
         stats->fused += counters[(size_t)g * 8 + 0];
@@ -694,6 +694,7 @@ int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band
         stats->cand_overflow += counters[(size_t)g * 8 + 3];
         invalid += counters[(size_t)g * 8 + 4];
         shared += counters[(size_t)g * 8 + 5];
+        out_of_range += counters[(size_t)g * 8 + 6];
         for (const Node &nd : p.nodes)
             if (nd.left >= 0 && on)
                 stats->sim_flops += 2.0 * (double)cnt[(size_t)g * w.n_slots + nd.left] *
@@ -708,6 +709,10 @@ int kvfuse_fuse_tree(kvfuse_ctx *ctx, kvfuse_plan *plan, double thr, double band
         return fail(c, KVFUSE_EINVAL, "block table is not injective on entry: " + std::to_string(shared) +
                                           " entries point at a block that another entry of their group holds as well "
                                           "(a table that was fused before, or a prefix cache); the result is undefined");
+    if (out_of_range)
+        return fail(c, KVFUSE_EINVAL, std::to_string(out_of_range) + " key blocks have a norm that is not finite or lies outside "
+                                          "[2^-40, 2^40]: products of such blocks leave binary32's range in the similarity screen "
+                                          "and pairs could be missed; rescale the cache");
     return KVFUSE_OK;
 #undef KVF_TRY
 }

@@ -227,24 +227,32 @@ __global__ void leaf_sets_kernel(WorkDesc w, int P, const int32_t *__restrict__ 
         w.set_cnt[i] = slot_init[i % w.n_slots];
 }
 
-// Caller errors that the tree cannot work with are counted per group: ids outside [0, P) in counters[g][4], and entries
+// Caller errors that the tree cannot work with are counted per group: ids outside [0, P) in counters[g][4], entries
 // whose block is also held by another entry in counters[g][5] (Algorithm 1 starts from unshared blocks: a shared block
-// would sit in several sets of one height and be rewritten by one node while another reads it).  refcount is the
-// count the norm pass has just taken.
-__global__ void check_ids_kernel(WorkDesc w, int P, const int32_t *__restrict__ bt, const int32_t *__restrict__ refcount)
+// would sit in several sets of one height and be rewritten by one node while another reads it), and in counters[g][6]
+// key blocks whose norm is not finite or, unless zero, outside [2^-40, 2^40]: the similarity screen multiplies the
+// stored values in binary32, where products of such blocks underflow or overflow, so that a pair could be missed.
+// refcount is the count the norm pass has just taken.
+__global__ void check_ids_kernel(WorkDesc w, int P, const int32_t *__restrict__ bt, const int32_t *__restrict__ refcount,
+                                 const double *__restrict__ norm_k)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < (int64_t)w.G * w.n) {
         const int p = bt[i];
         const int64_t g = i / w.n;
-        if (p < 0 || p >= P)
+        if (p < 0 || p >= P) {
             atomicAdd(&w.counters[g * 8 + 4], 1);
-        else if (refcount[g * P + p] > 1)
-            atomicAdd(&w.counters[g * 8 + 5], 1);
+        } else {
+            if (refcount[g * P + p] > 1)
+                atomicAdd(&w.counters[g * 8 + 5], 1);
+            const double nk = norm_k[g * P + p];
+            if (nk != 0.0 && !(nk >= 0x1p-40 && nk <= 0x1p40))
+                atomicAdd(&w.counters[g * 8 + 6], 1);
+        }
     }
 }
 
-void launch_leaf_sets(hipStream_t s, const WorkDesc &w, const TableDesc &tab, int P, const int32_t *slot_init)
+void launch_leaf_sets(hipStream_t s, const WorkDesc &w, const TableDesc &tab, int P, const int32_t *slot_init, const double *norm_k)
 {
     int64_t total = (int64_t)w.G * w.n;
     const int64_t ns = (int64_t)w.G * w.n_slots;
@@ -255,7 +263,7 @@ void launch_leaf_sets(hipStream_t s, const WorkDesc &w, const TableDesc &tab, in
     if (total > 0)
         leaf_sets_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(w, P, tab.bt, slot_init);
     if ((int64_t)w.G * w.n > 0)
-        check_ids_kernel<<<(unsigned)(((int64_t)w.G * w.n + 255) / 256), 256, 0, s>>>(w, P, tab.bt, tab.refcount);
+        check_ids_kernel<<<(unsigned)(((int64_t)w.G * w.n + 255) / 256), 256, 0, s>>>(w, P, tab.bt, tab.refcount, norm_k);
 }
 
 // Prefix screen (similarity.hip): rem[b] = |tail of block b| / |block b| for the key blocks, where the tail is everything

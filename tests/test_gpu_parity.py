@@ -980,6 +980,17 @@ def test_bad_arguments_are_reported_not_crashed(kb):
         kb.fuse_tree(ctx, plan3, 0.95)
     assert e.value.code == kb.EINVAL and "not injective" in str(e.value)
     torch.cuda.synchronize()
+    # key blocks whose products would leave binary32's range in the screen (here two copies of one block scaled by 2^-60,
+    # which the fp64 oracle would fuse and a binary32 product cannot see) are reported, not silently mishandled
+    mat4 = wl.materialise(rec, DEV)
+    mat4["K"][0, 5] = mat4["K"][0, 5] * 2.0 ** -60
+    mat4["K"][0, 20] = mat4["K"][0, 5]
+    cache4 = kb.Cache(mat4["K"], mat4["V"], mat4["bt"], rec.t, rec.d)
+    plan4 = kb.Plan(ctx, cache4, kb.tree_spec(rec.leaf_start, rec.leaf_count, rec.unit_leaf_ptr))
+    with pytest.raises(kb.KvfuseError) as e:
+        kb.fuse_tree(ctx, plan4, 0.95)
+    assert e.value.code == kb.EINVAL and "2^-40" in str(e.value)
+    torch.cuda.synchronize()
 
 
 # ------------------------------------------------------------------------------------------ a7 decode attention
