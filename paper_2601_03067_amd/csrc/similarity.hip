@@ -159,6 +159,12 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
     __shared__ __attribute__((aligned(16))) float lds_all[Q8 ? RT * BM : 1];         // Q8: alpha of the left rows
     __shared__ float lds_alr[Q8 ? BN : 1];               // Q8: alpha of the right blocks
     __shared__ float lds_alrs[Q8 ? BN : 1];              // Q8: the same / the block's scale
+    // Largest values over each group of 32 left rows (the rows of one MFMA tile): inverse norm, and what the screens
+    // subtract from the floor.  With them one test settles a whole 32 x 32 tile that holds no candidate.
+    __shared__ float lds_g_inv[RT * BM / 32];
+    __shared__ float lds_g_err[Q8 ? RT * BM / 32 : 1];
+    __shared__ float lds_g_al[Q8 ? RT * BM / 32 : 1];
+    __shared__ float lds_g_rem[PREFIX ? RT * BM / 32 : 1];
     // The column maximum (best_packed) is a diagnostic: the assignment step works from the candidate lists alone.  It
     // is kept only in the instantiation that also writes the dense matrix; in the production one it cost four of
     // the six vector instructions per accumulator in the epilogue, during which the MFMA units of the CU idle.
@@ -331,18 +337,51 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
                 lds_tcolb[x] = (col < mr && ir > 0.0f) ? rem[(int64_t)g * A.P + r_ids[col]] / ir : 0.0f;
         }
     }
+    static_assert((RT * BM) % NT == 0, "every wavefront takes whole groups of 32 rows");
     for (int x = tid; x < RT * BM; x += NT) {
         const int row = row0 + x;
+        float g_inv = 0.0f, g_err = 0.0f, g_al = 0.0f, g_rem = 0.0f;
         if constexpr (Q8) {
             const int64_t id = (int64_t)g * A.P + l_ids[min(row, row_end - 1)];
-            lds_invl[x] = row < row_end ? q8.scale[id] : __uint_as_float(0x7FC00000u);
-            lds_errl[x] = row < row_end ? q8.err[id] : 0.0f;
-            lds_all[x] = row < row_end ? q8.alpha[id] : 0.0f;
+            if (row < row_end) {
+                g_inv = q8.scale[id];
+                g_err = q8.err[id];
+                g_al = q8.alpha[id];
+            }
+            lds_invl[x] = row < row_end ? g_inv : __uint_as_float(0x7FC00000u);
+            lds_errl[x] = g_err;
+            lds_all[x] = g_al;
+            g_al = fabsf(g_al);
         } else {
-            lds_invl[x] = row < row_end ? inv_g[l_ids[row]] : __uint_as_float(0x7FC00000u);
+            if (row < row_end)
+                g_inv = inv_g[l_ids[row]];
+            lds_invl[x] = row < row_end ? g_inv : __uint_as_float(0x7FC00000u);
         }
-        if constexpr (PREFIX)
-            lds_reml[x] = row < row_end ? rem[(int64_t)g * A.P + l_ids[row]] : 0.0f;
+        if constexpr (PREFIX) {
+            if (row < row_end)
+                g_rem = rem[(int64_t)g * A.P + l_ids[row]];
+            lds_reml[x] = g_rem;
+        }
+        // maxima over the 32 rows that this half of the wavefront holds
+#pragma unroll
+        for (int off = 16; off >= 1; off >>= 1) {
+            g_inv = fmaxf(g_inv, __shfl_xor(g_inv, off, 64));
+            if constexpr (Q8) {
+                g_err = fmaxf(g_err, __shfl_xor(g_err, off, 64));
+                g_al = fmaxf(g_al, __shfl_xor(g_al, off, 64));
+            }
+            if constexpr (PREFIX)
+                g_rem = fmaxf(g_rem, __shfl_xor(g_rem, off, 64));
+        }
+        if ((x & 31) == 0) {
+            lds_g_inv[x >> 5] = g_inv;
+            if constexpr (Q8) {
+                lds_g_err[x >> 5] = g_err;
+                lds_g_al[x >> 5] = g_al;
+            }
+            if constexpr (PREFIX)
+                lds_g_rem[x >> 5] = g_rem;
+        }
     }
     if constexpr (BEST) {
 #pragma unroll
@@ -545,7 +584,37 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
                 alrs[nt] = Q8 ? lds_alrs[nt * NT_STRIDE + wn * 32 + (lane & 31)] : 0.0f;
             }
 #pragma unroll
-            for (int mt = 0; mt < TM; ++mt)
+            for (int mt = 0; mt < TM; ++mt) {
+                // One test per 32 x 32 tile first: no entry of this lane's column can clear its floor if the largest
+                // accumulator (or 0) times the largest inverse norm of the 32 rows stays below the floor lowered by
+                // the largest corrections of the 32 rows.  Candidates are rare, so this is all most tiles cost.
+                bool look[TN];
+                bool any_look = false;
+                {
+                    const int grp = (rt * BM + mt * MT_STRIDE + wm * 32) >> 5;
+                    const float gi = lds_g_inv[grp];
+                    const float ge = Q8 ? lds_g_err[grp] : 0.0f, ga = Q8 ? lds_g_al[grp] : 0.0f;
+                    const float gr = PREFIX ? lds_g_rem[grp] : 0.0f;
+#pragma unroll
+                    for (int nt = 0; nt < TN; ++nt) {
+                        float mx = 0.0f;
+#pragma unroll
+                        for (int e = 0; e < 16; e += 2)
+                            mx = fmaxf(fmaxf(acc[mt][nt][e], acc[mt][nt][e + 1]), mx);
+                        float low = tcol[nt];
+                        if constexpr (Q8) {
+                            low = fmaf(-ge, c1[nt], low);
+                            low = fmaf(-ga, fabsf(alrs[nt]), low);
+                        }
+                        if constexpr (PREFIX)
+                            low = fmaf(-gr, tcolb[nt], low);
+                        // (the binary32 roundings of this line and of the exact test differ by parts in 10^7; the factor
+                        // covers them, and the floor sits a whole band below anything that has to be listed)
+                        look[nt] = DENSE || !(mx * gi * (1.0f + 1e-6f) < low);      // (the diagnostic instance looks at everything)
+                        any_look |= look[nt];
+                    }
+                }
+                if (any_look) {
 #pragma unroll
                 for (int eg = 0; eg < 4; ++eg) {
                     const int rl0 = mt * MT_STRIDE + wm * 32 + eg * 8 + half * 4;
@@ -565,6 +634,8 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
                     }
 #pragma unroll
                     for (int nt = 0; nt < TN; ++nt) {
+                        if (!look[nt])
+                            continue;
                         float t[4], lim[4];
                         bool hit = false;
 #pragma unroll
@@ -606,8 +677,10 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
                                 }
                         }
                     }
-                    __builtin_amdgcn_sched_barrier(0);
                 }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
             if constexpr (DENSE) {
 #pragma unroll
                 for (int mt = 0; mt < TM; ++mt)
