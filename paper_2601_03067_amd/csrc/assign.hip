@@ -639,24 +639,35 @@ __global__ __launch_bounds__(256) void assign_finalize_kernel(int P, TableDesc t
     }
     __syncthreads();
 
-    // 2. segment offsets (exclusive scan) and the merge work list
+    // 2. segment offsets (exclusive scan) and the merge work list.  The node's targets get consecutive slots of the
+    // height's list: they are counted first, so that one atomic reserves them all (a reservation per 256 rows cost a
+    // round trip to memory each).
+    int n_targets = 0;
+    for (int i = tid; i < ml; i += 256)
+        n_targets += ld_relaxed(&seg_cnt[i]) > 0;
+    {
+        int64_t total;
+        (void)block_exscan_256((int64_t)n_targets, lds4, total);
+        if (tid == 0)
+            lds_base = total > 0 ? atomicAdd(&w.n_active[height], (int)total) : 0;
+        __syncthreads();
+    }
+    const int slot_base = lds_base;
     int64_t run = 0;
+    int slots = 0;
     for (int i0 = 0; i0 < ml; i0 += 256) {
         const int i = i0 + tid;
         const int cnt = i < ml ? ld_relaxed(&seg_cnt[i]) : 0;
         int64_t total;
         const int64_t pre = block_exscan_256(((int64_t)(cnt > 0) << 40) | (int64_t)cnt, lds4, total);
-        const int n_act = (int)(total >> 40);
-        if (tid == 0)
-            lds_base = n_act > 0 ? atomicAdd(&w.n_active[height], n_act) : 0;
-        __syncthreads();
         if (i < ml) {
             const int start = (int)(run + (pre & 0xFFFFFFFFFFll));
             seg_ptr[i] = start;
             if (cnt > 0)
-                seg_slot[i] = lds_base + (int)(pre >> 40);
+                seg_slot[i] = slot_base + slots + (int)(pre >> 40);
         }
         run += total & 0xFFFFFFFFFFll;
+        slots += (int)(total >> 40);
         __syncthreads();
     }
 
