@@ -405,6 +405,9 @@ def main():
                     help="run the timed steps with the fp8 screen (similarity over one-byte copies of the key blocks + error bound)")
     ap.add_argument("--centre", action="store_true",
                     help="with --screen-fp8: take each group's common key direction out of the one-byte copies first")
+    ap.add_argument("--common-direction", action="store_true",
+                    help="after the timed steps, also run the full product and the fp8 screen (plain and centred copies) on keys "
+                         "that share a direction (field fp8_screen.keys_with_a_common_direction; a few seconds)")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
     ap.add_argument("--per-height", action="store_true",
                     help="after the timed steps, run one more fusion height by height and add a per-height table of the "
@@ -700,31 +703,33 @@ def main():
         cerr = plan.k8_err[plan.k8_err > 0]
         fp8_screen["centred"] = brief(cst, tables_and_fused_keys_equal_to_full_screen=same_c,
                                       copy_error_mean=float(cerr.mean()) if cerr.numel() else 0.0)
-        # ... and all three screens on keys that do share one: every key block of a group gets the same random offset of
-        # 2.35 times the keys' own spread, which puts unrelated blocks at a cosine of about 0.85: within the plain copies'
-        # error bound (0.054 for a pair) of the threshold 0.9, outside that of the centred ones (0.02).  Still closer to
-        # the threshold (0.87 and up) the centred copies overflow their lists as well and only the full product is fast.
         del k_ref
-        gen = torch.Generator(device="cpu")
-        gen.manual_seed(2601)
-        mu = (2.35 * torch.randn(rec.G, 1, rec.r, generator=gen)).to(dev)
-        k_common = torch.empty_like(K0)
-        for g0 in range(0, rec.G, 16):
-            k_common[g0:g0 + 16] = (K0[g0:g0 + 16].float() + mu[g0:g0 + 16]).to(K0.dtype)
-        common = {"recipe": "every key block of group g + 2.35 * N(0, 1)[t * d] drawn once per group"}
-        kb.set_screen_fp8(ctx, plan, False)
-        fst = timed_fuse(k_common)
-        bt_c, k_c = cache.bt.clone(), cache.K.clone()
-        common["full_product"] = brief(fst)
-        for name, centre in (("fp8_copies", False), ("fp8_copies_centred", True)):
-            kb.set_screen_fp8(ctx, plan, centre=centre)
-            xst = timed_fuse(k_common, runs=2)
-            xerr = plan.k8_err[plan.k8_err > 0]
-            common[name] = brief(xst, copy_error_mean=float(xerr.mean()) if xerr.numel() else 0.0,
-                                 tables_and_fused_keys_equal_to_full_screen=bool(torch.equal(cache.bt, bt_c)) and
-                                 bool(torch.equal(cache.K, k_c)) and xst.fused == fst.fused)
-        fp8_screen["keys_with_a_common_direction"] = common
-        del bt_ref, bt_c, k_c, k_common, mu
+        if args.common_direction:
+            # ... and all three screens on keys that do share one: every key block of a group gets the same random offset of
+            # 2.35 times the keys' own spread, which puts unrelated blocks at a cosine of about 0.85: within the plain copies'
+            # error bound (0.054 for a pair) of the threshold 0.9, outside that of the centred ones (0.02).  Still closer to
+            # the threshold (0.87 and up) the centred copies overflow their lists as well and only the full product is fast.
+            gen = torch.Generator(device="cpu")
+            gen.manual_seed(2601)
+            mu = (2.35 * torch.randn(rec.G, 1, rec.r, generator=gen)).to(dev)
+            k_common = torch.empty_like(K0)
+            for g0 in range(0, rec.G, 16):
+                k_common[g0:g0 + 16] = (K0[g0:g0 + 16].float() + mu[g0:g0 + 16]).to(K0.dtype)
+            common = {"recipe": "every key block of group g + 2.35 * N(0, 1)[t * d] drawn once per group"}
+            kb.set_screen_fp8(ctx, plan, False)
+            fst = timed_fuse(k_common)
+            bt_c, k_c = cache.bt.clone(), cache.K.clone()
+            common["full_product"] = brief(fst)
+            for name, centre in (("fp8_copies", False), ("fp8_copies_centred", True)):
+                kb.set_screen_fp8(ctx, plan, centre=centre)
+                xst = timed_fuse(k_common, runs=2)
+                xerr = plan.k8_err[plan.k8_err > 0]
+                common[name] = brief(xst, copy_error_mean=float(xerr.mean()) if xerr.numel() else 0.0,
+                                     tables_and_fused_keys_equal_to_full_screen=bool(torch.equal(cache.bt, bt_c)) and
+                                     bool(torch.equal(cache.K, k_c)) and xst.fused == fst.fused)
+            fp8_screen["keys_with_a_common_direction"] = common
+            del bt_c, k_c, k_common, mu
+        del bt_ref
         kb.set_screen_fp8(ctx, plan, False)
 
     # The same step (fusion without the statistics read-back + decode) recorded once in a HIP graph on a stream of
