@@ -584,28 +584,6 @@ __global__ __launch_bounds__(256) void assign_q8_fill_kernel(PoolDesc pool, Work
     }
 }
 
-// Exclusive scan of one int64 per thread over a 256-thread workgroup; returns the exclusive prefix and the total.
-__device__ __forceinline__ int64_t block_exscan_256(int64_t x, int64_t *lds4, int64_t &total)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int64_t inc = x;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int64_t y = __shfl_up(inc, off, 64);
-        if (lane >= off)
-            inc += y;
-    }
-    __syncthreads();
-    if (lane == 63)
-        lds4[wave] = inc;
-    __syncthreads();
-    int64_t pre = 0;
-    for (int k = 0; k < wave; ++k)
-        pre += lds4[k];
-    total = lds4[0] + lds4[1] + lds4[2] + lds4[3];
-    return pre + inc - x;
-}
-
 __device__ __forceinline__ int ld_relaxed(const int32_t *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -44,13 +44,6 @@ struct kvfuse_ctx {
 
 namespace kvfuse {
 
-// Work items of the similarity launch of one height (device arrays, identical for every group): item k covers
-// right blocks [col0, col0 + BN) x left blocks [row0, row0 + rows) of node `node`.
-struct TileTable {
-    int32_t n_items;
-    const int32_t *node, *col0, *row0, *rows;
-};
-
 // Tables of one tree height, all device pointers into the plan workspace (identical for every group).
 struct HeightDesc {
     int32_t n_nodes;
@@ -58,7 +51,7 @@ struct HeightDesc {
     const int32_t *l_off, *r_off, *l_slot, *r_slot, *out_slot, *l_cap, *r_cap;
     const int32_t *l_base, *r_base;   // [n_nodes + 1] prefix sums of the capacities
     const int64_t *s_base;            // [n_nodes + 1] prefix sums of l_cap * r_cap
-    TileTable big, small;             // only the one selected by use_big_tiles is filled
+    int32_t item_cap;                 // most similarity work items one group can have at this height (see similarity.hip)
     bool use_big_tiles;
     int64_t total_s;
 };
@@ -102,6 +95,11 @@ struct WorkDesc {
     int32_t *leaf_src;   // [n] position in a set_ids row -> logical entry the leaf step fills it from, -1 = none
     float *rem_k;        // [G][P] prefix screen: share of each key block's norm that lies beyond the prefix, rounded up
     int32_t screen_prefix;   // elements of every block the similarity screen multiplies; 0 = the whole block
+    // similarity work items of the current height, built on the device from the sets' sizes (similarity.hip):
+    int4 *dyn_items;     // [G][item_cap of the height] node, first column, first row, rows
+    int32_t *dyn_base;   // [G][dyn_stride] first item of every node, and the total
+    int32_t *dyn_count;  // [G]
+    int32_t dyn_stride;
     Q8Desc q8;           // fp8 screen: the one-byte copies of the key blocks and what goes with them; q8.k null = off
 };
 
@@ -232,6 +230,28 @@ __device__ __forceinline__ double block_sum_256(double x, double *lds4)
         lds4[threadIdx.x >> 6] = x;
     __syncthreads();
     return ((lds4[0] + lds4[1]) + lds4[2]) + lds4[3];
+}
+
+// Exclusive scan of one int64 per thread over a 256-thread workgroup; returns the exclusive prefix and the total.
+__device__ __forceinline__ int64_t block_exscan_256(int64_t x, int64_t *lds4, int64_t &total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int64_t inc = x;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int64_t y = __shfl_up(inc, off, 64);
+        if (lane >= off)
+            inc += y;
+    }
+    __syncthreads();
+    if (lane == 63)
+        lds4[wave] = inc;
+    __syncthreads();
+    int64_t pre = 0;
+    for (int k = 0; k < wave; ++k)
+        pre += lds4[k];
+    total = lds4[0] + lds4[1] + lds4[2] + lds4[3];
+    return pre + inc - x;
 }
 
 // Prefix screen: share of a block's norm that lies beyond the prefix, from the sum of the tail squares and the norm,

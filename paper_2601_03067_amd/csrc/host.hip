@@ -31,7 +31,7 @@ struct Node {
 
 struct HostHeight {
     std::vector<int32_t> l_off, r_off, l_slot, r_slot, out_slot, l_cap, r_cap, l_base, r_base;
-    std::vector<int32_t> it_node, it_col0, it_row0, it_rows;   // similarity work items
+    int item_cap = 0;                                          // most similarity work items of one group
     bool big = false;
     std::vector<int64_t> s_base;
     HeightDesc dev;
@@ -204,26 +204,16 @@ static void build_heights(const std::vector<Node> &nodes, std::vector<HostHeight
         }
         h.big = wsum > 0.0 && wmin / wsum >= 256.0;
         const int bm = h.big ? kBigM : kSmallM, bn = h.big ? kBigN : kSmallN;
-        // Work items in patch order: 8 panels x all row chunks of a node are consecutive, so that the workgroups
-        // resident on one XCD at a time share left tiles and right panels in its L2.
+        // Room for the similarity work items of one group.  The items themselves are laid out on the device from the
+        // sets' current sizes (similarity.hip); a node whose left set spans a row tiles and whose right set c panels has
+        // c * ceil(a / min(ceil(a / 4), 4)) of them, which for a up to A is at most c * (A < 4 ? A : max(4, ceil(A / 4))).
+        int64_t cap = 0;
         for (int k = 0; k < nn; ++k) {
             const int n_cp = (h.r_cap[k] + bn - 1) / bn;
             const int n_rtile = (h.l_cap[k] + bm - 1) / bm;
-            if (n_cp == 0 || n_rtile == 0)
-                continue;
-            // row tiles per work item: about 4 chunks per panel; the kernel keeps the row ids of one item in registers
-            // and takes at most 4 row tiles per item
-            const int rt = std::min((n_rtile + 3) / 4, 4);
-            const int n_rc = (n_rtile + rt - 1) / rt;
-            for (int cpg = 0; cpg < n_cp; cpg += 8)
-                for (int rc = 0; rc < n_rc; ++rc)
-                    for (int cp = cpg; cp < std::min(cpg + 8, n_cp); ++cp) {
-                        h.it_node.push_back(k);
-                        h.it_col0.push_back(cp * bn);
-                        h.it_row0.push_back(rc * rt * bm);
-                        h.it_rows.push_back(rt * bm);
-                    }
+            cap += (int64_t)n_cp * (n_rtile < 4 ? n_rtile : std::max(4, (n_rtile + 3) / 4));
         }
+        h.item_cap = (int)std::min<int64_t>(cap, INT32_MAX);
     }
 }
 
@@ -269,6 +259,17 @@ static void carve(Carver &cv, int G, int n, int n_slots, int max_r, int max_l, i
     w.screen_prefix = 0;
     w.q8 = Q8Desc{};
     slot_init = cv.take<int32_t>(n_slots);
+    {
+        size_t items = 1, nodes = 1;
+        for (const HostHeight &h : hs) {
+            items = std::max(items, (size_t)h.item_cap);
+            nodes = std::max(nodes, h.l_off.size());
+        }
+        w.dyn_stride = (int32_t)(nodes + 1);
+        w.dyn_items = cv.take<int4>((size_t)G * items);
+        w.dyn_base = cv.take<int32_t>((size_t)G * w.dyn_stride);
+        w.dyn_count = cv.take<int32_t>((size_t)G);
+    }
     for (HostHeight &h : hs) {
         const size_t nn = h.l_off.size();
         HeightDesc &d = h.dev;
@@ -277,13 +278,7 @@ static void carve(Carver &cv, int G, int n, int n_slots, int max_r, int max_l, i
         d.total_r_cap = h.r_base[nn];
         d.total_s = h.s_base[nn];
         d.use_big_tiles = h.big;
-        TileTable tt;
-        tt.n_items = (int)h.it_node.size();
-        tt.node = cv.take<int32_t>(h.it_node.size());
-        tt.col0 = cv.take<int32_t>(h.it_col0.size());
-        tt.row0 = cv.take<int32_t>(h.it_row0.size());
-        tt.rows = cv.take<int32_t>(h.it_rows.size());
-        d.big = d.small = tt;
+        d.item_cap = h.item_cap;
         d.l_off = cv.take<int32_t>(nn);
         d.r_off = cv.take<int32_t>(nn);
         d.l_slot = cv.take<int32_t>(nn);
@@ -466,10 +461,6 @@ int kvfuse_plan_create(kvfuse_ctx *ctx, const kvfuse_pool *pool, const kvfuse_ta
         if (e == hipSuccess) e = upload(c->stream, d.l_base, h.l_base);
         if (e == hipSuccess) e = upload(c->stream, d.r_base, h.r_base);
         if (e == hipSuccess) e = upload(c->stream, d.s_base, h.s_base);
-        if (e == hipSuccess) e = upload(c->stream, d.big.node, h.it_node);
-        if (e == hipSuccess) e = upload(c->stream, d.big.col0, h.it_col0);
-        if (e == hipSuccess) e = upload(c->stream, d.big.row0, h.it_row0);
-        if (e == hipSuccess) e = upload(c->stream, d.big.rows, h.it_rows);
     }
     if (e == hipSuccess)
         e = hipStreamSynchronize(c->stream);   // the host vectors may now be reused or freed

@@ -126,8 +126,8 @@ constexpr int kRingRowTiles = 4;   // most row tiles of one work item (the host'
 template <typename T, bool BIG, bool DENSE, bool PREFIX>
 __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_kernel(
     SimArgs A, const char *__restrict__ kpool, const float *__restrict__ inv_norm, const int32_t *__restrict__ set_ids,
-    const int32_t *__restrict__ set_cnt, const int32_t *__restrict__ item_node, const int32_t *__restrict__ item_col0,
-    const int32_t *__restrict__ item_row0, const int32_t *__restrict__ item_rows, const int32_t *__restrict__ l_off,
+    const int32_t *__restrict__ set_cnt, const int4 *__restrict__ dyn_items, const int32_t *__restrict__ dyn_count,
+    const int32_t *__restrict__ l_off,
     const int32_t *__restrict__ r_off, const int32_t *__restrict__ l_slot, const int32_t *__restrict__ r_slot,
     const int32_t *__restrict__ r_base, const int32_t *__restrict__ r_cap, const int64_t *__restrict__ s_base,
     unsigned long long *__restrict__ best_packed, int32_t *__restrict__ cand_cnt, int32_t *__restrict__ cand_idx,
@@ -185,14 +185,17 @@ __global__ __launch_bounds__(BIG ? 512 : 256, BIG ? 1 : 2) void similarity_ring_
     if (group_enable && !group_enable[g])      // a switched-off group keeps empty candidate lists: nothing fuses
         return;
     const int item = (int)(v - (long long)g * A.n_items);
-    const int node = item_node[item];
-    const int col0 = item_col0[item];
-    const int row0 = item_row0[item];
+    if (item >= dyn_count[g])
+        return;
+    const int4 it_rec = dyn_items[(int64_t)g * A.n_items + item];
+    const int node = it_rec.x;
+    const int col0 = it_rec.y;
+    const int row0 = it_rec.z;
     const int ml = set_cnt[(int64_t)g * A.n_slots + l_slot[node]];
     const int mr = set_cnt[(int64_t)g * A.n_slots + r_slot[node]];
     if (col0 >= mr || row0 >= ml)
         return;
-    const int row_end = min(ml, row0 + min(item_rows[item], RT * BM));
+    const int row_end = min(ml, row0 + min(it_rec.w, RT * BM));
     const int32_t *__restrict__ l_ids = set_ids + (int64_t)g * A.n + l_off[node];
     const int32_t *__restrict__ r_ids = set_ids + (int64_t)g * A.n + r_off[node];
     const int64_t cbase = (int64_t)g * A.r_stride + r_base[node];
@@ -771,16 +774,97 @@ __global__ void similarity_clear_kernel(unsigned long long *__restrict__ best_pa
     }
 }
 
-template <typename T, bool BIG>
-static void launch_ring(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const HeightDesc &h, const TileTable &tt,
-                        float thr_floor, float *dense_s)
+// The work items of a height, laid out from the sizes the sets have NOW (they shrink as blocks fuse; the plan only knows
+// their capacities).  An item covers one panel of BN right blocks x up to 4 row tiles of BM left blocks of a node: a node
+// with c panels and a row tiles is cut into row chunks of rt = min(ceil(a / 4), 4) tiles, and its items are ordered in
+// patches of 8 panels x all row chunks, row chunk by row chunk within a patch.  The 32 workgroups that an XCD runs at a
+// time are then one patch (or what is left of a node and the start of the next): they start together, do equal work,
+// and share 8 panels and at most 4 row chunks in that XCD's L2.  Laid out from the capacities instead, a third of the
+// items of an upper height had nothing to do, ended at once and let the patches of an XCD drift apart.
+__device__ __forceinline__ int items_of_node(int ml, int mr, int bm, int bn, int &n_cp, int &rt, int &n_rc)
 {
-    const int64_t total = (int64_t)w.G * tt.n_items;
+    n_cp = (mr + bn - 1) / bn;
+    const int n_rtile = (ml + bm - 1) / bm;
+    rt = min((n_rtile + 3) / 4, 4);
+
+    n_rc = rt > 0 ? (n_rtile + rt - 1) / rt : 0;
+    return n_cp * n_rc;
+}
+
+// First item of every node of a group (exclusive scan over the nodes) and the group's number of items.
+__global__ __launch_bounds__(256) void items_count_kernel(WorkDesc w, HeightDesc h, int bm, int bn)
+{
+    __shared__ int64_t lds4[4];
+    const int g = blockIdx.x, tid = threadIdx.x;
+    int32_t *base = w.dyn_base + (int64_t)g * w.dyn_stride;
+    int64_t run = 0;
+    for (int k0 = 0; k0 < h.n_nodes; k0 += 256) {
+        const int k = k0 + tid;
+        int c = 0;
+        if (k < h.n_nodes) {
+            int n_cp, rt, n_rc;
+            c = items_of_node(w.set_cnt[(int64_t)g * w.n_slots + h.l_slot[k]], w.set_cnt[(int64_t)g * w.n_slots + h.r_slot[k]], bm, bn,
+                              n_cp, rt, n_rc);
+        }
+        int64_t total;
+        const int64_t pre = block_exscan_256((int64_t)c, lds4, total);
+        if (k < h.n_nodes)
+            base[k] = (int)min(run + pre, (int64_t)h.item_cap);
+        run += total;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        base[h.n_nodes] = (int)min(run, (int64_t)h.item_cap);
+        w.dyn_count[g] = (int)min(run, (int64_t)h.item_cap);      // (never more than the room: see the plan's bound)
+    }
+}
+
+// One thread per item slot: which node it falls into, and which panel and row chunk of that node it is.
+__global__ __launch_bounds__(256) void items_fill_kernel(WorkDesc w, HeightDesc h, int bm, int bn)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (int64_t)w.G * h.item_cap)
+        return;
+    const int g = (int)(i / h.item_cap);
+    const int item = (int)(i - (int64_t)g * h.item_cap);
+    if (item >= w.dyn_count[g])
+        return;
+    const int32_t *base = w.dyn_base + (int64_t)g * w.dyn_stride;
+    int lo = 0, hi = h.n_nodes;             // the last node whose first item is <= item (empty nodes share a first item
+    while (hi - lo > 1) {                   // with their successor and are skipped by taking the last)
+        const int mid = (lo + hi) >> 1;
+        if (base[mid] <= item)
+            lo = mid;
+        else
+            hi = mid;
+    }
+    const int k = lo;
+    int n_cp, rt, n_rc;
+    (void)items_of_node(w.set_cnt[(int64_t)g * w.n_slots + h.l_slot[k]], w.set_cnt[(int64_t)g * w.n_slots + h.r_slot[k]], bm, bn, n_cp,
+                        rt, n_rc);
+    const int local = item - base[k];
+    const int patch = local / (8 * n_rc);
+    const int within = local - patch * 8 * n_rc;
+    const int np = min(8, n_cp - 8 * patch);
+    const int rc = within / np;
+    const int cp = 8 * patch + within - rc * np;
+    w.dyn_items[(int64_t)g * h.item_cap + item] = make_int4(k, cp * bn, rc * rt * bm, rt * bm);
+}
+
+template <typename T, bool BIG>
+static void launch_ring(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, const HeightDesc &h, float thr_floor, float *dense_s)
+{
+    const int64_t total = (int64_t)w.G * h.item_cap;
     if (total <= 0)
         return;
+    {
+        const int bm = BIG ? 256 : 128;
+        items_count_kernel<<<w.G, 256, 0, s>>>(w, h, bm, bm);
+        items_fill_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(w, h, bm, bm);
+    }
     SimArgs A;
     A.G = w.G; A.n = w.n; A.n_slots = w.n_slots; A.r_stride = w.r_stride; A.cand_cap = w.cand_cap; A.P = pool.P;
-    A.n_items = tt.n_items;
+    A.n_items = h.item_cap;
     A.row_bytes = pool.r * (int)sizeof(T);
     const bool prefix = !dense_s && w.screen_prefix > 0 && w.screen_prefix < pool.r;
     const char *kpool = std::is_same<T, fp8_t>::value ? (const char *)w.q8.k : (const char *)pool.k;
@@ -790,7 +874,7 @@ static void launch_ring(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, 
     const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
 #define KVF_SIM_LAUNCH(D, PF)                                                                                          \
     similarity_ring_kernel<T, BIG, D, PF><<<grid, BIG ? 512 : 256, 0, s>>>(                                                             \
-        A, kpool, pool.inv_norm_k, w.set_ids, w.set_cnt, tt.node, tt.col0, tt.row0, tt.rows, h.l_off, h.r_off, \
+        A, kpool, pool.inv_norm_k, w.set_ids, w.set_cnt, w.dyn_items, w.dyn_count, h.l_off, h.r_off, \
         h.l_slot, h.r_slot, h.r_base, h.r_cap, h.s_base, w.best_packed, w.cand_cnt, w.cand_idx, w.cand_val, dense_s,           \
         w.group_enable, w.rem_k, w.q8)
     if (dense_s)
@@ -812,19 +896,19 @@ void launch_similarity(hipStream_t s, const PoolDesc &pool, const WorkDesc &w, c
     const bool big = h.use_big_tiles;
     if (w.q8.k) {
         if (big)
-            launch_ring<fp8_t, true>(s, pool, w, h, h.big, thr_floor, dense_s);
+            launch_ring<fp8_t, true>(s, pool, w, h, thr_floor, dense_s);
         else
-            launch_ring<fp8_t, false>(s, pool, w, h, h.small, thr_floor, dense_s);
+            launch_ring<fp8_t, false>(s, pool, w, h, thr_floor, dense_s);
     } else if (pool.dtype == KVFUSE_BF16) {
         if (big)
-            launch_ring<bf16_t, true>(s, pool, w, h, h.big, thr_floor, dense_s);
+            launch_ring<bf16_t, true>(s, pool, w, h, thr_floor, dense_s);
         else
-            launch_ring<bf16_t, false>(s, pool, w, h, h.small, thr_floor, dense_s);
+            launch_ring<bf16_t, false>(s, pool, w, h, thr_floor, dense_s);
     } else {
         if (big)
-            launch_ring<float, true>(s, pool, w, h, h.big, thr_floor, dense_s);
+            launch_ring<float, true>(s, pool, w, h, thr_floor, dense_s);
         else
-            launch_ring<float, false>(s, pool, w, h, h.small, thr_floor, dense_s);
+            launch_ring<float, false>(s, pool, w, h, thr_floor, dense_s);
     }
 }
 
