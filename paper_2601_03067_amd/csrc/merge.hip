@@ -73,7 +73,7 @@ __device__ __forceinline__ int find_base(const int32_t *__restrict__ base, int n
 // Q8 (fp8 screen on): the rebuilt key block's one-byte copy and its error are written here as well, from the rounded
 // values this kernel has just stored.
 template <typename T, int CPT, int GW, bool Q8>
-__global__ __launch_bounds__(256) void merge_group_kernel(PoolDesc pool, WorkDesc w, HeightDesc h, int height)
+__global__ __launch_bounds__(256, 3) void merge_group_kernel(PoolDesc pool, WorkDesc w, HeightDesc h, int height)
 {
     constexpr int PER = Elem<T>::PER16;
     constexpr int GT = 64 * GW;          // threads per item
