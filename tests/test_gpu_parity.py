@@ -249,6 +249,15 @@ def test_tree_small_bf16_bff(kb, oracle, cand_cap):
     _run_tree_case(kb, oracle, _small_bf16(), "small_bf16_bff", cand_cap=cand_cap)
 
 
+def test_tree_many_short_requests(kb, oracle):
+    """600 requests of 3 blocks: 300 nodes at the lowest height, more than one workgroup's worth of nodes in the kernels
+    that lay out the similarity work items of a height, 10 heights, and sets that stay far below their capacities."""
+    rec = wl.llama8b_bff(n_req=600, tokens=8 * 3, layers=1, kv_heads=2, prefix_tokens=8, near_pool=40, near_frac=0.5, t=8, d=32,
+                         dtype=torch.bfloat16, seed=77)
+    cache, plan, stats, res, mat = _run_tree_case(kb, oracle, rec, "bff_600_short_requests")
+    assert plan.n_heights == 10 and stats.fused > 1000
+
+
 def test_tree_seven_requests_non_power_of_two(kb, oracle):
     _run_tree_case(kb, oracle, _small_bf16(n_req=7, tokens=520, kv_heads=2), "bff_7_requests")
 
