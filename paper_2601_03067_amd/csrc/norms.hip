@@ -11,8 +11,9 @@ namespace kvfuse {
 // u = x / |x|: alpha = <m, u> rounded to binary32 (0 without a direction m), u_c = u - alpha m, the copy holds
 // e4m3(u_c * kQ8Scale / |u_c|) element by element, and err bounds what the similarity kernel's value
 // <copy_a, copy_b> scale_a scale_b + alpha_a alpha_b can miss of the cosine: the Euclidean distance between u_c and the
-// decoded copy (fp64, with the hardware's own decode, the one the matrix cores apply), plus what the rounding of alpha
-// and of m's norm take from the identity <u, v> = <u_c, v_c> + alpha_u alpha_v, rounded up with a margin.  Taking the
+// decoded copy (measured on the bytes written, with the hardware's own decode, the one the matrix cores apply), plus a
+// margin for the binary32 arithmetic of the measurement and for what the rounding of alpha and of m's norm take from
+// the identity <u, v> = <u_c, v_c> + alpha_u alpha_v (quantise_error in common.h), rounded up.  Taking the
 // common direction out first matters when unrelated blocks share one: the copies then spend their eight bits on what
 // tells the blocks apart.  One wavefront per block.  A block of norm 0 becomes zeros with err 0 (its cosines are 0 by
 // definition).
