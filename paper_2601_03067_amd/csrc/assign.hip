@@ -87,6 +87,56 @@ __device__ __forceinline__ double cosine_f64_reg(const T *__restrict__ pool_g, i
     return (na == 0.0 || nb == 0.0) ? 0.0 : dot / (na * nb);
 }
 
+// KW such cosines side by side (rows a[0 .. n), n the same in every lane): the blocks of all rows are on their way
+// together and the chains of fused multiply-adds are independent of each other, where one row after the other left a
+// wavefront waiting on one load and one chain at a time.  Each cosine is built by the operations of cosine_f64_reg in
+// their order, so the values are bit-identical to it.
+template <typename T, int CPL, int KW>
+__device__ __forceinline__ void cosines_f64_reg(const T *__restrict__ pool_g, int r, const double *__restrict__ norm_g,
+                                                const int (&a)[KW], int n, const uint4 *braw, double nb, int lane, double (&cs)[KW])
+{
+    const int chunks = r / Elem<T>::PER16;
+    uint4 araw[KW][CPL];
+    double na[KW], dot[KW];
+#pragma unroll
+    for (int k = 0; k < KW; ++k) {
+        dot[k] = 0.0;
+        na[k] = 0.0;
+        if (k < n) {
+            na[k] = norm_g[a[k]];
+            const uint4 *pa = reinterpret_cast<const uint4 *>(pool_g + (int64_t)a[k] * r);
+#pragma unroll
+            for (int c = 0; c < CPL; ++c)
+                araw[k][c] = pa[min(lane + 64 * c, chunks - 1)];
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        if (lane + 64 * c < chunks) {
+            double y[Elem<T>::PER16];
+            Elem<T>::widen(braw[c], y);
+#pragma unroll
+            for (int k = 0; k < KW; ++k) {
+                if (k < n) {
+                    double x[Elem<T>::PER16];
+                    Elem<T>::widen(araw[k][c], x);
+#pragma unroll
+                    for (int i = 0; i < Elem<T>::PER16; ++i)
+                        dot[k] = fma(x[i], y[i], dot[k]);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < KW; ++k) {
+        cs[k] = 0.0;
+        if (k < n) {
+            dot[k] = wave_sum(dot[k]);
+            cs[k] = (na[k] == 0.0 || nb == 0.0) ? 0.0 : dot[k] / (na[k] * nb);
+        }
+    }
+}
+
 __global__ void assign_reset_kernel(WorkDesc w, int height)
 {
     w.n_active[height] = 0;   // the finalize kernel appends to this list
@@ -244,6 +294,7 @@ template <typename T, int CPL>
 __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkDesc w, HeightDesc h, int height, double thr,
                                                             double band, int rule, int bound)
 {
+    constexpr int KW = CPL >= 8 ? 2 : 4;       // left rows multiplied side by side (cosines_f64_reg); two for the longest blocks, whose registers are full
     const int lane = threadIdx.x & 63;
     const int n_items = w.n_refine[height];
     const int n_waves = gridDim.x * 4;
@@ -306,6 +357,36 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
                 for (int off = 32; off >= 1; off >>= 1)
                     i_def = min(i_def, __shfl_xor(i_def, off, 64));
                 unsigned long long open = __ballot(lane < cnt && !certain && ci < i_def);
+                if constexpr (CPL > 0) {
+                    while (open && win < 0) {
+                        int rows[KW], a[KW], n = 0;
+#pragma unroll
+                        for (int k = 0; k < KW; ++k) {      // the lowest open rows come first
+                            int i = ((open >> lane) & 1ull) ? ci : 0x7FFFFFFF;
+#pragma unroll
+                            for (int off = 32; off >= 1; off >>= 1)
+                                i = min(i, __shfl_xor(i, off, 64));
+                            const bool on = open != 0ull;
+                            open &= ~__ballot(ci == i);
+                            rows[k] = i;
+                            a[k] = on ? l_ids[i] : 0;
+                            n += on;
+                        }
+                        double cs[KW];
+                        cosines_f64_reg<T, CPL, KW>(pool_g, pool.r, norm_g, a, n, braw, nb, lane, cs);
+#pragma unroll
+                        for (int k = 0; k < KW; ++k) {
+                            if (k < n && win < 0) {
+                                if (cs[k] > thr) {
+                                    win = rows[k];
+                                    bv = cs[k];
+                                } else {
+                                    bv = fmax(bv, cs[k]);
+                                }
+                            }
+                        }
+                    }
+                } else {
                 while (open) {
                     int i = ((open >> lane) & 1ull) ? ci : 0x7FFFFFFF;     // the lowest open row comes first
 #pragma unroll
@@ -320,9 +401,31 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
                     }
                     bv = fmax(bv, cs);
                 }
+                }
                 if (win < 0 && i_def != 0x7FFFFFFF) {
                     win = i_def;
                     bv = INFINITY;      // certain rows are more than band above thr
+                }
+            } else if constexpr (CPL > 0) {
+                for (int i0 = 0; i0 < ml && win < 0; i0 += KW) {
+                    const int n = min(KW, ml - i0);
+                    int a[KW];
+#pragma unroll
+                    for (int k = 0; k < KW; ++k)
+                        a[k] = l_ids[min(i0 + k, ml - 1)];
+                    double cs[KW];
+                    cosines_f64_reg<T, CPL, KW>(pool_g, pool.r, norm_g, a, n, braw, nb, lane, cs);
+#pragma unroll
+                    for (int k = 0; k < KW; ++k) {
+                        if (k < n && win < 0) {
+                            if (cs[k] > thr) {
+                                win = i0 + k;
+                                bv = cs[k];
+                            } else {
+                                bv = fmax(bv, cs[k]);
+                            }
+                        }
+                    }
                 }
             } else {
                 for (int i = 0; i < ml; ++i) {
@@ -360,52 +463,29 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
             }
             if constexpr (CPL > 0) {
                 // Every contender costs one block read that nothing else shares, so the chain "row -> physical id ->
-                // block -> dot product" is what a column waits for.  The ids and norms of all contenders are fetched
-                // at once (one per lane), and the block of the next contender is on its way while the current one
-                // is multiplied.  Same operations in the same order as cosine_f64_reg.
+                // block -> dot product" is what a column waits for.  The ids of all contenders are fetched at once (one
+                // per lane), and KW contenders are multiplied side by side.
                 const int pid = lane < cnt ? l_ids[ci] : 0;
-                const double pna = norm_g[pid];
-                const int chunks = pool.r / Elem<T>::PER16;
-                uint4 nraw[CPL];
-                int src = mask ? __ffsll((long long)mask) - 1 : 0;      // a listed column has at least its maximum in mask
-                if (mask) {
-                    const uint4 *pa = reinterpret_cast<const uint4 *>(pool_g + (int64_t)__shfl(pid, src, 64) * pool.r);
-#pragma unroll
-                    for (int q = 0; q < CPL; ++q)
-                        nraw[q] = pa[min(lane + 64 * q, chunks - 1)];
-                }
                 while (mask) {
-                    mask &= mask - 1;
-                    const int i = __shfl(ci, src, 64);
-                    const double na = __shfl(pna, src, 64);
-                    uint4 araw[CPL];
+                    int src[KW], a[KW], n = 0;
 #pragma unroll
-                    for (int q = 0; q < CPL; ++q)
-                        araw[q] = nraw[q];
-                    if (mask) {
-                        src = __ffsll((long long)mask) - 1;
-                        const uint4 *pa = reinterpret_cast<const uint4 *>(pool_g + (int64_t)__shfl(pid, src, 64) * pool.r);
-#pragma unroll
-                        for (int q = 0; q < CPL; ++q)
-                            nraw[q] = pa[min(lane + 64 * q, chunks - 1)];
+                    for (int k = 0; k < KW; ++k) {
+                        const bool on = mask != 0ull;
+                        src[k] = on ? __ffsll((long long)mask) - 1 : 0;
+                        if (on)
+                            mask &= mask - 1;
+                        a[k] = __shfl(pid, src[k], 64);
+                        n += on;
                     }
-                    double dot = 0.0;
+                    double cs[KW];
+                    cosines_f64_reg<T, CPL, KW>(pool_g, pool.r, norm_g, a, n, braw, nb, lane, cs);
 #pragma unroll
-                    for (int q = 0; q < CPL; ++q) {
-                        if (lane + 64 * q < chunks) {
-                            double x[Elem<T>::PER16], y[Elem<T>::PER16];
-                            Elem<T>::widen(araw[q], x);
-                            Elem<T>::widen(braw[q], y);
-#pragma unroll
-                            for (int e = 0; e < Elem<T>::PER16; ++e)
-                                dot = fma(x[e], y[e], dot);
+                    for (int k = 0; k < KW; ++k) {
+                        const int i = __shfl(ci, src[k], 64);
+                        if (k < n && (cs[k] > bv || (cs[k] == bv && i < bi))) {
+                            bv = cs[k];
+                            bi = i;
                         }
-                    }
-                    dot = wave_sum(dot);
-                    const double cs = (na == 0.0 || nb == 0.0) ? 0.0 : dot / (na * nb);
-                    if (cs > bv || (cs == bv && i < bi)) {
-                        bv = cs;
-                        bi = i;
                     }
                 }
             } else {
@@ -422,11 +502,30 @@ __global__ __launch_bounds__(256) void assign_refine_kernel(PoolDesc pool, WorkD
             }
         } else {
             // more screen candidates than slots: rescan the whole column (ascending rows, strict '>')
-            for (int i = 0; i < ml; ++i) {
-                const double cs = cosine(l_ids[i]);
-                if (cs > bv) {
-                    bv = cs;
-                    bi = i;
+            if constexpr (CPL > 0) {
+                for (int i0 = 0; i0 < ml; i0 += KW) {
+                    const int n = min(KW, ml - i0);
+                    int a[KW];
+#pragma unroll
+                    for (int k = 0; k < KW; ++k)
+                        a[k] = l_ids[min(i0 + k, ml - 1)];
+                    double cs[KW];
+                    cosines_f64_reg<T, CPL, KW>(pool_g, pool.r, norm_g, a, n, braw, nb, lane, cs);
+#pragma unroll
+                    for (int k = 0; k < KW; ++k) {
+                        if (k < n && cs[k] > bv) {
+                            bv = cs[k];
+                            bi = i0 + k;
+                        }
+                    }
+                }
+            } else {
+                for (int i = 0; i < ml; ++i) {
+                    const double cs = cosine(l_ids[i]);
+                    if (cs > bv) {
+                        bv = cs;
+                        bi = i;
+                    }
                 }
             }
         }
